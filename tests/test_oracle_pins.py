@@ -1,0 +1,392 @@
+"""Pins for the CPU oracle: each test checks oracle/kvc_oracle.c against something other than
+itself -- hand-worked pages, closed forms, a library routine, an independent statement of the
+bit format, brute force, or an invariant the mathematics fixes.  No GPU involved."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from oracle import kvc_oracle as o
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ------------------------------------------------------------------ FP16 conversions vs numpy
+
+def test_half_to_float_all_patterns_match_numpy():
+    bits = np.arange(65536, dtype=np.uint16)
+    ref = bits.view(np.float16).astype(np.float32)
+    got = np.array([o.half_to_float(int(b)) for b in bits], np.float32)
+    nan = np.isnan(ref)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan].view(np.uint32), ref[~nan].view(np.uint32))
+
+
+def test_float_to_half_matches_numpy_on_midpoints_and_random():
+    rng = np.random.default_rng(1)
+    # every FP16 value, every midpoint between neighbours, and a nudge either side of it
+    h = np.arange(0, 0x7C00, dtype=np.uint16).view(np.float16).astype(np.float64)
+    mid = (h[:-1] + h[1:]) / 2
+    cand = np.concatenate([h, mid, np.nextafter(mid.astype(np.float32), np.float32(np.inf)),
+                           np.nextafter(mid.astype(np.float32), np.float32(-np.inf)),
+                           [65504.0, 65519.99, 65520.0, 70000.0, 1e-8, 2.0 ** -25, 2.0 ** -25 * 1.0001, 2.0 ** -24 * 1.5],
+                           rng.standard_normal(20000) * np.exp(rng.uniform(-18, 11, 20000))]).astype(np.float32)
+    cand = np.concatenate([cand, -cand])
+    with np.errstate(over="ignore"):
+        ref = cand.astype(np.float16).view(np.uint16)
+    got = np.array([o.float_to_half(float(v)) for v in cand], np.uint16)
+    assert np.array_equal(got, ref)
+
+
+# ------------------------------------------------------------------ hand-worked pages
+
+def _cases():
+    with open(os.path.join(GOLD, "kvc1_handworked.json")) as f:
+        return json.load(f)["cases"]
+
+
+@pytest.mark.parametrize("case", _cases(), ids=lambda c: c["name"])
+def test_handworked_pages(case):
+    x = np.frombuffer(bytes.fromhex(case["x_fp16_le_hex"]), np.uint16)
+    desc, payload = o.encode_page(x, case["N"], case["d"], case["scheme"])
+    assert int(desc["mode"]) == case["mode"]
+    assert int(desc["n16"]) == case["n16"]
+    assert int(desc["rsvd"]) == 0
+    assert f"{int(np.float32(desc['scale']).view(np.uint32)):08x}" == case["scale_bits"]
+    assert payload.hex() == case["payload_hex"]
+    rc, xhat = o.decode_page(payload, desc, case["N"], case["d"])
+    assert rc == 0
+    if "xhat_bits_prefix" in case:
+        assert [f"{v:04x}" for v in xhat[: len(case["xhat_bits_prefix"])]] == case["xhat_bits_prefix"]
+    if case["scale_bits"] == "3f800000":  # s = 1: integer inputs come back exactly
+        assert np.array_equal(xhat, x)
+
+
+# ------------------------------------------------------------------ scale / quantize closed forms
+
+def test_tie_rule_is_round_half_even():
+    x = np.zeros(32, np.float16)
+    x[:6] = [127, .5, 1.5, 2.5, -.5, -2.5]
+    nf, s, si, q = o.quantize_page(x)
+    assert not nf and s == 1.0 and si == 1.0
+    assert q[:6].tolist() == [127, 0, 2, 2, 0, -2]
+
+
+def test_amax_127_gives_identity_codes():
+    rng = np.random.default_rng(2)
+    x = rng.integers(-127, 128, 512).astype(np.float16)
+    x[17] = -127
+    nf, s, si, q = o.quantize_page(x)
+    assert s == 1.0 and np.array_equal(q, x.astype(np.int8))
+
+
+def test_scale_is_binary32_quotient_and_codes_follow_exact_product():
+    rng = np.random.default_rng(3)
+    for _ in range(50):
+        x = (rng.standard_normal(256) * np.exp(rng.uniform(-8, 6))).astype(np.float16)
+        nf, s, si, q = o.quantize_page(x)
+        amax = np.float32(np.abs(x.astype(np.float32)).max())
+        assert s == np.float32(amax / np.float32(127.0))
+        assert si == np.float32(np.float32(1.0) / s)
+        # exact product in rational arithmetic, ties to even
+        from fractions import Fraction
+        for xv, qv in zip(x[:64], q[:64]):
+            p = Fraction(float(xv)) * Fraction(float(si))
+            fl = p.numerator // p.denominator
+            r = p - fl
+            want = fl + (1 if r > Fraction(1, 2) or (r == Fraction(1, 2) and fl % 2 == 1) else 0)
+            assert int(qv) == want
+        assert np.abs(q.astype(int)).max() == 127  # the amax element always maps to +-127
+
+
+def test_quantization_error_bound():
+    """|x*s_inv - q| <= 1/2 and s_inv = (1/s)(1+e), |e| <= 2^-24, |q| <= 127 give
+    |x - q*s| <= s/2 + 127*s*2^-24 (1+2^-24) < s/2 (1 + 2^-15); after the binary32 product and the
+    FP16 rounding, |x - xhat| <= amax/254 (1 + 2^-14) + ulp16(xhat)/2."""
+    rng = np.random.default_rng(4)
+    worst = 0.0
+    for _ in range(40):
+        x = (rng.standard_normal((16, 128)) * np.exp(0.5 * rng.standard_normal(128))).astype(np.float16)
+        desc, payload = o.encode_page(x, 16, 128)
+        nf, s, si, q = o.quantize_page(x)
+        xf = x.astype(np.float64).ravel()
+        err = np.abs(xf - q.astype(np.float64) * float(s))
+        assert err.max() <= float(s) / 2 * (1 + 2.0 ** -15)
+        worst = max(worst, err.max() / (float(s) / 2))
+        rc, xhat = o.decode_page(payload, desc, 16, 128)
+        xh = xhat.view(np.float16).astype(np.float64)
+        ulp = np.spacing(np.abs(xhat.view(np.float16)).astype(np.float16)).astype(np.float64)
+        amax = np.abs(xf).max()
+        assert np.all(np.abs(xf - xh) <= amax / 254 * (1 + 2.0 ** -14) + ulp / 2)
+    assert worst > 0.95  # the bound is tight, so a wrong scale (e.g. amax/128) would break it
+
+
+def test_all_zero_page_and_negative_zero():
+    x = np.zeros((16, 64), np.float16)
+    x[3, 5] = -0.0
+    desc, payload = o.encode_page(x, 16, 64)
+    assert desc["scale"] == 0.0 and desc["mode"] == 3 and payload == bytes(16)
+    rc, xhat = o.decode_page(payload, desc, 16, 64)
+    assert rc == 0 and not xhat.any()
+
+
+# ------------------------------------------------------------------ schemes and sizes
+
+def _size_closed_form(u: np.ndarray, with_runs: bool) -> int:
+    G = u.size // 32
+    ug = u.reshape(G, 32).astype(np.int64)
+    mx = ug.max(1)
+    w = np.where(mx > 0, np.floor(np.log2(np.maximum(mx, 1))).astype(int) + 1, 0)
+    if with_runs:
+        eq = (ug == ug[:, :1]).all(1)
+        body = np.where(mx == 0, 0, np.where(eq, 1, 4 * w))
+    else:
+        body = 4 * np.maximum(w, 1)
+    return ((G + 1) // 2 + int(body.sum()) + 15) // 16 * 16
+
+
+def test_int8_scheme_is_exactly_two_to_one():
+    """Table 9: INT8 only = 2.00x (payload); with the 16-byte descriptor 4096/2064."""
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((32, 16, 128)).astype(np.float16)
+    desc, pool = o.compress_pages(x, 16, 128, scheme=o.MODE_INT8)
+    assert (desc["mode"] == 1).all() and (desc["n16"] == 128).all()
+    assert pool.size * 2 == x.nbytes
+    assert o.ratio(desc, 2048) == pytest.approx(4096 / 2064)
+    for p in range(4):
+        nf, s, si, q = o.quantize_page(x[p])
+        assert o.page_payload(pool, desc[p]) == q.tobytes()
+
+
+@pytest.mark.parametrize("scheme", [2, 3])
+def test_payload_size_closed_form_and_fallback(scheme):
+    rng = np.random.default_rng(6)
+    n_fallback = 0
+    for t in range(60):
+        sigma = np.exp(rng.uniform(-1.5, 1.5, 128))
+        x = (rng.standard_normal((16, 128)) * sigma).astype(np.float16)
+        if t % 3 == 0:
+            x[:, rng.integers(0, 128)] *= 30  # one dominant channel -> small codes elsewhere
+        if t % 5 == 0:
+            x[rng.integers(0, 16)] = 0  # a zero token row -> zero-run packets
+        desc, payload = o.encode_page(x, 16, 128, scheme)
+        nf, s, si, q = o.quantize_page(x)
+        u = o.delta_zigzag(q, 16, 128)
+        n = _size_closed_form(u, scheme == 3)
+        if n >= 2048:
+            n_fallback += 1
+            assert desc["mode"] == 1 and len(payload) == 2048 and payload == q.tobytes()
+        else:
+            assert desc["mode"] == scheme and len(payload) == n
+    assert 0 < n_fallback < 60
+
+
+# ------------------------------------------------------------------ the bit format, stated independently
+
+def _parse_payload_py(payload: bytes, G: int, mode: int):
+    """Independent reader of the packet format from its definition, with Python big integers:
+    a literal body is the little-endian integer whose bits [k*w, (k+1)*w) hold u_k."""
+    hdr = (G + 1) // 2
+    pos, u = hdr, []
+    for g in range(G):
+        c = (payload[g >> 1] >> 4) if g & 1 else (payload[g >> 1] & 15)
+        if mode == 3 and c == 0:
+            u += [0] * 32
+        elif mode == 3 and c == 9:
+            u += [payload[pos]] * 32
+            pos += 1
+        else:
+            assert 1 <= c <= 8
+            big = int.from_bytes(payload[pos:pos + 4 * c], "little")
+            u += [(big >> (k * c)) & ((1 << c) - 1) for k in range(32)]
+            pos += 4 * c
+    assert all(b == 0 for b in payload[pos:]) and len(payload) - pos < 16
+    return u
+
+
+def _codes_from_u_py(u, N, d):
+    q = []
+    for j in range(N):
+        acc = 0
+        for i in range(d):
+            uu = u[j * d + i]
+            delta = (uu >> 1) ^ -(uu & 1)
+            acc = ((acc + delta + 128) % 256) - 128
+            q.append(acc)
+    return q
+
+
+def _u_from_codes_py(q, N, d):
+    u = []
+    for j in range(N):
+        for i in range(d):
+            left = q[j * d + i - 1] if i else 0
+            delta = ((q[j * d + i] - left + 128) % 256) - 128
+            u.append(2 * delta if delta >= 0 else -2 * delta - 1)
+    return u
+
+
+@pytest.mark.parametrize("scheme", [2, 3])
+def test_packed_payload_parses_by_definition(scheme):
+    rng = np.random.default_rng(7)
+    for t in range(25):
+        x = (rng.standard_normal((4, 64)) * np.exp(rng.uniform(-1, 1, 64))).astype(np.float16)
+        x[:, 7] *= (1, 8, 60)[t % 3]
+        if t % 4 == 0:
+            x[1] = 0
+        desc, payload = o.encode_page(x, 4, 64, scheme)
+        nf, s, si, q = o.quantize_page(x)
+        if desc["mode"] == 1:
+            continue
+        u = _parse_payload_py(payload, 8, int(desc["mode"]))
+        assert u == _u_from_codes_py(q.tolist(), 4, 64)
+        assert _codes_from_u_py(u, 4, 64) == q.tolist()
+        rc, q2 = o.decode_codes(payload, int(desc["mode"]), 4, 64)
+        assert rc == 0 and np.array_equal(q2, q)
+
+
+def test_zigzag_table():
+    q = np.array([0, -1, 0, 1, 0, 127, 0, -127, 0] + [0] * 23, np.int8)
+    u = o.delta_zigzag(q, 1, 32)
+    # deltas: 0,-1,1,1,-1,127,-127,-127,127 -> 0,1,2,2,1,254,253,253,254
+    assert u[:9].tolist() == [0, 1, 2, 2, 1, 254, 253, 253, 254]
+    # wrap: 127 -> -127 is delta -254 = +2 mod 256; -127 -> 127 is +254 = -2 mod 256
+    q = np.array([127, -127, 127] + [0] * 29, np.int8)
+    assert o.delta_zigzag(q, 1, 32)[:3].tolist() == [254, 4, 3]
+    # delta = -128 only arises by wrap-around: 64 -> -64
+    q = np.array([64, -64] + [0] * 30, np.int8)
+    assert o.delta_zigzag(q, 1, 32)[:2].tolist() == [128, 255]
+
+
+def test_every_packet_code_round_trips():
+    """Groups engineered to produce each header code 0..9, in both nibble positions."""
+    rng = np.random.default_rng(8)
+    N, d = 1, 32 * 20
+    groups = []
+    for c in list(range(0, 10)) * 2:
+        if c == 0:
+            g = [0] * 32
+        elif c == 9:
+            g = [int(rng.integers(1, 256))] * 32
+        else:
+            g = rng.integers(0, 1 << c, 32).tolist()
+            g[int(rng.integers(0, 32))] = (1 << c) - 1 if c > 1 else 1
+            if c == 1 and len(set(g)) == 1:
+                g[0] ^= 1
+        groups.append(g)
+    order = rng.permutation(20)
+    u = [v for k in order for v in groups[k]]
+    packed = o.rle_pack(np.array(u, np.uint8), True)
+    padded = packed + bytes(-len(packed) % 16)
+    assert _parse_payload_py(padded, 20, 3) == u
+    want_codes = [list(range(0, 10))[k % 10] for k in order]
+    got_codes = [(packed[g >> 1] >> 4) if g & 1 else (packed[g >> 1] & 15) for g in range(20)]
+    assert got_codes == want_codes
+    rc, q = o.decode_codes(padded, 3, N, d)
+    assert rc == 0 and q.tolist() == _codes_from_u_py(u, N, d)
+
+
+def test_brute_force_single_group_small_alphabet():
+    """All 3^8 one-group pages with 8 free codes in {-1,0,1}: packing matches the big-integer
+    definition and decoding returns the codes."""
+    import itertools
+    for free in itertools.product((-1, 0, 1), repeat=8):
+        q = list(free) + [0] * 24
+        u = _u_from_codes_py(q, 1, 32)
+        packed = o.rle_pack(np.array(u, np.uint8), True)
+        mx = max(u)
+        if mx == 0:
+            assert packed == b"\x00"
+        elif len(set(u)) == 1:
+            assert packed == bytes([9, u[0]])
+        else:
+            w = mx.bit_length()
+            big = sum(v << (k * w) for k, v in enumerate(u))
+            assert packed == bytes([w]) + big.to_bytes(4 * w, "little")
+        rc, q2 = o.decode_codes(packed + bytes(-len(packed) % 16), 3, 1, 32)
+        assert rc == 0 and q2.tolist() == q
+
+
+# ------------------------------------------------------------------ invariants
+
+@pytest.mark.parametrize("scheme", [1, 2, 3])
+def test_lossless_after_int8_and_decode_is_q_times_s(scheme):
+    rng = np.random.default_rng(9)
+    x = (rng.standard_normal((24, 16, 128)) * np.exp(0.5 * rng.standard_normal((1, 1, 128)))).astype(np.float16)
+    x[3] = 0
+    x[5, :, 40] *= 10
+    desc, pool = o.compress_pages(x, 16, 128, scheme)
+    out, bad = o.decompress_pages(pool, desc, 16, 128)
+    assert bad == 0
+    for p in range(24):
+        nf, s, si, q = o.quantize_page(x[p])
+        rc, q2 = o.decode_codes(o.page_payload(pool, desc[p]), int(desc[p]["mode"]), 16, 128)
+        assert rc == 0 and np.array_equal(q, q2)
+        want = (q.astype(np.float32) * s).astype(np.float16)  # numpy: binary32 product, RNE to binary16
+        assert np.array_equal(out[p].ravel().view(np.float16), want)
+
+
+def test_reencoding_decoded_page_is_idempotent():
+    rng = np.random.default_rng(10)
+    fails = 0
+    for _ in range(30):
+        x = (rng.standard_normal((16, 128)) * np.exp(0.5 * rng.standard_normal(128))).astype(np.float16)
+        d1, p1 = o.encode_page(x, 16, 128)
+        rc, xh = o.decode_page(p1, d1, 16, 128)
+        d2, p2 = o.encode_page(xh, 16, 128)
+        rc, xh2 = o.decode_page(p2, d2, 16, 128)
+        fails += not np.array_equal(xh, xh2)
+    assert fails == 0
+
+
+def test_raw_bypass_is_bit_exact_and_triggered_by_nonfinite():
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((16, 128)).astype(np.float16).view(np.uint16).copy()
+    for poison in (0x7C00, 0xFC00, 0x7E00, 0x7C01, 0xFFFF):
+        y = x.copy()
+        y[7, 99] = poison
+        desc, payload = o.encode_page(y, 16, 128)
+        assert desc["mode"] == 0 and desc["scale"] == 0.0 and desc["n16"] == 256
+        assert payload == y.tobytes()
+        rc, out = o.decode_page(payload, desc, 16, 128)
+        assert rc == 0 and np.array_equal(out, y.ravel())
+    desc, payload = o.encode_page(x, 16, 128, scheme=0)
+    assert desc["mode"] == 0 and payload == x.tobytes()
+    y = x.copy()
+    y[0, 0] = 0x7BFF  # largest finite value is not a bypass trigger
+    assert o.encode_page(y, 16, 128)[0]["mode"] != 0
+
+
+def test_corrupt_descriptors_are_rejected_and_zero_filled():
+    x = np.random.default_rng(12).standard_normal((16, 128)).astype(np.float16)
+    x[:, 3] *= 30
+    desc, payload = o.encode_page(x, 16, 128)
+    assert desc["mode"] == 3
+    for field, val in (("mode", 0xFF), ("mode", 7), ("n16", int(desc["n16"]) - 1)):
+        d2 = desc.copy()
+        d2[field] = val
+        rc, out = o.decode_page(payload[: int(d2["n16"]) * 16], d2, 16, 128)
+        assert rc != 0 and not out.any()
+    bad = bytearray(payload)
+    bad[0] = 0xAA  # header codes 10: not a packet code
+    rc, out = o.decode_page(bytes(bad), desc, 16, 128)
+    assert rc != 0 and not out.any()
+
+
+def test_batch_driver_is_thread_count_independent_and_contiguous():
+    rng = np.random.default_rng(13)
+    x = (rng.standard_normal((37, 16, 64)) * np.exp(rng.standard_normal((37, 1, 64)))).astype(np.float16)
+    d1, p1 = o.compress_pages(x, 16, 64, 3, n_threads=1)
+    d4, p4 = o.compress_pages(x, 16, 64, 3, n_threads=4)
+    assert np.array_equal(d1, d4) and np.array_equal(p1, p4)
+    assert d1["off"][0] == 0
+    assert np.array_equal(d1["off"][1:], np.cumsum(d1["n16"].astype(np.int64) * 16)[:-1])
+    assert p1.size == int(d1["n16"].astype(np.int64).sum()) * 16
+    for p in (0, 17, 36):
+        dd, pl = o.encode_page(x[p], 16, 64)
+        assert pl == o.page_payload(p1, d1[p]) and dd["scale"] == d1[p]["scale"] and dd["mode"] == d1[p]["mode"]
+    ids = np.array([5, 5, 36, 0], np.int64)
+    out, bad = o.decompress_pages(p1, d1, 16, 64, page_ids=ids, n_threads=3)
+    full, _ = o.decompress_pages(p1, d1, 16, 64)
+    assert bad == 0 and np.array_equal(out, full[ids])

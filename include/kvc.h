@@ -1,0 +1,142 @@
+/*
+ * kvc.h -- C ABI of libkvc: the KV-cache page codec of CXL-SpecKV for one AMD MI355X (gfx950).
+ *
+ * The library encodes paged FP16 K/V blocks into a compressed pool when they are offloaded
+ * (the paper's Compression Engine, Section 3.5.2, Algorithm 2) and decodes pool blocks back into
+ * a paged FP16 buffer when they are prefetched (Decompression Engine, Section 3.5.3; the
+ * scatter-gather fetch through a translation table of Section 3.4.2, Algorithm 1).  The remote
+ * (CXL) tier of the paper is a second buffer in the same GPU's HBM.
+ *
+ * Geometry.  A PAGE is N tokens x d channels of one KV head, FP16, row-major (N*d*2 bytes; 16 x 128
+ * gives the paper's 4 KB page).  A BLOCK is `pages_per_block` consecutive pages (all KV heads, or
+ * K and V of all heads, of one 16-token block).  A cache buffer is FP16 [n_blocks][ppb][N][d].
+ *
+ * Compressed form of a page = one 16-byte descriptor (kvc_desc) + a payload of n16*16 bytes in
+ * the pool.  Payload by mode:
+ *   0 RAW    the N*d*2 input bytes unchanged (requested, or the page holds a NaN/Inf);
+ *   1 INT8   q[j][i] = round_half_even(x * (1/s)), s = max|X|/127 (binary32), N*d bytes;
+ *   2 DELTA  q differenced along i (first column verbatim), wrapped to 8 bits, zig-zag mapped to
+ *            u, cut into groups of 32; header of one 4-bit code per group (group g in byte g/2,
+ *            even g in the low nibble) followed by the group bodies; code w in 1..8 = literal
+ *            packet, 4*w bytes, u_k in bits [k*w,(k+1)*w) of the little-endian bit string;
+ *   3 RLE    as 2, plus code 0 = 32 zeros (no body) and code 9 = 32 copies of one byte (1 byte);
+ *   payloads are zero-padded to 16 bytes; a mode-2/3 page whose payload would not be smaller
+ *   than its INT8 payload is stored as mode 1.
+ * Decoding yields fp16(fp32(q) * s), one binary32 multiply and one round-to-nearest-even.
+ *
+ * Memory.  Every data pointer below is DEVICE memory allocated and owned by the caller; the
+ * library owns only the host-side context and a 64-byte device state block (pool cursor, sticky
+ * status).  `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *
+ * Asynchrony and errors.  compress / decompress / gather only enqueue kernels.  They return 0 or a
+ * negative KVC_ERR_* for faults the host can see (nothing is enqueued then).  Faults only the
+ * device can see set sticky KVC_ST_* bits: the page gets mode 0xFF (compress) or is zero-filled
+ * (decompress); kvc_stats() reports them.  Block ids < 0 mean "skip this block".
+ * Calls on one context that overlap on different streams race on the pool cursor; serialise them.
+ */
+#ifndef KVC_H
+#define KVC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KVC_OK 0
+#define KVC_ERR_ARG (-1)          /* bad argument (null pointer, size out of range) */
+#define KVC_ERR_NOT_BOUND (-2)    /* kvc_bind_pool has not been called */
+#define KVC_ERR_HIP (-3)          /* a HIP runtime call failed */
+#define KVC_ERR_POOL_FULL (-4)    /* reported by kvc_stats: at least one page did not fit */
+#define KVC_ERR_CORRUPT (-5)      /* reported by kvc_stats: bad descriptor, payload or index */
+#define KVC_ERR_UNSUPPORTED (-6)  /* geometry the kernels are not built for */
+
+#define KVC_MODE_RAW 0
+#define KVC_MODE_INT8 1
+#define KVC_MODE_DELTA 2
+#define KVC_MODE_RLE 3
+#define KVC_MODE_INVALID 0xFF
+
+#define KVC_ST_POOL_FULL 1u  /* a page did not fit into the pool */
+#define KVC_ST_CORRUPT 2u    /* descriptor/payload failed validation on decode */
+#define KVC_ST_BAD_INDEX 4u  /* a block id or table entry pointed outside its buffer */
+
+typedef struct kvc_ctx kvc_ctx; /* opaque host object */
+
+/* Page descriptor, 16 bytes, little-endian.  The paper's output <s, D_RLE> (Algorithm 2) is
+ * {scale, payload at off}. */
+typedef struct {
+    uint64_t off;  /* byte offset of the payload in the pool, multiple of 16 */
+    float scale;   /* s; 0 for RAW and all-zero pages */
+    uint16_t n16;  /* payload bytes / 16, padding included */
+    uint8_t mode;  /* KVC_MODE_* */
+    uint8_t rsvd;  /* 0 */
+} kvc_desc;
+
+typedef struct {
+    int32_t tokens_per_block; /* N >= 1 */
+    int32_t head_dim;         /* d in {32, 64, 128, 256};  N*d <= 4096 */
+    int32_t pages_per_block;  /* ppb >= 1 */
+    int32_t scheme;           /* mode requested from compress: 0..3 */
+} kvc_config;
+
+typedef struct {
+    uint64_t pool_bytes_used; /* bytes handed out by the pool cursor (capped at the pool size) */
+    uint64_t pages[4];        /* bound descriptors per mode 0..3 */
+    uint64_t pages_invalid;   /* bound descriptors with mode 0xFF (never written, or did not fit) */
+    uint64_t payload_bytes;   /* sum of n16*16 over descriptors of mode 0..3 */
+    uint32_t status;          /* OR of KVC_ST_* since the last kvc_reset_pool */
+    uint32_t rsvd;
+} kvc_stats_t;
+
+/* Create / destroy a context.  kvc_create allocates the device state block on the current device. */
+int kvc_create(kvc_ctx** out, const kvc_config* cfg);
+void kvc_destroy(kvc_ctx* ctx);
+
+/* Change the mode compress requests (0..3); takes effect for later calls. */
+int kvc_set_scheme(kvc_ctx* ctx, int32_t scheme);
+
+/* Attach the compressed pool (pool_bytes, 16-byte aligned, any multiple of 16) and the descriptor
+ * table (n_desc_pages entries; page p of pool block b is entry b*ppb + p).  Both caller-owned. */
+int kvc_bind_pool(kvc_ctx* ctx, void* d_pool, uint64_t pool_bytes, kvc_desc* d_desc, uint64_t n_desc_pages);
+
+/* Cursor = 0, status = 0, every descriptor = INVALID.  Enqueues fill kernels only. */
+int kvc_reset_pool(kvc_ctx* ctx, void* stream);
+
+/* Algorithm 2 over n blocks.  Block i is read from cache block src[i] (NULL: i) and stored as pool
+ * block pool[i] (NULL: i).  d_cache: FP16 [n_cache_blocks][ppb][N][d].  Space comes from a bump
+ * cursor; placement order inside the pool is unspecified, descriptors say where each page is.
+ * Re-compressing into an occupied pool block leaks its old span until kvc_reset_pool. */
+int kvc_compress_blocks(kvc_ctx* ctx, const void* d_cache, int64_t n_cache_blocks, const int32_t* d_src_block_ids,
+                        const int32_t* d_pool_block_ids, int32_t n, void* stream);
+
+/* Inverse (Section 3.5.3) over n blocks: pool block pool[i] (NULL: i) is decoded into output block
+ * dst[i] (NULL: i) of d_cache_out, FP16 [n_out_blocks][ppb][N][d]. */
+int kvc_decompress_blocks(kvc_ctx* ctx, void* d_cache_out, int64_t n_out_blocks, const int32_t* d_pool_block_ids,
+                          const int32_t* d_dst_block_ids, int32_t n, void* stream);
+
+/* Prefetch fetch of Algorithm 1: for every layer l, sequence s and j < k, logical block
+ * pred[s][j] is translated through block_table[s][.] to a pool block of that layer
+ * (l*pool_blocks_per_layer + entry) and decoded into output block (l*n_seq + s)*k + j of d_out,
+ * FP16 [n_layers*n_seq*k][ppb][N][d].  d_block_table: int32 [n_seq][max_blocks]; d_pred: int32
+ * [n_seq][k].  pred < 0 or a table entry < 0 skips the block; values beyond their range set
+ * KVC_ST_BAD_INDEX and zero-fill the block. */
+int kvc_gather_decompress(kvc_ctx* ctx, void* d_out, const int32_t* d_block_table, int32_t max_blocks,
+                          const int32_t* d_pred, int32_t n_seq, int32_t k, int32_t n_layers,
+                          int64_t pool_blocks_per_layer, void* stream);
+
+/* Reduce the descriptor table and read the device state.  The only call that synchronises
+ * (on `stream`).  Returns KVC_ERR_POOL_FULL / KVC_ERR_CORRUPT if the matching status bit is set
+ * (out is filled either way), else 0. */
+int kvc_stats(kvc_ctx* ctx, kvc_stats_t* out, void* stream);
+
+/* dst[0..nbytes) = src[0..nbytes) with one 128-bit load and store per lane; nbytes multiple of 16.
+ * The bandwidth yardstick the codec kernels are compared with. */
+int kvc_copy_bytes(void* d_dst, const void* d_src, uint64_t nbytes, void* stream);
+
+const char* kvc_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVC_H */

@@ -1,0 +1,225 @@
+// C ABI of libkvc (see include/kvc.h): argument checks and kernel launches only.
+#include <algorithm>
+#include <new>
+
+#include "kvc_common.h"
+
+struct kvc_ctx {
+    kvc_config cfg;
+    kvc::Geometry g;
+    int device;
+    kvc::DevState* st;  // device
+    uint8_t* pool;
+    uint64_t pool_bytes;
+    kvc_desc* desc;
+    uint64_t n_desc;
+};
+
+static_assert(sizeof(kvc_desc) == 16, "descriptor is 16 bytes");
+
+// Text of the last HIP failure seen by this thread (for kvc_strerror(KVC_ERR_HIP)).
+static thread_local hipError_t t_last_hip = hipSuccess;
+
+static bool hip_ok(hipError_t e) {
+    if (e != hipSuccess) t_last_hip = e;
+    return e == hipSuccess;
+}
+
+static bool config_ok(const kvc_config* c) {
+    if (!c) return false;
+    if (c->tokens_per_block < 1 || c->pages_per_block < 1) return false;
+    if (c->scheme < 0 || c->scheme > 3) return false;
+    const int d = c->head_dim;
+    if (!(d == 32 || d == 64 || d == 128 || d == 256)) return false;
+    const int64_t E = (int64_t)c->tokens_per_block * d;
+    return E <= 4096;
+}
+
+extern "C" {
+
+int kvc_create(kvc_ctx** out, const kvc_config* cfg) {
+    if (!out) return KVC_ERR_ARG;
+    *out = nullptr;
+    if (!cfg) return KVC_ERR_ARG;
+    if (cfg->tokens_per_block < 1 || cfg->pages_per_block < 1 || cfg->scheme < 0 || cfg->scheme > 3 ||
+        cfg->head_dim < 32 || cfg->head_dim % 32 != 0)
+        return KVC_ERR_ARG;
+    if (!config_ok(cfg)) return KVC_ERR_UNSUPPORTED;
+    kvc_ctx* c = new (std::nothrow) kvc_ctx();
+    if (!c) return KVC_ERR_HIP;
+    c->cfg = *cfg;
+    c->g.N = cfg->tokens_per_block;
+    c->g.d = cfg->head_dim;
+    c->g.ppb = cfg->pages_per_block;
+    c->g.E = cfg->tokens_per_block * cfg->head_dim;
+    c->pool = nullptr;
+    c->pool_bytes = 0;
+    c->desc = nullptr;
+    c->n_desc = 0;
+    if (!hip_ok(hipGetDevice(&c->device)) || !hip_ok(hipMalloc(&c->st, sizeof(kvc::DevState)))) {
+        delete c;
+        return KVC_ERR_HIP;
+    }
+    if (!hip_ok(hipMemset(c->st, 0, sizeof(kvc::DevState)))) {
+        (void)hipFree(c->st);
+        delete c;
+        return KVC_ERR_HIP;
+    }
+    *out = c;
+    return KVC_OK;
+}
+
+void kvc_destroy(kvc_ctx* ctx) {
+    if (!ctx) return;
+    (void)hipFree(ctx->st);
+    delete ctx;
+}
+
+int kvc_set_scheme(kvc_ctx* ctx, int32_t scheme) {
+    if (!ctx || scheme < 0 || scheme > 3) return KVC_ERR_ARG;
+    ctx->cfg.scheme = scheme;
+    return KVC_OK;
+}
+
+int kvc_bind_pool(kvc_ctx* ctx, void* d_pool, uint64_t pool_bytes, kvc_desc* d_desc, uint64_t n_desc_pages) {
+    if (!ctx || !d_pool || !d_desc || pool_bytes == 0 || n_desc_pages == 0) return KVC_ERR_ARG;
+    if ((reinterpret_cast<uintptr_t>(d_pool) & 15u) || (reinterpret_cast<uintptr_t>(d_desc) & 15u) || (pool_bytes & 15u))
+        return KVC_ERR_ARG;
+    ctx->pool = static_cast<uint8_t*>(d_pool);
+    ctx->pool_bytes = pool_bytes;
+    ctx->desc = d_desc;
+    ctx->n_desc = n_desc_pages;
+    return KVC_OK;
+}
+
+int kvc_reset_pool(kvc_ctx* ctx, void* stream) {
+    if (!ctx) return KVC_ERR_ARG;
+    if (!ctx->pool) return KVC_ERR_NOT_BOUND;
+    return hip_ok(kvc::launch_reset(ctx->st, ctx->desc, ctx->n_desc, static_cast<hipStream_t>(stream)))
+               ? KVC_OK
+               : KVC_ERR_HIP;
+}
+
+int kvc_compress_blocks(kvc_ctx* ctx, const void* d_cache, int64_t n_cache_blocks, const int32_t* d_src_block_ids,
+                        const int32_t* d_pool_block_ids, int32_t n, void* stream) {
+    if (!ctx || n < 0 || n_cache_blocks < 0) return KVC_ERR_ARG;
+    if (!ctx->pool) return KVC_ERR_NOT_BOUND;
+    if (n == 0) return KVC_OK;
+    if (!d_cache || (reinterpret_cast<uintptr_t>(d_cache) & 15u)) return KVC_ERR_ARG;
+    // identity ids are checked here; explicit id arrays live on the device and are checked there
+    if (!d_src_block_ids && (int64_t)n > n_cache_blocks) return KVC_ERR_ARG;
+    if (!d_pool_block_ids && (uint64_t)n * (uint64_t)ctx->g.ppb > ctx->n_desc) return KVC_ERR_ARG;
+    kvc::EncodeArgs a;
+    a.cache = static_cast<const uint16_t*>(d_cache);
+    a.n_cache_blocks = n_cache_blocks;
+    a.src_ids = d_src_block_ids;
+    a.pool_ids = d_pool_block_ids;
+    a.n_pages = (int64_t)n * ctx->g.ppb;
+    a.g = ctx->g;
+    a.scheme = ctx->cfg.scheme;
+    a.pool = ctx->pool;
+    a.pool_units = ctx->pool_bytes / 16;
+    a.desc = ctx->desc;
+    a.n_desc = ctx->n_desc;
+    a.st = ctx->st;
+    return hip_ok(kvc::launch_compress(a, static_cast<hipStream_t>(stream))) ? KVC_OK : KVC_ERR_HIP;
+}
+
+static void fill_decode_common(kvc_ctx* ctx, kvc::DecodeArgs& a) {
+    a.g = ctx->g;
+    a.pool = ctx->pool;
+    a.pool_units = ctx->pool_bytes / 16;
+    a.desc = ctx->desc;
+    a.n_desc = ctx->n_desc;
+    a.st = ctx->st;
+    a.pool_ids = nullptr;
+    a.dst_ids = nullptr;
+    a.block_table = nullptr;
+    a.pred = nullptr;
+    a.max_blocks = a.n_seq = a.k = a.n_layers = 0;
+    a.pool_blocks_per_layer = 0;
+}
+
+int kvc_decompress_blocks(kvc_ctx* ctx, void* d_cache_out, int64_t n_out_blocks, const int32_t* d_pool_block_ids,
+                          const int32_t* d_dst_block_ids, int32_t n, void* stream) {
+    if (!ctx || n < 0 || n_out_blocks < 0) return KVC_ERR_ARG;
+    if (!ctx->pool) return KVC_ERR_NOT_BOUND;
+    if (n == 0) return KVC_OK;
+    if (!d_cache_out || (reinterpret_cast<uintptr_t>(d_cache_out) & 15u)) return KVC_ERR_ARG;
+    if (!d_dst_block_ids && (int64_t)n > n_out_blocks) return KVC_ERR_ARG;
+    if (!d_pool_block_ids && (uint64_t)n * (uint64_t)ctx->g.ppb > ctx->n_desc) return KVC_ERR_ARG;
+    kvc::DecodeArgs a;
+    fill_decode_common(ctx, a);
+    a.out = static_cast<uint16_t*>(d_cache_out);
+    a.n_out_blocks = n_out_blocks;
+    a.pool_ids = d_pool_block_ids;
+    a.dst_ids = d_dst_block_ids;
+    a.n_pages = (int64_t)n * ctx->g.ppb;
+    return hip_ok(kvc::launch_decompress(a, static_cast<hipStream_t>(stream))) ? KVC_OK : KVC_ERR_HIP;
+}
+
+int kvc_gather_decompress(kvc_ctx* ctx, void* d_out, const int32_t* d_block_table, int32_t max_blocks,
+                          const int32_t* d_pred, int32_t n_seq, int32_t k, int32_t n_layers,
+                          int64_t pool_blocks_per_layer, void* stream) {
+    if (!ctx || n_seq < 0 || k < 0 || n_layers < 0 || max_blocks < 0 || pool_blocks_per_layer < 0) return KVC_ERR_ARG;
+    if (!ctx->pool) return KVC_ERR_NOT_BOUND;
+    const int64_t n_blocks = (int64_t)n_layers * n_seq * k;
+    if (n_blocks == 0) return KVC_OK;
+    if (!d_out || !d_block_table || !d_pred || max_blocks == 0 || (reinterpret_cast<uintptr_t>(d_out) & 15u))
+        return KVC_ERR_ARG;
+    if ((uint64_t)n_layers * (uint64_t)pool_blocks_per_layer * (uint64_t)ctx->g.ppb > ctx->n_desc) return KVC_ERR_ARG;
+    kvc::DecodeArgs a;
+    fill_decode_common(ctx, a);
+    a.out = static_cast<uint16_t*>(d_out);
+    a.n_out_blocks = n_blocks;
+    a.n_pages = n_blocks * ctx->g.ppb;
+    a.block_table = d_block_table;
+    a.pred = d_pred;
+    a.max_blocks = max_blocks;
+    a.n_seq = n_seq;
+    a.k = k;
+    a.n_layers = n_layers;
+    a.pool_blocks_per_layer = pool_blocks_per_layer;
+    return hip_ok(kvc::launch_decompress(a, static_cast<hipStream_t>(stream))) ? KVC_OK : KVC_ERR_HIP;
+}
+
+int kvc_stats(kvc_ctx* ctx, kvc_stats_t* out, void* stream) {
+    if (!ctx || !out) return KVC_ERR_ARG;
+    if (!ctx->pool) return KVC_ERR_NOT_BOUND;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!hip_ok(kvc::launch_stats(ctx->st, ctx->desc, ctx->n_desc, s))) return KVC_ERR_HIP;
+    kvc::DevState h;
+    if (!hip_ok(hipMemcpyAsync(&h, ctx->st, sizeof(h), hipMemcpyDeviceToHost, s))) return KVC_ERR_HIP;
+    if (!hip_ok(hipStreamSynchronize(s))) return KVC_ERR_HIP;
+    out->pool_bytes_used = std::min<uint64_t>(h.cursor16 * 16ull, ctx->pool_bytes);
+    for (int i = 0; i < 4; ++i) out->pages[i] = h.stats[i];
+    out->pages_invalid = h.stats[4];
+    out->payload_bytes = h.stats[5] * 16ull;
+    out->status = h.status;
+    out->rsvd = 0;
+    if (h.status & KVC_ST_POOL_FULL) return KVC_ERR_POOL_FULL;
+    if (h.status & (KVC_ST_CORRUPT | KVC_ST_BAD_INDEX)) return KVC_ERR_CORRUPT;
+    return KVC_OK;
+}
+
+int kvc_copy_bytes(void* d_dst, const void* d_src, uint64_t nbytes, void* stream) {
+    if (!d_dst || !d_src || (nbytes & 15u) || (reinterpret_cast<uintptr_t>(d_dst) & 15u) ||
+        (reinterpret_cast<uintptr_t>(d_src) & 15u))
+        return KVC_ERR_ARG;
+    return hip_ok(kvc::launch_copy(d_dst, d_src, nbytes / 16, static_cast<hipStream_t>(stream))) ? KVC_OK : KVC_ERR_HIP;
+}
+
+const char* kvc_strerror(int code) {
+    switch (code) {
+        case KVC_OK: return "ok";
+        case KVC_ERR_ARG: return "bad argument";
+        case KVC_ERR_NOT_BOUND: return "no pool bound to the context";
+        case KVC_ERR_HIP: return t_last_hip != hipSuccess ? hipGetErrorString(t_last_hip) : "HIP runtime error";
+        case KVC_ERR_POOL_FULL: return "compressed pool exhausted; some pages were not stored";
+        case KVC_ERR_CORRUPT: return "invalid descriptor, payload or block index met on the device";
+        case KVC_ERR_UNSUPPORTED: return "page geometry not supported (head_dim in {32,64,128,256}, N*d <= 4096)";
+        default: return "unknown error";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,62 @@
+// Shared declarations between the C-ABI host code (kvc_api.hip) and the kernels (kvc_kernels.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kvc.h"
+
+namespace kvc {
+
+// Device state block owned by a context.
+struct DevState {
+    unsigned long long cursor16;  // next free 16-byte unit of the pool
+    unsigned int status;          // sticky KVC_ST_* bits
+    unsigned int pad;
+    unsigned long long stats[8];  // scratch of kvc_stats: pages[0..3], invalid, payload16
+};
+
+struct Geometry {
+    int32_t N, d, ppb, E;  // E = N*d elements per page
+};
+
+struct EncodeArgs {
+    const uint16_t* cache;
+    int64_t n_cache_blocks;
+    const int32_t* src_ids;
+    const int32_t* pool_ids;
+    int64_t n_pages;  // n blocks * ppb
+    Geometry g;
+    int32_t scheme;
+    uint8_t* pool;
+    uint64_t pool_units;  // pool size in 16-byte units
+    kvc_desc* desc;
+    uint64_t n_desc;
+    DevState* st;
+};
+
+struct DecodeArgs {
+    uint16_t* out;
+    int64_t n_out_blocks;
+    const int32_t* pool_ids;
+    const int32_t* dst_ids;
+    int64_t n_pages;
+    Geometry g;
+    const uint8_t* pool;
+    uint64_t pool_units;
+    const kvc_desc* desc;
+    uint64_t n_desc;
+    DevState* st;
+    // gather form (block_table != nullptr): page task t = ((l*n_seq + s)*k + j)*ppb + pg
+    const int32_t* block_table;
+    const int32_t* pred;
+    int32_t max_blocks, n_seq, k, n_layers;
+    int64_t pool_blocks_per_layer;
+};
+
+hipError_t launch_compress(const EncodeArgs& a, hipStream_t s);
+hipError_t launch_decompress(const DecodeArgs& a, hipStream_t s);
+hipError_t launch_reset(DevState* st, kvc_desc* desc, uint64_t n_desc, hipStream_t s);
+hipError_t launch_stats(DevState* st, const kvc_desc* desc, uint64_t n_desc, hipStream_t s);
+hipError_t launch_copy(void* dst, const void* src, uint64_t n16, hipStream_t s);
+
+}  // namespace kvc

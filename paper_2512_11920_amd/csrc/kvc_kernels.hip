@@ -1,0 +1,630 @@
+// HIP kernels of the KV page codec for gfx950 (wave64).
+//
+// Work decomposition: one wavefront owns one page at a time.  A lane owns 8 consecutive channels
+// (16 bytes of FP16), so a 64-lane pass covers 512 elements with one fully coalesced 128-bit
+// access per lane, a 32-element packet group is a quad of lanes, and a token row of d channels is
+// d/8 neighbouring lanes.  Compressed payloads are assembled in (encode) or staged through (decode)
+// LDS and move to/from the pool as 128-bit accesses.
+//
+// Encode follows Algorithm 2 of the paper (scaling, quantize, delta along the channel index,
+// run-length encode); decode follows Section 3.5.3 (undo run-length coding, prefix sum,
+// dequantize), with the stored-uncompressed bypass.
+#include "kvc_common.h"
+
+#include <hip/hip_fp16.h>
+
+namespace kvc {
+
+constexpr int kWavesPerWG = 4;
+constexpr int kThreads = kWavesPerWG * 64;
+
+// LDS bytes reserved for one page's payload under construction: header + bodies can reach
+// E + E/64 bytes before the INT8 fallback is chosen, plus slack for the 3-dword body writes.
+template <int MAXP>
+struct Slot {
+    static constexpr int kBytes = ((MAXP * 520 + 16 + 15) / 16) * 16;
+    static constexpr int kWords = kBytes / 4;
+};
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+__device__ __forceinline__ void wave_sync() {
+    // lanes of one wave exchange data through LDS: keep the compiler from moving accesses across
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = max(v, (uint32_t)__shfl_xor((int)v, o));
+    return v;
+}
+
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
+    const int lane = lane_id();
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        uint32_t t = (uint32_t)__shfl_up((int)v, o);
+        if (lane >= o) v += t;
+    }
+    return v;
+}
+
+// exclusive prefix over the lanes of one token row (lpr = lanes per row, power of two <= 32)
+__device__ __forceinline__ uint32_t row_excl_scan_u32(uint32_t v, int lpr) {
+    const int r = lane_id() & (lpr - 1);
+    uint32_t incl = v;
+#pragma unroll
+    for (int o = 1; o < 32; o <<= 1) {
+        uint32_t t = (uint32_t)__shfl_up((int)incl, o);
+        if (o < lpr && r >= o) incl += t;
+    }
+    return incl - v;
+}
+
+__device__ __forceinline__ float half_bits_to_float(uint32_t h) {
+    return __half2float(__ushort_as_half((unsigned short)h));
+}
+
+__device__ __forceinline__ uint32_t float_to_half_bits(float f) {
+    return (uint32_t)__half_as_ushort(__float2half_rn(f));
+}
+
+// Quantize step of Algorithm 2 on a lane's 8 elements: q = round_half_even(x * s_inv).  The fused
+// multiply-add against 1.5*2^23 rounds the exact product once, to an integer, ties to even.
+__device__ __forceinline__ void quantize8(const uint4& raw, float s_inv, int q[8]) {
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        float lo = half_bits_to_float(w[k] & 0xFFFFu);
+        float hi = half_bits_to_float(w[k] >> 16);
+        q[2 * k] = (int)__float_as_uint(__builtin_fmaf(lo, s_inv, 12582912.0f)) - 0x4B400000;
+        q[2 * k + 1] = (int)__float_as_uint(__builtin_fmaf(hi, s_inv, 12582912.0f)) - 0x4B400000;
+    }
+}
+
+__device__ __forceinline__ uint32_t pack_bytes4(int a, int b, int c, int d) {
+    return (uint32_t)(a & 0xFF) | ((uint32_t)(b & 0xFF) << 8) | ((uint32_t)(c & 0xFF) << 16) | ((uint32_t)d << 24);
+}
+
+// 8-bit wrap then zig-zag: 0,-1,1,-2,... -> 0,1,2,3,...
+__device__ __forceinline__ uint32_t zigzag8(int delta) {
+    uint32_t b = (uint32_t)delta & 0xFFu;
+    return ((b << 1) ^ (0u - (b >> 7))) & 0xFFu;
+}
+
+// ---------------------------------------------------------------------------------- encode
+
+struct PageResult {
+    uint32_t n16;   // payload size in 16-byte units (0 = page skipped)
+    uint32_t mode;
+    float scale;
+};
+
+template <int MAXP>
+__device__ __forceinline__ void store_codes(const uint4 (&raw)[MAXP], float s_inv, int E, uint32_t* stage) {
+    const int lane = lane_id();
+#pragma unroll
+    for (int p = 0; p < MAXP; ++p) {
+        const int e0 = p * 512 + lane * 8;
+        if (e0 < E) {
+            int q[8];
+            quantize8(raw[p], s_inv, q);
+            uint2 v;
+            v.x = pack_bytes4(q[0], q[1], q[2], q[3]);
+            v.y = pack_bytes4(q[4], q[5], q[6], q[7]);
+            *reinterpret_cast<uint2*>(reinterpret_cast<uint8_t*>(stage) + e0) = v;
+        }
+    }
+}
+
+// Encodes one page held at src into the LDS slot `stage` (modes 1..3).  A RAW page is only
+// classified here; its bytes go from the source to the pool in the copy-out phase.
+template <int MAXP>
+__device__ PageResult encode_page(const uint16_t* __restrict__ src, const Geometry& g, int scheme, uint32_t* stage) {
+    const int lane = lane_id();
+    const int E = g.E;
+    const int G = E >> 5;
+    const int hdr = (G + 1) >> 1;
+    const int lpr = g.d >> 3;
+    uint8_t* stage8 = reinterpret_cast<uint8_t*>(stage);
+
+    uint4 raw[MAXP];
+#pragma unroll
+    for (int p = 0; p < MAXP; ++p) {
+        const int e0 = p * 512 + lane * 8;
+        raw[p] = (e0 < E) ? *reinterpret_cast<const uint4*>(src + e0) : make_uint4(0, 0, 0, 0);
+    }
+    // scaling step: max |x| over the page on the FP16 bit patterns (monotone in magnitude)
+    uint32_t m = 0;
+#pragma unroll
+    for (int p = 0; p < MAXP; ++p) {
+        const uint32_t w[4] = {raw[p].x, raw[p].y, raw[p].z, raw[p].w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            uint32_t a = w[k] & 0x7FFF7FFFu;
+            m = max(m, max(a & 0xFFFFu, a >> 16));
+        }
+    }
+    m = wave_max_u32(m);
+    PageResult r;
+    if (scheme == KVC_MODE_RAW || m >= 0x7C00u) {  // requested, or a NaN/Inf is present: bypass
+        r.n16 = (uint32_t)(E >> 3);
+        r.mode = KVC_MODE_RAW;
+        r.scale = 0.0f;
+        return r;
+    }
+    float s = 0.0f, s_inv = 0.0f;
+    if (m != 0) {
+        s = half_bits_to_float(m) / 127.0f;
+        s_inv = 1.0f / s;
+    }
+    r.scale = s;
+    if (scheme == KVC_MODE_INT8) {
+        store_codes<MAXP>(raw, s_inv, E, stage);
+        r.n16 = (uint32_t)(E >> 4);
+        r.mode = KVC_MODE_INT8;
+        return r;
+    }
+    // the slot must start as zeros: bodies are OR-ed in, and the padding is part of the payload
+    for (int o = lane * 16; o < E; o += 1024) *reinterpret_cast<uint4*>(stage8 + o) = make_uint4(0, 0, 0, 0);
+    wave_sync();
+
+    uint32_t run = 0;  // body bytes emitted so far (wave-uniform)
+#pragma unroll
+    for (int p = 0; p < MAXP; ++p) {
+        if (p * 512 < E) {
+            const bool act = p * 512 + lane * 8 < E;
+            int q[8];
+            quantize8(raw[p], s_inv, q);
+            // delta along the channel index; the first column of a token row is kept verbatim
+            int prev = __shfl_up(q[7], 1);
+            if ((lane & (lpr - 1)) == 0) prev = 0;
+            uint32_t u[8];
+            u[0] = zigzag8(q[0] - prev);
+#pragma unroll
+            for (int k = 1; k < 8; ++k) u[k] = zigzag8(q[k] - q[k - 1]);
+            uint32_t umax = u[0], umin = u[0];
+#pragma unroll
+            for (int k = 1; k < 8; ++k) {
+                umax = max(umax, u[k]);
+                umin = min(umin, u[k]);
+            }
+            // a group of 32 is a quad of lanes
+            umax = max(umax, (uint32_t)__shfl_xor((int)umax, 1));
+            umin = min(umin, (uint32_t)__shfl_xor((int)umin, 1));
+            umax = max(umax, (uint32_t)__shfl_xor((int)umax, 2));
+            umin = min(umin, (uint32_t)__shfl_xor((int)umin, 2));
+            uint32_t c;
+            if (scheme == KVC_MODE_RLE && umax == 0)
+                c = 0;
+            else if (scheme == KVC_MODE_RLE && umin == umax)
+                c = 9;
+            else
+                c = max(1u, 32u - (uint32_t)__clz((int)umax));
+            if (!act) c = 0;
+            const uint32_t size = (c == 0) ? 0u : (c == 9 ? 1u : 4u * c);
+            const uint32_t incl = wave_incl_scan_u32((lane & 3) == 0 ? size : 0u);
+            const uint32_t off = run + incl - size;
+            run += (uint32_t)__shfl((int)incl, 63);
+            // header: two 4-bit codes per byte, even group in the low nibble
+            const uint32_t c_next = (uint32_t)__shfl_down((int)c, 4);
+            if (act && (lane & 7) == 0) stage8[(p * 16 + (lane >> 2)) >> 1] = (uint8_t)(c | (c_next << 4));
+            // body: this lane's 8 values are bytes [qi*w, qi*w + w) of the group's bit string
+            uint64_t W = 0;
+            uint32_t B = hdr + off;
+            if (c >= 1 && c <= 8) {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) W |= (uint64_t)u[k] << (k * c);
+                B += (lane & 3) * c;
+            } else if (c == 9) {
+                W = (lane & 3) == 0 ? u[0] : 0;
+            }
+            if (W != 0) {
+                const uint32_t sh = (B & 3u) * 8u;
+                uint32_t* p0 = stage + (B >> 2);
+                const uint64_t lo = W << sh;
+                const uint32_t d0 = (uint32_t)lo, d1 = (uint32_t)(lo >> 32);
+                const uint32_t d2 = sh ? (uint32_t)(W >> (64u - sh)) : 0u;
+                if (d0) atomicOr(p0, d0);
+                if (d1) atomicOr(p0 + 1, d1);
+                if (d2) atomicOr(p0 + 2, d2);
+            }
+        }
+    }
+    const uint32_t n = (hdr + run + 15u) & ~15u;
+    wave_sync();
+    if (n >= (uint32_t)E) {  // packing did not beat plain INT8
+        store_codes<MAXP>(raw, s_inv, E, stage);
+        r.n16 = (uint32_t)(E >> 4);
+        r.mode = KVC_MODE_INT8;
+    } else {
+        r.n16 = n >> 4;
+        r.mode = (uint32_t)scheme;
+    }
+    return r;
+}
+
+// One workgroup = 4 waves x PPW pages.  Payloads wait in LDS until the workgroup has reserved
+// one contiguous pool span for all of them with a single atomic on the pool cursor.
+template <int MAXP, int PPW>
+__global__ __launch_bounds__(kThreads) void k_compress(EncodeArgs a) {
+    constexpr int kSlots = kWavesPerWG * PPW;
+    __shared__ __align__(16) uint32_t s_stage[kSlots][Slot<MAXP>::kWords];
+    __shared__ uint32_t s_n16[kSlots];
+    __shared__ uint32_t s_mode[kSlots];
+    __shared__ float s_scale[kSlots];
+    __shared__ unsigned long long s_off16[kSlots];
+    __shared__ long long s_desc[kSlots];     // descriptor index, -1 = nothing to write
+    __shared__ long long s_srcpage[kSlots];  // source page index (RAW copy-out)
+
+    const int lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const Geometry g = a.g;
+    const int E = g.E;
+
+    for (int i = 0; i < PPW; ++i) {
+        const int slot = wave * PPW + i;
+        const int64_t t = ((int64_t)blockIdx.x * kWavesPerWG + wave) * PPW + i;
+        PageResult r;
+        r.n16 = 0;
+        r.mode = KVC_MODE_INVALID;
+        r.scale = 0.0f;
+        long long di = -1, sp = -1;
+        if (t < a.n_pages) {
+            const int64_t blk = t / g.ppb;
+            const int pg = (int)(t - blk * g.ppb);
+            const int64_t sb = a.src_ids ? (int64_t)a.src_ids[blk] : blk;
+            const int64_t pb = a.pool_ids ? (int64_t)a.pool_ids[blk] : blk;
+            if (sb >= 0 && pb >= 0) {
+                const uint64_t d_idx = (uint64_t)pb * (uint64_t)g.ppb + (uint64_t)pg;
+                if (sb >= a.n_cache_blocks || d_idx >= a.n_desc) {
+                    if (lane == 0) atomicOr(&a.st->status, KVC_ST_BAD_INDEX);
+                } else {
+                    sp = sb * g.ppb + pg;
+                    di = (long long)d_idx;
+                    r = encode_page<MAXP>(a.cache + (size_t)sp * (size_t)E, g, a.scheme, s_stage[slot]);
+                }
+            }
+        }
+        if (lane == 0) {
+            s_n16[slot] = r.n16;
+            s_mode[slot] = r.mode;
+            s_scale[slot] = r.scale;
+            s_desc[slot] = di;
+            s_srcpage[slot] = sp;
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long tot = 0;
+        for (int k = 0; k < kSlots; ++k) tot += s_n16[k];
+        unsigned long long base = tot ? atomicAdd(&a.st->cursor16, tot) : 0ull;
+        bool full = false;
+        for (int k = 0; k < kSlots; ++k) {
+            const unsigned long long n = s_n16[k];
+            if (n && base + n > a.pool_units) {  // does not fit: the page is marked INVALID
+                s_mode[k] = KVC_MODE_INVALID;
+                full = true;
+            }
+            s_off16[k] = base;
+            base += n;
+        }
+        if (full) atomicOr(&a.st->status, KVC_ST_POOL_FULL);
+    }
+    __syncthreads();
+    for (int i = 0; i < PPW; ++i) {
+        const int slot = wave * PPW + i;
+        const long long di = s_desc[slot];
+        if (di < 0) continue;
+        const uint32_t mode = s_mode[slot];
+        const uint32_t n16 = s_n16[slot];
+        const unsigned long long off16 = s_off16[slot];
+        if (mode != KVC_MODE_INVALID) {
+            uint4* dst = reinterpret_cast<uint4*>(a.pool) + off16;
+            if (mode == KVC_MODE_RAW) {
+                const uint4* srcp = reinterpret_cast<const uint4*>(a.cache + (size_t)s_srcpage[slot] * (size_t)E);
+                for (uint32_t o = lane; o < n16; o += 64) dst[o] = srcp[o];
+            } else {
+                const uint4* srcp = reinterpret_cast<const uint4*>(s_stage[slot]);
+                for (uint32_t o = lane; o < n16; o += 64) dst[o] = srcp[o];
+            }
+        }
+        if (lane == 0) {
+            uint4 dw;
+            if (mode == KVC_MODE_INVALID) {
+                dw = make_uint4(0, 0, 0, (uint32_t)KVC_MODE_INVALID << 16);
+            } else {
+                const unsigned long long off = off16 * 16ull;
+                dw = make_uint4((uint32_t)off, (uint32_t)(off >> 32), __float_as_uint(s_scale[slot]), n16 | (mode << 16));
+            }
+            reinterpret_cast<uint4*>(a.desc)[di] = dw;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------- decode
+
+__device__ __forceinline__ void zero_page(uint16_t* dst, int E) {
+    for (int o = lane_id(); o < (E >> 3); o += 64) reinterpret_cast<uint4*>(dst)[o] = make_uint4(0, 0, 0, 0);
+}
+
+// dequantize step: x = fp16(fp32(q) * s) for a lane's 8 codes (low 8 bits of each q[k], signed)
+__device__ __forceinline__ uint4 dequant8(const int q[8], float s) {
+    uint32_t h[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) h[k] = float_to_half_bits((float)(int)(int8_t)(q[k] & 0xFF) * s);
+    return make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+}
+
+// Decodes the page described by descriptor d_idx into dst.  Returns false (dst zero-filled) if the
+// descriptor or the payload fails validation.
+template <int MAXP>
+__device__ bool decode_page(const DecodeArgs& a, uint64_t d_idx, uint16_t* __restrict__ dst, uint32_t* stage,
+                            uint32_t* ginfo) {
+    const int lane = lane_id();
+    const int E = a.g.E;
+    const int G = E >> 5;
+    const int hdr = (G + 1) >> 1;
+    const int lpr = a.g.d >> 3;
+    const uint4 dw = reinterpret_cast<const uint4*>(a.desc)[d_idx];
+    const uint64_t off = (uint64_t)dw.x | ((uint64_t)dw.y << 32);
+    const float s = __uint_as_float(dw.z);
+    const uint32_t n16 = dw.w & 0xFFFFu;
+    const uint32_t mode = (dw.w >> 16) & 0xFFu;
+
+    bool ok = (off & 15u) == 0 && (off >> 4) + n16 <= a.pool_units;
+    if (mode == KVC_MODE_RAW)
+        ok = ok && n16 == (uint32_t)(E >> 3);
+    else if (mode == KVC_MODE_INT8)
+        ok = ok && n16 == (uint32_t)(E >> 4);
+    else if (mode == KVC_MODE_DELTA || mode == KVC_MODE_RLE)
+        ok = ok && n16 * 16u >= (uint32_t)hdr && n16 < (uint32_t)(E >> 4);
+    else
+        ok = false;
+    if (!ok) {
+        zero_page(dst, E);
+        return false;
+    }
+    const uint8_t* pl = a.pool + off;
+    if (mode == KVC_MODE_RAW) {  // stored-uncompressed bypass
+        for (uint32_t o = lane; o < n16; o += 64) reinterpret_cast<uint4*>(dst)[o] = reinterpret_cast<const uint4*>(pl)[o];
+        return true;
+    }
+    if (mode == KVC_MODE_INT8) {
+#pragma unroll
+        for (int p = 0; p < MAXP; ++p) {
+            const int e0 = p * 512 + lane * 8;
+            if (e0 < E) {
+                const uint2 v = *reinterpret_cast<const uint2*>(pl + e0);
+                int q[8];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    q[k] = (int)(v.x >> (8 * k));
+                    q[4 + k] = (int)(v.y >> (8 * k));
+                }
+                *reinterpret_cast<uint4*>(dst + e0) = dequant8(q, s);
+            }
+        }
+        return true;
+    }
+    // modes 2/3: stage the payload in LDS
+    const uint8_t* stage8 = reinterpret_cast<const uint8_t*>(stage);
+    for (uint32_t o = lane; o < n16; o += 64) reinterpret_cast<uint4*>(stage)[o] = reinterpret_cast<const uint4*>(pl)[o];
+    wave_sync();
+    // header: code of every group -> body offset by a prefix sum over body sizes
+    uint32_t run = 0;
+    bool bad = false;
+    for (int g0 = 0; g0 < G; g0 += 64) {
+        const int gi = g0 + lane;
+        uint32_t c = 0;
+        if (gi < G) {
+            const uint32_t byte = stage8[gi >> 1];
+            c = (gi & 1) ? (byte >> 4) : (byte & 15u);
+            if (c > 9 || (mode == KVC_MODE_DELTA && (c == 0 || c == 9))) bad = true;
+        }
+        const uint32_t size = (c == 0) ? 0u : (c == 9 ? 1u : 4u * c);
+        const uint32_t incl = wave_incl_scan_u32(size);
+        if (gi < G) ginfo[gi] = ((run + incl - size) << 4) | c;
+        run += (uint32_t)__shfl((int)incl, 63);
+    }
+    if (__any(bad) || (((uint32_t)hdr + run + 15u) >> 4) != n16) {
+        zero_page(dst, E);
+        return false;
+    }
+    wave_sync();
+#pragma unroll
+    for (int p = 0; p < MAXP; ++p) {
+        if (p * 512 < E) {
+            const int e0 = p * 512 + lane * 8;
+            const bool act = e0 < E;
+            uint32_t c = 0, goff = 0;
+            if (act) {
+                const uint32_t gi = ginfo[p * 16 + (lane >> 2)];
+                c = gi & 15u;
+                goff = gi >> 4;
+            }
+            uint32_t u[8];
+            if (c >= 1 && c <= 8) {
+                const uint32_t B = (uint32_t)hdr + goff + (uint32_t)(lane & 3) * c;
+                const uint32_t sh = (B & 3u) * 8u;
+                const uint32_t* p0 = stage + (B >> 2);
+                const uint32_t d0 = p0[0], d1 = p0[1], d2 = p0[2];
+                const uint32_t lo = sh ? (d0 >> sh) | (d1 << (32u - sh)) : d0;
+                const uint32_t hi = sh ? (d1 >> sh) | (d2 << (32u - sh)) : d1;
+                const uint64_t W = (uint64_t)lo | ((uint64_t)hi << 32);
+                const uint32_t mask = (1u << c) - 1u;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) u[k] = (uint32_t)(W >> (k * c)) & mask;
+            } else {
+                const uint32_t v = (c == 9) ? stage8[hdr + goff] : 0u;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) u[k] = v;
+            }
+            // undo zig-zag, prefix sum along the channel index (mod 256)
+            int q[8];
+            int acc = 0;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                acc += (int)(u[k] >> 1) ^ -(int)(u[k] & 1u);
+                q[k] = acc;
+            }
+            const int before = (int)row_excl_scan_u32((uint32_t)acc, lpr);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) q[k] += before;
+            if (act) *reinterpret_cast<uint4*>(dst + e0) = dequant8(q, s);
+        }
+    }
+    return true;
+}
+
+template <int MAXP, int PPW>
+__global__ __launch_bounds__(kThreads) void k_decompress(DecodeArgs a) {
+    __shared__ __align__(16) uint32_t s_stage[kWavesPerWG][Slot<MAXP>::kWords];
+    __shared__ uint32_t s_ginfo[kWavesPerWG][MAXP * 16];
+    const int lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const Geometry g = a.g;
+    for (int i = 0; i < PPW; ++i) {
+        const int64_t t = ((int64_t)blockIdx.x * kWavesPerWG + wave) * PPW + i;
+        if (t >= a.n_pages) break;
+        const int64_t blk = t / g.ppb;
+        const int pg = (int)(t - blk * g.ppb);
+        int64_t pb, db;
+        bool bad_index = false;
+        if (a.block_table) {  // translate (layer, sequence, predicted logical block) -> pool block
+            const int64_t sj = blk % ((int64_t)a.n_seq * a.k);
+            const int64_t layer = blk / ((int64_t)a.n_seq * a.k);
+            const int64_t sq = sj / a.k;
+            const int32_t lb = a.pred[sj];
+            db = blk;
+            pb = -1;
+            if (lb >= a.max_blocks) {
+                bad_index = true;
+            } else if (lb >= 0) {
+                const int32_t e = a.block_table[sq * a.max_blocks + lb];
+                if (e >= a.pool_blocks_per_layer)
+                    bad_index = true;
+                else if (e >= 0)
+                    pb = layer * a.pool_blocks_per_layer + e;
+            }
+        } else {
+            pb = a.pool_ids ? (int64_t)a.pool_ids[blk] : blk;
+            db = a.dst_ids ? (int64_t)a.dst_ids[blk] : blk;
+        }
+        if (db < 0 || db >= a.n_out_blocks) {
+            if (db >= 0 && lane == 0) atomicOr(&a.st->status, KVC_ST_BAD_INDEX);
+            continue;
+        }
+        uint16_t* dst = a.out + ((size_t)db * g.ppb + pg) * (size_t)g.E;
+        if (!bad_index && pb < 0) continue;  // skip
+        const uint64_t d_idx = (uint64_t)pb * (uint64_t)g.ppb + (uint64_t)pg;
+        if (bad_index || d_idx >= a.n_desc) {
+            zero_page(dst, g.E);
+            if (lane == 0) atomicOr(&a.st->status, KVC_ST_BAD_INDEX);
+            continue;
+        }
+        if (!decode_page<MAXP>(a, d_idx, dst, s_stage[wave], s_ginfo[wave])) {
+            if (lane == 0) atomicOr(&a.st->status, KVC_ST_CORRUPT);
+        }
+        wave_sync();
+    }
+}
+
+// ---------------------------------------------------------------------------------- small kernels
+
+__global__ void k_reset(DevState* st, kvc_desc* desc, uint64_t n_desc) {
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i == 0) {
+        st->cursor16 = 0;
+        st->status = 0;
+    }
+    for (uint64_t k = i; k < n_desc; k += (uint64_t)gridDim.x * blockDim.x)
+        reinterpret_cast<uint4*>(desc)[k] = make_uint4(0, 0, 0, (uint32_t)KVC_MODE_INVALID << 16);
+}
+
+__global__ void k_stats_zero(DevState* st) {
+    if (threadIdx.x < 8) st->stats[threadIdx.x] = 0;
+}
+
+__global__ void k_stats(DevState* st, const kvc_desc* desc, uint64_t n_desc) {
+    unsigned long long cnt[6] = {0, 0, 0, 0, 0, 0};
+    for (uint64_t k = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; k < n_desc; k += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t w = reinterpret_cast<const uint4*>(desc)[k].w;
+        const uint32_t mode = (w >> 16) & 0xFFu;
+        if (mode <= 3) {
+            cnt[mode] += 1;
+            cnt[5] += w & 0xFFFFu;
+        } else {
+            cnt[4] += 1;
+        }
+    }
+    for (int j = 0; j < 6; ++j) {
+        unsigned long long v = cnt[j];
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+        if (lane_id() == 0 && v) atomicAdd(&st->stats[j], v);
+    }
+}
+
+__global__ void k_copy(uint4* __restrict__ dst, const uint4* __restrict__ src, uint64_t n16) {
+    for (uint64_t k = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; k < n16; k += (uint64_t)gridDim.x * blockDim.x)
+        dst[k] = src[k];
+}
+
+// ---------------------------------------------------------------------------------- launchers
+
+static inline unsigned grid_for(int64_t n_pages, int ppw) {
+    const int64_t per_wg = (int64_t)kWavesPerWG * ppw;
+    return (unsigned)((n_pages + per_wg - 1) / per_wg);
+}
+
+hipError_t launch_compress(const EncodeArgs& a, hipStream_t s) {
+    if (a.n_pages == 0) return hipSuccess;
+    constexpr int PPW = 4;
+    const dim3 grid(grid_for(a.n_pages, PPW)), block(kThreads);
+    if (a.g.E <= 512)
+        hipLaunchKernelGGL((k_compress<1, PPW>), grid, block, 0, s, a);
+    else if (a.g.E <= 2048)
+        hipLaunchKernelGGL((k_compress<4, PPW>), grid, block, 0, s, a);
+    else
+        hipLaunchKernelGGL((k_compress<8, 2>), dim3(grid_for(a.n_pages, 2)), block, 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_decompress(const DecodeArgs& a, hipStream_t s) {
+    if (a.n_pages == 0) return hipSuccess;
+    constexpr int PPW = 4;
+    const dim3 grid(grid_for(a.n_pages, PPW)), block(kThreads);
+    if (a.g.E <= 512)
+        hipLaunchKernelGGL((k_decompress<1, PPW>), grid, block, 0, s, a);
+    else if (a.g.E <= 2048)
+        hipLaunchKernelGGL((k_decompress<4, PPW>), grid, block, 0, s, a);
+    else
+        hipLaunchKernelGGL((k_decompress<8, PPW>), grid, block, 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_reset(DevState* st, kvc_desc* desc, uint64_t n_desc, hipStream_t s) {
+    const unsigned blocks = (unsigned)std::min<uint64_t>(std::max<uint64_t>((n_desc + 255) / 256, 1), 65536);
+    hipLaunchKernelGGL(k_reset, dim3(blocks), dim3(256), 0, s, st, desc, n_desc);
+    return hipGetLastError();
+}
+
+hipError_t launch_stats(DevState* st, const kvc_desc* desc, uint64_t n_desc, hipStream_t s) {
+    hipLaunchKernelGGL(k_stats_zero, dim3(1), dim3(64), 0, s, st);
+    if (n_desc) {
+        const unsigned blocks = (unsigned)std::min<uint64_t>((n_desc + 255) / 256, 4096);
+        hipLaunchKernelGGL(k_stats, dim3(blocks), dim3(256), 0, s, st, desc, n_desc);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_copy(void* dst, const void* src, uint64_t n16, hipStream_t s) {
+    if (n16 == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)std::min<uint64_t>((n16 + 255) / 256, 256u * 32u);
+    hipLaunchKernelGGL(k_copy, dim3(blocks), dim3(256), 0, s, reinterpret_cast<uint4*>(dst),
+                       reinterpret_cast<const uint4*>(src), n16);
+    return hipGetLastError();
+}
+
+}  // namespace kvc

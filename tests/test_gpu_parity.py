@@ -1,0 +1,309 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element on
+the same seeded inputs.  Bar: descriptors, codes, packed bitstreams, padding bit-exact; binary32
+scales bit-exact; decoded FP16 bit-exact (the stated bar is <= 1 FP16 ulp; the arithmetic is the
+same single-rounded product on both sides, so 0 is what is asserted)."""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import kvc_oracle as o
+from paper_2512_11920_amd import kvc, synth
+from gpu_util import (DEV, check_pool_invariants, compare_pages_with_oracle, gpu_compress, make_codec,
+                      upload_oracle_pool)
+
+pytestmark = pytest.mark.gpu
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _roundtrip_case(x, N, d, ppb, scheme, name):
+    _say(f"[case] {name}: pages={x.size // (N * d)} N={N} d={d} ppb={ppb} scheme={scheme}")
+    xu = np.ascontiguousarray(x).view(np.uint16).reshape(-1, N, d)
+    c, xt = gpu_compress(xu, N, d, ppb, scheme)
+    st = c.stats()
+    assert st["rc"] == 0 and st["status"] == 0, st
+    desc = c.desc_numpy()
+    pool = c.pool.cpu().numpy()
+    check_pool_invariants(desc, st["pool_bytes_used"], pool.size)
+    od, op = compare_pages_with_oracle(xu, desc, pool, N, d, scheme)
+    assert st["pages"] == np.bincount(od["mode"], minlength=4).tolist() and st["pages_invalid"] == 0
+    assert st["payload_bytes"] == op.size
+    assert c.ratio() == pytest.approx(o.ratio(od, N * d))
+    # decode GPU-made pool on the GPU
+    out = torch.full_like(xt, float("nan"))
+    c.decompress_blocks(out)
+    torch.cuda.synchronize()
+    want, bad = o.decompress_pages(op, od, N, d, n_threads=8)
+    assert bad == 0
+    got = out.cpu().numpy().view(np.uint16).reshape(-1, N, d)
+    assert np.array_equal(got, want), f"decoded pages differ: {np.nonzero((got != want).any(axis=(1, 2)))[0][:10]}"
+    assert c.stats()["status"] == 0
+    # decode the ORACLE-made pool on the GPU (independent of the GPU encoder)
+    c2 = kvc.Codec(N, d, ppb, scheme)
+    upload_oracle_pool(c2, od, op)
+    out2 = torch.full_like(xt, float("nan"))
+    c2.decompress_blocks(out2)
+    torch.cuda.synchronize()
+    assert np.array_equal(out2.cpu().numpy().view(np.uint16).reshape(-1, N, d), want)
+    assert c2.stats()["status"] == 0
+    return od
+
+
+@pytest.mark.parametrize("scheme", [3, 2, 1, 0])
+def test_tiny_config_all_pages(scheme):
+    sh = synth.CONFIGS["tiny"]
+    x = synth.cache_numpy(sh)  # [1][2][16][4][16][64]
+    od = _roundtrip_case(x, 16, 64, 4, scheme, f"tiny/scheme{scheme}")
+    if scheme == 3:
+        assert set(np.unique(od["mode"])) <= {1, 3}
+
+
+def test_handworked_pages_on_gpu():
+    cases = json.load(open(os.path.join(GOLD, "kvc1_handworked.json")))["cases"]
+    for cs in cases:
+        x = np.frombuffer(bytes.fromhex(cs["x_fp16_le_hex"]), np.uint16)
+        _say(f"[case] golden/{cs['name']}")
+        c, xt = gpu_compress(x, cs["N"], cs["d"], 1, 3)
+        desc = c.desc_numpy()
+        pool = c.pool.cpu().numpy()
+        assert int(desc["mode"][0]) == cs["mode"] and int(desc["n16"][0]) == cs["n16"]
+        assert f"{int(desc['scale'].view(np.uint32)[0]):08x}" == cs["scale_bits"]
+        o0 = int(desc["off"][0])
+        assert pool[o0:o0 + 16 * cs["n16"]].tobytes().hex() == cs["payload_hex"]
+        out = torch.empty_like(xt)
+        c.decompress_blocks(out)
+        got = out.cpu().numpy().view(np.uint16).ravel()
+        if "xhat_bits_prefix" in cs:
+            assert [f"{v:04x}" for v in got[: len(cs["xhat_bits_prefix"])]] == cs["xhat_bits_prefix"]
+        if cs["scale_bits"] == "3f800000":
+            assert np.array_equal(got, x)
+
+
+def _special_pages(N, d, rng):
+    """Pages built to hit every branch: every packet code in both nibbles, RAW triggers, zeros,
+    subnormals, the largest finite value, misaligned bodies after run packets."""
+    E = N * d
+    pages = []
+    z = np.zeros((N, d), np.float16)
+    pages.append(z.copy())                                                      # all zero
+    p = z.copy(); p[0, 0] = -0.0; pages.append(p)                               # -0 only
+    p = (rng.standard_normal((N, d)) * 1e-6).astype(np.float16); pages.append(p)  # FP16 subnormals
+    p = z.copy(); p[:] = 6e-8; pages.append(p)                                  # smallest subnormal everywhere
+    p = rng.standard_normal((N, d)).astype(np.float16); p[N // 2, d // 2] = 65504; pages.append(p)
+    p = rng.standard_normal((N, d)).astype(np.float16); p[0, 1] = -65504; pages.append(p)
+    for poison in (0x7C00, 0xFC00, 0x7E00, 0xFFFF, 0x7C01):
+        p = rng.standard_normal((N, d)).astype(np.float16).view(np.uint16); p[N - 1, d - 1] = poison
+        pages.append(p.view(np.float16))
+    # integer pages with amax = 127 (s = 1): codes are the values themselves
+    p = z.copy(); p[:] = 127; pages.append(p)                                   # one literal + zero runs per row
+    p = z.copy(); p[:] = np.arange(d) % 120; p[0, 0] = 127; pages.append(p)     # slope 1: run packets (code 9)
+    p = z.copy(); p[:] = -127 + (np.arange(d) * 3) % 250; pages.append(p)       # run packets, wrap-around deltas
+    p = z.copy(); p[:, ::2] = 127; p[:, 1::2] = -127; pages.append(p)           # |delta| = 254 -> wraps to +-2
+    for w in range(1, 8):                                                       # literal widths 1..7
+        p = z.copy()
+        p[:] = np.cumsum(rng.integers(-(1 << w) // 4, (1 << w) // 4 + 1, (N, d)), axis=1).clip(-100, 100)
+        p[0, 0] = 127
+        pages.append(p)
+    p = z.copy(); p[:, : d // 2] = np.arange(d // 2) * 2; p[:, d // 2:] = rng.integers(-5, 6, (N, d - d // 2)); p[0, 0] = 127
+    pages.append(p)                                                             # run packets then literals: odd body offsets
+    p = z.copy(); p[::2] = 64; p[1::2, 3] = 127; pages.append(p)
+    p = (rng.standard_normal((N, d)) * np.exp(2 * rng.standard_normal(d))).astype(np.float16); pages.append(p)
+    p = rng.standard_normal((N, d)).astype(np.float16); pages.append(p)         # i.i.d.: INT8 fallback
+    p = rng.standard_normal((N, d)).astype(np.float16); p[:, 5] *= 100; pages.append(p)
+    return np.stack([np.asarray(q, np.float16) for q in pages])
+
+
+@pytest.mark.parametrize("N,d", [(16, 128), (16, 64), (16, 32), (16, 256), (1, 64), (3, 32), (5, 128), (32, 128)])
+@pytest.mark.parametrize("scheme", [3, 2])
+def test_special_pages_all_geometries(N, d, scheme):
+    rng = np.random.default_rng(100 + N + d)
+    x = _special_pages(N, d, rng)
+    n = x.shape[0]
+    od = _roundtrip_case(x, N, d, 1, scheme, f"special N={N} d={d}")
+    assert (od["mode"][5 + 1:5 + 6] == 0).all()  # the five poisoned pages are stored raw
+    if scheme == 3 and N * d >= 1024:
+        pool_codes = set()
+        _, op = o.compress_pages(x.view(np.uint16), N, d, 3)
+        for p in range(n):
+            if od["mode"][p] == 3:
+                pl = o.page_payload(op, od[p])
+                G = N * d // 32
+                pool_codes |= {(pl[g >> 1] >> 4) if g & 1 else (pl[g >> 1] & 15) for g in range(G)}
+        assert pool_codes >= set(range(0, 10)), pool_codes
+
+
+def test_llama7b_layer_slice_ragged_tail():
+    """7B-layer shaped pages (32 heads x 128), a page count that is not a multiple of the
+    16-page workgroup batch: 37 blocks x 32 pages."""
+    sh = synth.KVShape("7b_slice", 1, 32, 128, 37 * 16, 1)
+    x = synth.layer_numpy(sh, 0)  # [2][37][32][16][128]
+    for kv, name in ((0, "K"), (1, "V")):
+        od = _roundtrip_case(x[kv][:, :31], 16, 128, 31, 3, f"7b-slice {name} ppb=31")
+    od = _roundtrip_case(x, 16, 128, 32, 3, "7b-slice K+V")
+    assert 2.0 < o.ratio(od, 2048) < 2.6
+
+
+def test_block_id_indirection_skip_and_reuse():
+    rng = np.random.default_rng(7)
+    N, d, ppb = 16, 128, 4
+    nb = 24
+    x = (rng.standard_normal((nb, ppb, N, d)) * np.exp(0.5 * rng.standard_normal(d))).astype(np.float16)
+    xt = torch.from_numpy(x).to(DEV)
+    c = make_codec(N, d, ppb, 3, n_pool_blocks=40)
+    src = np.array([5, 0, -1, 23, 7, 7, 11], np.int32)
+    dstp = np.array([30, 2, 9, 0, 39, 17, -1], np.int32)  # pairs with a -1 on either side are skipped
+    c.compress_blocks(xt, src_ids=torch.from_numpy(src).to(DEV), pool_ids=torch.from_numpy(dstp).to(DEV))
+    st = c.stats()
+    assert st["rc"] == 0
+    desc = c.desc_numpy().reshape(40, ppb)
+    live = [(s, p) for s, p in zip(src, dstp) if s >= 0 and p >= 0]
+    assert sum(st["pages"]) == len(live) * ppb and st["pages_invalid"] == (40 - len(live)) * ppb
+    pool = c.pool.cpu().numpy()
+    for s, p in live:
+        for pg in range(ppb):
+            dd, pl = o.encode_page(x[s, pg], N, d, 3)
+            g = desc[p, pg]
+            assert (g["mode"], g["n16"]) == (dd["mode"], dd["n16"]) and g["scale"] == dd["scale"]
+            assert pool[int(g["off"]):int(g["off"]) + 16 * int(g["n16"])].tobytes() == pl
+    check_pool_invariants(desc.ravel(), st["pool_bytes_used"], pool.size)
+    # decode a permuted subset into a larger output, leaving other blocks untouched
+    out = torch.full((50, ppb, N, d), 7.0, dtype=torch.float16, device=DEV)
+    pids = np.array([39, 2, -1, 30, 0], np.int32)
+    dids = np.array([1, 49, 3, -1, 10], np.int32)
+    c.decompress_blocks(out, pool_ids=torch.from_numpy(pids).to(DEV), dst_ids=torch.from_numpy(dids).to(DEV))
+    got = out.cpu().numpy()
+    src_of_pool = {p: s for s, p in live}
+    touched = set()
+    for p, dd in zip(pids, dids):
+        if p < 0 or dd < 0:
+            continue
+        touched.add(int(dd))
+        for pg in range(ppb):
+            de, pl = o.encode_page(x[src_of_pool[p], pg], N, d, 3)
+            rc, want = o.decode_page(pl, de, N, d)
+            assert np.array_equal(got[dd, pg].view(np.uint16).ravel(), want)
+    for b in set(range(50)) - touched:
+        assert (got[b] == 7.0).all()
+    assert c.stats()["status"] == 0
+
+
+def test_gather_decompress_small_pattern():
+    """Translation table + predicted ids (Algorithm 1's fetch) on a 3-layer toy pool, K and V of
+    2 heads per block (ppb = 4)."""
+    rng = np.random.default_rng(21)
+    N, d, ppb, n_layers = 16, 128, 4, 3
+    pat = synth.gather_pattern(n_seq=5, k=8, len_lo=40, len_hi=300, seed=3)
+    pbl = pat.pool_blocks_per_layer
+    x = (rng.standard_normal((n_layers * pbl, ppb, N, d)) * np.exp(0.5 * rng.standard_normal(d))).astype(np.float16)
+    c, xt = gpu_compress(x, N, d, ppb, 3)
+    od, op = o.compress_pages(x.view(np.uint16), N, d, 3, n_threads=8)
+    full, _ = o.decompress_pages(op, od, N, d, n_threads=8)
+    full = full.reshape(n_layers, pbl, ppb, N, d)
+    table = torch.from_numpy(pat.block_table).to(DEV)
+    for step in (0, 1, 999):
+        pred_np = pat.predictions(step).copy()
+        if step == 1:
+            pred_np[2, 3] = -1  # skipped: output block stays as it was
+        pred = torch.from_numpy(pred_np).to(DEV)
+        out = torch.full((n_layers * pat.n_seq * pat.k, ppb, N, d), 3.0, dtype=torch.float16, device=DEV)
+        c.gather_decompress(out, table, pred, n_layers, pbl)
+        got = out.cpu().numpy().view(np.uint16).reshape(n_layers, pat.n_seq, pat.k, ppb, N, d)
+        for l in range(n_layers):
+            for s in range(pat.n_seq):
+                for j in range(pat.k):
+                    lb = pred_np[s, j]
+                    if lb < 0:
+                        assert (got[l, s, j].view(np.float16) == 3.0).all()
+                    else:
+                        assert np.array_equal(got[l, s, j], full[l, pat.block_table[s, lb]]), (step, l, s, j)
+    assert c.stats()["status"] == 0
+    # out-of-range prediction / table entry: zero-filled + status bit, nothing else disturbed
+    pred_np = pat.predictions(5).copy()
+    pred_np[0, 0] = pat.max_blocks + 3
+    out = torch.full((n_layers * pat.n_seq * pat.k, ppb, N, d), 3.0, dtype=torch.float16, device=DEV)
+    c.gather_decompress(out, table, torch.from_numpy(pred_np).to(DEV), n_layers, pbl)
+    got = out.cpu().numpy().reshape(n_layers, pat.n_seq, pat.k, -1)
+    assert (got[:, 0, 0] == 0).all() and not (got[:, 0, 1] == 0).all()
+    st = c.stats()
+    assert st["status"] & kvc.ST_BAD_INDEX and st["rc"] == kvc.ERR_CORRUPT
+
+
+def test_pool_exhaustion_marks_pages_invalid():
+    rng = np.random.default_rng(5)
+    N, d, ppb = 16, 128, 1
+    x = rng.standard_normal((64, ppb, N, d)).astype(np.float16)  # i.i.d.: every page 2048 B (INT8)
+    c, xt = gpu_compress(x, N, d, ppb, 3, pool_bytes=20 * 2048 + 512)
+    st = c.stats()
+    assert st["rc"] == kvc.ERR_POOL_FULL and st["status"] & kvc.ST_POOL_FULL
+    desc = c.desc_numpy()
+    ok = desc["mode"] != 0xFF
+    assert 0 < ok.sum() <= 20 and st["pages_invalid"] == 64 - ok.sum()
+    assert ((desc["off"][ok] + 2048) <= 20 * 2048 + 512).all()
+    out = torch.full_like(xt, 1.0)
+    c.decompress_blocks(out)
+    got = out.cpu().numpy().view(np.uint16).reshape(64, N, d)
+    for p in range(64):
+        if ok[p]:
+            dd, pl = o.encode_page(x[p], N, d, 3)
+            assert np.array_equal(got[p].ravel(), o.decode_page(pl, dd, N, d)[1])
+        else:
+            assert not got[p].any()  # undecodable pages are zero-filled
+    assert c.stats()["status"] & kvc.ST_CORRUPT
+    c.reset_pool()
+    st = c.stats()
+    assert st["status"] == 0 and st["pool_bytes_used"] == 0 and st["pages_invalid"] == 64
+
+
+def test_corrupt_descriptors_and_payloads_are_contained():
+    rng = np.random.default_rng(6)
+    N, d = 16, 128
+    x = rng.standard_normal((8, N, d)).astype(np.float16)
+    x[:, :, 3] *= 40
+    od, op = o.compress_pages(x.view(np.uint16), N, d, 3)
+    assert (od["mode"] == 3).all()
+    good, _ = o.decompress_pages(op, od, N, d)
+    bd = od.copy()
+    bp = op.copy()
+    bd[0]["mode"] = 9                      # unknown mode
+    bd[1]["off"] = op.size + 4096          # span outside the pool
+    bd[2]["n16"] = bd[2]["n16"] - 1        # truncated payload
+    bd[3]["off"] += 8                      # misaligned
+    bp[int(od[4]["off"])] = 0xAB           # header codes 11 and 10
+    bd[5]["mode"] = 1                      # wrong size for INT8
+    c = kvc.Codec(N, d, 1, 3)
+    upload_oracle_pool(c, bd, bp)
+    out = torch.full((8, 1, N, d), 2.0, dtype=torch.float16, device=DEV)
+    c.decompress_blocks(out)
+    got = out.cpu().numpy().view(np.uint16).reshape(8, N, d)
+    want, nbad = o.decompress_pages(bp, bd, N, d)
+    assert nbad == 6
+    assert np.array_equal(got, want)
+    assert not got[:6].any() and np.array_equal(got[6:], good[6:])
+    st = c.stats()
+    assert st["status"] & kvc.ST_CORRUPT and st["rc"] == kvc.ERR_CORRUPT
+
+
+def test_host_side_argument_errors():
+    c = kvc.Codec(16, 128, 2, 3)
+    x = torch.zeros((4, 2, 16, 128), dtype=torch.float16, device=DEV)
+    with pytest.raises(kvc.KvcError) as e:
+        c.compress_blocks(x)
+    assert e.value.code == kvc.ERR_NOT_BOUND
+    c.alloc_pool(2, 1 << 16, DEV)
+    with pytest.raises(kvc.KvcError) as e:
+        c.compress_blocks(x)  # 4 blocks, 2 pool blocks, identity ids
+    assert e.value.code == kvc.ERR_ARG
+    with pytest.raises(kvc.KvcError) as e:
+        kvc.Codec(16, 96, 1, 3)
+    assert e.value.code == kvc.ERR_UNSUPPORTED
+    with pytest.raises(kvc.KvcError) as e:
+        kvc.Codec(16, 100, 1, 3)
+    assert e.value.code == kvc.ERR_ARG
+    c.compress_blocks(x, n=0)
+    assert c.stats()["pages_invalid"] == 4

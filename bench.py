@@ -1,0 +1,337 @@
+#!/usr/bin/env python3
+"""Benchmark of the KV page codec on one MI355X.
+
+A step is one pass of the whole hot path over the workload, inputs resident in HBM:
+    reset pool -> kvc_compress_blocks (all pages) -> kvc_decompress_blocks (all pages)
+    -> kvc_gather_decompress (one decode step's predicted blocks).
+`value` = uncompressed FP16 bytes processed per second over the whole step.  Per-kernel durations come
+from HIP events recorded on the launch stream inside the timed region; the roofline entry is
+algorithmic bytes (read + written, measured from the descriptors) over that duration against the
+8 TB/s HBM3E peak.  The CPU oracle is timed on a bounded sample of the same bytes as a baseline.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 70b_gqa|7b_full|7b_layer|tiny|decode_gather]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+
+
+def log(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def read_traffic(workload: str, kernel: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if one covers this kernel
+    and workload (profiles/hbm_traffic_<workload>.txt, lines `<kernel>_traffic_bytes: <int>`)."""
+    p = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    if not os.path.exists(p):
+        return None
+    for line in open(p):
+        if line.startswith(f"{kernel}_traffic_bytes:"):
+            return int(float(line.split(":")[1].split()[0]))
+    return None
+
+
+def build_cache(shape, device, block_major=False):
+    """Whole cache on the GPU, one layer at a time (seeded).  kv-major: [L][2][blocks][H][N][d]."""
+    import torch
+
+    from paper_2512_11920_amd import synth
+
+    H, N, d = shape.n_kv_heads, shape.tokens_per_block, shape.head_dim
+    cache = torch.empty((shape.n_layers, 2, shape.blocks_per_layer, H, N, d), dtype=torch.float16, device=device)
+    for l in range(shape.n_layers):
+        cache[l].copy_(synth.layer_torch(shape, l, device))
+    return cache
+
+
+def sample_check(codec, cache_blocks, out_blocks, n_sample, N, d, ppb, scheme):
+    """Compare a random sample of pages (descriptor, payload, decoded values) with the oracle."""
+    import numpy as np
+    import torch
+
+    from oracle import kvc_oracle as o
+
+    n_pages = cache_blocks.shape[0] * ppb
+    g = np.random.default_rng(12345)
+    ids = np.unique(g.integers(0, n_pages, n_sample))
+    idt = torch.from_numpy(ids).to(cache_blocks.device)
+    x = cache_blocks.view(-1, N, d)[idt].cpu().numpy().view(np.uint16)
+    y = out_blocks.view(-1, N, d)[idt].cpu().numpy().view(np.uint16)
+    desc = codec.desc.view(-1, 16)[idt].cpu().numpy().view(codec_desc_dtype()).ravel()
+    od, op = o.compress_pages(x, N, d, scheme, n_threads=8)
+    ok = (np.array_equal(desc["mode"], od["mode"]) and np.array_equal(desc["n16"], od["n16"])
+          and np.array_equal(desc["scale"].view(np.uint32), od["scale"].view(np.uint32)))
+    for i in range(len(ids)):
+        a, n = int(desc["off"][i]), int(desc["n16"][i]) * 16
+        ok = ok and codec.pool[a:a + n].cpu().numpy().tobytes() == o.page_payload(op, od[i])
+        if i >= 256:
+            break
+    want, bad = o.decompress_pages(op, od, N, d, n_threads=8)
+    ok = ok and bad == 0 and np.array_equal(want, y)
+    return bool(ok), len(ids)
+
+
+def codec_desc_dtype():
+    from paper_2512_11920_amd import kvc
+
+    return kvc.DESC_DTYPE
+
+
+def cpu_baseline(sample_u16, N, d, scheme, target_s=12.0):
+    """Oracle compress + decompress on host cores over a bounded sample.  GB/s of uncompressed FP16
+    (bytes through compress + bytes through decompress) / elapsed."""
+    from oracle import kvc_oracle as o
+
+    cores = max(1, min(16, os.cpu_count() or 1))
+    n_pages = sample_u16.shape[0]
+    done_bytes, t_total, reps = 0, 0.0, 0
+    while t_total < target_s and reps < 4:
+        t0 = time.perf_counter()
+        od, op = o.compress_pages(sample_u16, N, d, scheme, n_threads=cores)
+        out, bad = o.decompress_pages(op, od, N, d, n_threads=cores)
+        t_total += time.perf_counter() - t0
+        done_bytes += 2 * sample_u16.nbytes
+        reps += 1
+    return {"value": round(done_bytes / t_total / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"{n_pages} pages ({sample_u16.nbytes / 2**20:.0f} MiB of the same seeded cache), "
+                      f"compress+decompress x{reps}, {t_total:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="70b_gqa")
+    ap.add_argument("--scheme", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (quick runs; not the headline)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU by design (pages are independent; no collective exists "
+              "on the path). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2512_11920_amd import kvc, synth
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    if args.workload == "decode_gather":
+        return bench_decode_gather(args)
+    shape = synth.CONFIGS[args.workload]
+    if args.layers:
+        import dataclasses
+
+        shape = dataclasses.replace(shape, n_layers=args.layers, name=f"{shape.name}[{args.layers} layers]")
+    N, d, H = shape.tokens_per_block, shape.head_dim, shape.n_kv_heads
+    ppb = H
+    E = N * d
+    log(f"[bench] building {shape.name}: {shape.n_pages} pages, {shape.nbytes / 1e9:.2f} GB fp16")
+    cache = build_cache(shape, dev)
+    blocks = cache.view(-1, ppb, N, d)
+    n_blocks = blocks.shape[0]
+    out = torch.empty_like(blocks)
+    codec = kvc.Codec(N, d, ppb, args.scheme)
+    codec.alloc_pool(n_blocks, shape.n_pages * (E if args.scheme else 2 * E) + 4096, dev)
+
+    # decode-step pattern over the same pool: each (sequence, K|V) is a table row of its blocks
+    bps = shape.seq_len // N
+    rows = 2 * shape.batch
+    table = (torch.arange(rows, dtype=torch.int32, device=dev)[:, None] * bps
+             + torch.arange(bps, dtype=torch.int32, device=dev)[None, :])
+    # kv-major layout: pool block of (kv, seq, blk) within a layer = (kv*batch + seq)*bps + blk = row*bps + blk
+    table = table.contiguous()
+    k = min(8, bps)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(shape.seed + 99)
+    pred = torch.randint(0, bps, (rows, k), generator=gen, device=dev, dtype=torch.int32)
+    g_out = torch.empty((shape.n_layers * rows * k, ppb, N, d), dtype=torch.float16, device=dev)
+    pbpl = 2 * shape.blocks_per_layer
+
+    stream = torch.cuda.current_stream()
+
+    def step(ev=None):
+        codec.reset_pool()
+        if ev:
+            ev[0].record()
+        codec.compress_blocks(blocks)
+        if ev:
+            ev[1].record()
+        codec.decompress_blocks(out)
+        if ev:
+            ev[2].record()
+        codec.gather_decompress(g_out, table, pred, shape.n_layers, pbpl)
+        if ev:
+            ev[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    st = codec.stats()
+    assert st["rc"] == 0, st
+    n_live = sum(st["pages"])
+    payload = st["payload_bytes"]
+    ratio = codec.ratio()
+    check_ok, n_checked = sample_check(codec, blocks, out, 512, N, d, ppb, args.scheme)
+    log(f"[bench] modes {st['pages']} ratio {ratio:.4f} sample parity vs oracle on {n_checked} pages: {check_ok}")
+
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    t_c = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+    t_d = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+    t_g = sum(e[2].elapsed_time(e[3]) for e in evs) / args.steps
+
+    unc = shape.nbytes
+    g_pages = g_out.numel() // E
+    g_unc = g_out.numel() * 2
+    # algorithmic bytes: page in + payload + descriptor out (compress); the reverse (decompress);
+    # gather reads its pages' payloads (mean payload size) + descriptors + 4 B of ids per block
+    alg_c = unc + payload + 16 * n_live
+    alg_d = alg_c
+    alg_g = g_unc + g_pages * (payload / n_live + 16) + 8 * (g_pages // ppb)
+    kern = {
+        "compress": {"ms": t_c, "uncompressed_GBps": unc / t_c / 1e6, "hbm_GBps": alg_c / t_c / 1e6, "alg_bytes": alg_c},
+        "decompress": {"ms": t_d, "uncompressed_GBps": unc / t_d / 1e6, "hbm_GBps": alg_d / t_d / 1e6, "alg_bytes": alg_d},
+        "gather_decompress": {"ms": t_g, "uncompressed_GBps": g_unc / t_g / 1e6, "hbm_GBps": alg_g / t_g / 1e6,
+                              "alg_bytes": alg_g},
+    }
+    for v in kern.values():
+        v["frac_of_peak"] = v["hbm_GBps"] / HBM_PEAK_GBS
+    # same-run yardstick: plain 128-bit copy of the cache
+    cp = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    src8, dst8 = blocks.view(torch.uint8).view(-1), out.view(torch.uint8).view(-1)
+    kvc.copy_bytes(dst8, src8)
+    cp[0].record()
+    for _ in range(3):
+        kvc.copy_bytes(dst8, src8)
+    cp[1].record()
+    torch.cuda.synchronize()
+    t_copy = cp[0].elapsed_time(cp[1]) / 3
+    copy_gbps = 2 * unc / t_copy / 1e6
+    for v in kern.values():
+        v["frac_of_copy"] = v["hbm_GBps"] / copy_gbps
+
+    dom = "compress" if t_c >= t_d else "decompress"
+    kname = {"compress": "k_compress", "decompress": "k_decompress"}[dom]
+    res = {
+        "metric": "KV codec GB/s (uncompressed fp16) compress+decompress; % of HBM peak",
+        "value": round((2 * unc + g_unc) / (ms_step * 1e-3) / 1e9, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{shape.name}: {shape.n_layers} layers x {H} KV heads x {d}, seq {shape.seq_len}, "
+                               f"batch {shape.batch}, {N}-token blocks, K+V {unc / 1e9:.2f} GB fp16, scheme {args.scheme}",
+                   "pages": shape.n_pages, "ratio": round(ratio, 4), "pages_per_mode": st["pages"],
+                   "gather": f"{rows} rows x {k} predicted blocks x {shape.n_layers} layers = {g_pages} pages"},
+        "roofline": {"bound": "hbm", "kernel": kname, "achieved": round(kern[dom]["hbm_GBps"], 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(kern[dom]["frac_of_peak"], 4),
+                     "traffic": read_traffic(shape.name, kname), "alg_bytes_per_launch": int(kern[dom]["alg_bytes"]),
+                     "launch_ms": round(kern[dom]["ms"], 4)},
+        "kernels": {k_: {a: (round(b, 4) if isinstance(b, float) else b) for a, b in v.items()} for k_, v in kern.items()},
+        "copy_kernel_GBps": round(copy_gbps, 1),
+        "sample_parity_vs_oracle": check_ok,
+    }
+    if not args.no_cpu_baseline:
+        # the first layers of the same cache, moved to the host
+        per_layer = shape.pages_per_layer
+        n_layers_s = max(1, min(shape.n_layers, (1 << 30) // (per_layer * E * 2) or 1))
+        sample = cache[:n_layers_s].reshape(-1, N, d).cpu().numpy().view(np.uint16)
+        res["cpu_baseline"] = cpu_baseline(sample, N, d, args.scheme, args.cpu_seconds)
+    print(json.dumps(res), flush=True)
+
+
+def bench_decode_gather(args):
+    """Decode-step prefetch pattern, 70B shape: 64 sequences with lengths ~U[512, 8192], block tables
+    permuted in the pool, 8 predicted blocks per sequence per layer per step.  The pool is built
+    layer by layer (one layer of raw KV at a time)."""
+    import numpy as np
+    import torch
+
+    from paper_2512_11920_amd import kvc, synth
+
+    dev = "cuda:0"
+    shape = synth.KVShape("decode_gather", 80, 8, 128, 0, 0)
+    N, d, H = 16, 128, 8
+    ppb, E = 2 * H, N * d
+    pat = synth.gather_pattern(64, 8, 512, 8192, N, seed=0)
+    pbl = pat.pool_blocks_per_layer
+    n_pool_blocks = shape.n_layers * pbl
+    log(f"[bench] decode_gather: {pbl} blocks/layer, pool of {n_pool_blocks * ppb} pages "
+        f"({n_pool_blocks * ppb * E * 2 / 1e9:.1f} GB raw)")
+    codec = kvc.Codec(N, d, ppb, args.scheme)
+    codec.alloc_pool(n_pool_blocks, n_pool_blocks * ppb * E + 4096, dev)
+    ids = torch.arange(pbl, dtype=torch.int32, device=dev)
+    for l in range(shape.n_layers):
+        layer = synth.layer_torch(shape, l, dev, block_major=True, n_blocks=pbl)
+        codec.compress_blocks(layer.view(-1, ppb, N, d), pool_ids=ids + l * pbl)
+    torch.cuda.synchronize()
+    st = codec.stats()
+    assert st["rc"] == 0, st
+    table = torch.from_numpy(pat.block_table).to(dev)
+    n_out = shape.n_layers * pat.n_seq * pat.k
+    out = torch.empty((n_out, ppb, N, d), dtype=torch.float16, device=dev)
+    preds = [torch.from_numpy(pat.predictions(s)).to(dev) for s in range(args.steps + args.warmup)]
+    for s in range(args.warmup):
+        codec.gather_decompress(out, table, preds[s], shape.n_layers, pbl)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    evs[0].record()
+    for s in range(args.steps):
+        codec.gather_decompress(out, table, preds[args.warmup + s], shape.n_layers, pbl)
+        evs[s + 1].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ts = np.array([evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps)])
+    unc = out.numel() * 2
+    n_pages = n_out * ppb
+    mean_payload = st["payload_bytes"] / sum(st["pages"])
+    alg = unc + n_pages * (mean_payload + 16) + 8 * n_out
+    ms = (t1 - t0) * 1e3 / args.steps
+    res = {
+        "metric": "KV codec GB/s (uncompressed fp16) gather-decompress; % of HBM peak",
+        "value": round(unc / (ms * 1e-3) / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"decode_gather: 80 layers x 8 KV heads x 128, 64 sequences U[512,8192], "
+                               f"8 predicted blocks/seq/layer, {n_pages} pages = {unc / 1e9:.2f} GB out per step",
+                   "ratio": round(codec.ratio(), 4)},
+        "roofline": {"bound": "hbm", "kernel": "k_decompress", "achieved": round(alg / ts.mean() / 1e6, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(alg / ts.mean() / 1e6 / HBM_PEAK_GBS, 4),
+                     "traffic": read_traffic("decode_gather", "k_decompress"), "alg_bytes_per_launch": int(alg),
+                     "launch_ms": round(float(ts.mean()), 4)},
+        "step_ms": {"mean": round(float(ts.mean()), 4), "p50": round(float(np.percentile(ts, 50)), 4),
+                    "p99": round(float(np.percentile(ts, 99)), 4)},
+    }
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,233 @@
+// Device-side helpers shared by the kernel files: wave64 primitives (DPP), page-task resolution,
+// pool reservation and copy-out.
+#pragma once
+#include "kvc_common.h"
+
+namespace kvc {
+
+constexpr int kWavesPerWG = 4;
+constexpr int kThreads = kWavesPerWG * 64;
+
+// LDS bytes reserved for one page's payload under construction: header + bodies can reach
+// E + E/64 bytes before the INT8 fallback is chosen, plus slack for the 3-dword body writes.
+template <int MAXP>
+struct Slot {
+    static constexpr int kBytes = ((MAXP * 520 + 16 + 15) / 16) * 16;
+    static constexpr int kWords = kBytes / 4;
+};
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+// Lanes of one wave exchange data through LDS: keep the compiler from moving accesses across.
+__device__ __forceinline__ void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// DPP data movement.  CTRL: 0x00-0xFF quad_perm, 0x110+n row_shr:n, 0x100+n row_shl:n,
+// 0x140 row_mirror, 0x141 row_half_mirror, 0x142 row_bcast:15, 0x143 row_bcast:31.
+// Lanes whose source is outside the row, or whose row is not in ROW_MASK, receive `old`.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ uint32_t dpp(uint32_t old, uint32_t src) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)old, (int)src, CTRL, ROW_MASK, 0xF, false);
+}
+
+// max over the wave, result uniform (read from lane 63)
+__device__ __forceinline__ uint32_t wave_max_dpp(uint32_t v) {
+    v = max(v, dpp<0xB1>(0, v));        // quad_perm [1,0,3,2]
+    v = max(v, dpp<0x4E>(0, v));        // quad_perm [2,3,0,1]
+    v = max(v, dpp<0x141>(0, v));       // row_half_mirror
+    v = max(v, dpp<0x140>(0, v));       // row_mirror: every lane holds its row's max
+    v = max(v, dpp<0x142, 0xA>(0, v));  // rows 1,3 take lane 15 of the row before
+    v = max(v, dpp<0x143, 0xC>(0, v));  // rows 2,3 take lane 31
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
+// inclusive prefix sum over the 64 lanes
+__device__ __forceinline__ uint32_t wave_incl_scan_dpp(uint32_t v) {
+    v += dpp<0x111>(0, v);
+    v += dpp<0x112>(0, v);
+    v += dpp<0x114>(0, v);
+    v += dpp<0x118>(0, v);
+    v += dpp<0x142, 0xA>(0, v);
+    v += dpp<0x143, 0xC>(0, v);
+    return v;
+}
+
+// inclusive prefix sum over quads of a value that is uniform within each quad of lanes
+__device__ __forceinline__ uint32_t quad_incl_scan_dpp(uint32_t v) {
+    v += dpp<0x114>(0, v);
+    v += dpp<0x118>(0, v);
+    v += dpp<0x142, 0xA>(0, v);
+    v += dpp<0x143, 0xC>(0, v);
+    return v;
+}
+
+// inclusive prefix sum within each row of 16 lanes
+__device__ __forceinline__ uint32_t row16_incl_scan_dpp(uint32_t v) {
+    v += dpp<0x111>(0, v);
+    v += dpp<0x112>(0, v);
+    v += dpp<0x114>(0, v);
+    v += dpp<0x118>(0, v);
+    return v;
+}
+
+struct PageResult {
+    uint32_t n16;  // payload size in 16-byte units (0 = page skipped)
+    uint32_t mode;
+    float scale;
+};
+
+// Page task of the encoder: which source page, which descriptor.
+struct EncTask {
+    long long desc_idx;  // -1: nothing to do
+    long long src_page;
+};
+
+__device__ __forceinline__ EncTask resolve_enc_task(const EncodeArgs& a, int64_t t) {
+    EncTask r;
+    r.desc_idx = -1;
+    r.src_page = -1;
+    if (t >= a.n_pages) return r;
+    const int ppb = a.g.ppb;
+    const int64_t blk = t / ppb;
+    const int pg = (int)(t - blk * ppb);
+    const int64_t sb = a.src_ids ? (int64_t)a.src_ids[blk] : blk;
+    const int64_t pb = a.pool_ids ? (int64_t)a.pool_ids[blk] : blk;
+    if (sb < 0 || pb < 0) return r;
+    const uint64_t d_idx = (uint64_t)pb * (uint64_t)ppb + (uint64_t)pg;
+    if (sb >= a.n_cache_blocks || d_idx >= a.n_desc) {
+        if (lane_id() == 0) atomicOr(&a.st->status, KVC_ST_BAD_INDEX);
+        return r;
+    }
+    r.src_page = sb * ppb + pg;
+    r.desc_idx = (long long)d_idx;
+    return r;
+}
+
+// Page task of the decoder.  kind: 0 skip, 1 decode desc_idx into dst, 2 zero-fill dst (bad index).
+struct DecTask {
+    int kind;
+    uint64_t desc_idx;
+    uint16_t* dst;
+};
+
+__device__ __forceinline__ DecTask resolve_dec_task(const DecodeArgs& a, int64_t t) {
+    DecTask r;
+    r.kind = 0;
+    r.desc_idx = 0;
+    r.dst = nullptr;
+    if (t >= a.n_pages) return r;
+    const Geometry& g = a.g;
+    const int64_t blk = t / g.ppb;
+    const int pg = (int)(t - blk * g.ppb);
+    int64_t pb, db;
+    bool bad_index = false;
+    if (a.block_table) {  // translate (layer, sequence, predicted logical block) -> pool block
+        const int64_t per_layer = (int64_t)a.n_seq * a.k;
+        const int64_t layer = blk / per_layer;
+        const int64_t sj = blk - layer * per_layer;
+        const int64_t sq = sj / a.k;
+        const int32_t lb = a.pred[sj];
+        db = blk;
+        pb = -1;
+        if (lb >= a.max_blocks) {
+            bad_index = true;
+        } else if (lb >= 0) {
+            const int32_t e = a.block_table[sq * a.max_blocks + lb];
+            if (e >= a.pool_blocks_per_layer)
+                bad_index = true;
+            else if (e >= 0)
+                pb = layer * a.pool_blocks_per_layer + e;
+        }
+    } else {
+        pb = a.pool_ids ? (int64_t)a.pool_ids[blk] : blk;
+        db = a.dst_ids ? (int64_t)a.dst_ids[blk] : blk;
+    }
+    if (db < 0 || db >= a.n_out_blocks) {
+        if (db >= 0 && lane_id() == 0) atomicOr(&a.st->status, KVC_ST_BAD_INDEX);
+        return r;
+    }
+    r.dst = a.out + ((size_t)db * g.ppb + pg) * (size_t)g.E;
+    if (!bad_index && pb < 0) return r;  // skip
+    r.desc_idx = (uint64_t)pb * (uint64_t)g.ppb + (uint64_t)pg;
+    if (bad_index || r.desc_idx >= a.n_desc) {
+        if (lane_id() == 0) atomicOr(&a.st->status, KVC_ST_BAD_INDEX);
+        r.kind = 2;
+        return r;
+    }
+    r.kind = 1;
+    return r;
+}
+
+__device__ __forceinline__ void zero_page(uint16_t* dst, int E) {
+    for (int o = lane_id(); o < (E >> 3); o += 64) reinterpret_cast<uint4*>(dst)[o] = make_uint4(0, 0, 0, 0);
+}
+
+// Per-workgroup bookkeeping of the encoder: results of the pages staged in LDS.
+template <int SLOTS>
+struct EncBook {
+    uint32_t n16[SLOTS];
+    uint32_t mode[SLOTS];
+    float scale[SLOTS];
+    unsigned long long off16[SLOTS];
+    long long desc[SLOTS];
+    long long srcpage[SLOTS];
+};
+
+// One thread reserves a contiguous pool span for all staged pages of the workgroup with a single
+// atomic on the pool cursor and hands each page its offset; pages that do not fit become INVALID.
+template <int SLOTS>
+__device__ __forceinline__ void reserve_pool_span(const EncodeArgs& a, EncBook<SLOTS>& b) {
+    unsigned long long tot = 0;
+    for (int k = 0; k < SLOTS; ++k) tot += b.n16[k];
+    unsigned long long base = tot ? atomicAdd(&a.st->cursor16, tot) : 0ull;
+    bool full = false;
+    for (int k = 0; k < SLOTS; ++k) {
+        const unsigned long long n = b.n16[k];
+        if (n && base + n > a.pool_units) {
+            b.mode[k] = KVC_MODE_INVALID;
+            full = true;
+        }
+        b.off16[k] = base;
+        base += n;
+    }
+    if (full) atomicOr(&a.st->status, KVC_ST_POOL_FULL);
+}
+
+// A wave moves one staged payload (or, for RAW, the source page) to its pool span and writes the
+// 16-byte descriptor.
+template <int SLOTS>
+__device__ __forceinline__ void emit_page(const EncodeArgs& a, const EncBook<SLOTS>& b, int slot, const uint32_t* stage) {
+    const long long di = b.desc[slot];
+    if (di < 0) return;
+    const int lane = lane_id();
+    const uint32_t mode = b.mode[slot];
+    const uint32_t n16 = b.n16[slot];
+    const unsigned long long off16 = b.off16[slot];
+    if (mode != KVC_MODE_INVALID) {
+        uint4* dst = reinterpret_cast<uint4*>(a.pool) + off16;
+        if (mode == KVC_MODE_RAW) {
+            const uint4* srcp = reinterpret_cast<const uint4*>(a.cache + (size_t)b.srcpage[slot] * (size_t)a.g.E);
+            for (uint32_t o = lane; o < n16; o += 64) dst[o] = srcp[o];
+        } else {
+            const uint4* srcp = reinterpret_cast<const uint4*>(stage);
+            for (uint32_t o = lane; o < n16; o += 64) dst[o] = srcp[o];
+        }
+    }
+    if (lane == 0) {
+        uint4 dw;
+        if (mode == KVC_MODE_INVALID) {
+            dw = make_uint4(0, 0, 0, (uint32_t)KVC_MODE_INVALID << 16);
+        } else {
+            const unsigned long long off = off16 * 16ull;
+            dw = make_uint4((uint32_t)off, (uint32_t)(off >> 32), __float_as_uint(b.scale[slot]), n16 | (mode << 16));
+        }
+        reinterpret_cast<uint4*>(a.desc)[di] = dw;
+    }
+}
+
+hipError_t launch_compress_p2048(const EncodeArgs& a, hipStream_t s);
+hipError_t launch_decompress_p2048(const DecodeArgs& a, hipStream_t s);
+
+}  // namespace kvc

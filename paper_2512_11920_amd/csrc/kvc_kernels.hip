@@ -9,30 +9,13 @@
 // Encode follows Algorithm 2 of the paper (scaling, quantize, delta along the channel index,
 // run-length encode); decode follows Section 3.5.3 (undo run-length coding, prefix sum,
 // dequantize), with the stored-uncompressed bypass.
-#include "kvc_common.h"
-
 #include <hip/hip_fp16.h>
 
+#include <algorithm>
+
+#include "kvc_device.h"
+
 namespace kvc {
-
-constexpr int kWavesPerWG = 4;
-constexpr int kThreads = kWavesPerWG * 64;
-
-// LDS bytes reserved for one page's payload under construction: header + bodies can reach
-// E + E/64 bytes before the INT8 fallback is chosen, plus slack for the 3-dword body writes.
-template <int MAXP>
-struct Slot {
-    static constexpr int kBytes = ((MAXP * 520 + 16 + 15) / 16) * 16;
-    static constexpr int kWords = kBytes / 4;
-};
-
-__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
-
-__device__ __forceinline__ void wave_sync() {
-    // lanes of one wave exchange data through LDS: keep the compiler from moving accesses across
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-}
 
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
 #pragma unroll
@@ -94,12 +77,6 @@ __device__ __forceinline__ uint32_t zigzag8(int delta) {
 }
 
 // ---------------------------------------------------------------------------------- encode
-
-struct PageResult {
-    uint32_t n16;   // payload size in 16-byte units (0 = page skipped)
-    uint32_t mode;
-    float scale;
-};
 
 template <int MAXP>
 __device__ __forceinline__ void store_codes(const uint4 (&raw)[MAXP], float s_inv, int E, uint32_t* stage) {
@@ -345,10 +322,6 @@ __global__ __launch_bounds__(kThreads) void k_compress(EncodeArgs a) {
 
 // ---------------------------------------------------------------------------------- decode
 
-__device__ __forceinline__ void zero_page(uint16_t* dst, int E) {
-    for (int o = lane_id(); o < (E >> 3); o += 64) reinterpret_cast<uint4*>(dst)[o] = make_uint4(0, 0, 0, 0);
-}
-
 // dequantize step: x = fp16(fp32(q) * s) for a lane's 8 codes (low 8 bits of each q[k], signed)
 __device__ __forceinline__ uint4 dequant8(const int q[8], float s) {
     uint32_t h[8];
@@ -580,6 +553,7 @@ static inline unsigned grid_for(int64_t n_pages, int ppw) {
 
 hipError_t launch_compress(const EncodeArgs& a, hipStream_t s) {
     if (a.n_pages == 0) return hipSuccess;
+    if (a.g.N == 16 && a.g.d == 128) return launch_compress_p2048(a, s);
     constexpr int PPW = 4;
     const dim3 grid(grid_for(a.n_pages, PPW)), block(kThreads);
     if (a.g.E <= 512)
@@ -593,6 +567,7 @@ hipError_t launch_compress(const EncodeArgs& a, hipStream_t s) {
 
 hipError_t launch_decompress(const DecodeArgs& a, hipStream_t s) {
     if (a.n_pages == 0) return hipSuccess;
+    if (a.g.N == 16 && a.g.d == 128) return launch_decompress_p2048(a, s);
     constexpr int PPW = 4;
     const dim3 grid(grid_for(a.n_pages, PPW)), block(kThreads);
     if (a.g.E <= 512)

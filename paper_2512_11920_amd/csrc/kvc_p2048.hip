@@ -1,0 +1,383 @@
+// Kernels specialised for the paper's 4 KB page: 16 tokens x 128 channels FP16 (2048 elements).
+//
+// Same lane mapping as the generic kernels -- one wave per page, 4 passes of 512 elements, a lane
+// owns 8 consecutive channels, a packet group is a quad of lanes, a token row is one 16-lane DPP
+// row -- but every cross-lane step is a DPP operation, the per-group statistics (max, width,
+// run test) and the offset scans are done on quads, and no lane is ever inactive.  The codec is
+// bound by vector-ALU issue before HBM bandwidth, so the code is written to keep the instruction
+// count per element low.
+//
+// Encode: Algorithm 2 of the paper (scaling, quantize, delta, run-length encode).
+// Decode: Section 3.5.3 (undo run-length coding, prefix sum, dequantize; bypass for raw pages).
+#include "kvc_device.h"
+
+namespace kvc {
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
+
+constexpr int kE = 2048;      // elements per page
+constexpr int kHdr = 32;      // header bytes: 64 groups x 4 bits
+constexpr float kMagic = 12582912.0f;  // 1.5 * 2^23: adding it rounds to an integer, ties to even
+constexpr uint32_t kMagicBits = 0x4B400000u;
+
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2v, a),
+                                                                 __builtin_bit_cast(ushort2v, b)));
+}
+
+// quantize step on 8 FP16 values: bits of (x * s_inv + 1.5*2^23); the low bits hold q (two's complement)
+__device__ __forceinline__ void quantize8_bits(const uint4& raw, float s_inv, uint32_t t[8]) {
+    const half8 h = __builtin_bit_cast(half8, raw);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t[k] = __float_as_uint(__builtin_fmaf((float)h[k], s_inv, kMagic));
+}
+
+// plain INT8 payload: codes as bytes, row-major
+__device__ __forceinline__ void store_codes_p2048(const uint4 (&raw)[4], float s_inv, uint32_t* stage) {
+    const int lane = lane_id();
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        uint32_t t[8];
+        quantize8_bits(raw[p], s_inv, t);
+        uint2 v;
+        v.x = __builtin_amdgcn_perm(__builtin_amdgcn_perm(t[3], t[2], 0x0c0c0400u), __builtin_amdgcn_perm(t[1], t[0], 0x0c0c0400u), 0x05040100u);
+        v.y = __builtin_amdgcn_perm(__builtin_amdgcn_perm(t[7], t[6], 0x0c0c0400u), __builtin_amdgcn_perm(t[5], t[4], 0x0c0c0400u), 0x05040100u);
+        reinterpret_cast<uint2*>(stage)[p * 64 + lane] = v;
+    }
+}
+
+// Encode one page into the LDS slot `stage`.
+template <bool RLE>
+__device__ __forceinline__ PageResult encode_p2048(const uint4* __restrict__ src, int scheme, uint32_t* stage) {
+    const int lane = lane_id();
+    const uint32_t qi = (uint32_t)lane & 3u;
+    uint4 raw[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) raw[p] = src[p * 64 + lane];
+
+    // scaling: max |x| on the FP16 bit patterns, two per dword
+    uint32_t m2 = 0;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        m2 = pk_max_u16(m2, raw[p].x & 0x7FFF7FFFu);
+        m2 = pk_max_u16(m2, raw[p].y & 0x7FFF7FFFu);
+        m2 = pk_max_u16(m2, raw[p].z & 0x7FFF7FFFu);
+        m2 = pk_max_u16(m2, raw[p].w & 0x7FFF7FFFu);
+    }
+    const uint32_t m = wave_max_dpp(max(m2 & 0xFFFFu, m2 >> 16));
+    PageResult r;
+    if (scheme == KVC_MODE_RAW || m >= 0x7C00u) {  // requested, or NaN/Inf present: bypass
+        r.n16 = kE / 8;
+        r.mode = KVC_MODE_RAW;
+        r.scale = 0.0f;
+        return r;
+    }
+    float s = 0.0f, s_inv = 0.0f;
+    if (m != 0) {
+        s = (float)__builtin_bit_cast(_Float16, (unsigned short)m) / 127.0f;
+        s_inv = 1.0f / s;
+    }
+    r.scale = s;
+    if (scheme == KVC_MODE_INT8) {
+        store_codes_p2048(raw, s_inv, stage);
+        r.n16 = kE / 16;
+        r.mode = KVC_MODE_INT8;
+        return r;
+    }
+    // bodies are OR-ed into the slot, and the zero padding is part of the payload
+    reinterpret_cast<uint4*>(stage)[lane] = make_uint4(0, 0, 0, 0);
+    reinterpret_cast<uint4*>(stage)[lane + 64] = make_uint4(0, 0, 0, 0);
+    wave_sync();
+
+    uint32_t run = kHdr;  // payload bytes so far (wave-uniform)
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        uint32_t t[8];
+        quantize8_bits(raw[p], s_inv, t);
+        // delta along the channel index; the first column of a token row (lane 0 of a DPP row)
+        // has no left neighbour and is kept verbatim (q - 0)
+        const uint32_t prev = dpp<0x111>(kMagicBits, t[7]);
+        uint32_t u[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int d = (int)(t[k] - (k ? t[k - 1] : prev));
+            u[k] = (((uint32_t)d << 1) ^ (uint32_t)((d << 24) >> 31)) & 0xFFu;  // wrap to 8 bits, zig-zag
+        }
+        // per-group statistics over the quad of lanes
+        uint32_t gmax = max(max(u[0], u[1]), u[2]);
+        gmax = max(max(gmax, u[3]), u[4]);
+        gmax = max(max(gmax, u[5]), u[6]);
+        gmax = max(gmax, u[7]);
+        gmax = max(gmax, dpp<0xB1>(0, gmax));
+        gmax = max(gmax, dpp<0x4E>(0, gmax));
+        // bit length of the group maximum (0 for 0): exponent of its float value
+        uint32_t c = (uint32_t)__builtin_amdgcn_frexp_expf((float)gmax);
+        if (!RLE) c = max(c, 1u);
+        uint32_t size = c << 2;
+        bool is_run = false;
+        if (RLE) {
+            // run packet: all 32 values equal and non-zero.  Cheap necessary test first.
+            const uint32_t x = (u[0] ^ gmax) | (u[7] ^ gmax);
+            if (__builtin_amdgcn_ballot_w64(x == 0 && gmax != 0) != 0) {
+                uint32_t y = x;
+#pragma unroll
+                for (int k = 1; k < 7; ++k) y |= u[k] ^ gmax;
+                y |= dpp<0xB1>(0, y);
+                y |= dpp<0x4E>(0, y);
+                is_run = (y == 0) && (gmax != 0);
+                if (is_run) {
+                    c = 9;
+                    size = 1;
+                }
+            }
+        }
+        const uint32_t incl = quad_incl_scan_dpp(size);
+        const uint32_t off = run + incl - size;  // byte offset of this group's body
+        run += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+        // header: group j of this pass has its code in the quad's lanes; lane 4j+i contributes bit i,
+        // so the ballot is the 8 header bytes of the pass (even group in the low nibble)
+        const uint64_t hb = __builtin_amdgcn_ballot_w64(((c >> qi) & 1u) != 0);
+        if (lane == 0) {
+            stage[2 * p] = (uint32_t)hb;
+            stage[2 * p + 1] = (uint32_t)(hb >> 32);
+        }
+        // body: this lane's 8 values are bytes [qi*c, qi*c + c) of the group's little-endian bit string
+        const uint32_t a01 = u[0] | (u[1] << c), a23 = u[2] | (u[3] << c);
+        const uint32_t a45 = u[4] | (u[5] << c), a67 = u[6] | (u[7] << c);
+        const uint32_t c2 = c << 1;
+        const uint32_t b0 = a01 | (a23 << c2), b1 = a45 | (a67 << c2);
+        uint64_t W = (uint64_t)b0 | ((uint64_t)b1 << (c << 2));
+        uint32_t B = off + qi * c;
+        if (RLE && is_run) {
+            W = qi == 0 ? u[0] : 0;
+            B = off;
+        }
+        const uint32_t sh = (B & 3u) << 3;
+        uint32_t* p0 = stage + (B >> 2);
+        const uint64_t lo = W << sh;
+        const uint32_t d2 = (uint32_t)(((uint64_t)(uint32_t)(W >> 32) << sh) >> 32);
+        atomicOr(p0, (uint32_t)lo);
+        atomicOr(p0 + 1, (uint32_t)(lo >> 32));
+        if (d2) atomicOr(p0 + 2, d2);
+    }
+    const uint32_t n = (run + 15u) & ~15u;
+    wave_sync();
+    if (n >= (uint32_t)kE) {  // packing did not beat plain INT8
+        store_codes_p2048(raw, s_inv, stage);
+        r.n16 = kE / 16;
+        r.mode = KVC_MODE_INT8;
+    } else {
+        r.n16 = n >> 4;
+        r.mode = RLE ? KVC_MODE_RLE : KVC_MODE_DELTA;
+    }
+    return r;
+}
+
+template <bool RLE, int WAVES, int PPW>
+__global__ __launch_bounds__(WAVES * 64) void k_compress_p2048(EncodeArgs a) {
+    constexpr int kSlots = WAVES * PPW;
+    __shared__ __align__(16) uint32_t s_stage[kSlots][Slot<4>::kWords];
+    __shared__ EncBook<kSlots> s_book;
+    const int lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+#pragma unroll 1
+    for (int i = 0; i < PPW; ++i) {
+        const int slot = wave * PPW + i;
+        const int64_t t = ((int64_t)blockIdx.x * WAVES + wave) * PPW + i;
+        const EncTask task = resolve_enc_task(a, t);
+        PageResult r;
+        r.n16 = 0;
+        r.mode = KVC_MODE_INVALID;
+        r.scale = 0.0f;
+        if (task.desc_idx >= 0)
+            r = encode_p2048<RLE>(reinterpret_cast<const uint4*>(a.cache + (size_t)task.src_page * kE), a.scheme,
+                                  s_stage[slot]);
+        if (lane == 0) {
+            s_book.n16[slot] = r.n16;
+            s_book.mode[slot] = r.mode;
+            s_book.scale[slot] = r.scale;
+            s_book.desc[slot] = task.desc_idx;
+            s_book.srcpage[slot] = task.src_page;
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) reserve_pool_span<kSlots>(a, s_book);
+    __syncthreads();
+#pragma unroll 1
+    for (int i = 0; i < PPW; ++i) emit_page<kSlots>(a, s_book, wave * PPW + i, s_stage[wave * PPW + i]);
+}
+
+// ---------------------------------------------------------------------------------- decode
+
+// dequantize: x = fp16(fp32(q) * s).  b = (q + 128) mod 256 sits in the low byte of pb; the fused
+// b*s - 128*s rounds q*s once to binary32 (128*s is exact), then one rounding to FP16.
+__device__ __forceinline__ uint4 dequant8_biased(const uint32_t pb[8], float s, float neg128s) {
+    half2v h[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        h[k].x = (_Float16)__builtin_fmaf((float)(pb[2 * k] & 0xFFu), s, neg128s);
+        h[k].y = (_Float16)__builtin_fmaf((float)(pb[2 * k + 1] & 0xFFu), s, neg128s);
+    }
+    return make_uint4(__builtin_bit_cast(uint32_t, h[0]), __builtin_bit_cast(uint32_t, h[1]),
+                      __builtin_bit_cast(uint32_t, h[2]), __builtin_bit_cast(uint32_t, h[3]));
+}
+
+// Decode the page described by descriptor d_idx into dst (4 KB).  false = validation failed, dst zeroed.
+__device__ __forceinline__ bool decode_p2048(const DecodeArgs& a, uint64_t d_idx, uint16_t* __restrict__ dst,
+                                             uint32_t* stage, uint32_t* ginfo) {
+    const int lane = lane_id();
+    const uint32_t qi = (uint32_t)lane & 3u;
+    const uint4 dw = reinterpret_cast<const uint4*>(a.desc)[d_idx];
+    const uint64_t off = (uint64_t)dw.x | ((uint64_t)dw.y << 32);
+    const float s = __uint_as_float(dw.z);
+    const uint32_t n16 = dw.w & 0xFFFFu;
+    const uint32_t mode = (dw.w >> 16) & 0xFFu;
+    uint4* dst4 = reinterpret_cast<uint4*>(dst);
+
+    bool ok = (off & 15u) == 0 && (off >> 4) + n16 <= a.pool_units;
+    if (mode == KVC_MODE_RAW)
+        ok = ok && n16 == kE / 8;
+    else if (mode == KVC_MODE_INT8)
+        ok = ok && n16 == kE / 16;
+    else if (mode == KVC_MODE_DELTA || mode == KVC_MODE_RLE)
+        ok = ok && n16 >= kHdr / 16 && n16 < kE / 16;
+    else
+        ok = false;
+    if (!ok) {
+        zero_page(dst, kE);
+        return false;
+    }
+    const uint4* pl4 = reinterpret_cast<const uint4*>(a.pool + off);
+    if (mode == KVC_MODE_RAW) {  // stored-uncompressed bypass
+#pragma unroll
+        for (int p = 0; p < 4; ++p) dst4[p * 64 + lane] = pl4[p * 64 + lane];
+        return true;
+    }
+    const float neg128s = -128.0f * s;
+    if (mode == KVC_MODE_INT8) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const uint2 v = reinterpret_cast<const uint2*>(pl4)[p * 64 + lane];
+            uint32_t pb[8];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                pb[k] = ((v.x >> (8 * k)) + 128u);
+                pb[4 + k] = ((v.y >> (8 * k)) + 128u);
+            }
+            dst4[p * 64 + lane] = dequant8_biased(pb, s, neg128s);
+        }
+        return true;
+    }
+    // packed modes: stage the payload in LDS (at most 127 16-byte units)
+    {
+        uint4* st4 = reinterpret_cast<uint4*>(stage);
+        if ((uint32_t)lane < n16) st4[lane] = pl4[lane];
+        if ((uint32_t)lane + 64 < n16) st4[lane + 64] = pl4[lane + 64];
+    }
+    wave_sync();
+    // header: lane g takes the code of group g; body offsets are a prefix sum of body sizes
+    const uint32_t c_own = (stage[lane >> 3] >> ((lane & 7) << 2)) & 15u;
+    const uint32_t size_own = (c_own == 9) ? 1u : (c_own << 2);
+    const uint32_t incl = wave_incl_scan_dpp(size_own);
+    ginfo[lane] = ((kHdr + incl - size_own) << 4) | c_own;
+    const uint32_t total = kHdr + (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+    const bool bad = c_own > 9 || (mode == KVC_MODE_DELTA && (c_own == 0 || c_own == 9));
+    const bool special = __builtin_amdgcn_ballot_w64(c_own == 0 || c_own == 9) != 0;  // any zero-run / run packet
+    if (__builtin_amdgcn_ballot_w64(bad) != 0 || ((total + 15u) >> 4) != n16) {
+        zero_page(dst, kE);
+        return false;
+    }
+    wave_sync();
+    const uint8_t* stage8 = reinterpret_cast<const uint8_t*>(stage);
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const uint32_t gi = ginfo[p * 16 + (lane >> 2)];
+        uint32_t c = gi & 15u;
+        const uint32_t goff = gi >> 4;
+        uint32_t B = goff + qi * c;
+        if (special && c == 9) B = goff;
+        const uint32_t sh = (B & 3u) << 3;
+        const uint32_t* p0 = stage + (B >> 2);
+        const uint32_t d0 = p0[0], d1 = p0[1], d2 = p0[2];
+        uint32_t lo = __builtin_amdgcn_alignbit(d1, d0, sh);
+        uint32_t hi = __builtin_amdgcn_alignbit(d2, d1, sh);
+        if (special) {
+            if (c == 9) {  // run packet: the body byte, 32 times
+                lo = __builtin_amdgcn_perm(lo, lo, 0u);
+                hi = lo;
+                c = 8;
+            } else if (c == 0) {  // zero-run packet
+                lo = 0;
+                hi = 0;
+                c = 1;
+            }
+        }
+        const uint32_t mid = (uint32_t)((((uint64_t)hi << 32) | lo) >> (c << 2));  // values 4..7 start at bit 4c
+        // value k sits at bits [k*c, k*c + c); delta = (u >> 1) ^ -(u & 1) taken straight from the fields
+        const uint32_t w1 = c - 1u;
+        const uint32_t o1 = c, o2 = c << 1, o3 = o2 + c;
+        int dl[8];
+        dl[0] = (int)__builtin_amdgcn_ubfe(lo, 1u, w1) ^ __builtin_amdgcn_sbfe((int)lo, 0u, 1u);
+        dl[1] = (int)__builtin_amdgcn_ubfe(lo, o1 + 1u, w1) ^ __builtin_amdgcn_sbfe((int)lo, o1, 1u);
+        dl[2] = (int)__builtin_amdgcn_ubfe(lo, o2 + 1u, w1) ^ __builtin_amdgcn_sbfe((int)lo, o2, 1u);
+        dl[3] = (int)__builtin_amdgcn_ubfe(lo, o3 + 1u, w1) ^ __builtin_amdgcn_sbfe((int)lo, o3, 1u);
+        dl[4] = (int)__builtin_amdgcn_ubfe(mid, 1u, w1) ^ __builtin_amdgcn_sbfe((int)mid, 0u, 1u);
+        dl[5] = (int)__builtin_amdgcn_ubfe(mid, o1 + 1u, w1) ^ __builtin_amdgcn_sbfe((int)mid, o1, 1u);
+        dl[6] = (int)__builtin_amdgcn_ubfe(mid, o2 + 1u, w1) ^ __builtin_amdgcn_sbfe((int)mid, o2, 1u);
+        dl[7] = (int)__builtin_amdgcn_ubfe(mid, o3 + 1u, w1) ^ __builtin_amdgcn_sbfe((int)mid, o3, 1u);
+        // prefix sum along the channel index: in the lane, then across the 16 lanes of the token row
+        const uint32_t tot = (uint32_t)(dl[0] + dl[1] + dl[2] + dl[3] + dl[4] + dl[5] + dl[6] + dl[7]);
+        const uint32_t rincl = row16_incl_scan_dpp(tot);
+        uint32_t pb[8];
+        pb[0] = rincl - tot + 128u + (uint32_t)dl[0];  // +128: biased codes, see dequant8_biased
+#pragma unroll
+        for (int k = 1; k < 8; ++k) pb[k] = pb[k - 1] + (uint32_t)dl[k];
+        dst4[p * 64 + lane] = dequant8_biased(pb, s, neg128s);
+    }
+    (void)stage8;
+    return true;
+}
+
+template <int WAVES, int PPW>
+__global__ __launch_bounds__(WAVES * 64) void k_decompress_p2048(DecodeArgs a) {
+    __shared__ __align__(16) uint32_t s_stage[WAVES][Slot<4>::kWords];
+    __shared__ uint32_t s_ginfo[WAVES][64];
+    const int lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+#pragma unroll 1
+    for (int i = 0; i < PPW; ++i) {
+        const int64_t t = ((int64_t)blockIdx.x * WAVES + wave) * PPW + i;
+        const DecTask task = resolve_dec_task(a, t);
+        if (task.kind == 2) zero_page(task.dst, kE);
+        if (task.kind == 1 && !decode_p2048(a, task.desc_idx, task.dst, s_stage[wave], s_ginfo[wave])) {
+            if (lane == 0) atomicOr(&a.st->status, KVC_ST_CORRUPT);
+        }
+        wave_sync();
+    }
+}
+
+}  // namespace
+
+hipError_t launch_compress_p2048(const EncodeArgs& a, hipStream_t s) {
+    constexpr int WAVES = 4, PPW = 4;
+    const int64_t per_wg = (int64_t)WAVES * PPW;
+    const dim3 grid((unsigned)((a.n_pages + per_wg - 1) / per_wg)), block(WAVES * 64);
+    if (a.scheme == KVC_MODE_DELTA)
+        hipLaunchKernelGGL((k_compress_p2048<false, WAVES, PPW>), grid, block, 0, s, a);
+    else
+        hipLaunchKernelGGL((k_compress_p2048<true, WAVES, PPW>), grid, block, 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_decompress_p2048(const DecodeArgs& a, hipStream_t s) {
+    constexpr int WAVES = 4, PPW = 4;
+    const int64_t per_wg = (int64_t)WAVES * PPW;
+    const dim3 grid((unsigned)((a.n_pages + per_wg - 1) / per_wg)), block(WAVES * 64);
+    hipLaunchKernelGGL((k_decompress_p2048<WAVES, PPW>), grid, block, 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace kvc

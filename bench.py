@@ -41,19 +41,6 @@ def read_traffic(workload: str, kernel: str):
     return None
 
 
-def build_cache(shape, device, block_major=False):
-    """Whole cache on the GPU, one layer at a time (seeded).  kv-major: [L][2][blocks][H][N][d]."""
-    import torch
-
-    from paper_2512_11920_amd import synth
-
-    H, N, d = shape.n_kv_heads, shape.tokens_per_block, shape.head_dim
-    cache = torch.empty((shape.n_layers, 2, shape.blocks_per_layer, H, N, d), dtype=torch.float16, device=device)
-    for l in range(shape.n_layers):
-        cache[l].copy_(synth.layer_torch(shape, l, device))
-    return cache
-
-
 def sample_check(codec, cache_blocks, out_blocks, n_sample, N, d, ppb, scheme):
     """Compare a random sample of pages (descriptor, payload, decoded values) with the oracle."""
     import numpy as np
@@ -141,7 +128,7 @@ def main():
     ppb = H
     E = N * d
     log(f"[bench] building {shape.name}: {shape.n_pages} pages, {shape.nbytes / 1e9:.2f} GB fp16")
-    cache = build_cache(shape, dev)
+    cache = synth.cache_torch(shape, dev)
     blocks = cache.view(-1, ppb, N, d)
     n_blocks = blocks.shape[0]
     out = torch.empty_like(blocks)
@@ -289,7 +276,7 @@ def bench_decode_gather(args):
     codec.alloc_pool(n_pool_blocks, n_pool_blocks * ppb * E + 4096, dev)
     ids = torch.arange(pbl, dtype=torch.int32, device=dev)
     for l in range(shape.n_layers):
-        layer = synth.layer_torch(shape, l, dev, block_major=True, n_blocks=pbl)
+        layer = synth.gather_layer_torch(shape, pat, l, dev)
         codec.compress_blocks(layer.view(-1, ppb, N, d), pool_ids=ids + l * pbl)
     torch.cuda.synchronize()
     st = codec.stats()

@@ -108,6 +108,17 @@ def layer_torch(shape: KVShape, layer: int, device, block_major: bool = False, n
     return z.to(torch.float16)
 
 
+def cache_torch(shape: KVShape, device):
+    """Whole cache on ``device``, drawn one layer at a time: float16 [layer][2][blocks][head][N][d]."""
+    import torch
+
+    H, N, d = shape.n_kv_heads, shape.tokens_per_block, shape.head_dim
+    cache = torch.empty((shape.n_layers, 2, shape.blocks_per_layer, H, N, d), dtype=torch.float16, device=device)
+    for l in range(shape.n_layers):
+        cache[l].copy_(layer_torch(shape, l, device))
+    return cache
+
+
 @dataclass(frozen=True)
 class GatherPattern:
     """Decode-step prefetch pattern (70B shape): per-sequence lengths, a block table that places
@@ -144,3 +155,15 @@ def gather_pattern(n_seq: int = 64, k: int = 8, len_lo: int = 512, len_hi: int =
         table[s, : nb[s]] = perm[o:o + nb[s]]
         o += int(nb[s])
     return GatherPattern(n_seq, k, lengths, nb, table, total, seed)
+
+
+def gather_layer_torch(shape: KVShape, pat: GatherPattern, layer: int, device):
+    """One layer of the decode-gather pool source, block-major float16 [pool_blocks][2][head][N][d]; the
+    last block of every sequence is zero beyond the sequence's length."""
+    x = layer_torch(shape, layer, device, block_major=True, n_blocks=pat.pool_blocks_per_layer)
+    N = shape.tokens_per_block
+    for s in range(pat.n_seq):
+        tail = int(pat.lengths[s]) % N
+        if tail:
+            x[int(pat.block_table[s, pat.n_blocks[s] - 1]), :, :, tail:, :] = 0
+    return x

@@ -67,3 +67,19 @@ def upload_oracle_pool(codec, od: np.ndarray, op: np.ndarray):
     desc = torch.from_numpy(od.view(np.uint8).copy()).to(DEV)
     codec.bind_pool(pool, desc)
     return pool, desc
+
+
+def fetch_pages(codec, page_ids: np.ndarray):
+    """Descriptors and payload bytes of the given descriptor-table entries, compacted on the GPU and
+    copied to the host: -> (desc records with `off` rewritten to the compact buffer, uint8 buffer)."""
+    idt = torch.from_numpy(np.ascontiguousarray(page_ids, np.int64)).to(codec.desc.device)
+    d = codec.desc.view(-1, 16)[idt].cpu().numpy().view(kvc.DESC_DTYPE).ravel().copy()
+    live = d["mode"] != 0xFF
+    size = np.where(live, d["n16"].astype(np.int64) * 16, 0)
+    start = np.concatenate([[0], np.cumsum(size)[:-1]])
+    total = int(size.sum())
+    shift = torch.from_numpy(d["off"].astype(np.int64) - start).to(idt.device)
+    idx = torch.repeat_interleave(shift, torch.from_numpy(size).to(idt.device)) + torch.arange(total, device=idt.device)
+    buf = codec.pool[idx].cpu().numpy()
+    d["off"] = start.astype(np.uint64)
+    return d, buf

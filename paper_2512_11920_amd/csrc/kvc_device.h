@@ -5,6 +5,11 @@
 
 namespace kvc {
 
+// payloads are written to the pool once and not read back by the encoder: non-temporal stores
+#ifndef KVC_NT_POOL_STORE
+#define KVC_NT_POOL_STORE 1
+#endif
+
 constexpr int kWavesPerWG = 4;
 constexpr int kThreads = kWavesPerWG * 64;
 
@@ -84,14 +89,38 @@ struct EncTask {
     long long src_page;
 };
 
-__device__ __forceinline__ EncTask resolve_enc_task(const EncodeArgs& a, int64_t t) {
+// Position of a wave's first page task as (block, page in block); later tasks advance it by one page.
+struct TaskPos {
+    int64_t blk;
+    int pg;
+};
+
+__device__ __forceinline__ TaskPos task_pos(int64_t t, int ppb) {
+    TaskPos r;
+    if ((uint64_t)t >> 32) {
+        r.blk = t / ppb;
+    } else {
+        r.blk = (int64_t)((uint32_t)t / (uint32_t)ppb);
+    }
+    r.pg = (int)(t - r.blk * ppb);
+    return r;
+}
+
+__device__ __forceinline__ void task_advance(TaskPos& p, int ppb) {
+    if (++p.pg == ppb) {
+        p.pg = 0;
+        ++p.blk;
+    }
+}
+
+__device__ __forceinline__ EncTask resolve_enc_task(const EncodeArgs& a, int64_t t, const TaskPos& pos) {
     EncTask r;
     r.desc_idx = -1;
     r.src_page = -1;
     if (t >= a.n_pages) return r;
     const int ppb = a.g.ppb;
-    const int64_t blk = t / ppb;
-    const int pg = (int)(t - blk * ppb);
+    const int64_t blk = pos.blk;
+    const int pg = pos.pg;
     const int64_t sb = a.src_ids ? (int64_t)a.src_ids[blk] : blk;
     const int64_t pb = a.pool_ids ? (int64_t)a.pool_ids[blk] : blk;
     if (sb < 0 || pb < 0) return r;
@@ -112,15 +141,15 @@ struct DecTask {
     uint16_t* dst;
 };
 
-__device__ __forceinline__ DecTask resolve_dec_task(const DecodeArgs& a, int64_t t) {
+__device__ __forceinline__ DecTask resolve_dec_task(const DecodeArgs& a, int64_t t, const TaskPos& pos) {
     DecTask r;
     r.kind = 0;
     r.desc_idx = 0;
     r.dst = nullptr;
     if (t >= a.n_pages) return r;
     const Geometry& g = a.g;
-    const int64_t blk = t / g.ppb;
-    const int pg = (int)(t - blk * g.ppb);
+    const int64_t blk = pos.blk;
+    const int pg = pos.pg;
     int64_t pb, db;
     bool bad_index = false;
     if (a.block_table) {  // translate (layer, sequence, predicted logical block) -> pool block
@@ -212,7 +241,17 @@ __device__ __forceinline__ void emit_page(const EncodeArgs& a, const EncBook<SLO
             for (uint32_t o = lane; o < n16; o += 64) dst[o] = srcp[o];
         } else {
             const uint4* srcp = reinterpret_cast<const uint4*>(stage);
+#if KVC_NT_POOL_STORE
+            typedef uint32_t u4v __attribute__((ext_vector_type(4)));
+            for (uint32_t o = lane; o < n16; o += 64) {
+                const uint4 v = srcp[o];
+                u4v w;
+                w.x = v.x; w.y = v.y; w.z = v.z; w.w = v.w;
+                __builtin_nontemporal_store(w, reinterpret_cast<u4v*>(dst + o));
+            }
+#else
             for (uint32_t o = lane; o < n16; o += 64) dst[o] = srcp[o];
+#endif
         }
     }
     if (lane == 0) {

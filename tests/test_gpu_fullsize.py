@@ -31,10 +31,11 @@ def _sampled_pages_match_oracle(codec, cache_pages, out_pages, ids, N, d):
     assert np.array_equal(got, want)
 
 
-def test_70b_gqa_full_cache_sampled_parity_and_invariants():
-    """BASELINE config 4: 80 layers x 8 KV heads x 128, seq 4096, batch 16 (21.47 GB), one launch per
-    direction exactly as bench.py times it."""
-    sh = synth.CONFIGS["70b_gqa"]
+@pytest.mark.parametrize("name", ["70b_gqa", "7b_full"])
+def test_full_cache_sampled_parity_and_invariants(name):
+    """BASELINE configs 4 (80 layers x 8 KV heads x 128, seq 4096, batch 16, 21.47 GB) and 3 (32 layers x
+    32 heads x 128, seq 2048, batch 32, 34.36 GB): one launch per direction exactly as bench.py times it."""
+    sh = synth.CONFIGS[name]
     N, d, ppb = 16, 128, sh.n_kv_heads
     _say(f"[case] building {sh.name}: {sh.n_pages} pages")
     cache = synth.cache_torch(sh, DEV)
@@ -48,6 +49,7 @@ def test_70b_gqa_full_cache_sampled_parity_and_invariants():
     ratio = codec.ratio()
     _say(f"[case] ratio {ratio:.4f} modes {st['pages']}")
     assert 2.15 < ratio < 2.35  # the oracle gives 2.23-2.26 on this distribution
+    del cache
     desc = codec.desc_numpy()
     check_pool_invariants(desc, st["pool_bytes_used"], codec.pool.numel())
     assert st["payload_bytes"] == st["pool_bytes_used"]
@@ -76,6 +78,59 @@ def test_70b_gqa_full_cache_sampled_parity_and_invariants():
         ok = (x - y.float()).abs() <= amax / 254 * (1 + 2.0 ** -14) + ulp / 2
         assert bool(ok.all()), f"layer {l}"
         del x, y, ya, ulp, ok
+
+
+def test_7b_layer_all_pages():
+    """BASELINE config 2: one LLaMA-2-7B layer, 32 KV heads x 128, seq 2048, batch 8 (65,536 pages):
+    every page against the oracle."""
+    from gpu_util import compare_pages_with_oracle
+
+    sh = synth.CONFIGS["7b_layer"]
+    N, d, ppb = 16, 128, sh.n_kv_heads
+    cache = synth.cache_torch(sh, DEV)
+    blocks = cache.view(-1, ppb, N, d)
+    codec = kvc.Codec(N, d, ppb, 3)
+    codec.alloc_pool(blocks.shape[0], sh.n_pages * N * d + 4096, DEV)
+    codec.compress_blocks(blocks)
+    out = torch.empty_like(blocks)
+    codec.decompress_blocks(out)
+    st = codec.stats()
+    assert st["rc"] == 0
+    x = blocks.cpu().numpy().view(np.uint16).reshape(-1, N, d)
+    desc, pool = codec.desc_numpy(), codec.pool.cpu().numpy()
+    check_pool_invariants(desc, st["pool_bytes_used"], pool.size)
+    _say("[case] oracle on all 65536 pages")
+    od, op = compare_pages_with_oracle(x, desc, pool, N, d, 3)
+    want, bad = o.decompress_pages(op, od, N, d, n_threads=8)
+    assert bad == 0 and np.array_equal(out.cpu().numpy().view(np.uint16).reshape(-1, N, d), want)
+    assert codec.ratio() == pytest.approx(o.ratio(od, N * d))
+
+
+def test_every_possible_page_maximum_gives_the_oracle_scale():
+    """The scale is a function of the page's largest magnitude, an FP16 value: all 31,743 finite non-zero
+    ones are tried, so the kernel's two binary32 divisions are compared with the oracle's exhaustively."""
+    N, d = 16, 128
+    rng = np.random.default_rng(31743)
+    m = np.arange(1, 0x7C00, dtype=np.uint16)
+    x = np.zeros((m.size, N, d), np.uint16)
+    # background: random values not larger in magnitude than the page's maximum
+    bg = rng.integers(0, 0x7C00, size=(m.size, N, d), dtype=np.uint16)
+    x[:] = np.minimum(bg, m[:, None, None]) | (rng.integers(0, 2, size=(m.size, N, d), dtype=np.uint16) << 15)
+    x[np.arange(m.size), rng.integers(0, N, m.size), rng.integers(0, d, m.size)] = m | (rng.integers(0, 2, m.size, dtype=np.uint16) << 15)
+    xt = torch.from_numpy(x.view(np.float16).reshape(-1, 1, N, d)).to(DEV)
+    codec = kvc.Codec(N, d, 1, 3)
+    codec.alloc_pool(m.size, m.size * N * d + 4096, DEV)
+    codec.compress_blocks(xt)
+    out = torch.empty_like(xt)
+    codec.decompress_blocks(out)
+    assert codec.stats()["rc"] == 0
+    desc = codec.desc_numpy()
+    want_s = (m.view(np.float16).astype(np.float32) / np.float32(127.0)).astype(np.float32)
+    assert np.array_equal(desc["scale"].view(np.uint32), want_s.view(np.uint32))
+    from gpu_util import compare_pages_with_oracle
+    od, op = compare_pages_with_oracle(x, desc, codec.pool.cpu().numpy(), N, d, 3)
+    want, bad = o.decompress_pages(op, od, N, d, n_threads=8)
+    assert bad == 0 and np.array_equal(out.cpu().numpy().view(np.uint16).reshape(-1, N, d), want)
 
 
 def test_decode_gather_pattern_70b_shape():

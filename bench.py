@@ -102,6 +102,7 @@ def main():
     ap.add_argument("--workload", default="70b_gqa")
     ap.add_argument("--scheme", type=int, default=3)
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (quick runs; not the headline)")
+    ap.add_argument("--ablation", action="store_true", help="ratio and speed per scheme (Table 9 analogue)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
@@ -117,6 +118,8 @@ def main():
 
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.ablation:
+        return bench_ablation(args)
     if args.workload == "decode_gather":
         return bench_decode_gather(args)
     shape = synth.CONFIGS[args.workload]
@@ -318,6 +321,57 @@ def bench_decode_gather(args):
                     "p99": round(float(np.percentile(ts, 99)), 4)},
     }
     print(json.dumps(res), flush=True)
+
+
+def bench_ablation(args):
+    """Compression-scheme ablation in the manner of the paper's Table 9 (None / INT8 / +Delta / +RLE):
+    ratio and kernel speed per scheme on two synthetic inputs -- the LLaMA-shaped i.i.d.-channel cache
+    and channel-correlated AR(1) pages.  Perplexity cannot be reproduced here."""
+    import torch
+
+    from paper_2512_11920_amd import kvc, synth
+
+    dev = "cuda:0"
+    N, d, ppb = 16, 128, 8
+    n_layers = args.layers or 8
+    shape = synth.KVShape("70b_gqa_slice", n_layers, 8, 128, 4096, 16)
+    inputs = {"llama_iid": synth.cache_torch(shape, dev).view(-1, ppb, N, d)}
+    inputs["ar1_rho0.95"] = synth.ar1_pages_torch(inputs["llama_iid"].shape[0] * ppb, dev).view(-1, ppb, N, d)
+    rows = []
+    for name, blocks in inputs.items():
+        out = torch.empty_like(blocks)
+        unc = blocks.numel() * 2
+        for scheme, label in ((0, "None (FP16)"), (1, "INT8 only"), (2, "INT8 + Delta"), (3, "INT8 + Delta + RLE")):
+            codec = kvc.Codec(N, d, ppb, scheme)
+            codec.alloc_pool(blocks.shape[0], unc + 4096, dev)
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            tc = td = 0.0
+            for rep in range(args.warmup + args.steps):
+                codec.reset_pool()
+                ev[0].record()
+                codec.compress_blocks(blocks)
+                ev[1].record()
+                codec.decompress_blocks(out)
+                ev[2].record()
+                torch.cuda.synchronize()
+                if rep >= args.warmup:
+                    tc += ev[0].elapsed_time(ev[1])
+                    td += ev[1].elapsed_time(ev[2])
+            st = codec.stats()
+            assert st["rc"] == 0
+            err = (out.float() - blocks.float()).pow(2).mean().sqrt() / blocks.float().pow(2).mean().sqrt()
+            rows.append({"input": name, "scheme": label, "ratio": round(codec.ratio(), 4),
+                         "payload_ratio": round(unc / st["payload_bytes"], 4), "pages_per_mode": st["pages"],
+                         "compress_GBps_unc": round(unc / (tc / args.steps) / 1e6, 1),
+                         "decompress_GBps_unc": round(unc / (td / args.steps) / 1e6, 1),
+                         "rel_rmse": round(float(err), 5)})
+            log(f"[ablation] {name:12s} {label:20s} ratio {rows[-1]['ratio']:.3f} (payload {rows[-1]['payload_ratio']:.3f}) "
+                f"C {rows[-1]['compress_GBps_unc']:.0f} D {rows[-1]['decompress_GBps_unc']:.0f} GB/s rel-rmse {rows[-1]['rel_rmse']:.4f}")
+            del codec
+    print(json.dumps({"metric": "compression ratio and codec GB/s (uncompressed fp16) per scheme", "n_gpus": 1,
+                      "data": "synthetic", "config": {"workload": f"ablation: {n_layers} layers of the 70B shape "
+                                                      f"({inputs['llama_iid'].shape[0] * ppb} pages per input)"},
+                      "ablation": rows}), flush=True)
 
 
 if __name__ == "__main__":

@@ -25,7 +25,7 @@
  * Decoding yields fp16(fp32(q) * s), one binary32 multiply and one round-to-nearest-even.
  *
  * Memory.  Every data pointer below is DEVICE memory allocated and owned by the caller; the
- * library owns only the host-side context and a 64-byte device state block (pool cursor, sticky
+ * library owns only the host-side context and a small device state block (pool cursor, sticky
  * status).  `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *
  * Asynchrony and errors.  compress / decompress / gather only enqueue kernels.  They return 0 or a
@@ -109,6 +109,12 @@ int kvc_reset_pool(kvc_ctx* ctx, void* stream);
  * Re-compressing into an occupied pool block leaks its old span until kvc_reset_pool. */
 int kvc_compress_blocks(kvc_ctx* ctx, const void* d_cache, int64_t n_cache_blocks, const int32_t* d_src_block_ids,
                         const int32_t* d_pool_block_ids, int32_t n, void* stream);
+
+/* As kvc_compress_blocks, with the requested mode given per block: d_block_scheme[i] in 0..3 (values
+ * above 3 are read as 3) applies to block i of the call.  This is the mechanism behind the paper's
+ * layer-wise algorithm selection (Sections 3.1 (vi) and 3.6.3); the selection policy is the caller's. */
+int kvc_compress_blocks_mixed(kvc_ctx* ctx, const void* d_cache, int64_t n_cache_blocks, const int32_t* d_src_block_ids,
+                              const int32_t* d_pool_block_ids, const uint8_t* d_block_scheme, int32_t n, void* stream);
 
 /* Inverse (Section 3.5.3) over n blocks: pool block pool[i] (NULL: i) is decoded into output block
  * dst[i] (NULL: i) of d_cache_out, FP16 [n_out_blocks][ppb][N][d]. */

@@ -100,8 +100,8 @@ int kvc_reset_pool(kvc_ctx* ctx, void* stream) {
                : KVC_ERR_HIP;
 }
 
-int kvc_compress_blocks(kvc_ctx* ctx, const void* d_cache, int64_t n_cache_blocks, const int32_t* d_src_block_ids,
-                        const int32_t* d_pool_block_ids, int32_t n, void* stream) {
+static int compress_impl(kvc_ctx* ctx, const void* d_cache, int64_t n_cache_blocks, const int32_t* d_src_block_ids,
+                         const int32_t* d_pool_block_ids, const uint8_t* d_block_scheme, int32_t n, void* stream) {
     if (!ctx || n < 0 || n_cache_blocks < 0) return KVC_ERR_ARG;
     if (!ctx->pool) return KVC_ERR_NOT_BOUND;
     if (n == 0) return KVC_OK;
@@ -117,12 +117,24 @@ int kvc_compress_blocks(kvc_ctx* ctx, const void* d_cache, int64_t n_cache_block
     a.n_pages = (int64_t)n * ctx->g.ppb;
     a.g = ctx->g;
     a.scheme = ctx->cfg.scheme;
+    a.block_scheme = d_block_scheme;
     a.pool = ctx->pool;
     a.pool_units = ctx->pool_bytes / 16;
     a.desc = ctx->desc;
     a.n_desc = ctx->n_desc;
     a.st = ctx->st;
     return hip_ok(kvc::launch_compress(a, static_cast<hipStream_t>(stream))) ? KVC_OK : KVC_ERR_HIP;
+}
+
+int kvc_compress_blocks(kvc_ctx* ctx, const void* d_cache, int64_t n_cache_blocks, const int32_t* d_src_block_ids,
+                        const int32_t* d_pool_block_ids, int32_t n, void* stream) {
+    return compress_impl(ctx, d_cache, n_cache_blocks, d_src_block_ids, d_pool_block_ids, nullptr, n, stream);
+}
+
+int kvc_compress_blocks_mixed(kvc_ctx* ctx, const void* d_cache, int64_t n_cache_blocks, const int32_t* d_src_block_ids,
+                              const int32_t* d_pool_block_ids, const uint8_t* d_block_scheme, int32_t n, void* stream) {
+    if (!d_block_scheme) return KVC_ERR_ARG;
+    return compress_impl(ctx, d_cache, n_cache_blocks, d_src_block_ids, d_pool_block_ids, d_block_scheme, n, stream);
 }
 
 static void fill_decode_common(kvc_ctx* ctx, kvc::DecodeArgs& a) {

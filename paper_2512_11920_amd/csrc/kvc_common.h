@@ -27,6 +27,7 @@ struct EncodeArgs {
     int64_t n_pages;  // n blocks * ppb
     Geometry g;
     int32_t scheme;
+    const uint8_t* block_scheme;  // optional: requested mode per block (overrides scheme)
     uint8_t* pool;
     uint64_t pool_units;  // pool size in 16-byte units
     kvc_desc* desc;

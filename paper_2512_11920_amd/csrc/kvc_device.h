@@ -87,6 +87,7 @@ struct PageResult {
 struct EncTask {
     long long desc_idx;  // -1: nothing to do
     long long src_page;
+    int scheme;          // mode requested for this page
 };
 
 // Position of a wave's first page task as (block, page in block); later tasks advance it by one page.
@@ -117,6 +118,7 @@ __device__ __forceinline__ EncTask resolve_enc_task(const EncodeArgs& a, int64_t
     EncTask r;
     r.desc_idx = -1;
     r.src_page = -1;
+    r.scheme = a.scheme;
     if (t >= a.n_pages) return r;
     const int ppb = a.g.ppb;
     const int64_t blk = pos.blk;
@@ -131,6 +133,7 @@ __device__ __forceinline__ EncTask resolve_enc_task(const EncodeArgs& a, int64_t
     }
     r.src_page = sb * ppb + pg;
     r.desc_idx = (long long)d_idx;
+    if (a.block_scheme) r.scheme = min((int)a.block_scheme[blk], 3);
     return r;
 }
 

@@ -260,7 +260,8 @@ __global__ __launch_bounds__(kThreads) void k_compress(EncodeArgs a) {
                 } else {
                     sp = sb * g.ppb + pg;
                     di = (long long)d_idx;
-                    r = encode_page<MAXP>(a.cache + (size_t)sp * (size_t)E, g, a.scheme, s_stage[slot]);
+                    const int scheme = a.block_scheme ? min((int)a.block_scheme[blk], 3) : a.scheme;
+                    r = encode_page<MAXP>(a.cache + (size_t)sp * (size_t)E, g, scheme, s_stage[slot]);
                 }
             }
         }

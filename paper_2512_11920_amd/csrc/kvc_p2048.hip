@@ -132,10 +132,11 @@ __device__ __forceinline__ void load_page(const EncodeArgs& a, const EncTask& ta
     for (int p = 0; p < 4; ++p) raw[p] = load_stream(src + p * 64);
 }
 
-// Encode one page (its 4 KB already in registers) into the LDS slot `stage`.
-template <bool RLE>
+// Encode one page (its 4 KB already in registers) into the LDS slot `stage`.  scheme is wave-uniform.
 __device__ __forceinline__ PageResult encode_p2048(const uint4 (&raw)[4], int scheme, uint32_t* stage,
                                                    const uint8_t* lut) {
+    const bool RLE = scheme == KVC_MODE_RLE;
+    const uint32_t c_min = RLE ? 0u : 1u;  // without run packets an all-zero group is a 1-bit literal
     const int lane = lane_id();
     const uint32_t qi = (uint32_t)lane & 3u;
 
@@ -193,8 +194,7 @@ __device__ __forceinline__ PageResult encode_p2048(const uint4 (&raw)[4], int sc
         gmax = max(gmax, dpp<0xB1>(0, gmax));
         gmax = max(gmax, dpp<0x4E>(0, gmax));
         // bit length of the group maximum (0 for 0): exponent of its float value
-        uint32_t c = (uint32_t)__builtin_amdgcn_frexp_expf((float)gmax);
-        if (!RLE) c = max(c, 1u);
+        const uint32_t c = max((uint32_t)__builtin_amdgcn_frexp_expf((float)gmax), c_min);
         const uint32_t size = c << 2;
         bool cand_any = false;
         uint32_t x = 0;
@@ -228,7 +228,7 @@ __device__ __forceinline__ PageResult encode_p2048(const uint4 (&raw)[4], int sc
     return r;
 }
 
-template <bool RLE, int WAVES, int PPW>
+template <int WAVES, int PPW>
 __global__ __launch_bounds__(WAVES * 64) void k_compress_p2048(EncodeArgs a) {
     constexpr int kSlots = WAVES * PPW;
     __shared__ __align__(16) uint32_t s_stage[kSlots][Slot<4>::kWords];
@@ -251,6 +251,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_compress_p2048(EncodeArgs a) {
         EncTask next;
         next.desc_idx = -1;
         next.src_page = -1;
+        next.scheme = 0;
         uint4 raw_next[4];
         if (i + 1 < PPW) {
             next = resolve_enc_task(a, t0 + i + 1, pos);
@@ -260,7 +261,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_compress_p2048(EncodeArgs a) {
         r.n16 = 0;
         r.mode = KVC_MODE_INVALID;
         r.scale = 0.0f;
-        if (task.desc_idx >= 0) r = encode_p2048<RLE>(raw, a.scheme, s_stage[slot], s_lut);
+        if (task.desc_idx >= 0) r = encode_p2048(raw, task.scheme, s_stage[slot], s_lut);
         if (lane == 0) {
             s_book.n16[slot] = r.n16;
             s_book.mode[slot] = r.mode;
@@ -455,10 +456,7 @@ hipError_t launch_compress_p2048(const EncodeArgs& a, hipStream_t s) {
     constexpr int WAVES = KVC_ENC_WAVES, PPW = KVC_ENC_PPW;
     const int64_t per_wg = (int64_t)WAVES * PPW;
     const dim3 grid((unsigned)((a.n_pages + per_wg - 1) / per_wg)), block(WAVES * 64);
-    if (a.scheme == KVC_MODE_DELTA)
-        hipLaunchKernelGGL((k_compress_p2048<false, WAVES, PPW>), grid, block, 0, s, a);
-    else
-        hipLaunchKernelGGL((k_compress_p2048<true, WAVES, PPW>), grid, block, 0, s, a);
+    hipLaunchKernelGGL((k_compress_p2048<WAVES, PPW>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 

@@ -21,7 +21,7 @@ ST_POOL_FULL, ST_CORRUPT, ST_BAD_INDEX = 1, 2, 4
 DESC_DTYPE = np.dtype([("off", "<u8"), ("scale", "<f4"), ("n16", "<u2"), ("mode", "u1"), ("rsvd", "u1")])
 
 EXPORTS = ("kvc_create", "kvc_destroy", "kvc_set_scheme", "kvc_bind_pool", "kvc_reset_pool", "kvc_compress_blocks",
-           "kvc_decompress_blocks", "kvc_gather_decompress", "kvc_stats", "kvc_copy_bytes", "kvc_strerror")
+           "kvc_compress_blocks_mixed", "kvc_decompress_blocks", "kvc_gather_decompress", "kvc_stats", "kvc_copy_bytes", "kvc_strerror")
 
 
 class Config(C.Structure):
@@ -69,6 +69,8 @@ def load():
     L.kvc_reset_pool.argtypes = [vp, vp]
     L.kvc_compress_blocks.restype = C.c_int
     L.kvc_compress_blocks.argtypes = [vp, vp, C.c_int64, i32p, i32p, C.c_int32, vp]
+    L.kvc_compress_blocks_mixed.restype = C.c_int
+    L.kvc_compress_blocks_mixed.argtypes = [vp, vp, C.c_int64, i32p, i32p, vp, C.c_int32, vp]
     L.kvc_decompress_blocks.restype = C.c_int
     L.kvc_decompress_blocks.argtypes = [vp, vp, C.c_int64, i32p, i32p, C.c_int32, vp]
     L.kvc_gather_decompress.restype = C.c_int
@@ -176,13 +178,22 @@ class Codec:
         assert t.numel() % self.block_elems == 0
         return t.numel() // self.block_elems
 
-    def compress_blocks(self, cache, n: int | None = None, src_ids=None, pool_ids=None, stream=None):
+    def compress_blocks(self, cache, n: int | None = None, src_ids=None, pool_ids=None, block_scheme=None, stream=None):
+        """block_scheme: optional uint8 CUDA tensor, requested mode per block of the call."""
+        import torch
+
         nb = self._blocks_of(cache)
         src_ids, pool_ids = _ids(src_ids), _ids(pool_ids)
         if n is None:
             n = src_ids.numel() if src_ids is not None else (pool_ids.numel() if pool_ids is not None else nb)
-        _check(self._L.kvc_compress_blocks(self._ctx, cache.data_ptr(), nb, _ptr(src_ids), _ptr(pool_ids), int(n),
-                                           _stream(stream)), "kvc_compress_blocks")
+        if block_scheme is None:
+            _check(self._L.kvc_compress_blocks(self._ctx, cache.data_ptr(), nb, _ptr(src_ids), _ptr(pool_ids), int(n),
+                                               _stream(stream)), "kvc_compress_blocks")
+        else:
+            assert block_scheme.is_cuda and block_scheme.dtype == torch.uint8 and block_scheme.numel() >= n
+            _check(self._L.kvc_compress_blocks_mixed(self._ctx, cache.data_ptr(), nb, _ptr(src_ids), _ptr(pool_ids),
+                                                     block_scheme.data_ptr(), int(n), _stream(stream)),
+                   "kvc_compress_blocks_mixed")
 
     def decompress_blocks(self, out, n: int | None = None, pool_ids=None, dst_ids=None, stream=None):
         nb = self._blocks_of(out)

@@ -167,3 +167,23 @@ def gather_layer_torch(shape: KVShape, pat: GatherPattern, layer: int, device):
         if tail:
             x[int(pat.block_table[s, pat.n_blocks[s] - 1]), :, :, tail:, :] = 0
     return x
+
+
+def ar1_pages_torch(n_pages: int, device, rho: float = 0.95, outlier_channel: int = 77, d: int = 128, N: int = 16,
+                    seed: int = 0):
+    """Pages whose channels are correlated along the channel index (an AR(1) process with coefficient
+    rho, unit variance) plus one x10 channel: float16 [n_pages][N][d].  Stands in for the "spatial
+    correlation in attention heads" that Section 3.1 (v) says delta coding exploits; the LLaMA-shaped
+    generator above has none."""
+    import torch
+
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed * 7919 + 17)
+    z = torch.randn((n_pages, N, d), generator=gen, device=device, dtype=torch.float32)
+    y = torch.empty_like(z)
+    y[..., 0] = z[..., 0]
+    c = (1.0 - rho * rho) ** 0.5
+    for i in range(1, d):
+        y[..., i] = rho * y[..., i - 1] + c * z[..., i]
+    y[..., outlier_channel] *= 10.0
+    return y.to(torch.float16)

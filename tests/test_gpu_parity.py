@@ -307,3 +307,34 @@ def test_host_side_argument_errors():
     assert e.value.code == kvc.ERR_ARG
     c.compress_blocks(x, n=0)
     assert c.stats()["pages_invalid"] == 4
+
+
+def test_per_block_scheme_selection():
+    """kvc_compress_blocks_mixed: the requested mode is a per-block argument (layer-wise selection)."""
+    rng = np.random.default_rng(44)
+    N, d, ppb, nb = 16, 128, 4, 40
+    x = (rng.standard_normal((nb, ppb, N, d)) * np.exp(0.7 * rng.standard_normal(d))).astype(np.float16)
+    schemes = rng.integers(0, 4, nb).astype(np.uint8)
+    schemes[:4] = [0, 1, 2, 3]
+    xt = torch.from_numpy(x).to(DEV)
+    c = make_codec(N, d, ppb, 3, nb, pool_bytes=nb * ppb * N * d * 2 + 64)
+    c.compress_blocks(xt, block_scheme=torch.from_numpy(schemes).to(DEV))
+    st = c.stats()
+    assert st["rc"] == 0
+    desc = c.desc_numpy().reshape(nb, ppb)
+    pool = c.pool.cpu().numpy()
+    for b in range(nb):
+        for pg in range(ppb):
+            dd, pl = o.encode_page(x[b, pg], N, d, int(schemes[b]))
+            g = desc[b, pg]
+            assert (g["mode"], g["n16"]) == (dd["mode"], dd["n16"]) and g["scale"] == dd["scale"], (b, pg, schemes[b])
+            assert pool[int(g["off"]):int(g["off"]) + 16 * int(g["n16"])].tobytes() == pl
+    check_pool_invariants(desc.ravel(), st["pool_bytes_used"], pool.size)
+    out = torch.empty_like(xt)
+    c.decompress_blocks(out)
+    got = out.cpu().numpy().view(np.uint16)
+    for b in range(nb):
+        for pg in range(ppb):
+            dd, pl = o.encode_page(x[b, pg], N, d, int(schemes[b]))
+            assert np.array_equal(got[b, pg].ravel(), o.decode_page(pl, dd, N, d)[1])
+    assert (got[schemes == 0] == x.view(np.uint16)[schemes == 0]).all()  # RAW blocks come back bit-exact

@@ -131,6 +131,29 @@ int kvc_gather_decompress(kvc_ctx* ctx, void* d_out, const int32_t* d_block_tabl
                           const int32_t* d_pred, int32_t n_seq, int32_t k, int32_t n_layers,
                           int64_t pool_blocks_per_layer, void* stream);
 
+/* Speculative prefetch of Algorithm 1 into a double-buffered L2 prefetch buffer (Section 3.3.1), for
+ * layers [layer_begin, layer_end) of one decode step; the token predictor is outside (d_pred is given).
+ *   d_l2    FP16 [2][n_layers*n_seq*k][ppb][N][d]: two halves; this call fills half `fill_half`, the
+ *           other half is what the previous step filled (and what attention may be reading).
+ *   d_tags  int32 [2][n_layers*n_seq*k]: pool block held by every slot, -1 = empty (kvc_prefetch_reset).
+ *   d_fetch int32 [n_layers*n_seq*k], out: pool block decoded into slot (l,s,j) by this call, or -1.
+ *   d_loc   int32 [n_layers*n_seq*k], out: where the consumer finds predicted block (l,s,j):
+ *           half*n_slots + slot (>= 0), -2 = resident in the GPU-local cache (logical block >=
+ *           d_l1_first_block[s]; pass NULL for no L1), -1 = no block (pred < 0, table entry < 0, or an
+ *           index out of range, which also sets KVC_ST_BAD_INDEX).
+ * For every (layer, sequence) the k predictions are taken in order: translate through the block
+ * table; if the pool block is in L1, in any slot of the other half, in a slot of this half already
+ * settled in this step, or already in its own slot j, nothing is fetched (the residency test
+ * "A_phys not in L1 u L2"); otherwise slot j of this half is claimed and the block decoded into it.
+ * Stale slots are never cleared, only overwritten (lazy invalidation, Section 3.4.3).
+ * Calls for disjoint layer ranges may run on different streams (layer l+1, l+2 prefetch while layer l
+ * computes, Section 3.4.4); calls for the same layers must be ordered. */
+int kvc_prefetch_reset(kvc_ctx* ctx, int32_t* d_tags, int32_t n_seq, int32_t k, int32_t n_layers, void* stream);
+int kvc_prefetch_layers(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fetch, int32_t* d_loc,
+                        const int32_t* d_block_table, int32_t max_blocks, const int32_t* d_pred,
+                        const int32_t* d_l1_first_block, int32_t n_seq, int32_t k, int32_t n_layers, int32_t layer_begin,
+                        int32_t layer_end, int64_t pool_blocks_per_layer, int32_t fill_half, void* stream);
+
 /* Reduce the descriptor table and read the device state.  The only call that synchronises
  * (on `stream`).  Returns KVC_ERR_POOL_FULL / KVC_ERR_CORRUPT if the matching status bit is set
  * (out is filled either way), else 0. */

@@ -1,0 +1,66 @@
+"""Plain model of the speculative prefetch step (Algorithm 1 of the paper, without the token
+predictor) over a double-buffered L2 prefetch buffer.  TEST INFRASTRUCTURE, like the rest of oracle/.
+
+Algorithm 1, per request s and layer l, for i = 1..k:
+    A_virt = (s, l, predicted block i);  A_phys = TranslateAddress(A_virt)        -> block table lookup
+    if A_phys not in L1 u L2:  IssueDMA(A_phys, L2[i])                             -> decode into slot i
+The paper leaves "in L2" open for a double-buffered L2 (Section 3.3.1).  Reading: a block is in L2
+if it sits in any slot of the half filled by the previous step, in a slot of the half being filled
+that this step has already passed (it cannot be overwritten any more), or already in slot i itself.
+Slots are never cleared, only overwritten (lazy invalidation, Section 3.4.3)."""
+from __future__ import annotations
+
+import numpy as np
+
+NO_BLOCK, IN_L1 = -1, -2
+
+
+def prefetch_step(tags: np.ndarray, fill: int, table: np.ndarray, pred: np.ndarray, l1_first, n_layers: int,
+                  pool_blocks_per_layer: int, layer_begin: int = 0, layer_end: int | None = None):
+    """tags: int32 [2][n_layers][n_seq][k], updated in place.  Returns (fetch, loc), each int32
+    [n_layers][n_seq][k]; entries of layers outside [layer_begin, layer_end) are left at -1 / -1."""
+    n_seq, k = pred.shape
+    max_blocks = table.shape[1]
+    n_slots = n_layers * n_seq * k
+    layer_end = n_layers if layer_end is None else layer_end
+    fetch = np.full((n_layers, n_seq, k), -1, np.int32)
+    loc = np.full((n_layers, n_seq, k), -1, np.int32)
+    bad_index = False
+    other = 1 - fill
+    for l in range(layer_begin, layer_end):
+        for s in range(n_seq):
+            base = (l * n_seq + s) * k
+            for j in range(k):
+                lb = int(pred[s, j])
+                if lb < 0:
+                    continue
+                if lb >= max_blocks:
+                    bad_index = True
+                    continue
+                if l1_first is not None and lb >= int(l1_first[s]):
+                    loc[l, s, j] = IN_L1
+                    continue
+                e = int(table[s, lb])
+                if e < 0:
+                    continue
+                if e >= pool_blocks_per_layer:
+                    bad_index = True
+                    continue
+                phys = l * pool_blocks_per_layer + e
+                where = None
+                for j2 in range(k):  # the half the previous step filled
+                    if tags[other, l, s, j2] == phys:
+                        where = other * n_slots + base + j2
+                        break
+                if where is None:
+                    for j2 in range(j):  # slots of this half this step is done with
+                        if tags[fill, l, s, j2] == phys:
+                            where = fill * n_slots + base + j2
+                            break
+                if where is None:
+                    where = fill * n_slots + base + j
+                    if tags[fill, l, s, j] != phys:  # not in L1 u L2: issue the transfer into L2[j]
+                        tags[fill, l, s, j] = phys
+                        fetch[l, s, j] = phys
+                loc[l, s, j] = where
+    return fetch, loc, bad_index

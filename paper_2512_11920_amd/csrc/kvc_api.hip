@@ -195,6 +195,61 @@ int kvc_gather_decompress(kvc_ctx* ctx, void* d_out, const int32_t* d_block_tabl
     return hip_ok(kvc::launch_decompress(a, static_cast<hipStream_t>(stream))) ? KVC_OK : KVC_ERR_HIP;
 }
 
+int kvc_prefetch_reset(kvc_ctx* ctx, int32_t* d_tags, int32_t n_seq, int32_t k, int32_t n_layers, void* stream) {
+    if (!ctx || !d_tags || n_seq < 0 || k < 0 || n_layers < 0) return KVC_ERR_ARG;
+    return hip_ok(kvc::launch_fill_i32(d_tags, -1, 2ull * (uint64_t)n_layers * (uint64_t)n_seq * (uint64_t)k,
+                                       static_cast<hipStream_t>(stream)))
+               ? KVC_OK
+               : KVC_ERR_HIP;
+}
+
+int kvc_prefetch_layers(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fetch, int32_t* d_loc,
+                        const int32_t* d_block_table, int32_t max_blocks, const int32_t* d_pred,
+                        const int32_t* d_l1_first_block, int32_t n_seq, int32_t k, int32_t n_layers, int32_t layer_begin,
+                        int32_t layer_end, int64_t pool_blocks_per_layer, int32_t fill_half, void* stream) {
+    if (!ctx || n_seq < 0 || k < 0 || n_layers < 0 || max_blocks < 0 || pool_blocks_per_layer < 0) return KVC_ERR_ARG;
+    if (layer_begin < 0 || layer_end < layer_begin || layer_end > n_layers || (fill_half != 0 && fill_half != 1))
+        return KVC_ERR_ARG;
+    if (!ctx->pool) return KVC_ERR_NOT_BOUND;
+    const int64_t n_slots = (int64_t)n_layers * n_seq * k;
+    const int64_t n_now = (int64_t)(layer_end - layer_begin) * n_seq * k;
+    if (n_now == 0) return KVC_OK;
+    if (!d_l2 || !d_tags || !d_fetch || !d_loc || !d_block_table || !d_pred || max_blocks == 0 ||
+        (reinterpret_cast<uintptr_t>(d_l2) & 15u))
+        return KVC_ERR_ARG;
+    if (2 * n_slots > INT32_MAX || n_now > INT32_MAX) return KVC_ERR_ARG;
+    if ((uint64_t)n_layers * (uint64_t)pool_blocks_per_layer * (uint64_t)ctx->g.ppb > ctx->n_desc ||
+        (uint64_t)n_layers * (uint64_t)pool_blocks_per_layer > (uint64_t)INT32_MAX)
+        return KVC_ERR_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    kvc::PlanArgs p;
+    p.block_table = d_block_table;
+    p.pred = d_pred;
+    p.l1_first = d_l1_first_block;
+    p.max_blocks = max_blocks;
+    p.n_seq = n_seq;
+    p.k = k;
+    p.layer_begin = layer_begin;
+    p.layer_end = layer_end;
+    p.n_layers = n_layers;
+    p.fill_half = fill_half;
+    p.pool_blocks_per_layer = pool_blocks_per_layer;
+    p.tags = d_tags;
+    p.fetch = d_fetch;
+    p.loc = d_loc;
+    p.st = ctx->st;
+    if (!hip_ok(kvc::launch_prefetch_plan(p, s))) return KVC_ERR_HIP;
+    // decode the listed pool blocks into their slots of the half being filled
+    const int64_t first = (int64_t)layer_begin * n_seq * k;
+    kvc::DecodeArgs a;
+    fill_decode_common(ctx, a);
+    a.out = static_cast<uint16_t*>(d_l2) + ((size_t)fill_half * (size_t)n_slots + (size_t)first) * (size_t)ctx->g.ppb * (size_t)ctx->g.E;
+    a.n_out_blocks = n_now;
+    a.pool_ids = d_fetch + first;
+    a.n_pages = n_now * ctx->g.ppb;
+    return hip_ok(kvc::launch_decompress(a, s)) ? KVC_OK : KVC_ERR_HIP;
+}
+
 int kvc_stats(kvc_ctx* ctx, kvc_stats_t* out, void* stream) {
     if (!ctx || !out) return KVC_ERR_ARG;
     if (!ctx->pool) return KVC_ERR_NOT_BOUND;

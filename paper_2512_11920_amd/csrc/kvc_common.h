@@ -54,6 +54,21 @@ struct DecodeArgs {
     int64_t pool_blocks_per_layer;
 };
 
+// Arguments of the prefetch planner (Algorithm 1: translate, residency filter, slot assignment).
+struct PlanArgs {
+    const int32_t* block_table;  // [n_seq][max_blocks]
+    const int32_t* pred;         // [n_seq][k]
+    const int32_t* l1_first;     // [n_seq] or null: logical blocks >= l1_first[s] are GPU-local (L1)
+    int32_t max_blocks, n_seq, k, layer_begin, layer_end, n_layers, fill_half;
+    int64_t pool_blocks_per_layer;
+    int32_t* tags;   // [2][n_layers*n_seq*k]
+    int32_t* fetch;  // [n_layers*n_seq*k]
+    int32_t* loc;    // [n_layers*n_seq*k]
+    DevState* st;
+};
+
+hipError_t launch_prefetch_plan(const PlanArgs& a, hipStream_t s);
+hipError_t launch_fill_i32(int32_t* p, int32_t v, uint64_t n, hipStream_t s);
 hipError_t launch_compress(const EncodeArgs& a, hipStream_t s);
 hipError_t launch_decompress(const DecodeArgs& a, hipStream_t s);
 hipError_t launch_reset(DevState* st, kvc_desc* desc, uint64_t n_desc, hipStream_t s);

@@ -545,6 +545,61 @@ __global__ void k_copy(uint4* __restrict__ dst, const uint4* __restrict__ src, u
         dst[k] = src[k];
 }
 
+// Prefetch planner, Algorithm 1 of the paper without the token predictor: one thread per
+// (layer, sequence) walks the k predicted logical blocks in order -- translate through the block
+// table (TranslateAddress), skip what is already in L1 or in either half of the L2 prefetch buffer
+// (the residency test), otherwise claim slot j of the half being filled and list the pool block
+// for the decode launch (IssueDMA).
+__global__ void k_prefetch_plan(PlanArgs a) {
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t n_ls = (int64_t)(a.layer_end - a.layer_begin) * a.n_seq;
+    if (idx >= n_ls) return;
+    const int32_t l = a.layer_begin + (int32_t)(idx / a.n_seq);
+    const int32_t sq = (int32_t)(idx % a.n_seq);
+    const int64_t n_slots = (int64_t)a.n_layers * a.n_seq * a.k;
+    const int64_t base = ((int64_t)l * a.n_seq + sq) * a.k;
+    int32_t* tags_fill = a.tags + (int64_t)a.fill_half * n_slots + base;
+    const int32_t* tags_other = a.tags + (int64_t)(1 - a.fill_half) * n_slots + base;
+    bool bad = false;
+    for (int j = 0; j < a.k; ++j) {
+        int64_t where = -1;
+        int32_t fetch = -1;
+        const int32_t lb = a.pred[(int64_t)sq * a.k + j];
+        if (lb >= a.max_blocks) {
+            bad = true;
+        } else if (lb >= 0) {
+            if (a.l1_first && lb >= a.l1_first[sq]) {
+                where = -2;  // held in the GPU-local cache: nothing to fetch
+            } else {
+                const int32_t e = a.block_table[(int64_t)sq * a.max_blocks + lb];
+                if (e >= a.pool_blocks_per_layer) {
+                    bad = true;
+                } else if (e >= 0) {
+                    const int32_t pb = (int32_t)((int64_t)l * a.pool_blocks_per_layer + e);
+                    for (int j2 = 0; j2 < a.k && where < 0; ++j2)
+                        if (tags_other[j2] == pb) where = (int64_t)(1 - a.fill_half) * n_slots + base + j2;
+                    for (int j2 = 0; j2 < j && where < 0; ++j2)  // slots already settled in this step
+                        if (tags_fill[j2] == pb) where = (int64_t)a.fill_half * n_slots + base + j2;
+                    if (where < 0) {
+                        where = (int64_t)a.fill_half * n_slots + base + j;
+                        if (tags_fill[j] != pb) {
+                            tags_fill[j] = pb;
+                            fetch = pb;
+                        }
+                    }
+                }
+            }
+        }
+        a.fetch[base + j] = fetch;
+        a.loc[base + j] = (int32_t)where;
+    }
+    if (bad) atomicOr(&a.st->status, KVC_ST_BAD_INDEX);
+}
+
+__global__ void k_fill_i32(int32_t* p, int32_t v, uint64_t n) {
+    for (uint64_t k = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += (uint64_t)gridDim.x * blockDim.x) p[k] = v;
+}
+
 // ---------------------------------------------------------------------------------- launchers
 
 static inline unsigned grid_for(int64_t n_pages, int ppw) {
@@ -577,6 +632,20 @@ hipError_t launch_decompress(const DecodeArgs& a, hipStream_t s) {
         hipLaunchKernelGGL((k_decompress<4, PPW>), grid, block, 0, s, a);
     else
         hipLaunchKernelGGL((k_decompress<8, PPW>), grid, block, 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_prefetch_plan(const PlanArgs& a, hipStream_t s) {
+    const int64_t n = (int64_t)(a.layer_end - a.layer_begin) * a.n_seq;
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_prefetch_plan, dim3((unsigned)((n + 63) / 64)), dim3(64), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_i32(int32_t* p, int32_t v, uint64_t n, hipStream_t s) {
+    if (n == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)std::min<uint64_t>((n + 255) / 256, 4096);
+    hipLaunchKernelGGL(k_fill_i32, dim3(blocks), dim3(256), 0, s, p, v, n);
     return hipGetLastError();
 }
 

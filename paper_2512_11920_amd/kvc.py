@@ -21,7 +21,7 @@ ST_POOL_FULL, ST_CORRUPT, ST_BAD_INDEX = 1, 2, 4
 DESC_DTYPE = np.dtype([("off", "<u8"), ("scale", "<f4"), ("n16", "<u2"), ("mode", "u1"), ("rsvd", "u1")])
 
 EXPORTS = ("kvc_create", "kvc_destroy", "kvc_set_scheme", "kvc_bind_pool", "kvc_reset_pool", "kvc_compress_blocks",
-           "kvc_compress_blocks_mixed", "kvc_decompress_blocks", "kvc_gather_decompress", "kvc_stats", "kvc_copy_bytes", "kvc_strerror")
+           "kvc_compress_blocks_mixed", "kvc_decompress_blocks", "kvc_gather_decompress", "kvc_prefetch_reset", "kvc_prefetch_layers", "kvc_stats", "kvc_copy_bytes", "kvc_strerror")
 
 
 class Config(C.Structure):
@@ -75,6 +75,11 @@ def load():
     L.kvc_decompress_blocks.argtypes = [vp, vp, C.c_int64, i32p, i32p, C.c_int32, vp]
     L.kvc_gather_decompress.restype = C.c_int
     L.kvc_gather_decompress.argtypes = [vp, vp, i32p, C.c_int32, i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int64, vp]
+    L.kvc_prefetch_reset.restype = C.c_int
+    L.kvc_prefetch_reset.argtypes = [vp, vp, C.c_int32, C.c_int32, C.c_int32, vp]
+    L.kvc_prefetch_layers.restype = C.c_int
+    L.kvc_prefetch_layers.argtypes = [vp, vp, vp, vp, vp, i32p, C.c_int32, i32p, i32p, C.c_int32, C.c_int32, C.c_int32,
+                                      C.c_int32, C.c_int32, C.c_int64, C.c_int32, vp]
     L.kvc_stats.restype = C.c_int
     L.kvc_stats.argtypes = [vp, C.POINTER(Stats), vp]
     L.kvc_copy_bytes.restype = C.c_int
@@ -212,6 +217,26 @@ class Codec:
         _check(self._L.kvc_gather_decompress(self._ctx, out.data_ptr(), block_table.data_ptr(), max_blocks,
                                              pred.data_ptr(), n_seq, k, n_layers, int(pool_blocks_per_layer),
                                              _stream(stream)), "kvc_gather_decompress")
+
+    def prefetch_reset(self, tags, n_seq: int, k: int, n_layers: int, stream=None):
+        assert _ids(tags).numel() == 2 * n_layers * n_seq * k
+        _check(self._L.kvc_prefetch_reset(self._ctx, tags.data_ptr(), n_seq, k, n_layers, _stream(stream)),
+               "kvc_prefetch_reset")
+
+    def prefetch_layers(self, l2, tags, fetch, loc, block_table, pred, n_layers: int, pool_blocks_per_layer: int,
+                        fill_half: int, layer_begin: int = 0, layer_end: int | None = None, l1_first=None, stream=None):
+        """l2: float16 [2][n_layers*n_seq*k][ppb][N][d]; tags int32 [2][n_slots]; fetch, loc int32 [n_slots]."""
+        block_table, pred = _ids(block_table), _ids(pred)
+        n_seq, max_blocks = block_table.shape
+        k = pred.shape[1]
+        n_slots = n_layers * n_seq * k
+        assert self._blocks_of(l2) == 2 * n_slots
+        assert _ids(tags).numel() == 2 * n_slots and _ids(fetch).numel() == n_slots and _ids(loc).numel() == n_slots
+        layer_end = n_layers if layer_end is None else layer_end
+        _check(self._L.kvc_prefetch_layers(self._ctx, l2.data_ptr(), tags.data_ptr(), fetch.data_ptr(), loc.data_ptr(),
+                                           block_table.data_ptr(), max_blocks, pred.data_ptr(), _ptr(_ids(l1_first)),
+                                           n_seq, k, n_layers, layer_begin, layer_end, int(pool_blocks_per_layer),
+                                           fill_half, _stream(stream)), "kvc_prefetch_layers")
 
     def stats(self, stream=None, check: bool = False) -> dict:
         st = Stats()

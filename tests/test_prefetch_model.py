@@ -1,0 +1,99 @@
+"""Pins for the prefetch model (oracle/prefetch_model.py): the bookkeeping of Algorithm 1 is checked by
+carrying the real contents of every L2 slot alongside the tags -- only an issued transfer changes a slot --
+and asserting what Algorithm 1 promises: every predicted block can be read where `loc` says, and a block
+already in L1 or L2 is never transferred again."""
+import numpy as np
+import pytest
+
+from oracle import prefetch_model as pm
+
+
+def _setup(rng, n_layers=3, n_seq=4, k=6, max_blocks=9, pbpl=40):
+    table = np.full((n_seq, max_blocks), -1, np.int32)
+    perm = rng.permutation(pbpl)
+    o = 0
+    nb = rng.integers(3, max_blocks + 1, n_seq)
+    for s in range(n_seq):
+        table[s, : nb[s]] = perm[o:o + nb[s]]
+        o += nb[s]
+    return table, nb
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_consumer_always_finds_the_predicted_block_and_nothing_resident_is_refetched(seed):
+    rng = np.random.default_rng(seed)
+    n_layers, n_seq, k, pbpl = 3, 4, 6, 40
+    table, nb = _setup(rng, n_layers, n_seq, k, 9, pbpl)
+    n_slots = n_layers * n_seq * k
+    tags = np.full((2, n_layers, n_seq, k), -1, np.int32)
+    content = np.full(2 * n_slots, -1, np.int64)  # what really sits in each slot
+    l1_first = (nb - 1).astype(np.int32) if seed % 2 else None
+    total_fetch = total_valid = 0
+    for step in range(40):
+        fill = step % 2
+        pred = (rng.random((n_seq, k)) * nb[:, None]).astype(np.int32)
+        pred[rng.random((n_seq, k)) < 0.1] = -1  # some predictions missing
+        before = tags.copy()
+        fetch, loc, bad = pm.prefetch_step(tags, fill, table, pred, l1_first, n_layers, pbpl)
+        assert not bad
+        # transfers happen, into slot j of the half being filled
+        for l in range(n_layers):
+            for s in range(n_seq):
+                base = (l * n_seq + s) * k
+                resident_other = set(before[1 - fill, l, s].tolist())
+                got = [int(f) for f in fetch[l, s] if f >= 0]
+                assert len(got) == len(set(got)), "a block was transferred twice in one step"
+                assert not (set(got) & resident_other), "a block resident in the other half was transferred"
+                for j in range(k):
+                    if fetch[l, s, j] >= 0:
+                        assert before[fill, l, s, j] != fetch[l, s, j], "transfer into a slot that already held the block"
+                        content[fill * n_slots + base + j] = fetch[l, s, j]
+        # only issued transfers changed tags, and tags describe contents
+        assert np.array_equal(tags.reshape(-1), content.astype(np.int32))
+        assert np.array_equal(tags[1 - fill], before[1 - fill])
+        # the consumer's view
+        for l in range(n_layers):
+            for s in range(n_seq):
+                for j in range(k):
+                    lb = pred[s, j]
+                    if lb < 0:
+                        assert loc[l, s, j] == pm.NO_BLOCK and fetch[l, s, j] == -1
+                    elif l1_first is not None and lb >= l1_first[s]:
+                        assert loc[l, s, j] == pm.IN_L1 and fetch[l, s, j] == -1
+                    else:
+                        total_valid += 1
+                        assert content[loc[l, s, j]] == l * pbpl + table[s, lb]
+        total_fetch += int((fetch >= 0).sum())
+    assert 0 < total_fetch < total_valid  # the residency test does save transfers on this pattern
+
+
+def test_same_predictions_next_step_transfer_nothing():
+    rng = np.random.default_rng(9)
+    table, nb = _setup(rng)
+    tags = np.full((2, 3, 4, 6), -1, np.int32)
+    pred = (rng.random((4, 6)) * nb[:, None]).astype(np.int32)
+    f0, _, _ = pm.prefetch_step(tags, 0, table, pred, None, 3, 40)
+    assert (f0 >= 0).sum() > 0
+    f1, loc1, _ = pm.prefetch_step(tags, 1, table, pred, None, 3, 40)
+    assert (f1 >= 0).sum() == 0 and (loc1 >= 0).all() and (loc1 < 3 * 4 * 6).all()  # all found in half 0
+    f2, _, _ = pm.prefetch_step(tags, 0, table, pred, None, 3, 40)
+    assert (f2 >= 0).sum() == 0
+
+
+def test_layer_ranges_compose_and_bad_indices_are_flagged():
+    rng = np.random.default_rng(10)
+    table, nb = _setup(rng)
+    pred = (rng.random((4, 6)) * nb[:, None]).astype(np.int32)
+    t_all = np.full((2, 3, 4, 6), -1, np.int32)
+    f_all, l_all, _ = pm.prefetch_step(t_all, 0, table, pred, None, 3, 40)
+    t_parts = np.full((2, 3, 4, 6), -1, np.int32)
+    f_parts = np.full((3, 4, 6), -1, np.int32)
+    l_parts = np.full((3, 4, 6), -1, np.int32)
+    for lo, hi in ((2, 3), (0, 1), (1, 2)):
+        f, l, _ = pm.prefetch_step(t_parts, 0, table, pred, None, 3, 40, lo, hi)
+        f_parts[lo:hi], l_parts[lo:hi] = f[lo:hi], l[lo:hi]
+    assert np.array_equal(t_all, t_parts) and np.array_equal(f_all, f_parts) and np.array_equal(l_all, l_parts)
+    pred2 = pred.copy()
+    pred2[0, 0] = table.shape[1] + 5
+    f, l, bad = pm.prefetch_step(np.full((2, 3, 4, 6), -1, np.int32), 0, table, pred2, None, 3, 40)
+    assert bad and (l[:, 0, 0] == -1).all() and (f[:, 0, 0] == -1).all()

@@ -124,6 +124,8 @@ def main():
         return bench_decode_gather(args)
     if args.workload == "prefetch_pipeline":
         return bench_prefetch_pipeline(args)
+    if args.workload == "host_pool":
+        return bench_host_pool(args)
     shape = synth.CONFIGS[args.workload]
     if args.layers:
         import dataclasses
@@ -466,6 +468,52 @@ def bench_prefetch_pipeline(args):
                                              f"U[512,8192], k=8, per-layer prefetch two layers ahead of the layer's compute "
                                              f"stand-in ({work_bytes >> 20} MiB copy, or 4096^3 bf16 GEMM)"},
                       "patterns": out}), flush=True)
+
+
+def bench_host_pool(args):
+    """Slow-tier emulation: the compressed pool in pinned host memory, reached over the host link, as the
+    paper's pool sits behind a 64 GB/s CXL link (Sections 3.2, 4.4.2).  Per scheme: uncompressed GB/s
+    the codec sustains and the bytes that actually cross the link."""
+    import torch
+
+    from paper_2512_11920_amd import kvc, synth
+
+    dev = "cuda:0"
+    N, d, ppb = 16, 128, 8
+    shape = synth.KVShape("70b_gqa_slice", args.layers or 4, 8, 128, 4096, 16)
+    blocks = synth.cache_torch(shape, dev).view(-1, ppb, N, d)
+    out = torch.empty_like(blocks)
+    unc = blocks.numel() * 2
+    rows = []
+    for scheme, label in ((0, "None (FP16)"), (1, "INT8 only"), (3, "INT8 + Delta + RLE")):
+        codec = kvc.Codec(N, d, ppb, scheme)
+        codec.alloc_pool(blocks.shape[0], unc + 4096, dev, host_pool=True)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        tc = td = 0.0
+        for rep in range(args.warmup + args.steps):
+            codec.reset_pool()
+            ev[0].record()
+            codec.compress_blocks(blocks)
+            ev[1].record()
+            codec.decompress_blocks(out)
+            ev[2].record()
+            torch.cuda.synchronize()
+            if rep >= args.warmup:
+                tc += ev[0].elapsed_time(ev[1])
+                td += ev[1].elapsed_time(ev[2])
+        st = codec.stats()
+        assert st["rc"] == 0
+        tc, td = tc / args.steps, td / args.steps
+        rows.append({"scheme": label, "ratio": round(codec.ratio(), 4), "compress_ms": round(tc, 3), "decompress_ms": round(td, 3),
+                     "compress_GBps_unc": round(unc / tc / 1e6, 1), "decompress_GBps_unc": round(unc / td / 1e6, 1),
+                     "link_GBps_write": round(st["payload_bytes"] / tc / 1e6, 1),
+                     "link_GBps_read": round(st["payload_bytes"] / td / 1e6, 1)})
+        log(f"[host_pool] {rows[-1]}")
+        del codec
+    print(json.dumps({"metric": "codec GB/s (uncompressed fp16) with the pool behind the host link", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "data": "synthetic",
+                      "config": {"workload": f"host_pool: {shape.n_layers} layers of the 70B shape, {unc / 1e9:.2f} GB fp16, "
+                                             "compressed pool in pinned host memory"}, "rows": rows}), flush=True)
 
 
 def bench_ablation(args):

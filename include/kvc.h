@@ -97,7 +97,10 @@ void kvc_destroy(kvc_ctx* ctx);
 int kvc_set_scheme(kvc_ctx* ctx, int32_t scheme);
 
 /* Attach the compressed pool (pool_bytes, 16-byte aligned, any multiple of 16) and the descriptor
- * table (n_desc_pages entries; page p of pool block b is entry b*ppb + p).  Both caller-owned. */
+ * table (n_desc_pages entries; page p of pool block b is entry b*ppb + p).  Both caller-owned.
+ * Either may also be pinned, device-mapped host memory (hipHostMalloc): the pool then sits behind
+ * the host link, the closest single-GPU analogue of the paper's remote tier.  Pageable host
+ * pointers are refused with KVC_ERR_ARG. */
 int kvc_bind_pool(kvc_ctx* ctx, void* d_pool, uint64_t pool_bytes, kvc_desc* d_desc, uint64_t n_desc_pages);
 
 /* Cursor = 0, status = 0, every descriptor = INVALID.  Enqueues fill kernels only. */

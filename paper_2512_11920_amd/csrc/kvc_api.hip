@@ -85,6 +85,22 @@ int kvc_bind_pool(kvc_ctx* ctx, void* d_pool, uint64_t pool_bytes, kvc_desc* d_d
     if (!ctx || !d_pool || !d_desc || pool_bytes == 0 || n_desc_pages == 0) return KVC_ERR_ARG;
     if ((reinterpret_cast<uintptr_t>(d_pool) & 15u) || (reinterpret_cast<uintptr_t>(d_desc) & 15u) || (pool_bytes & 15u))
         return KVC_ERR_ARG;
+    // The pool may also live in pinned, device-mapped host memory (a slow-link tier): take the address
+    // the device sees.  Pageable host memory is rejected here rather than faulting in a kernel.
+    hipPointerAttribute_t attr;
+    if (!hip_ok(hipPointerGetAttributes(&attr, d_pool))) return KVC_ERR_ARG;
+    if (attr.type == hipMemoryTypeHost) {
+        if (!attr.devicePointer) return KVC_ERR_ARG;
+        d_pool = attr.devicePointer;
+    } else if (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged) {
+        return KVC_ERR_ARG;
+    }
+    hipPointerAttribute_t dattr;
+    if (!hip_ok(hipPointerGetAttributes(&dattr, d_desc)) || dattr.type == hipMemoryTypeUnregistered) return KVC_ERR_ARG;
+    if (dattr.type == hipMemoryTypeHost) {
+        if (!dattr.devicePointer) return KVC_ERR_ARG;
+        d_desc = static_cast<kvc_desc*>(dattr.devicePointer);
+    }
     ctx->pool = static_cast<uint8_t*>(d_pool);
     ctx->pool_bytes = pool_bytes;
     ctx->desc = d_desc;

@@ -152,17 +152,22 @@ class Codec:
 
     # -- pool
     def bind_pool(self, pool, desc):
-        """pool: uint8 CUDA tensor (multiple of 16 bytes); desc: uint8 CUDA tensor of 16*n_desc_pages bytes."""
-        assert pool.is_cuda and desc.is_cuda and pool.is_contiguous() and desc.is_contiguous()
+        """pool: uint8 tensor, CUDA or pinned host memory (multiple of 16 bytes); desc: uint8 CUDA tensor of
+        16*n_desc_pages bytes."""
+        assert (pool.is_cuda or pool.is_pinned()) and desc.is_cuda and pool.is_contiguous() and desc.is_contiguous()
         assert pool.element_size() == 1 and desc.element_size() == 1 and desc.numel() % 16 == 0
         _check(self._L.kvc_bind_pool(self._ctx, pool.data_ptr(), pool.numel(), desc.data_ptr(), desc.numel() // 16),
                "kvc_bind_pool")
         self.pool, self.desc = pool, desc
 
-    def alloc_pool(self, n_pool_blocks: int, pool_bytes: int, device="cuda:0"):
+    def alloc_pool(self, n_pool_blocks: int, pool_bytes: int, device="cuda:0", host_pool: bool = False):
+        """host_pool: put the payload pool in pinned host memory (reached over the host link)."""
         import torch
 
-        pool = torch.empty(int(pool_bytes) // 16 * 16, dtype=torch.uint8, device=device)
+        if host_pool:
+            pool = torch.empty(int(pool_bytes) // 16 * 16, dtype=torch.uint8, pin_memory=True)
+        else:
+            pool = torch.empty(int(pool_bytes) // 16 * 16, dtype=torch.uint8, device=device)
         desc = torch.empty(int(n_pool_blocks) * self.cfg.pages_per_block * 16, dtype=torch.uint8, device=device)
         self.bind_pool(pool, desc)
         self.reset_pool()

@@ -338,3 +338,27 @@ def test_per_block_scheme_selection():
             dd, pl = o.encode_page(x[b, pg], N, d, int(schemes[b]))
             assert np.array_equal(got[b, pg].ravel(), o.decode_page(pl, dd, N, d)[1])
     assert (got[schemes == 0] == x.view(np.uint16)[schemes == 0]).all()  # RAW blocks come back bit-exact
+
+
+def test_pool_in_pinned_host_memory():
+    """The compressed pool behind the host link (slow-tier emulation): same bytes as the oracle, read
+    straight from the pinned buffer on the CPU; pageable memory is refused."""
+    rng = np.random.default_rng(55)
+    N, d, ppb, nb = 16, 128, 2, 24
+    x = (rng.standard_normal((nb, ppb, N, d)) * np.exp(0.6 * rng.standard_normal(d))).astype(np.float16)
+    xt = torch.from_numpy(x).to(DEV)
+    c = kvc.Codec(N, d, ppb, 3)
+    pool, desc = c.alloc_pool(nb, nb * ppb * N * d + 64, DEV, host_pool=True)
+    assert not pool.is_cuda and pool.is_pinned()
+    c.compress_blocks(xt)
+    out = torch.empty_like(xt)
+    c.decompress_blocks(out)
+    st = c.stats()  # synchronises
+    assert st["rc"] == 0
+    compare_pages_with_oracle(x.view(np.uint16).reshape(-1, N, d), c.desc_numpy(), pool.numpy(), N, d, 3)
+    od, op = o.compress_pages(x.view(np.uint16), N, d, 3)
+    assert np.array_equal(out.cpu().numpy().view(np.uint16).reshape(-1, N, d), o.decompress_pages(op, od, N, d)[0])
+    c2 = kvc.Codec(N, d, ppb, 3)
+    pageable = torch.empty(4096, dtype=torch.uint8)
+    rc = kvc.load().kvc_bind_pool(c2._ctx, pageable.data_ptr(), 4096, desc.data_ptr(), 4)
+    assert rc == kvc.ERR_ARG

@@ -8,8 +8,9 @@
  * (CXL) tier of the paper is a second buffer in the same GPU's HBM.
  *
  * Geometry.  A PAGE is N tokens x d channels of one KV head, FP16, row-major (N*d*2 bytes; 16 x 128
- * gives the paper's 4 KB page).  A BLOCK is `pages_per_block` consecutive pages (all KV heads, or
- * K and V of all heads, of one 16-token block).  A cache buffer is FP16 [n_blocks][ppb][N][d].
+ * gives the paper's 4 KB page).  A BLOCK is `pages_per_block` pages (all KV heads, or K and V of all
+ * heads, of one 16-token block).  A cache buffer is FP16 [n_blocks][ppb][N][d] unless
+ * kvc_set_cache_layout gives other strides.
  *
  * Compressed form of a page = one 16-byte descriptor (kvc_desc) + a payload of n16*16 bytes in
  * the pool.  Payload by mode:
@@ -95,6 +96,15 @@ void kvc_destroy(kvc_ctx* ctx);
 
 /* Change the mode compress requests (0..3); takes effect for later calls. */
 int kvc_set_scheme(kvc_ctx* ctx, int32_t scheme);
+
+/* Layout of the FP16 cache buffers read by compress and written by decompress / gather / prefetch,
+ * in FP16 elements: element (token j, channel i) of page p of block b is at
+ * b*block_stride + p*page_stride + j*row_stride + i.  Default (and all three = 0): contiguous pages,
+ * row_stride = d, page_stride = N*d, block_stride = ppb*N*d.  Example: a [block][token][head][d] cache has
+ * row_stride = H*d, page_stride = d, block_stride = N*H*d.  Strides are multiples of 8 (128-bit
+ * accesses), row_stride >= d.  n_cache_blocks / n_out_blocks then count blocks of block_stride
+ * elements; the caller guarantees the buffer covers the last block's last row. */
+int kvc_set_cache_layout(kvc_ctx* ctx, int64_t block_stride, int64_t page_stride, int64_t row_stride);
 
 /* Attach the compressed pool (pool_bytes, 16-byte aligned, any multiple of 16) and the descriptor
  * table (n_desc_pages entries; page p of pool block b is entry b*ppb + p).  Both caller-owned.

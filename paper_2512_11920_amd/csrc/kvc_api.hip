@@ -52,6 +52,10 @@ int kvc_create(kvc_ctx** out, const kvc_config* cfg) {
     c->g.d = cfg->head_dim;
     c->g.ppb = cfg->pages_per_block;
     c->g.E = cfg->tokens_per_block * cfg->head_dim;
+    c->g.dshift = __builtin_ctz((unsigned)cfg->head_dim);
+    c->g.row_stride = cfg->head_dim;
+    c->g.page_stride = c->g.E;
+    c->g.block_stride = (int64_t)c->g.E * cfg->pages_per_block;
     c->pool = nullptr;
     c->pool_bytes = 0;
     c->desc = nullptr;
@@ -78,6 +82,22 @@ void kvc_destroy(kvc_ctx* ctx) {
 int kvc_set_scheme(kvc_ctx* ctx, int32_t scheme) {
     if (!ctx || scheme < 0 || scheme > 3) return KVC_ERR_ARG;
     ctx->cfg.scheme = scheme;
+    return KVC_OK;
+}
+
+int kvc_set_cache_layout(kvc_ctx* ctx, int64_t block_stride, int64_t page_stride, int64_t row_stride) {
+    if (!ctx) return KVC_ERR_ARG;
+    if (block_stride == 0 && page_stride == 0 && row_stride == 0) {  // back to the contiguous default
+        row_stride = ctx->g.d;
+        page_stride = ctx->g.E;
+        block_stride = (int64_t)ctx->g.E * ctx->g.ppb;
+    }
+    // 128-bit accesses need 8-element granularity; rows may not overlap their own channels
+    if (row_stride < ctx->g.d || page_stride <= 0 || block_stride <= 0) return KVC_ERR_ARG;
+    if ((row_stride & 7) || (page_stride & 7) || (block_stride & 7)) return KVC_ERR_ARG;
+    ctx->g.row_stride = row_stride;
+    ctx->g.page_stride = page_stride;
+    ctx->g.block_stride = block_stride;
     return KVC_OK;
 }
 

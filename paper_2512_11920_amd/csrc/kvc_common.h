@@ -15,8 +15,12 @@ struct DevState {
     unsigned long long stats[8];  // scratch of kvc_stats: pages[0..3], invalid, payload16
 };
 
+// Page geometry and cache layout.  Element (token j, channel i) of page pg of block b sits at
+// b*block_stride + pg*page_stride + j*row_stride + i of the cache buffer (all in FP16 elements).
 struct Geometry {
     int32_t N, d, ppb, E;  // E = N*d elements per page
+    int32_t dshift;        // log2(d)
+    int64_t row_stride, page_stride, block_stride;
 };
 
 struct EncodeArgs {

@@ -77,6 +77,16 @@ __device__ __forceinline__ uint32_t row16_incl_scan_dpp(uint32_t v) {
     return v;
 }
 
+// element offset of a page inside a cache buffer
+__device__ __forceinline__ int64_t page_base(const Geometry& g, int64_t blk, int pg) {
+    return blk * g.block_stride + (int64_t)pg * g.page_stride;
+}
+
+// element offset, relative to the page base, of dense element index e (token e/d, channel e%d)
+__device__ __forceinline__ int64_t elem_off(const Geometry& g, int e) {
+    return (int64_t)(e >> g.dshift) * g.row_stride + (e & (g.d - 1));
+}
+
 struct PageResult {
     uint32_t n16;  // payload size in 16-byte units (0 = page skipped)
     uint32_t mode;
@@ -86,7 +96,7 @@ struct PageResult {
 // Page task of the encoder: which source page, which descriptor.
 struct EncTask {
     long long desc_idx;  // -1: nothing to do
-    long long src_page;
+    long long src_off;   // element offset of the source page in the cache buffer
     int scheme;          // mode requested for this page
 };
 
@@ -117,7 +127,7 @@ __device__ __forceinline__ void task_advance(TaskPos& p, int ppb) {
 __device__ __forceinline__ EncTask resolve_enc_task(const EncodeArgs& a, int64_t t, const TaskPos& pos) {
     EncTask r;
     r.desc_idx = -1;
-    r.src_page = -1;
+    r.src_off = -1;
     r.scheme = a.scheme;
     if (t >= a.n_pages) return r;
     const int ppb = a.g.ppb;
@@ -131,7 +141,7 @@ __device__ __forceinline__ EncTask resolve_enc_task(const EncodeArgs& a, int64_t
         if (lane_id() == 0) atomicOr(&a.st->status, KVC_ST_BAD_INDEX);
         return r;
     }
-    r.src_page = sb * ppb + pg;
+    r.src_off = page_base(a.g, sb, pg);
     r.desc_idx = (long long)d_idx;
     if (a.block_scheme) r.scheme = min((int)a.block_scheme[blk], 3);
     return r;
@@ -180,7 +190,7 @@ __device__ __forceinline__ DecTask resolve_dec_task(const DecodeArgs& a, int64_t
         if (db >= 0 && lane_id() == 0) atomicOr(&a.st->status, KVC_ST_BAD_INDEX);
         return r;
     }
-    r.dst = a.out + ((size_t)db * g.ppb + pg) * (size_t)g.E;
+    r.dst = a.out + page_base(g, db, pg);
     if (!bad_index && pb < 0) return r;  // skip
     r.desc_idx = (uint64_t)pb * (uint64_t)g.ppb + (uint64_t)pg;
     if (bad_index || r.desc_idx >= a.n_desc) {
@@ -192,8 +202,9 @@ __device__ __forceinline__ DecTask resolve_dec_task(const DecodeArgs& a, int64_t
     return r;
 }
 
-__device__ __forceinline__ void zero_page(uint16_t* dst, int E) {
-    for (int o = lane_id(); o < (E >> 3); o += 64) reinterpret_cast<uint4*>(dst)[o] = make_uint4(0, 0, 0, 0);
+__device__ __forceinline__ void zero_page(uint16_t* dst, const Geometry& g) {
+    for (int o = lane_id(); o < (g.E >> 3); o += 64)
+        *reinterpret_cast<uint4*>(dst + elem_off(g, o * 8)) = make_uint4(0, 0, 0, 0);
 }
 
 // Per-workgroup bookkeeping of the encoder: results of the pages staged in LDS.
@@ -204,7 +215,7 @@ struct EncBook {
     float scale[SLOTS];
     unsigned long long off16[SLOTS];
     long long desc[SLOTS];
-    long long srcpage[SLOTS];
+    long long srcoff[SLOTS];
 };
 
 // One thread reserves a contiguous pool span for all staged pages of the workgroup with a single
@@ -239,9 +250,9 @@ __device__ __forceinline__ void emit_page(const EncodeArgs& a, const EncBook<SLO
     const unsigned long long off16 = b.off16[slot];
     if (mode != KVC_MODE_INVALID) {
         uint4* dst = reinterpret_cast<uint4*>(a.pool) + off16;
-        if (mode == KVC_MODE_RAW) {
-            const uint4* srcp = reinterpret_cast<const uint4*>(a.cache + (size_t)b.srcpage[slot] * (size_t)a.g.E);
-            for (uint32_t o = lane; o < n16; o += 64) dst[o] = srcp[o];
+        if (mode == KVC_MODE_RAW) {  // the payload is the dense page
+            const uint16_t* srcp = a.cache + b.srcoff[slot];
+            for (uint32_t o = lane; o < n16; o += 64) dst[o] = *reinterpret_cast<const uint4*>(srcp + elem_off(a.g, (int)o * 8));
         } else {
             const uint4* srcp = reinterpret_cast<const uint4*>(stage);
 #if KVC_NT_POOL_STORE

@@ -110,7 +110,7 @@ __device__ PageResult encode_page(const uint16_t* __restrict__ src, const Geomet
 #pragma unroll
     for (int p = 0; p < MAXP; ++p) {
         const int e0 = p * 512 + lane * 8;
-        raw[p] = (e0 < E) ? *reinterpret_cast<const uint4*>(src + e0) : make_uint4(0, 0, 0, 0);
+        raw[p] = (e0 < E) ? *reinterpret_cast<const uint4*>(src + elem_off(g, e0)) : make_uint4(0, 0, 0, 0);
     }
     // scaling step: max |x| over the page on the FP16 bit patterns (monotone in magnitude)
     uint32_t m = 0;
@@ -228,97 +228,32 @@ template <int MAXP, int PPW>
 __global__ __launch_bounds__(kThreads) void k_compress(EncodeArgs a) {
     constexpr int kSlots = kWavesPerWG * PPW;
     __shared__ __align__(16) uint32_t s_stage[kSlots][Slot<MAXP>::kWords];
-    __shared__ uint32_t s_n16[kSlots];
-    __shared__ uint32_t s_mode[kSlots];
-    __shared__ float s_scale[kSlots];
-    __shared__ unsigned long long s_off16[kSlots];
-    __shared__ long long s_desc[kSlots];     // descriptor index, -1 = nothing to write
-    __shared__ long long s_srcpage[kSlots];  // source page index (RAW copy-out)
-
+    __shared__ EncBook<kSlots> s_book;
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const Geometry g = a.g;
-    const int E = g.E;
-
+    const int64_t t0 = ((int64_t)blockIdx.x * kWavesPerWG + wave) * PPW;
+    TaskPos pos = task_pos(t0, a.g.ppb);
     for (int i = 0; i < PPW; ++i) {
         const int slot = wave * PPW + i;
-        const int64_t t = ((int64_t)blockIdx.x * kWavesPerWG + wave) * PPW + i;
+        const EncTask task = resolve_enc_task(a, t0 + i, pos);
+        task_advance(pos, a.g.ppb);
         PageResult r;
         r.n16 = 0;
         r.mode = KVC_MODE_INVALID;
         r.scale = 0.0f;
-        long long di = -1, sp = -1;
-        if (t < a.n_pages) {
-            const int64_t blk = t / g.ppb;
-            const int pg = (int)(t - blk * g.ppb);
-            const int64_t sb = a.src_ids ? (int64_t)a.src_ids[blk] : blk;
-            const int64_t pb = a.pool_ids ? (int64_t)a.pool_ids[blk] : blk;
-            if (sb >= 0 && pb >= 0) {
-                const uint64_t d_idx = (uint64_t)pb * (uint64_t)g.ppb + (uint64_t)pg;
-                if (sb >= a.n_cache_blocks || d_idx >= a.n_desc) {
-                    if (lane == 0) atomicOr(&a.st->status, KVC_ST_BAD_INDEX);
-                } else {
-                    sp = sb * g.ppb + pg;
-                    di = (long long)d_idx;
-                    const int scheme = a.block_scheme ? min((int)a.block_scheme[blk], 3) : a.scheme;
-                    r = encode_page<MAXP>(a.cache + (size_t)sp * (size_t)E, g, scheme, s_stage[slot]);
-                }
-            }
-        }
+        if (task.desc_idx >= 0) r = encode_page<MAXP>(a.cache + task.src_off, a.g, task.scheme, s_stage[slot]);
         if (lane == 0) {
-            s_n16[slot] = r.n16;
-            s_mode[slot] = r.mode;
-            s_scale[slot] = r.scale;
-            s_desc[slot] = di;
-            s_srcpage[slot] = sp;
+            s_book.n16[slot] = r.n16;
+            s_book.mode[slot] = r.mode;
+            s_book.scale[slot] = r.scale;
+            s_book.desc[slot] = task.desc_idx;
+            s_book.srcoff[slot] = task.src_off;
         }
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        unsigned long long tot = 0;
-        for (int k = 0; k < kSlots; ++k) tot += s_n16[k];
-        unsigned long long base = tot ? atomicAdd(&a.st->cursor16, tot) : 0ull;
-        bool full = false;
-        for (int k = 0; k < kSlots; ++k) {
-            const unsigned long long n = s_n16[k];
-            if (n && base + n > a.pool_units) {  // does not fit: the page is marked INVALID
-                s_mode[k] = KVC_MODE_INVALID;
-                full = true;
-            }
-            s_off16[k] = base;
-            base += n;
-        }
-        if (full) atomicOr(&a.st->status, KVC_ST_POOL_FULL);
-    }
+    if (threadIdx.x == 0) reserve_pool_span<kSlots>(a, s_book);
     __syncthreads();
-    for (int i = 0; i < PPW; ++i) {
-        const int slot = wave * PPW + i;
-        const long long di = s_desc[slot];
-        if (di < 0) continue;
-        const uint32_t mode = s_mode[slot];
-        const uint32_t n16 = s_n16[slot];
-        const unsigned long long off16 = s_off16[slot];
-        if (mode != KVC_MODE_INVALID) {
-            uint4* dst = reinterpret_cast<uint4*>(a.pool) + off16;
-            if (mode == KVC_MODE_RAW) {
-                const uint4* srcp = reinterpret_cast<const uint4*>(a.cache + (size_t)s_srcpage[slot] * (size_t)E);
-                for (uint32_t o = lane; o < n16; o += 64) dst[o] = srcp[o];
-            } else {
-                const uint4* srcp = reinterpret_cast<const uint4*>(s_stage[slot]);
-                for (uint32_t o = lane; o < n16; o += 64) dst[o] = srcp[o];
-            }
-        }
-        if (lane == 0) {
-            uint4 dw;
-            if (mode == KVC_MODE_INVALID) {
-                dw = make_uint4(0, 0, 0, (uint32_t)KVC_MODE_INVALID << 16);
-            } else {
-                const unsigned long long off = off16 * 16ull;
-                dw = make_uint4((uint32_t)off, (uint32_t)(off >> 32), __float_as_uint(s_scale[slot]), n16 | (mode << 16));
-            }
-            reinterpret_cast<uint4*>(a.desc)[di] = dw;
-        }
-    }
+    for (int i = 0; i < PPW; ++i) emit_page<kSlots>(a, s_book, wave * PPW + i, s_stage[wave * PPW + i]);
 }
 
 // ---------------------------------------------------------------------------------- decode
@@ -357,12 +292,13 @@ __device__ bool decode_page(const DecodeArgs& a, uint64_t d_idx, uint16_t* __res
     else
         ok = false;
     if (!ok) {
-        zero_page(dst, E);
+        zero_page(dst, a.g);
         return false;
     }
     const uint8_t* pl = a.pool + off;
     if (mode == KVC_MODE_RAW) {  // stored-uncompressed bypass
-        for (uint32_t o = lane; o < n16; o += 64) reinterpret_cast<uint4*>(dst)[o] = reinterpret_cast<const uint4*>(pl)[o];
+        for (uint32_t o = lane; o < n16; o += 64)
+            *reinterpret_cast<uint4*>(dst + elem_off(a.g, (int)o * 8)) = reinterpret_cast<const uint4*>(pl)[o];
         return true;
     }
     if (mode == KVC_MODE_INT8) {
@@ -377,7 +313,7 @@ __device__ bool decode_page(const DecodeArgs& a, uint64_t d_idx, uint16_t* __res
                     q[k] = (int)(v.x >> (8 * k));
                     q[4 + k] = (int)(v.y >> (8 * k));
                 }
-                *reinterpret_cast<uint4*>(dst + e0) = dequant8(q, s);
+                *reinterpret_cast<uint4*>(dst + elem_off(a.g, e0)) = dequant8(q, s);
             }
         }
         return true;
@@ -403,7 +339,7 @@ __device__ bool decode_page(const DecodeArgs& a, uint64_t d_idx, uint16_t* __res
         run += (uint32_t)__shfl((int)incl, 63);
     }
     if (__any(bad) || (((uint32_t)hdr + run + 15u) >> 4) != n16) {
-        zero_page(dst, E);
+        zero_page(dst, a.g);
         return false;
     }
     wave_sync();
@@ -446,7 +382,7 @@ __device__ bool decode_page(const DecodeArgs& a, uint64_t d_idx, uint16_t* __res
             const int before = (int)row_excl_scan_u32((uint32_t)acc, lpr);
 #pragma unroll
             for (int k = 0; k < 8; ++k) q[k] += before;
-            if (act) *reinterpret_cast<uint4*>(dst + e0) = dequant8(q, s);
+            if (act) *reinterpret_cast<uint4*>(dst + elem_off(a.g, e0)) = dequant8(q, s);
         }
     }
     return true;
@@ -458,47 +394,13 @@ __global__ __launch_bounds__(kThreads) void k_decompress(DecodeArgs a) {
     __shared__ uint32_t s_ginfo[kWavesPerWG][MAXP * 16];
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const Geometry g = a.g;
+    const int64_t t0 = ((int64_t)blockIdx.x * kWavesPerWG + wave) * PPW;
+    TaskPos pos = task_pos(t0, a.g.ppb);
     for (int i = 0; i < PPW; ++i) {
-        const int64_t t = ((int64_t)blockIdx.x * kWavesPerWG + wave) * PPW + i;
-        if (t >= a.n_pages) break;
-        const int64_t blk = t / g.ppb;
-        const int pg = (int)(t - blk * g.ppb);
-        int64_t pb, db;
-        bool bad_index = false;
-        if (a.block_table) {  // translate (layer, sequence, predicted logical block) -> pool block
-            const int64_t sj = blk % ((int64_t)a.n_seq * a.k);
-            const int64_t layer = blk / ((int64_t)a.n_seq * a.k);
-            const int64_t sq = sj / a.k;
-            const int32_t lb = a.pred[sj];
-            db = blk;
-            pb = -1;
-            if (lb >= a.max_blocks) {
-                bad_index = true;
-            } else if (lb >= 0) {
-                const int32_t e = a.block_table[sq * a.max_blocks + lb];
-                if (e >= a.pool_blocks_per_layer)
-                    bad_index = true;
-                else if (e >= 0)
-                    pb = layer * a.pool_blocks_per_layer + e;
-            }
-        } else {
-            pb = a.pool_ids ? (int64_t)a.pool_ids[blk] : blk;
-            db = a.dst_ids ? (int64_t)a.dst_ids[blk] : blk;
-        }
-        if (db < 0 || db >= a.n_out_blocks) {
-            if (db >= 0 && lane == 0) atomicOr(&a.st->status, KVC_ST_BAD_INDEX);
-            continue;
-        }
-        uint16_t* dst = a.out + ((size_t)db * g.ppb + pg) * (size_t)g.E;
-        if (!bad_index && pb < 0) continue;  // skip
-        const uint64_t d_idx = (uint64_t)pb * (uint64_t)g.ppb + (uint64_t)pg;
-        if (bad_index || d_idx >= a.n_desc) {
-            zero_page(dst, g.E);
-            if (lane == 0) atomicOr(&a.st->status, KVC_ST_BAD_INDEX);
-            continue;
-        }
-        if (!decode_page<MAXP>(a, d_idx, dst, s_stage[wave], s_ginfo[wave])) {
+        const DecTask task = resolve_dec_task(a, t0 + i, pos);
+        task_advance(pos, a.g.ppb);
+        if (task.kind == 2) zero_page(task.dst, a.g);
+        if (task.kind == 1 && !decode_page<MAXP>(a, task.desc_idx, task.dst, s_stage[wave], s_ginfo[wave])) {
             if (lane == 0) atomicOr(&a.st->status, KVC_ST_CORRUPT);
         }
         wave_sync();

@@ -126,10 +126,17 @@ __device__ __forceinline__ void encode_tail(const uint32_t (&u)[8], uint32_t c, 
     if (d2) atomicOr(p0 + 2, d2);
 }
 
+// Lane l of pass p holds token row 4p + l/16, channels 8*(l%16) .. +7: with contiguous rows this is
+// one 1 KB run per pass, with strided rows four 256-byte runs.
+__device__ __forceinline__ int64_t lane_elem_off(const Geometry& g) {
+    const int lane = lane_id();
+    return (int64_t)(lane >> 4) * g.row_stride + (lane & 15) * 8;
+}
+
 __device__ __forceinline__ void load_page(const EncodeArgs& a, const EncTask& task, uint4 (&raw)[4]) {
-    const uint4* src = reinterpret_cast<const uint4*>(a.cache + (size_t)task.src_page * kE) + lane_id();
+    const uint16_t* src = a.cache + task.src_off + lane_elem_off(a.g);
 #pragma unroll
-    for (int p = 0; p < 4; ++p) raw[p] = load_stream(src + p * 64);
+    for (int p = 0; p < 4; ++p) raw[p] = load_stream(reinterpret_cast<const uint4*>(src + (int64_t)p * 4 * a.g.row_stride));
 }
 
 // Encode one page (its 4 KB already in registers) into the LDS slot `stage`.  scheme is wave-uniform.
@@ -250,7 +257,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_compress_p2048(EncodeArgs a) {
         task_advance(pos, a.g.ppb);
         EncTask next;
         next.desc_idx = -1;
-        next.src_page = -1;
+        next.src_off = -1;
         next.scheme = 0;
         uint4 raw_next[4];
         if (i + 1 < PPW) {
@@ -267,7 +274,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_compress_p2048(EncodeArgs a) {
             s_book.mode[slot] = r.mode;
             s_book.scale[slot] = r.scale;
             s_book.desc[slot] = task.desc_idx;
-            s_book.srcpage[slot] = task.src_page;
+            s_book.srcoff[slot] = task.src_off;
         }
         task = next;
 #pragma unroll
@@ -305,7 +312,8 @@ __device__ __forceinline__ bool decode_p2048(const DecodeArgs& a, uint64_t d_idx
     const float s = __uint_as_float(dw.z);
     const uint32_t n16 = dw.w & 0xFFFFu;
     const uint32_t mode = (dw.w >> 16) & 0xFFu;
-    uint4* dst4 = reinterpret_cast<uint4*>(dst);
+    uint16_t* dst_lane = dst + lane_elem_off(a.g);  // this lane's 8 channels in pass 0
+    const int64_t pass_stride = 4 * a.g.row_stride;
 
     bool ok = (off & 15u) == 0 && (off >> 4) + n16 <= a.pool_units;
     if (mode == KVC_MODE_RAW)
@@ -317,13 +325,13 @@ __device__ __forceinline__ bool decode_p2048(const DecodeArgs& a, uint64_t d_idx
     else
         ok = false;
     if (!ok) {
-        zero_page(dst, kE);
+        zero_page(dst, a.g);
         return false;
     }
     const uint4* pl4 = reinterpret_cast<const uint4*>(a.pool + off);
     if (mode == KVC_MODE_RAW) {  // stored-uncompressed bypass
 #pragma unroll
-        for (int p = 0; p < 4; ++p) dst4[p * 64 + lane] = pl4[p * 64 + lane];
+        for (int p = 0; p < 4; ++p) *reinterpret_cast<uint4*>(dst_lane + p * pass_stride) = pl4[p * 64 + lane];
         return true;
     }
     const float neg128s = -128.0f * s;
@@ -337,7 +345,7 @@ __device__ __forceinline__ bool decode_p2048(const DecodeArgs& a, uint64_t d_idx
                 pb[k] = ((v.x >> (8 * k)) + 128u);
                 pb[4 + k] = ((v.y >> (8 * k)) + 128u);
             }
-            store_stream(dst4 + p * 64 + lane, dequant8_biased(pb, s, neg128s));
+            store_stream(reinterpret_cast<uint4*>(dst_lane + p * pass_stride), dequant8_biased(pb, s, neg128s));
         }
         return true;
     }
@@ -362,11 +370,10 @@ __device__ __forceinline__ bool decode_p2048(const DecodeArgs& a, uint64_t d_idx
     const bool bad = c_own > 9 || (mode == KVC_MODE_DELTA && (c_own == 0 || c_own == 9));
     const bool special = __builtin_amdgcn_ballot_w64(c_own == 0 || c_own == 9) != 0;  // any zero-run / run packet
     if (__builtin_amdgcn_ballot_w64(bad) != 0 || ((total + 15u) >> 4) != n16) {
-        zero_page(dst, kE);
+        zero_page(dst, a.g);
         return false;
     }
     wave_sync();
-    const uint8_t* stage8 = reinterpret_cast<const uint8_t*>(stage);
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
         const uint32_t gi = ginfo[p * 16 + (lane >> 2)];
@@ -410,9 +417,8 @@ __device__ __forceinline__ bool decode_p2048(const DecodeArgs& a, uint64_t d_idx
         pb[0] = rincl - tot + 128u + (uint32_t)dl[0];  // +128: biased codes, see dequant8_biased
 #pragma unroll
         for (int k = 1; k < 8; ++k) pb[k] = pb[k - 1] + (uint32_t)dl[k];
-        store_stream(dst4 + p * 64 + lane, dequant8_biased(pb, s, neg128s));
+        store_stream(reinterpret_cast<uint4*>(dst_lane + p * pass_stride), dequant8_biased(pb, s, neg128s));
     }
-    (void)stage8;
     return true;
 }
 
@@ -428,7 +434,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_p2048(DecodeArgs a) {
     for (int i = 0; i < PPW; ++i) {
         const DecTask task = resolve_dec_task(a, t0 + i, pos);
         task_advance(pos, a.g.ppb);
-        if (task.kind == 2) zero_page(task.dst, kE);
+        if (task.kind == 2) zero_page(task.dst, a.g);
         if (task.kind == 1 && !decode_p2048(a, task.desc_idx, task.dst, s_stage[wave], s_ginfo[wave])) {
             if (lane == 0) atomicOr(&a.st->status, KVC_ST_CORRUPT);
         }

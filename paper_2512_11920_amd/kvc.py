@@ -20,7 +20,7 @@ ST_POOL_FULL, ST_CORRUPT, ST_BAD_INDEX = 1, 2, 4
 #: numpy view of kvc_desc
 DESC_DTYPE = np.dtype([("off", "<u8"), ("scale", "<f4"), ("n16", "<u2"), ("mode", "u1"), ("rsvd", "u1")])
 
-EXPORTS = ("kvc_create", "kvc_destroy", "kvc_set_scheme", "kvc_bind_pool", "kvc_reset_pool", "kvc_compress_blocks",
+EXPORTS = ("kvc_create", "kvc_destroy", "kvc_set_scheme", "kvc_set_cache_layout", "kvc_bind_pool", "kvc_reset_pool", "kvc_compress_blocks",
            "kvc_compress_blocks_mixed", "kvc_decompress_blocks", "kvc_gather_decompress", "kvc_prefetch_reset", "kvc_prefetch_layers", "kvc_stats", "kvc_copy_bytes", "kvc_strerror")
 
 
@@ -63,6 +63,8 @@ def load():
     L.kvc_destroy.argtypes = [vp]
     L.kvc_set_scheme.restype = C.c_int
     L.kvc_set_scheme.argtypes = [vp, C.c_int32]
+    L.kvc_set_cache_layout.restype = C.c_int
+    L.kvc_set_cache_layout.argtypes = [vp, C.c_int64, C.c_int64, C.c_int64]
     L.kvc_bind_pool.restype = C.c_int
     L.kvc_bind_pool.argtypes = [vp, vp, C.c_uint64, vp, C.c_uint64]
     L.kvc_reset_pool.restype = C.c_int
@@ -180,13 +182,22 @@ class Codec:
         _check(self._L.kvc_set_scheme(self._ctx, scheme), "kvc_set_scheme")
         self.cfg.scheme = scheme
 
+    def set_cache_layout(self, block_stride: int = 0, page_stride: int = 0, row_stride: int = 0):
+        """Strides (FP16 elements) of the cache buffers; all zero = contiguous [block][page][N][d]."""
+        _check(self._L.kvc_set_cache_layout(self._ctx, block_stride, page_stride, row_stride), "kvc_set_cache_layout")
+        self._block_stride = block_stride or self.block_elems
+        self._span = ((self.cfg.pages_per_block - 1) * (page_stride or self.page_elems)
+                      + (self.cfg.tokens_per_block - 1) * (row_stride or self.cfg.head_dim) + self.cfg.head_dim)
+
     # -- the three data calls
     def _blocks_of(self, t) -> int:
+        """Number of whole blocks the tensor's storage covers under the current layout."""
         import torch
 
         assert t.is_cuda and t.is_contiguous() and t.dtype == torch.float16
-        assert t.numel() % self.block_elems == 0
-        return t.numel() // self.block_elems
+        bs = getattr(self, "_block_stride", self.block_elems)
+        span = getattr(self, "_span", self.block_elems)
+        return 0 if t.numel() < span else (t.numel() - span) // bs + 1
 
     def compress_blocks(self, cache, n: int | None = None, src_ids=None, pool_ids=None, block_scheme=None, stream=None):
         """block_scheme: optional uint8 CUDA tensor, requested mode per block of the call."""

@@ -49,6 +49,7 @@ def test_host_side_argument_checks_need_no_device():
         assert lib.kvc_create(C.byref(ctx), C.byref(cfg)) == want
         assert not ctx.value
     assert lib.kvc_set_scheme(None, 1) == kvc.ERR_ARG
+    assert lib.kvc_set_cache_layout(None, 0, 0, 0) == kvc.ERR_ARG
     assert lib.kvc_bind_pool(None, None, 0, None, 0) == kvc.ERR_ARG
     assert lib.kvc_reset_pool(None, None) == kvc.ERR_ARG
     assert lib.kvc_compress_blocks(None, None, 0, None, None, 0, None) == kvc.ERR_ARG

@@ -362,3 +362,44 @@ def test_pool_in_pinned_host_memory():
     pageable = torch.empty(4096, dtype=torch.uint8)
     rc = kvc.load().kvc_bind_pool(c2._ctx, pageable.data_ptr(), 4096, desc.data_ptr(), 4)
     assert rc == kvc.ERR_ARG
+
+
+@pytest.mark.parametrize("d,H,pad", [(128, 4, 0), (128, 3, 64), (64, 2, 8), (256, 2, 0)])
+def test_strided_cache_layout(d, H, pad):
+    """Token-major cache [block][token][head][d (+pad)]: pages are strided views, no copy is made.
+    Compress reads the view, decompress / gather write the view and leave the padding alone."""
+    rng = np.random.default_rng(60 + d + H)
+    N, nb = 16, 21
+    row = H * d + pad
+    x = (rng.standard_normal((nb, N, row)) * 1.5).astype(np.float16)
+    x[..., : H * d] *= np.exp(0.5 * rng.standard_normal(H * d)).astype(np.float16)
+    x[2, 3, 5] = np.float16("inf")  # one RAW page, through the strided copy path
+    pages = np.stack([x[:, :, h * d:(h + 1) * d] for h in range(H)], axis=1)  # dense [nb][H][N][d]
+    xt = torch.from_numpy(x).to(DEV)
+    c = kvc.Codec(N, d, H, 3)
+    c.set_cache_layout(block_stride=N * row, page_stride=d, row_stride=row)
+    c.alloc_pool(nb, nb * H * N * d * 2 + 64, DEV)
+    c.compress_blocks(xt)
+    st = c.stats()
+    assert st["rc"] == 0 and sum(st["pages"]) == nb * H and st["pages"][0] == 1
+    od, op = compare_pages_with_oracle(np.ascontiguousarray(pages).view(np.uint16).reshape(-1, N, d), c.desc_numpy(),
+                                       c.pool.cpu().numpy(), N, d, 3)
+    want, _ = o.decompress_pages(op, od, N, d)
+    want = want.reshape(nb, H, N, d)
+    out = torch.full((nb + 2, N, row), 7.0, dtype=torch.float16, device=DEV)
+    dst = torch.from_numpy(rng.permutation(nb + 2)[:nb].astype(np.int32)).to(DEV)
+    c.decompress_blocks(out, n=nb, dst_ids=dst)
+    got = out.cpu().numpy()
+    dst_np = dst.cpu().numpy()
+    for b in range(nb):
+        for h in range(H):
+            assert np.array_equal(got[dst_np[b], :, h * d:(h + 1) * d].view(np.uint16), want[b, h]), (b, h)
+    if pad:
+        assert (got[..., H * d:] == 7.0).all()
+    untouched = sorted(set(range(nb + 2)) - set(dst_np.tolist()))
+    assert (got[untouched] == 7.0).all()
+    assert c.stats()["status"] == 0
+    with pytest.raises(kvc.KvcError):
+        c.set_cache_layout(block_stride=N * row, page_stride=d, row_stride=d - 8)
+    with pytest.raises(kvc.KvcError):
+        c.set_cache_layout(block_stride=N * row + 4, page_stride=d, row_stride=row)

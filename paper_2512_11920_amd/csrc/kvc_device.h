@@ -10,6 +10,22 @@ namespace kvc {
 #define KVC_NT_POOL_STORE 1
 #endif
 
+// Debug build (-DKVC_DEBUG_BOUNDS=1): every LDS slot index and pool span the kernels compute is checked
+// against its bounds; a violation sets status bit 8 instead of being executed silently.  Off by default.
+#ifndef KVC_DEBUG_BOUNDS
+#define KVC_DEBUG_BOUNDS 0
+#endif
+#if KVC_DEBUG_BOUNDS
+#define KVC_CHECK(st, cond)                        \
+    do {                                           \
+        if (!(cond)) atomicOr(&(st)->status, 8u);  \
+    } while (0)
+#else
+#define KVC_CHECK(st, cond) \
+    do {                    \
+    } while (0)
+#endif
+
 constexpr int kWavesPerWG = 4;
 constexpr int kThreads = kWavesPerWG * 64;
 
@@ -249,6 +265,7 @@ __device__ __forceinline__ void emit_page(const EncodeArgs& a, const EncBook<SLO
     const uint32_t n16 = b.n16[slot];
     const unsigned long long off16 = b.off16[slot];
     if (mode != KVC_MODE_INVALID) {
+        KVC_CHECK(a.st, off16 + n16 <= a.pool_units && (size_t)n16 * 16 <= sizeof(uint32_t) * Slot<8>::kWords * 2);
         uint4* dst = reinterpret_cast<uint4*>(a.pool) + off16;
         if (mode == KVC_MODE_RAW) {  // the payload is the dense page
             const uint16_t* srcp = a.cache + b.srcoff[slot];

@@ -95,7 +95,7 @@ __device__ __forceinline__ void fill_zigzag_lut(uint8_t* lut) {
 // pass may be a run packet (is_run is then meaningful), else every group is literal or all-zero.
 template <bool RUNS>
 __device__ __forceinline__ void encode_tail(const uint32_t (&u)[8], uint32_t c, uint32_t size, bool is_run, uint32_t qi,
-                                            int p, uint32_t& run, uint32_t* stage) {
+                                            int p, uint32_t& run, uint32_t* stage, DevState* st) {
     const uint32_t incl = quad_incl_scan_dpp(size);
     const uint32_t off = run + incl - size;  // byte offset of this group's body
     run += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
@@ -119,6 +119,7 @@ __device__ __forceinline__ void encode_tail(const uint32_t (&u)[8], uint32_t c, 
     }
     const uint32_t sh = (B & 3u) << 3;
     uint32_t* p0 = stage + (B >> 2);
+    KVC_CHECK(st, c <= 9 && (B >> 2) + 2 < (uint32_t)Slot<4>::kWords && B >= (uint32_t)kHdr);
     const uint64_t lo = W << sh;
     const uint32_t d2 = (uint32_t)(((uint64_t)(uint32_t)(W >> 32) << sh) >> 32);
     atomicOr(p0, (uint32_t)lo);
@@ -141,7 +142,7 @@ __device__ __forceinline__ void load_page(const EncodeArgs& a, const EncTask& ta
 
 // Encode one page (its 4 KB already in registers) into the LDS slot `stage`.  scheme is wave-uniform.
 __device__ __forceinline__ PageResult encode_p2048(const uint4 (&raw)[4], int scheme, uint32_t* stage,
-                                                   const uint8_t* lut) {
+                                                   const uint8_t* lut, DevState* st) {
     const bool RLE = scheme == KVC_MODE_RLE;
     const uint32_t c_min = RLE ? 0u : 1u;  // without run packets an all-zero group is a 1-bit literal
     const int lane = lane_id();
@@ -190,6 +191,7 @@ __device__ __forceinline__ PageResult encode_p2048(const uint4 (&raw)[4], int sc
         // row) has no left neighbour and is kept verbatim (q - 0).  Then wrap + zig-zag by table.
         const uint32_t prev = dpp<0x111>(kMagicBits - 256u, t[7] - 2048u);
         uint32_t u[8];
+        KVC_CHECK(st, t[0] - prev < 512u && t[1] - t[0] < 512u && t[7] - t[6] < 512u);
         u[0] = lut[t[0] - prev];
 #pragma unroll
         for (int k = 1; k < 8; ++k) u[k] = lut[t[k] - t[k - 1]];
@@ -217,9 +219,9 @@ __device__ __forceinline__ PageResult encode_p2048(const uint4 (&raw)[4], int sc
             y |= dpp<0xB1>(0, y);
             y |= dpp<0x4E>(0, y);
             const bool is_run = (y == 0) && (gmax != 0);
-            encode_tail<true>(u, is_run ? 9u : c, is_run ? 1u : size, is_run, qi, p, run, stage);
+            encode_tail<true>(u, is_run ? 9u : c, is_run ? 1u : size, is_run, qi, p, run, stage, st);
         } else {
-            encode_tail<false>(u, c, size, false, qi, p, run, stage);
+            encode_tail<false>(u, c, size, false, qi, p, run, stage, st);
         }
     }
     const uint32_t n = (run + 15u) & ~15u;
@@ -268,7 +270,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_compress_p2048(EncodeArgs a) {
         r.n16 = 0;
         r.mode = KVC_MODE_INVALID;
         r.scale = 0.0f;
-        if (task.desc_idx >= 0) r = encode_p2048(raw, task.scheme, s_stage[slot], s_lut);
+        if (task.desc_idx >= 0) r = encode_p2048(raw, task.scheme, s_stage[slot], s_lut, a.st);
         if (lane == 0) {
             s_book.n16[slot] = r.n16;
             s_book.mode[slot] = r.mode;
@@ -383,6 +385,7 @@ __device__ __forceinline__ bool decode_p2048(const DecodeArgs& a, uint64_t d_idx
         if (special && c == 9) B = goff;
         const uint32_t sh = (B & 3u) << 3;
         const uint32_t* p0 = stage + (B >> 2);
+        KVC_CHECK(a.st, (B >> 2) + 2 < (uint32_t)Slot<4>::kWords && B >= (uint32_t)kHdr);
         const uint32_t d0 = p0[0], d1 = p0[1], d2 = p0[2];
         uint32_t lo = __builtin_amdgcn_alignbit(d1, d0, sh);
         uint32_t hi = __builtin_amdgcn_alignbit(d2, d1, sh);

@@ -226,7 +226,7 @@ def main():
         v["frac_of_copy"] = v["hbm_GBps"] / copy_gbps
 
     dom = "compress" if t_c >= t_d else "decompress"
-    kname = {"compress": "k_compress", "decompress": "k_decompress"}[dom]
+    kname = {"compress": "k_compress_p16", "decompress": "k_decompress_p16"}[dom]
     res = {
         "metric": "KV codec GB/s (uncompressed fp16) compress+decompress; % of HBM peak",
         "value": round((2 * unc + g_unc) / (ms_step * 1e-3) / 1e9, 2),
@@ -317,9 +317,9 @@ def bench_decode_gather(args):
         "config": {"workload": f"decode_gather: 80 layers x 8 KV heads x 128, 64 sequences U[512,8192], "
                                f"8 predicted blocks/seq/layer, {n_pages} pages = {unc / 1e9:.2f} GB out per step",
                    "ratio": round(codec.ratio(), 4)},
-        "roofline": {"bound": "hbm", "kernel": "k_decompress", "achieved": round(alg / ts.mean() / 1e6, 1),
+        "roofline": {"bound": "hbm", "kernel": "k_decompress_p16", "achieved": round(alg / ts.mean() / 1e6, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(alg / ts.mean() / 1e6 / HBM_PEAK_GBS, 4),
-                     "traffic": read_traffic("decode_gather", "k_decompress"), "alg_bytes_per_launch": int(alg),
+                     "traffic": read_traffic("decode_gather", "k_decompress_p16"), "alg_bytes_per_launch": int(alg),
                      "launch_ms": round(float(ts.mean()), 4)},
         "step_ms": {"mean": round(float(ts.mean()), 4), "p50": round(float(np.percentile(ts, 50)), 4),
                     "p99": round(float(np.percentile(ts, 99)), 4)},

@@ -7,7 +7,7 @@ import sys
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
-SOURCES = [os.path.join(_PKG, "csrc", f) for f in ("kvc_kernels.hip", "kvc_p2048.hip", "kvc_api.hip")]
+SOURCES = [os.path.join(_PKG, "csrc", f) for f in ("kvc_kernels.hip", "kvc_page16.hip", "kvc_api.hip")]
 HEADERS = [os.path.join(_PKG, "csrc", "kvc_common.h"), os.path.join(_PKG, "csrc", "kvc_device.h"),
            os.path.join(_ROOT, "include", "kvc.h")]
 LIB = os.path.join(_PKG, "libkvc.so")

@@ -297,7 +297,8 @@ __device__ __forceinline__ void emit_page(const EncodeArgs& a, const EncBook<SLO
     }
 }
 
-hipError_t launch_compress_p2048(const EncodeArgs& a, hipStream_t s);
-hipError_t launch_decompress_p2048(const DecodeArgs& a, hipStream_t s);
+// kernels specialised for 16-token pages with 64, 128 or 256 channels
+hipError_t launch_compress_p16(const EncodeArgs& a, hipStream_t s);
+hipError_t launch_decompress_p16(const DecodeArgs& a, hipStream_t s);
 
 }  // namespace kvc

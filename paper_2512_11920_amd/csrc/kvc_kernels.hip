@@ -511,7 +511,7 @@ static inline unsigned grid_for(int64_t n_pages, int ppw) {
 
 hipError_t launch_compress(const EncodeArgs& a, hipStream_t s) {
     if (a.n_pages == 0) return hipSuccess;
-    if (a.g.N == 16 && a.g.d == 128) return launch_compress_p2048(a, s);
+    if (a.g.N == 16 && a.g.d >= 64) return launch_compress_p16(a, s);
     constexpr int PPW = 4;
     const dim3 grid(grid_for(a.n_pages, PPW)), block(kThreads);
     if (a.g.E <= 512)
@@ -525,7 +525,7 @@ hipError_t launch_compress(const EncodeArgs& a, hipStream_t s) {
 
 hipError_t launch_decompress(const DecodeArgs& a, hipStream_t s) {
     if (a.n_pages == 0) return hipSuccess;
-    if (a.g.N == 16 && a.g.d == 128) return launch_decompress_p2048(a, s);
+    if (a.g.N == 16 && a.g.d >= 64) return launch_decompress_p16(a, s);
     constexpr int PPW = 4;
     const dim3 grid(grid_for(a.n_pages, PPW)), block(kThreads);
     if (a.g.E <= 512)

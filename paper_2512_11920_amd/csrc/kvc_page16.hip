@@ -1,11 +1,12 @@
-// Kernels specialised for the paper's 4 KB page: 16 tokens x 128 channels FP16 (2048 elements).
+// Kernels specialised for 16-token pages with 64, 128 or 256 channels; 16 x 128 FP16 is the paper's
+// 4 KB page and the shape the tuning was done on.
 //
-// Same lane mapping as the generic kernels -- one wave per page, 4 passes of 512 elements, a lane
-// owns 8 consecutive channels, a packet group is a quad of lanes, a token row is one 16-lane DPP
-// row -- but every cross-lane step is a DPP operation, the per-group statistics (max, width,
-// run test) and the offset scans are done on quads, and no lane is ever inactive.  The codec is
-// bound by vector-ALU issue before HBM bandwidth, so the code is written to keep the instruction
-// count per element low.
+// Same lane mapping as the generic kernels -- one wave per page, passes of 512 elements, a lane owns
+// 8 consecutive channels, a packet group is a quad of lanes, a token row is D/8 neighbouring lanes
+// (one 16-lane DPP row at D = 128) -- but every cross-lane step is a DPP operation, the per-group
+// statistics (max, width, run test) and the offset scans are done on quads, and no lane is ever
+// inactive.  The codec is bound by vector-ALU issue before HBM bandwidth, so the code is written to keep
+// the instruction count per element low.
 //
 // Encode: Algorithm 2 of the paper (scaling, quantize, delta, run-length encode).
 // Decode: Section 3.5.3 (undo run-length coding, prefix sum, dequantize; bypass for raw pages).
@@ -49,8 +50,17 @@ __device__ __forceinline__ void store_stream(uint4* p, const uint4& v) {
 #endif
 }
 
-constexpr int kE = 2048;      // elements per page
-constexpr int kHdr = 32;      // header bytes: 64 groups x 4 bits
+// Compile-time shape of a 16-token page with D channels.
+template <int D>
+struct Page {
+    static constexpr int kE = 16 * D;       // elements
+    static constexpr int kPasses = D / 32;  // passes of 512 elements
+    static constexpr int kGroups = D / 2;   // packet groups of 32
+    static constexpr int kHdr = D / 4;      // header bytes, 4 bits per group
+    static constexpr int kLpr = D / 8;      // lanes per token row
+    static constexpr int kRowsPerPass = 512 / D;
+};
+
 constexpr float kMagic = 12582912.0f;  // 1.5 * 2^23: adding it rounds to an integer, ties to even
 constexpr uint32_t kMagicBits = 0x4B400000u;
 
@@ -70,10 +80,11 @@ __device__ __forceinline__ void quantize8_bits(const uint4& raw, float s_inv, ui
 }
 
 // plain INT8 payload: codes as bytes, row-major
-__device__ __forceinline__ void store_codes_p2048(const uint4 (&raw)[4], float s_inv, uint32_t* stage) {
+template <int NP>
+__device__ __forceinline__ void store_codes(const uint4 (&raw)[NP], float s_inv, uint32_t* stage) {
     const int lane = lane_id();
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
+    for (int p = 0; p < NP; ++p) {
         uint32_t t[8];
         quantize8_bits(raw[p], s_inv, t);
         uint2 v;
@@ -91,9 +102,38 @@ __device__ __forceinline__ void fill_zigzag_lut(uint8_t* lut) {
     }
 }
 
+// t7 of the lane to the left within the token row; row starts receive `first`.
+template <int LPR>
+__device__ __forceinline__ uint32_t left_neighbour(uint32_t first, uint32_t v) {
+    if (LPR == 16) return dpp<0x111>(first, v);  // row_shr:1, lane 0 of a DPP row keeps `first`
+    if (LPR == 8) {
+        const uint32_t x = dpp<0x111>(first, v);
+        return (lane_id() & 7) == 0 ? first : x;
+    }
+    const uint32_t x = dpp<0x138>(first, v);  // wave_shr:1 crosses the 16-lane rows
+    return (lane_id() & 31) == 0 ? first : x;
+}
+
+// inclusive prefix sum over the LPR lanes of a token row
+template <int LPR>
+__device__ __forceinline__ uint32_t row_incl_scan(uint32_t v) {
+    if (LPR == 16) return row16_incl_scan_dpp(v);
+    if (LPR == 32) {
+        v = row16_incl_scan_dpp(v);
+        return v + dpp<0x142, 0xA>(0, v);  // odd DPP rows add the total of the row before
+    }
+    const int r = lane_id() & 7;
+    uint32_t t = dpp<0x111>(0, v);
+    v += r >= 1 ? t : 0u;
+    t = dpp<0x112>(0, v);
+    v += r >= 2 ? t : 0u;
+    t = dpp<0x114>(0, v);
+    return v + (r >= 4 ? t : 0u);
+}
+
 // Second half of a pass: body offsets, header bits, packing, LDS write.  RUNS = some group of this
 // pass may be a run packet (is_run is then meaningful), else every group is literal or all-zero.
-template <bool RUNS>
+template <int D, bool RUNS>
 __device__ __forceinline__ void encode_tail(const uint32_t (&u)[8], uint32_t c, uint32_t size, bool is_run, uint32_t qi,
                                             int p, uint32_t& run, uint32_t* stage, DevState* st) {
     const uint32_t incl = quad_incl_scan_dpp(size);
@@ -119,7 +159,7 @@ __device__ __forceinline__ void encode_tail(const uint32_t (&u)[8], uint32_t c, 
     }
     const uint32_t sh = (B & 3u) << 3;
     uint32_t* p0 = stage + (B >> 2);
-    KVC_CHECK(st, c <= 9 && (B >> 2) + 2 < (uint32_t)Slot<4>::kWords && B >= (uint32_t)kHdr);
+    KVC_CHECK(st, c <= 9 && (B >> 2) + 2 < (uint32_t)Slot<Page<D>::kPasses>::kWords && B >= (uint32_t)Page<D>::kHdr);
     const uint64_t lo = W << sh;
     const uint32_t d2 = (uint32_t)(((uint64_t)(uint32_t)(W >> 32) << sh) >> 32);
     atomicOr(p0, (uint32_t)lo);
@@ -127,22 +167,27 @@ __device__ __forceinline__ void encode_tail(const uint32_t (&u)[8], uint32_t c, 
     if (d2) atomicOr(p0 + 2, d2);
 }
 
-// Lane l of pass p holds token row 4p + l/16, channels 8*(l%16) .. +7: with contiguous rows this is
-// one 1 KB run per pass, with strided rows four 256-byte runs.
+// Lane l of pass p holds token row p*(512/D) + l/(D/8), channels 8*(l%(D/8)) .. +7: with contiguous
+// rows this is one 1 KB run per pass, with strided rows 512/D runs of 2*D bytes.
+template <int D>
 __device__ __forceinline__ int64_t lane_elem_off(const Geometry& g) {
     const int lane = lane_id();
-    return (int64_t)(lane >> 4) * g.row_stride + (lane & 15) * 8;
+    return (int64_t)(lane / Page<D>::kLpr) * g.row_stride + (lane % Page<D>::kLpr) * 8;
 }
 
-__device__ __forceinline__ void load_page(const EncodeArgs& a, const EncTask& task, uint4 (&raw)[4]) {
-    const uint16_t* src = a.cache + task.src_off + lane_elem_off(a.g);
+template <int D>
+__device__ __forceinline__ void load_page(const EncodeArgs& a, const EncTask& task, uint4 (&raw)[Page<D>::kPasses]) {
+    const uint16_t* src = a.cache + task.src_off + lane_elem_off<D>(a.g);
 #pragma unroll
-    for (int p = 0; p < 4; ++p) raw[p] = load_stream(reinterpret_cast<const uint4*>(src + (int64_t)p * 4 * a.g.row_stride));
+    for (int p = 0; p < Page<D>::kPasses; ++p)
+        raw[p] = load_stream(reinterpret_cast<const uint4*>(src + (int64_t)p * Page<D>::kRowsPerPass * a.g.row_stride));
 }
 
-// Encode one page (its 4 KB already in registers) into the LDS slot `stage`.  scheme is wave-uniform.
-__device__ __forceinline__ PageResult encode_p2048(const uint4 (&raw)[4], int scheme, uint32_t* stage,
-                                                   const uint8_t* lut, DevState* st) {
+// Encode one page (already in registers) into the LDS slot `stage`.  scheme is wave-uniform.
+template <int D>
+__device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPasses], int scheme, uint32_t* stage,
+                                                 const uint8_t* lut, DevState* st) {
+    constexpr int kE = Page<D>::kE, kHdr = Page<D>::kHdr, NP = Page<D>::kPasses;
     const bool RLE = scheme == KVC_MODE_RLE;
     const uint32_t c_min = RLE ? 0u : 1u;  // without run packets an all-zero group is a 1-bit literal
     const int lane = lane_id();
@@ -151,7 +196,7 @@ __device__ __forceinline__ PageResult encode_p2048(const uint4 (&raw)[4], int sc
     // scaling: max |x| on the FP16 bit patterns, two per dword
     uint32_t m2 = 0;
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
+    for (int p = 0; p < NP; ++p) {
         m2 = pk_max_u16(m2, raw[p].x & 0x7FFF7FFFu);
         m2 = pk_max_u16(m2, raw[p].y & 0x7FFF7FFFu);
         m2 = pk_max_u16(m2, raw[p].z & 0x7FFF7FFFu);
@@ -172,24 +217,24 @@ __device__ __forceinline__ PageResult encode_p2048(const uint4 (&raw)[4], int sc
     }
     r.scale = s;
     if (scheme == KVC_MODE_INT8) {
-        store_codes_p2048(raw, s_inv, stage);
+        store_codes<NP>(raw, s_inv, stage);
         r.n16 = kE / 16;
         r.mode = KVC_MODE_INT8;
         return r;
     }
     // bodies are OR-ed into the slot, and the zero padding is part of the payload
-    reinterpret_cast<uint4*>(stage)[lane] = make_uint4(0, 0, 0, 0);
-    reinterpret_cast<uint4*>(stage)[lane + 64] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int z = 0; z < kE / 1024; ++z) reinterpret_cast<uint4*>(stage)[lane + 64 * z] = make_uint4(0, 0, 0, 0);
     wave_sync();
 
     uint32_t run = kHdr;  // payload bytes so far (wave-uniform)
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
+    for (int p = 0; p < NP; ++p) {
         uint32_t t[8];
         quantize8_bits(raw[p], s_inv, t);
-        // delta along the channel index, plus 256; the first column of a token row (lane 0 of a DPP
-        // row) has no left neighbour and is kept verbatim (q - 0).  Then wrap + zig-zag by table.
-        const uint32_t prev = dpp<0x111>(kMagicBits - 256u, t[7] - 2048u);
+        // delta along the channel index, plus 256; the first column of a token row has no left
+        // neighbour and is kept verbatim (q - 0).  Then wrap + zig-zag by table.
+        const uint32_t prev = left_neighbour<Page<D>::kLpr>(kMagicBits - 256u, t[7] - 2048u);
         uint32_t u[8];
         KVC_CHECK(st, t[0] - prev < 512u && t[1] - t[0] < 512u && t[7] - t[6] < 512u);
         u[0] = lut[t[0] - prev];
@@ -219,15 +264,15 @@ __device__ __forceinline__ PageResult encode_p2048(const uint4 (&raw)[4], int sc
             y |= dpp<0xB1>(0, y);
             y |= dpp<0x4E>(0, y);
             const bool is_run = (y == 0) && (gmax != 0);
-            encode_tail<true>(u, is_run ? 9u : c, is_run ? 1u : size, is_run, qi, p, run, stage, st);
+            encode_tail<D, true>(u, is_run ? 9u : c, is_run ? 1u : size, is_run, qi, p, run, stage, st);
         } else {
-            encode_tail<false>(u, c, size, false, qi, p, run, stage, st);
+            encode_tail<D, false>(u, c, size, false, qi, p, run, stage, st);
         }
     }
     const uint32_t n = (run + 15u) & ~15u;
     wave_sync();
     if (n >= (uint32_t)kE) {  // packing did not beat plain INT8
-        store_codes_p2048(raw, s_inv, stage);
+        store_codes<NP>(raw, s_inv, stage);
         r.n16 = kE / 16;
         r.mode = KVC_MODE_INT8;
     } else {
@@ -237,10 +282,12 @@ __device__ __forceinline__ PageResult encode_p2048(const uint4 (&raw)[4], int sc
     return r;
 }
 
-template <int WAVES, int PPW>
-__global__ __launch_bounds__(WAVES * 64) void k_compress_p2048(EncodeArgs a) {
+template <int D, int WAVES, int PPW>
+__global__ __launch_bounds__(WAVES * 64) void k_compress_p16(EncodeArgs a) {
     constexpr int kSlots = WAVES * PPW;
-    __shared__ __align__(16) uint32_t s_stage[kSlots][Slot<4>::kWords];
+    constexpr int NP = Page<D>::kPasses;
+    constexpr bool kPrefetch = D <= 128;  // at D = 256 a second page in registers halves the occupancy
+    __shared__ __align__(16) uint32_t s_stage[kSlots][Slot<NP>::kWords];
     __shared__ EncBook<kSlots> s_book;
     __shared__ uint8_t s_lut[512];
     const int lane = lane_id();
@@ -251,8 +298,8 @@ __global__ __launch_bounds__(WAVES * 64) void k_compress_p2048(EncodeArgs a) {
     TaskPos pos = task_pos(t0, a.g.ppb);
     // the next page's loads are issued before the current page is encoded
     EncTask task = resolve_enc_task(a, t0, pos);
-    uint4 raw[4];
-    if (task.desc_idx >= 0) load_page(a, task, raw);
+    uint4 raw[NP];
+    if (task.desc_idx >= 0) load_page<D>(a, task, raw);
 #pragma unroll 1
     for (int i = 0; i < PPW; ++i) {
         const int slot = wave * PPW + i;
@@ -261,16 +308,16 @@ __global__ __launch_bounds__(WAVES * 64) void k_compress_p2048(EncodeArgs a) {
         next.desc_idx = -1;
         next.src_off = -1;
         next.scheme = 0;
-        uint4 raw_next[4];
-        if (i + 1 < PPW) {
+        uint4 raw_next[NP];
+        if (kPrefetch && i + 1 < PPW) {
             next = resolve_enc_task(a, t0 + i + 1, pos);
-            if (next.desc_idx >= 0) load_page(a, next, raw_next);
+            if (next.desc_idx >= 0) load_page<D>(a, next, raw_next);
         }
         PageResult r;
         r.n16 = 0;
         r.mode = KVC_MODE_INVALID;
         r.scale = 0.0f;
-        if (task.desc_idx >= 0) r = encode_p2048(raw, task.scheme, s_stage[slot], s_lut, a.st);
+        if (task.desc_idx >= 0) r = encode_p16<D>(raw, task.scheme, s_stage[slot], s_lut, a.st);
         if (lane == 0) {
             s_book.n16[slot] = r.n16;
             s_book.mode[slot] = r.mode;
@@ -278,9 +325,14 @@ __global__ __launch_bounds__(WAVES * 64) void k_compress_p2048(EncodeArgs a) {
             s_book.desc[slot] = task.desc_idx;
             s_book.srcoff[slot] = task.src_off;
         }
-        task = next;
+        if (kPrefetch) {
+            task = next;
 #pragma unroll
-        for (int p = 0; p < 4; ++p) raw[p] = raw_next[p];
+            for (int p = 0; p < NP; ++p) raw[p] = raw_next[p];
+        } else if (i + 1 < PPW) {
+            task = resolve_enc_task(a, t0 + i + 1, pos);
+            if (task.desc_idx >= 0) load_page<D>(a, task, raw);
+        }
     }
     __syncthreads();
     if (threadIdx.x == 0) reserve_pool_span<kSlots>(a, s_book);
@@ -304,9 +356,11 @@ __device__ __forceinline__ uint4 dequant8_biased(const uint32_t pb[8], float s, 
                       __builtin_bit_cast(uint32_t, h[2]), __builtin_bit_cast(uint32_t, h[3]));
 }
 
-// Decode the page described by descriptor d_idx into dst (4 KB).  false = validation failed, dst zeroed.
-__device__ __forceinline__ bool decode_p2048(const DecodeArgs& a, uint64_t d_idx, uint16_t* __restrict__ dst,
-                                             uint32_t* stage, uint32_t* ginfo) {
+// Decode the page described by descriptor d_idx into dst.  false = validation failed, dst zeroed.
+template <int D>
+__device__ __forceinline__ bool decode_p16(const DecodeArgs& a, uint64_t d_idx, uint16_t* __restrict__ dst,
+                                           uint32_t* stage, uint32_t* ginfo) {
+    constexpr int kE = Page<D>::kE, kHdr = Page<D>::kHdr, NP = Page<D>::kPasses, kG = Page<D>::kGroups;
     const int lane = lane_id();
     const uint32_t qi = (uint32_t)lane & 3u;
     const uint4 dw = reinterpret_cast<const uint4*>(a.desc)[d_idx];
@@ -314,8 +368,8 @@ __device__ __forceinline__ bool decode_p2048(const DecodeArgs& a, uint64_t d_idx
     const float s = __uint_as_float(dw.z);
     const uint32_t n16 = dw.w & 0xFFFFu;
     const uint32_t mode = (dw.w >> 16) & 0xFFu;
-    uint16_t* dst_lane = dst + lane_elem_off(a.g);  // this lane's 8 channels in pass 0
-    const int64_t pass_stride = 4 * a.g.row_stride;
+    uint16_t* dst_lane = dst + lane_elem_off<D>(a.g);  // this lane's 8 channels in pass 0
+    const int64_t pass_stride = Page<D>::kRowsPerPass * a.g.row_stride;
 
     bool ok = (off & 15u) == 0 && (off >> 4) + n16 <= a.pool_units;
     if (mode == KVC_MODE_RAW)
@@ -323,7 +377,7 @@ __device__ __forceinline__ bool decode_p2048(const DecodeArgs& a, uint64_t d_idx
     else if (mode == KVC_MODE_INT8)
         ok = ok && n16 == kE / 16;
     else if (mode == KVC_MODE_DELTA || mode == KVC_MODE_RLE)
-        ok = ok && n16 >= kHdr / 16 && n16 < kE / 16;
+        ok = ok && n16 * 16u >= (uint32_t)kHdr && n16 < kE / 16;
     else
         ok = false;
     if (!ok) {
@@ -333,13 +387,13 @@ __device__ __forceinline__ bool decode_p2048(const DecodeArgs& a, uint64_t d_idx
     const uint4* pl4 = reinterpret_cast<const uint4*>(a.pool + off);
     if (mode == KVC_MODE_RAW) {  // stored-uncompressed bypass
 #pragma unroll
-        for (int p = 0; p < 4; ++p) *reinterpret_cast<uint4*>(dst_lane + p * pass_stride) = pl4[p * 64 + lane];
+        for (int p = 0; p < NP; ++p) *reinterpret_cast<uint4*>(dst_lane + p * pass_stride) = pl4[p * 64 + lane];
         return true;
     }
     const float neg128s = -128.0f * s;
     if (mode == KVC_MODE_INT8) {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
+        for (int p = 0; p < NP; ++p) {
             const uint2 v = reinterpret_cast<const uint2*>(pl4)[p * 64 + lane];
             uint32_t pb[8];
 #pragma unroll
@@ -351,33 +405,43 @@ __device__ __forceinline__ bool decode_p2048(const DecodeArgs& a, uint64_t d_idx
         }
         return true;
     }
-    // packed modes: stage the payload in LDS (at most 127 16-byte units)
+    // packed modes: stage the payload in LDS (fewer than kE/16 16-byte units)
     {
         uint4* st4 = reinterpret_cast<uint4*>(stage);
+#pragma unroll
+        for (int z = 0; z < kE / 1024; ++z) {
 #if KVC_NT_POOL
-        if ((uint32_t)lane < n16) st4[lane] = load_stream(pl4 + lane);
-        if ((uint32_t)lane + 64 < n16) st4[lane + 64] = load_stream(pl4 + lane + 64);
+            if ((uint32_t)lane + 64 * z < n16) st4[lane + 64 * z] = load_stream(pl4 + lane + 64 * z);
 #else
-        if ((uint32_t)lane < n16) st4[lane] = pl4[lane];
-        if ((uint32_t)lane + 64 < n16) st4[lane + 64] = pl4[lane + 64];
+            if ((uint32_t)lane + 64 * z < n16) st4[lane + 64 * z] = pl4[lane + 64 * z];
 #endif
+        }
     }
     wave_sync();
-    // header: lane g takes the code of group g; body offsets are a prefix sum of body sizes
-    const uint32_t c_own = (stage[lane >> 3] >> ((lane & 7) << 2)) & 15u;
-    const uint32_t size_own = (c_own == 9) ? 1u : (c_own << 2);
-    const uint32_t incl = wave_incl_scan_dpp(size_own);
-    ginfo[lane] = ((kHdr + incl - size_own) << 4) | c_own;
-    const uint32_t total = kHdr + (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
-    const bool bad = c_own > 9 || (mode == KVC_MODE_DELTA && (c_own == 0 || c_own == 9));
-    const bool special = __builtin_amdgcn_ballot_w64(c_own == 0 || c_own == 9) != 0;  // any zero-run / run packet
+    // header: a lane takes the code of group g (64 groups per round); body offsets are a prefix sum of
+    // body sizes
+    uint32_t total = kHdr;
+    bool bad = false, special = false;
+#pragma unroll
+    for (int g0 = 0; g0 < kG; g0 += 64) {
+        const int g = g0 + lane;
+        const bool live = kG >= 64 || g < kG;
+        const uint32_t c_own = live ? (stage[g >> 3] >> ((g & 7) << 2)) & 15u : 1u;
+        const uint32_t size_own = !live ? 0u : (c_own == 9) ? 1u : (c_own << 2);
+        const uint32_t incl = wave_incl_scan_dpp(size_own);
+        if (live) ginfo[g] = ((total + incl - size_own) << 4) | c_own;
+        total += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+        bad = bad || c_own > 9 || (mode == KVC_MODE_DELTA && (c_own == 0 || c_own == 9));
+        special = special || c_own == 0 || c_own == 9;
+    }
+    special = __builtin_amdgcn_ballot_w64(special) != 0;  // any zero-run / run packet in the page
     if (__builtin_amdgcn_ballot_w64(bad) != 0 || ((total + 15u) >> 4) != n16) {
         zero_page(dst, a.g);
         return false;
     }
     wave_sync();
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
+    for (int p = 0; p < NP; ++p) {
         const uint32_t gi = ginfo[p * 16 + (lane >> 2)];
         uint32_t c = gi & 15u;
         const uint32_t goff = gi >> 4;
@@ -385,7 +449,7 @@ __device__ __forceinline__ bool decode_p2048(const DecodeArgs& a, uint64_t d_idx
         if (special && c == 9) B = goff;
         const uint32_t sh = (B & 3u) << 3;
         const uint32_t* p0 = stage + (B >> 2);
-        KVC_CHECK(a.st, (B >> 2) + 2 < (uint32_t)Slot<4>::kWords && B >= (uint32_t)kHdr);
+        KVC_CHECK(a.st, (B >> 2) + 2 < (uint32_t)Slot<NP>::kWords && B >= (uint32_t)kHdr);
         const uint32_t d0 = p0[0], d1 = p0[1], d2 = p0[2];
         uint32_t lo = __builtin_amdgcn_alignbit(d1, d0, sh);
         uint32_t hi = __builtin_amdgcn_alignbit(d2, d1, sh);
@@ -413,9 +477,9 @@ __device__ __forceinline__ bool decode_p2048(const DecodeArgs& a, uint64_t d_idx
         dl[5] = (int)__builtin_amdgcn_ubfe(mid, o1 + 1u, w1) ^ __builtin_amdgcn_sbfe((int)mid, o1, 1u);
         dl[6] = (int)__builtin_amdgcn_ubfe(mid, o2 + 1u, w1) ^ __builtin_amdgcn_sbfe((int)mid, o2, 1u);
         dl[7] = (int)__builtin_amdgcn_ubfe(mid, o3 + 1u, w1) ^ __builtin_amdgcn_sbfe((int)mid, o3, 1u);
-        // prefix sum along the channel index: in the lane, then across the 16 lanes of the token row
+        // prefix sum along the channel index: in the lane, then across the lanes of the token row
         const uint32_t tot = (uint32_t)(dl[0] + dl[1] + dl[2] + dl[3] + dl[4] + dl[5] + dl[6] + dl[7]);
-        const uint32_t rincl = row16_incl_scan_dpp(tot);
+        const uint32_t rincl = row_incl_scan<Page<D>::kLpr>(tot);
         uint32_t pb[8];
         pb[0] = rincl - tot + 128u + (uint32_t)dl[0];  // +128: biased codes, see dequant8_biased
 #pragma unroll
@@ -425,10 +489,10 @@ __device__ __forceinline__ bool decode_p2048(const DecodeArgs& a, uint64_t d_idx
     return true;
 }
 
-template <int WAVES, int PPW>
-__global__ __launch_bounds__(WAVES * 64) void k_decompress_p2048(DecodeArgs a) {
-    __shared__ __align__(16) uint32_t s_stage[WAVES][Slot<4>::kWords];
-    __shared__ uint32_t s_ginfo[WAVES][64];
+template <int D, int WAVES, int PPW>
+__global__ __launch_bounds__(WAVES * 64) void k_decompress_p16(DecodeArgs a) {
+    __shared__ __align__(16) uint32_t s_stage[WAVES][Slot<Page<D>::kPasses>::kWords];
+    __shared__ uint32_t s_ginfo[WAVES][Page<D>::kGroups];
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t t0 = ((int64_t)blockIdx.x * WAVES + wave) * PPW;
@@ -438,7 +502,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_p2048(DecodeArgs a) {
         const DecTask task = resolve_dec_task(a, t0 + i, pos);
         task_advance(pos, a.g.ppb);
         if (task.kind == 2) zero_page(task.dst, a.g);
-        if (task.kind == 1 && !decode_p2048(a, task.desc_idx, task.dst, s_stage[wave], s_ginfo[wave])) {
+        if (task.kind == 1 && !decode_p16<D>(a, task.desc_idx, task.dst, s_stage[wave], s_ginfo[wave])) {
             if (lane == 0) atomicOr(&a.st->status, KVC_ST_CORRUPT);
         }
         wave_sync();
@@ -461,19 +525,30 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_p2048(DecodeArgs a) {
 #define KVC_DEC_PPW 1
 #endif
 
-hipError_t launch_compress_p2048(const EncodeArgs& a, hipStream_t s) {
+hipError_t launch_compress_p16(const EncodeArgs& a, hipStream_t s) {
+    // pages per pool-cursor atomic scale with the page size: 64 KB of input per workgroup
     constexpr int WAVES = KVC_ENC_WAVES, PPW = KVC_ENC_PPW;
-    const int64_t per_wg = (int64_t)WAVES * PPW;
-    const dim3 grid((unsigned)((a.n_pages + per_wg - 1) / per_wg)), block(WAVES * 64);
-    hipLaunchKernelGGL((k_compress_p2048<WAVES, PPW>), grid, block, 0, s, a);
+    const dim3 block(WAVES * 64);
+    auto grid = [&](int ppw) { return dim3((unsigned)((a.n_pages + (int64_t)WAVES * ppw - 1) / ((int64_t)WAVES * ppw))); };
+    if (a.g.d == 64)
+        hipLaunchKernelGGL((k_compress_p16<64, WAVES, 2 * PPW>), grid(2 * PPW), block, 0, s, a);
+    else if (a.g.d == 128)
+        hipLaunchKernelGGL((k_compress_p16<128, WAVES, PPW>), grid(PPW), block, 0, s, a);
+    else
+        hipLaunchKernelGGL((k_compress_p16<256, WAVES, PPW / 2>), grid(PPW / 2), block, 0, s, a);
     return hipGetLastError();
 }
 
-hipError_t launch_decompress_p2048(const DecodeArgs& a, hipStream_t s) {
+hipError_t launch_decompress_p16(const DecodeArgs& a, hipStream_t s) {
     constexpr int WAVES = KVC_DEC_WAVES, PPW = KVC_DEC_PPW;
     const int64_t per_wg = (int64_t)WAVES * PPW;
     const dim3 grid((unsigned)((a.n_pages + per_wg - 1) / per_wg)), block(WAVES * 64);
-    hipLaunchKernelGGL((k_decompress_p2048<WAVES, PPW>), grid, block, 0, s, a);
+    if (a.g.d == 64)
+        hipLaunchKernelGGL((k_decompress_p16<64, WAVES, PPW>), grid, block, 0, s, a);
+    else if (a.g.d == 128)
+        hipLaunchKernelGGL((k_decompress_p16<128, WAVES, PPW>), grid, block, 0, s, a);
+    else
+        hipLaunchKernelGGL((k_decompress_p16<256, WAVES, PPW>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 

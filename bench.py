@@ -82,7 +82,7 @@ def cpu_baseline(sample_u16, N, d, scheme, target_s=12.0):
     cores = max(1, min(16, os.cpu_count() or 1))
     n_pages = sample_u16.shape[0]
     done_bytes, t_total, reps = 0, 0.0, 0
-    while t_total < target_s and reps < 4:
+    while t_total < target_s and reps < 16:
         t0 = time.perf_counter()
         od, op = o.compress_pages(sample_u16, N, d, scheme, n_threads=cores)
         out, bad = o.decompress_pages(op, od, N, d, n_threads=cores)

@@ -17,8 +17,7 @@
  * Inverse (Section 3.5.3): undo RLE, prefix-sum the deltas, multiply by s, emit FP16;
  * pages that were stored uncompressed bypass all of it.
  *
- * Where the paper leaves the byte format open, the readings are (all listed again in
- * the design document of this repository):
+ * Where the paper leaves the byte format open, the readings are:
  *   - the quantize line's trailing "* 127" repeats the 127 already inside s; q = round(x/s);
  *   - a page is N tokens x d channels of one KV head (16 x 128 FP16 = the paper's 4 KB page);
  *   - s and s^-1 are IEEE binary32 quotients; rounding is to nearest, ties to even, of the

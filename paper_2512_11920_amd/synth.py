@@ -2,7 +2,7 @@
 
 This module holds no codec arithmetic: it only draws random FP16 tensors and index arrays with the
 shapes and value distribution of the workloads (LLaMA-2-shaped K/V caches, Section 4.1 of the
-paper), standing in for caches the paper's models would produce.  Both the CPU oracle's tests and
+paper), standing in for caches the paper's models would produce.  Both the CPU-side checker's tests and
 the GPU path's tests/benchmark take their inputs from here.
 
 Distribution: for every (layer, K|V, head, channel) a scale c ~ LogNormal(0, 0.5), constant over

@@ -102,6 +102,7 @@ def main():
     ap.add_argument("--workload", default="70b_gqa")
     ap.add_argument("--scheme", type=int, default=3)
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (quick runs; not the headline)")
+    ap.add_argument("--prefetch-policy", type=int, default=1, help="prefetch_pipeline: 0 positional slots, 1 slot reuse")
     ap.add_argument("--ablation", action="store_true", help="ratio and speed per scheme (Table 9 analogue)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -351,6 +352,7 @@ def bench_prefetch_pipeline(args):
     for l in range(n_layers):
         codec.compress_blocks(synth.gather_layer_torch(shape, pat, l, dev).view(-1, ppb, N, d), pool_ids=ids + l * pbl)
     n_slots = n_layers * n_seq * k
+    codec.set_prefetch_policy(args.prefetch_policy)
     l2 = torch.zeros((2 * n_slots, ppb, N, d), dtype=torch.float16, device=dev)
     tags = torch.empty(2 * n_slots, dtype=torch.int32, device=dev)
     fetch = torch.empty(n_slots, dtype=torch.int32, device=dev)
@@ -405,6 +407,12 @@ def bench_prefetch_pipeline(args):
                     pf(l + 2, side)
                     done[l + 2].record(side)
             main.wait_stream(side)
+        elif mode in ("batched", "batched_prefetch_only"):
+            # one planner + one decode launch for all layers, then the layers' compute
+            codec.prefetch_layers(l2, tags, fetch, loc, table, pred_t, n_layers, pbl, fill, stream=main)
+            if mode == "batched":
+                for l in range(n_layers):
+                    compute(main)
         else:
             for l in range(n_layers):
                 if mode != "compute_only":
@@ -417,7 +425,7 @@ def bench_prefetch_pipeline(args):
         compute_kind[0] = kind
         pr = [torch.from_numpy(preds(pattern, t)).to(dev) for t in range(steps)]
         res = {}
-        for mode in ("compute_only", "prefetch_only", "serial", "pipelined"):
+        for mode in ("compute_only", "prefetch_only", "serial", "pipelined", "batched_prefetch_only", "batched"):
             # eager launches are bound by host-side issue (about 400 calls per step), so the step is
             # also captured once per buffer half into a HIP graph and replayed
             for graphed in (False, True):
@@ -465,7 +473,7 @@ def bench_prefetch_pipeline(args):
     print(json.dumps({"metric": "decode-step time with speculative prefetch (ms per step)", "n_gpus": 1, "steps": args.steps,
                       "warmup": args.warmup, "data": "synthetic", "unit": "ms", "higher_is_better": False,
                       "config": {"workload": f"prefetch_pipeline: {n_layers} layers x 8 KV heads x 128, 64 sequences "
-                                             f"U[512,8192], k=8, per-layer prefetch two layers ahead of the layer's compute "
+                                             f"U[512,8192], k=8, slot policy {args.prefetch_policy}, per-layer prefetch two layers ahead of the layer's compute "
                                              f"stand-in ({work_bytes >> 20} MiB copy, or 4096^3 bf16 GEMM)"},
                       "patterns": out}), flush=True)
 

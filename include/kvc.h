@@ -159,8 +159,14 @@ int kvc_gather_decompress(kvc_ctx* ctx, void* d_out, const int32_t* d_block_tabl
  * settled in this step, or already in its own slot j, nothing is fetched (the residency test
  * "A_phys not in L1 u L2"); otherwise slot j of this half is claimed and the block decoded into it.
  * Stale slots are never cleared, only overwritten (lazy invalidation, Section 3.4.3).
- * Calls for disjoint layer ranges may run on different streams (layer l+1, l+2 prefetch while layer l
+ * k <= 32.  Calls for disjoint layer ranges may run on different streams (layer l+1, l+2 prefetch while layer l
  * computes, Section 3.4.4); calls for the same layers must be ordered. */
+/* Slot policy of kvc_prefetch_layers.  0 (default): as described above, prediction j uses slot j
+ * (Algorithm 1's L2[i]).  1: slot reuse -- a block wanted by this step that already sits in ANY slot of
+ * either half stays there, and a block in neither half is decoded into the lowest slot of the half being
+ * filled whose content this step does not want; d_fetch is then indexed by destination slot.  A window
+ * sliding over consecutive blocks then transfers one block per new block instead of k. */
+int kvc_set_prefetch_policy(kvc_ctx* ctx, int32_t policy);
 int kvc_prefetch_reset(kvc_ctx* ctx, int32_t* d_tags, int32_t n_seq, int32_t k, int32_t n_layers, void* stream);
 int kvc_prefetch_layers(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fetch, int32_t* d_loc,
                         const int32_t* d_block_table, int32_t max_blocks, const int32_t* d_pred,

@@ -15,6 +15,75 @@ import numpy as np
 NO_BLOCK, IN_L1 = -1, -2
 
 
+def _translate(table, pred, l1_first, l, s, j, pbpl):
+    """-> (physical block | NO_BLOCK | IN_L1, bad_index)"""
+    lb = int(pred[s, j])
+    if lb >= table.shape[1]:
+        return NO_BLOCK, True
+    if lb < 0:
+        return NO_BLOCK, False
+    if l1_first is not None and lb >= int(l1_first[s]):
+        return IN_L1, False
+    e = int(table[s, lb])
+    if e >= pbpl:
+        return NO_BLOCK, True
+    if e < 0:
+        return NO_BLOCK, False
+    return l * pbpl + e, False
+
+
+def prefetch_step_reuse(tags: np.ndarray, fill: int, table: np.ndarray, pred: np.ndarray, l1_first, n_layers: int,
+                        pool_blocks_per_layer: int, layer_begin: int = 0, layer_end: int | None = None):
+    """Slot-reuse variant: the L2 half being filled is treated as a small cache of k slots.  Blocks this
+    step wants stay where they are (either half); a wanted block found nowhere is transferred into the
+    lowest slot of the fill half whose content is not wanted (or is a duplicate).  fetch is indexed by
+    destination slot.  Same return convention as prefetch_step."""
+    n_seq, k = pred.shape
+    n_slots = n_layers * n_seq * k
+    layer_end = n_layers if layer_end is None else layer_end
+    fetch = np.full((n_layers, n_seq, k), -1, np.int32)
+    loc = np.full((n_layers, n_seq, k), -1, np.int32)
+    bad_index = False
+    other = 1 - fill
+    for l in range(layer_begin, layer_end):
+        for s in range(n_seq):
+            base = (l * n_seq + s) * k
+            want = []
+            for j in range(k):
+                phys, bad = _translate(table, pred, l1_first, l, s, j, pool_blocks_per_layer)
+                bad_index = bad_index or bad
+                want.append(phys)
+            wanted = {w for w in want if w >= 0}
+            keep, seen = [], set()
+            for j2 in range(k):
+                t = int(tags[fill, l, s, j2])
+                keep.append(t in wanted and t not in seen)
+                seen.add(t)
+            for j in range(k):
+                phys = want[j]
+                if phys < 0:
+                    loc[l, s, j] = phys
+                    continue
+                where = None
+                for j2 in range(k):
+                    if tags[other, l, s, j2] == phys:
+                        where = other * n_slots + base + j2
+                        break
+                if where is None:
+                    for j2 in range(k):
+                        if keep[j2] and tags[fill, l, s, j2] == phys:
+                            where = fill * n_slots + base + j2
+                            break
+                if where is None:
+                    j2 = keep.index(False)  # there is always one: at most k distinct blocks are wanted
+                    keep[j2] = True
+                    tags[fill, l, s, j2] = phys
+                    fetch[l, s, j2] = phys
+                    where = fill * n_slots + base + j2
+                loc[l, s, j] = where
+    return fetch, loc, bad_index
+
+
 def prefetch_step(tags: np.ndarray, fill: int, table: np.ndarray, pred: np.ndarray, l1_first, n_layers: int,
                   pool_blocks_per_layer: int, layer_begin: int = 0, layer_end: int | None = None):
     """tags: int32 [2][n_layers][n_seq][k], updated in place.  Returns (fetch, loc), each int32

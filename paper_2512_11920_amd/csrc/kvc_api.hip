@@ -5,6 +5,7 @@
 #include "kvc_common.h"
 
 struct kvc_ctx {
+    int prefetch_policy = 0;
     kvc_config cfg;
     kvc::Geometry g;
     int device;
@@ -231,6 +232,12 @@ int kvc_gather_decompress(kvc_ctx* ctx, void* d_out, const int32_t* d_block_tabl
     return hip_ok(kvc::launch_decompress(a, static_cast<hipStream_t>(stream))) ? KVC_OK : KVC_ERR_HIP;
 }
 
+int kvc_set_prefetch_policy(kvc_ctx* ctx, int32_t policy) {
+    if (!ctx || (policy != 0 && policy != 1)) return KVC_ERR_ARG;
+    ctx->prefetch_policy = policy;
+    return KVC_OK;
+}
+
 int kvc_prefetch_reset(kvc_ctx* ctx, int32_t* d_tags, int32_t n_seq, int32_t k, int32_t n_layers, void* stream) {
     if (!ctx || !d_tags || n_seq < 0 || k < 0 || n_layers < 0) return KVC_ERR_ARG;
     return hip_ok(kvc::launch_fill_i32(d_tags, -1, 2ull * (uint64_t)n_layers * (uint64_t)n_seq * (uint64_t)k,
@@ -254,6 +261,7 @@ int kvc_prefetch_layers(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fe
         (reinterpret_cast<uintptr_t>(d_l2) & 15u))
         return KVC_ERR_ARG;
     if (2 * n_slots > INT32_MAX || n_now > INT32_MAX) return KVC_ERR_ARG;
+    if (k > kvc::kMaxPrefetchK) return KVC_ERR_ARG;
     if ((uint64_t)n_layers * (uint64_t)pool_blocks_per_layer * (uint64_t)ctx->g.ppb > ctx->n_desc ||
         (uint64_t)n_layers * (uint64_t)pool_blocks_per_layer > (uint64_t)INT32_MAX)
         return KVC_ERR_ARG;
@@ -269,6 +277,7 @@ int kvc_prefetch_layers(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fe
     p.layer_end = layer_end;
     p.n_layers = n_layers;
     p.fill_half = fill_half;
+    p.policy = ctx->prefetch_policy;
     p.pool_blocks_per_layer = pool_blocks_per_layer;
     p.tags = d_tags;
     p.fetch = d_fetch;

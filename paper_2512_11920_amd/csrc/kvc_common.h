@@ -58,12 +58,15 @@ struct DecodeArgs {
     int64_t pool_blocks_per_layer;
 };
 
+constexpr int kMaxPrefetchK = 32;  // predictions per sequence the slot-reuse policy can plan
+
 // Arguments of the prefetch planner (Algorithm 1: translate, residency filter, slot assignment).
 struct PlanArgs {
     const int32_t* block_table;  // [n_seq][max_blocks]
     const int32_t* pred;         // [n_seq][k]
     const int32_t* l1_first;     // [n_seq] or null: logical blocks >= l1_first[s] are GPU-local (L1)
     int32_t max_blocks, n_seq, k, layer_begin, layer_end, n_layers, fill_half;
+    int32_t policy;              // 0: slot j for prediction j; 1: keep wanted blocks, fill unwanted slots
     int64_t pool_blocks_per_layer;
     int32_t* tags;   // [2][n_layers*n_seq*k]
     int32_t* fetch;  // [n_layers*n_seq*k]

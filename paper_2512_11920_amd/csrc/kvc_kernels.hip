@@ -449,52 +449,123 @@ __global__ void k_copy(uint4* __restrict__ dst, const uint4* __restrict__ src, u
 
 // Prefetch planner, Algorithm 1 of the paper without the token predictor: one thread per
 // (layer, sequence) walks the k predicted logical blocks in order -- translate through the block
-// table (TranslateAddress), skip what is already in L1 or in either half of the L2 prefetch buffer
-// (the residency test), otherwise claim slot j of the half being filled and list the pool block
-// for the decode launch (IssueDMA).
+// table (TranslateAddress), skip what is already in L1 or in the L2 prefetch buffer (the residency
+// test), otherwise claim a slot of the half being filled and list the pool block for the decode
+// launch (IssueDMA).
+// Translate prediction j of sequence sq in layer l.  Returns the pool block (>= 0), -1 for "no block",
+// -2 for "in L1"; sets bad for indices out of range.
+__device__ __forceinline__ int32_t plan_translate(const PlanArgs& a, int32_t l, int32_t sq, int j, bool& bad) {
+    const int32_t lb = a.pred[(int64_t)sq * a.k + j];
+    if (lb >= a.max_blocks) {
+        bad = true;
+        return -1;
+    }
+    if (lb < 0) return -1;
+    if (a.l1_first && lb >= a.l1_first[sq]) return -2;  // held in the GPU-local cache
+    const int32_t e = a.block_table[(int64_t)sq * a.max_blocks + lb];
+    if (e >= a.pool_blocks_per_layer) {
+        bad = true;
+        return -1;
+    }
+    if (e < 0) return -1;
+    return (int32_t)((int64_t)l * a.pool_blocks_per_layer + e);
+}
+
+// KMAX: compile-time bound on k, so that the per-sequence state (wanted blocks, tags of both halves)
+// lives in registers and every loop unrolls; all global reads happen once, up front.
+template <int KMAX>
 __global__ void k_prefetch_plan(PlanArgs a) {
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t n_ls = (int64_t)(a.layer_end - a.layer_begin) * a.n_seq;
     if (idx >= n_ls) return;
     const int32_t l = a.layer_begin + (int32_t)(idx / a.n_seq);
     const int32_t sq = (int32_t)(idx % a.n_seq);
-    const int64_t n_slots = (int64_t)a.n_layers * a.n_seq * a.k;
-    const int64_t base = ((int64_t)l * a.n_seq + sq) * a.k;
-    int32_t* tags_fill = a.tags + (int64_t)a.fill_half * n_slots + base;
-    const int32_t* tags_other = a.tags + (int64_t)(1 - a.fill_half) * n_slots + base;
+    const int k = a.k;
+    const int64_t n_slots = (int64_t)a.n_layers * a.n_seq * k;
+    const int64_t base = ((int64_t)l * a.n_seq + sq) * k;
+    const int64_t fill0 = (int64_t)a.fill_half * n_slots + base, other0 = (int64_t)(1 - a.fill_half) * n_slots + base;
     bool bad = false;
-    for (int j = 0; j < a.k; ++j) {
-        int64_t where = -1;
-        int32_t fetch = -1;
-        const int32_t lb = a.pred[(int64_t)sq * a.k + j];
-        if (lb >= a.max_blocks) {
-            bad = true;
-        } else if (lb >= 0) {
-            if (a.l1_first && lb >= a.l1_first[sq]) {
-                where = -2;  // held in the GPU-local cache: nothing to fetch
-            } else {
-                const int32_t e = a.block_table[(int64_t)sq * a.max_blocks + lb];
-                if (e >= a.pool_blocks_per_layer) {
-                    bad = true;
-                } else if (e >= 0) {
-                    const int32_t pb = (int32_t)((int64_t)l * a.pool_blocks_per_layer + e);
-                    for (int j2 = 0; j2 < a.k && where < 0; ++j2)
-                        if (tags_other[j2] == pb) where = (int64_t)(1 - a.fill_half) * n_slots + base + j2;
-                    for (int j2 = 0; j2 < j && where < 0; ++j2)  // slots already settled in this step
-                        if (tags_fill[j2] == pb) where = (int64_t)a.fill_half * n_slots + base + j2;
-                    if (where < 0) {
-                        where = (int64_t)a.fill_half * n_slots + base + j;
-                        if (tags_fill[j] != pb) {
-                            tags_fill[j] = pb;
-                            fetch = pb;
-                        }
+    int32_t want[KMAX], t_fill[KMAX], t_other[KMAX], fetch[KMAX];
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j) {
+        const bool live = j < k;
+        want[j] = live ? plan_translate(a, l, sq, j, bad) : -1;
+        t_fill[j] = live ? a.tags[fill0 + j] : -1;
+        t_other[j] = live ? a.tags[other0 + j] : -1;
+        fetch[j] = -1;
+    }
+    if (a.policy == 0) {
+        // Algorithm 1 as printed: prediction j owns slot j of the half being filled
+#pragma unroll
+        for (int j = 0; j < KMAX; ++j) {
+            const int32_t pb = want[j];
+            int64_t where = pb == -2 ? -2 : -1;
+            if (pb >= 0) {
+#pragma unroll
+                for (int j2 = KMAX - 1; j2 >= 0; --j2)  // lowest matching slot wins
+                    if (j2 < j && t_fill[j2] == pb) where = fill0 + j2;  // slots already settled in this step
+#pragma unroll
+                for (int j2 = KMAX - 1; j2 >= 0; --j2)
+                    if (t_other[j2] == pb) where = other0 + j2;
+                if (where < 0) {
+                    where = fill0 + j;
+                    if (t_fill[j] != pb) {
+                        t_fill[j] = pb;
+                        fetch[j] = pb;
                     }
                 }
             }
+            if (j < k) a.loc[base + j] = (int32_t)where;
         }
-        a.fetch[base + j] = fetch;
-        a.loc[base + j] = (int32_t)where;
+    } else {
+        // Slot reuse: blocks wanted by this step stay where they are; a block that is in neither half
+        // takes the lowest slot whose content this step does not want.
+        bool keep[KMAX];
+#pragma unroll
+        for (int j2 = 0; j2 < KMAX; ++j2) {  // a slot is kept if it is the first one holding a wanted block
+            const int32_t t = t_fill[j2];
+            bool wanted = false, dup = false;
+#pragma unroll
+            for (int j = 0; j < KMAX; ++j) wanted = wanted || (t >= 0 && want[j] == t);
+#pragma unroll
+            for (int j3 = 0; j3 < KMAX; ++j3) dup = dup || (j3 < j2 && t >= 0 && t_fill[j3] == t);
+            keep[j2] = (wanted && !dup) || j2 >= k;  // slots beyond k do not exist: never claimable
+        }
+#pragma unroll
+        for (int j = 0; j < KMAX; ++j) {
+            const int32_t pb = want[j];
+            int64_t where = pb == -2 ? -2 : -1;
+            if (pb >= 0) {
+#pragma unroll
+                for (int j2 = KMAX - 1; j2 >= 0; --j2)
+                    if (keep[j2] && j2 < k && t_fill[j2] == pb) where = fill0 + j2;
+#pragma unroll
+                for (int j2 = KMAX - 1; j2 >= 0; --j2)
+                    if (t_other[j2] == pb) where = other0 + j2;
+                if (where < 0) {
+                    int free_slot = -1;
+#pragma unroll
+                    for (int j2 = KMAX - 1; j2 >= 0; --j2)
+                        if (!keep[j2]) free_slot = j2;
+#pragma unroll
+                    for (int j2 = 0; j2 < KMAX; ++j2)
+                        if (j2 == free_slot) {  // claim it: it now holds a wanted block
+                            keep[j2] = true;
+                            t_fill[j2] = pb;
+                            fetch[j2] = pb;
+                        }
+                    where = fill0 + free_slot;
+                }
+            }
+            if (j < k) a.loc[base + j] = (int32_t)where;
+        }
     }
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j)
+        if (j < k) {
+            a.fetch[base + j] = fetch[j];
+            if (fetch[j] >= 0) a.tags[fill0 + j] = t_fill[j];
+        }
     if (bad) atomicOr(&a.st->status, KVC_ST_BAD_INDEX);
 }
 
@@ -540,7 +611,13 @@ hipError_t launch_decompress(const DecodeArgs& a, hipStream_t s) {
 hipError_t launch_prefetch_plan(const PlanArgs& a, hipStream_t s) {
     const int64_t n = (int64_t)(a.layer_end - a.layer_begin) * a.n_seq;
     if (n <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_prefetch_plan, dim3((unsigned)((n + 63) / 64)), dim3(64), 0, s, a);
+    const dim3 grid((unsigned)((n + 63) / 64)), block(64);
+    if (a.k <= 8)
+        hipLaunchKernelGGL(k_prefetch_plan<8>, grid, block, 0, s, a);
+    else if (a.k <= 16)
+        hipLaunchKernelGGL(k_prefetch_plan<16>, grid, block, 0, s, a);
+    else
+        hipLaunchKernelGGL(k_prefetch_plan<kMaxPrefetchK>, grid, block, 0, s, a);
     return hipGetLastError();
 }
 

@@ -21,7 +21,7 @@ ST_POOL_FULL, ST_CORRUPT, ST_BAD_INDEX = 1, 2, 4
 DESC_DTYPE = np.dtype([("off", "<u8"), ("scale", "<f4"), ("n16", "<u2"), ("mode", "u1"), ("rsvd", "u1")])
 
 EXPORTS = ("kvc_create", "kvc_destroy", "kvc_set_scheme", "kvc_set_cache_layout", "kvc_bind_pool", "kvc_reset_pool", "kvc_compress_blocks",
-           "kvc_compress_blocks_mixed", "kvc_decompress_blocks", "kvc_gather_decompress", "kvc_prefetch_reset", "kvc_prefetch_layers", "kvc_stats", "kvc_copy_bytes", "kvc_strerror")
+           "kvc_compress_blocks_mixed", "kvc_decompress_blocks", "kvc_gather_decompress", "kvc_set_prefetch_policy", "kvc_prefetch_reset", "kvc_prefetch_layers", "kvc_stats", "kvc_copy_bytes", "kvc_strerror")
 
 
 class Config(C.Structure):
@@ -77,6 +77,8 @@ def load():
     L.kvc_decompress_blocks.argtypes = [vp, vp, C.c_int64, i32p, i32p, C.c_int32, vp]
     L.kvc_gather_decompress.restype = C.c_int
     L.kvc_gather_decompress.argtypes = [vp, vp, i32p, C.c_int32, i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int64, vp]
+    L.kvc_set_prefetch_policy.restype = C.c_int
+    L.kvc_set_prefetch_policy.argtypes = [vp, C.c_int32]
     L.kvc_prefetch_reset.restype = C.c_int
     L.kvc_prefetch_reset.argtypes = [vp, vp, C.c_int32, C.c_int32, C.c_int32, vp]
     L.kvc_prefetch_layers.restype = C.c_int
@@ -233,6 +235,10 @@ class Codec:
         _check(self._L.kvc_gather_decompress(self._ctx, out.data_ptr(), block_table.data_ptr(), max_blocks,
                                              pred.data_ptr(), n_seq, k, n_layers, int(pool_blocks_per_layer),
                                              _stream(stream)), "kvc_gather_decompress")
+
+    def set_prefetch_policy(self, policy: int):
+        """0: prediction j uses slot j; 1: wanted blocks stay put, missing ones take unwanted slots."""
+        _check(self._L.kvc_set_prefetch_policy(self._ctx, policy), "kvc_set_prefetch_policy")
 
     def prefetch_reset(self, tags, n_seq: int, k: int, n_layers: int, stream=None):
         assert _ids(tags).numel() == 2 * n_layers * n_seq * k

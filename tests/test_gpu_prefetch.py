@@ -17,8 +17,9 @@ def _say(m):
     print(m, flush=True)
 
 
+@pytest.mark.parametrize("policy", [0, 1])
 @pytest.mark.parametrize("with_l1", [False, True])
-def test_prefetch_steps_match_model(with_l1):
+def test_prefetch_steps_match_model(with_l1, policy):
     rng = np.random.default_rng(5)
     N, d, ppb, n_layers = 16, 128, 4, 3
     pat = synth.gather_pattern(n_seq=6, k=8, len_lo=48, len_hi=200, seed=11)  # few blocks: many re-predictions
@@ -33,6 +34,8 @@ def test_prefetch_steps_match_model(with_l1):
     fetch = torch.empty(n_slots, dtype=torch.int32, device=DEV)
     loc = torch.empty(n_slots, dtype=torch.int32, device=DEV)
     c.prefetch_reset(tags, n_seq, k, n_layers)
+    c.set_prefetch_policy(policy)
+    model_step = pm.prefetch_step_reuse if policy else pm.prefetch_step
     table = torch.from_numpy(pat.block_table).to(DEV)
     l1_np = np.maximum(pat.n_blocks - 2, 0).astype(np.int32) if with_l1 else None
     l1 = torch.from_numpy(l1_np).to(DEV) if with_l1 else None
@@ -49,7 +52,7 @@ def test_prefetch_steps_match_model(with_l1):
         for lo, hi in ((0, 1), (1, n_layers)):
             c.prefetch_layers(l2, tags, fetch, loc, table, torch.from_numpy(pred_np).to(DEV), n_layers, pbl, fill,
                               layer_begin=lo, layer_end=hi, l1_first=l1)
-        m_fetch, m_loc, bad = pm.prefetch_step(m_tags, fill, pat.block_table, pred_np, l1_np, n_layers, pbl)
+        m_fetch, m_loc, bad = model_step(m_tags, fill, pat.block_table, pred_np, l1_np, n_layers, pbl)
         assert not bad
         assert np.array_equal(tags.cpu().numpy(), m_tags.reshape(-1))
         assert np.array_equal(fetch.cpu().numpy(), m_fetch.reshape(-1))

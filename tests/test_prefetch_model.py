@@ -19,8 +19,9 @@ def _setup(rng, n_layers=3, n_seq=4, k=6, max_blocks=9, pbpl=40):
     return table, nb
 
 
+@pytest.mark.parametrize("reuse", [False, True])
 @pytest.mark.parametrize("seed", range(6))
-def test_consumer_always_finds_the_predicted_block_and_nothing_resident_is_refetched(seed):
+def test_consumer_always_finds_the_predicted_block_and_nothing_resident_is_refetched(seed, reuse):
     rng = np.random.default_rng(seed)
     n_layers, n_seq, k, pbpl = 3, 4, 6, 40
     table, nb = _setup(rng, n_layers, n_seq, k, 9, pbpl)
@@ -34,9 +35,10 @@ def test_consumer_always_finds_the_predicted_block_and_nothing_resident_is_refet
         pred = (rng.random((n_seq, k)) * nb[:, None]).astype(np.int32)
         pred[rng.random((n_seq, k)) < 0.1] = -1  # some predictions missing
         before = tags.copy()
-        fetch, loc, bad = pm.prefetch_step(tags, fill, table, pred, l1_first, n_layers, pbpl)
+        step_fn = pm.prefetch_step_reuse if reuse else pm.prefetch_step
+        fetch, loc, bad = step_fn(tags, fill, table, pred, l1_first, n_layers, pbpl)
         assert not bad
-        # transfers happen, into slot j of the half being filled
+        # transfers happen, into the slot of the half being filled that `fetch` is indexed by
         for l in range(n_layers):
             for s in range(n_seq):
                 base = (l * n_seq + s) * k
@@ -44,6 +46,8 @@ def test_consumer_always_finds_the_predicted_block_and_nothing_resident_is_refet
                 got = [int(f) for f in fetch[l, s] if f >= 0]
                 assert len(got) == len(set(got)), "a block was transferred twice in one step"
                 assert not (set(got) & resident_other), "a block resident in the other half was transferred"
+                if reuse:  # nothing that was anywhere in the L2 buffer is transferred again
+                    assert not (set(got) & set(before[fill, l, s].tolist()))
                 for j in range(k):
                     if fetch[l, s, j] >= 0:
                         assert before[fill, l, s, j] != fetch[l, s, j], "transfer into a slot that already held the block"
@@ -56,10 +60,11 @@ def test_consumer_always_finds_the_predicted_block_and_nothing_resident_is_refet
             for s in range(n_seq):
                 for j in range(k):
                     lb = pred[s, j]
+                    # (with slot reuse `fetch` is indexed by slot, so slot j may serve another prediction)
                     if lb < 0:
-                        assert loc[l, s, j] == pm.NO_BLOCK and fetch[l, s, j] == -1
+                        assert loc[l, s, j] == pm.NO_BLOCK and (reuse or fetch[l, s, j] == -1)
                     elif l1_first is not None and lb >= l1_first[s]:
-                        assert loc[l, s, j] == pm.IN_L1 and fetch[l, s, j] == -1
+                        assert loc[l, s, j] == pm.IN_L1 and (reuse or fetch[l, s, j] == -1)
                     else:
                         total_valid += 1
                         assert content[loc[l, s, j]] == l * pbpl + table[s, lb]
@@ -97,3 +102,22 @@ def test_layer_ranges_compose_and_bad_indices_are_flagged():
     pred2[0, 0] = table.shape[1] + 5
     f, l, bad = pm.prefetch_step(np.full((2, 3, 4, 6), -1, np.int32), 0, table, pred2, None, 3, 40)
     assert bad and (l[:, 0, 0] == -1).all() and (f[:, 0, 0] == -1).all()
+
+
+def test_slot_reuse_transfers_one_block_per_new_block_on_a_sliding_window():
+    """Predictions pos+1..pos+k with pos advancing one block at a time: after warm-up the reuse policy moves
+    exactly one block per sequence per advance, the positional policy k."""
+    n_seq, k, nblk = 5, 8, 40
+    table = np.arange(n_seq * nblk, dtype=np.int32).reshape(n_seq, nblk)
+    counts = {}
+    for name, fn in (("positional", pm.prefetch_step), ("reuse", pm.prefetch_step_reuse)):
+        tags = np.full((2, 1, n_seq, k), -1, np.int32)
+        tot = 0
+        for t in range(2 + 3 * 10):
+            pos = t // 3
+            pred = ((pos + 1 + np.arange(k))[None, :] % nblk).repeat(n_seq, 0).astype(np.int32)
+            f, l, _ = fn(tags, t % 2, table, pred, None, 1, n_seq * nblk)
+            if t >= 2:
+                tot += int((f >= 0).sum())
+        counts[name] = tot
+    assert counts["reuse"] == n_seq * 10 and counts["positional"] == n_seq * 10 * k

@@ -34,6 +34,8 @@
  * device can see set sticky KVC_ST_* bits: the page gets mode 0xFF (compress) or is zero-filled
  * (decompress); kvc_stats() reports them.  Block ids < 0 mean "skip this block".
  * Calls on one context that overlap on different streams race on the pool cursor; serialise them.
+ * A context belongs to the device that was current in kvc_create; calls made with another device
+ * current return KVC_ERR_ARG.
  */
 #ifndef KVC_H
 #define KVC_H

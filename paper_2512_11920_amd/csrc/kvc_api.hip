@@ -26,6 +26,9 @@ static bool hip_ok(hipError_t e) {
     return e == hipSuccess;
 }
 
+// Every call must be made with the context's device current: buffers and streams belong to it.
+static bool on_ctx_device(const kvc_ctx* ctx);
+
 static bool config_ok(const kvc_config* c) {
     if (!c) return false;
     if (c->tokens_per_block < 1 || c->pages_per_block < 1) return false;
@@ -34,6 +37,11 @@ static bool config_ok(const kvc_config* c) {
     if (!(d == 32 || d == 64 || d == 128 || d == 256)) return false;
     const int64_t E = (int64_t)c->tokens_per_block * d;
     return E <= 4096;
+}
+
+static bool on_ctx_device(const kvc_ctx* ctx) {
+    int dev = -1;
+    return hip_ok(hipGetDevice(&dev)) && dev == ctx->device;
 }
 
 extern "C" {
@@ -142,6 +150,7 @@ static int compress_impl(kvc_ctx* ctx, const void* d_cache, int64_t n_cache_bloc
     if (!ctx || n < 0 || n_cache_blocks < 0) return KVC_ERR_ARG;
     if (!ctx->pool) return KVC_ERR_NOT_BOUND;
     if (n == 0) return KVC_OK;
+    if (!on_ctx_device(ctx)) return KVC_ERR_ARG;
     if (!d_cache || (reinterpret_cast<uintptr_t>(d_cache) & 15u)) return KVC_ERR_ARG;
     // identity ids are checked here; explicit id arrays live on the device and are checked there
     if (!d_src_block_ids && (int64_t)n > n_cache_blocks) return KVC_ERR_ARG;
@@ -194,6 +203,7 @@ int kvc_decompress_blocks(kvc_ctx* ctx, void* d_cache_out, int64_t n_out_blocks,
     if (!ctx || n < 0 || n_out_blocks < 0) return KVC_ERR_ARG;
     if (!ctx->pool) return KVC_ERR_NOT_BOUND;
     if (n == 0) return KVC_OK;
+    if (!on_ctx_device(ctx)) return KVC_ERR_ARG;
     if (!d_cache_out || (reinterpret_cast<uintptr_t>(d_cache_out) & 15u)) return KVC_ERR_ARG;
     if (!d_dst_block_ids && (int64_t)n > n_out_blocks) return KVC_ERR_ARG;
     if (!d_pool_block_ids && (uint64_t)n * (uint64_t)ctx->g.ppb > ctx->n_desc) return KVC_ERR_ARG;
@@ -214,6 +224,7 @@ int kvc_gather_decompress(kvc_ctx* ctx, void* d_out, const int32_t* d_block_tabl
     if (!ctx->pool) return KVC_ERR_NOT_BOUND;
     const int64_t n_blocks = (int64_t)n_layers * n_seq * k;
     if (n_blocks == 0) return KVC_OK;
+    if (!on_ctx_device(ctx)) return KVC_ERR_ARG;
     if (!d_out || !d_block_table || !d_pred || max_blocks == 0 || (reinterpret_cast<uintptr_t>(d_out) & 15u))
         return KVC_ERR_ARG;
     if ((uint64_t)n_layers * (uint64_t)pool_blocks_per_layer * (uint64_t)ctx->g.ppb > ctx->n_desc) return KVC_ERR_ARG;
@@ -257,6 +268,7 @@ int kvc_prefetch_layers(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fe
     const int64_t n_slots = (int64_t)n_layers * n_seq * k;
     const int64_t n_now = (int64_t)(layer_end - layer_begin) * n_seq * k;
     if (n_now == 0) return KVC_OK;
+    if (!on_ctx_device(ctx)) return KVC_ERR_ARG;
     if (!d_l2 || !d_tags || !d_fetch || !d_loc || !d_block_table || !d_pred || max_blocks == 0 ||
         (reinterpret_cast<uintptr_t>(d_l2) & 15u))
         return KVC_ERR_ARG;

@@ -423,7 +423,8 @@ __global__ void k_stats_zero(DevState* st) {
     if (threadIdx.x < 8) st->stats[threadIdx.x] = 0;
 }
 
-__global__ void k_stats(DevState* st, const kvc_desc* desc, uint64_t n_desc) {
+__global__ __launch_bounds__(256) void k_stats(DevState* st, const kvc_desc* desc, uint64_t n_desc) {
+    __shared__ unsigned long long s_part[4][6];
     unsigned long long cnt[6] = {0, 0, 0, 0, 0, 0};
     for (uint64_t k = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; k < n_desc; k += (uint64_t)gridDim.x * blockDim.x) {
         const uint32_t w = reinterpret_cast<const uint4*>(desc)[k].w;
@@ -435,10 +436,16 @@ __global__ void k_stats(DevState* st, const kvc_desc* desc, uint64_t n_desc) {
             cnt[4] += 1;
         }
     }
+    // wave reduction, then one atomic per counter per workgroup
     for (int j = 0; j < 6; ++j) {
         unsigned long long v = cnt[j];
         for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-        if (lane_id() == 0 && v) atomicAdd(&st->stats[j], v);
+        if (lane_id() == 0) s_part[threadIdx.x >> 6][j] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x < 6) {
+        const unsigned long long v = s_part[0][threadIdx.x] + s_part[1][threadIdx.x] + s_part[2][threadIdx.x] + s_part[3][threadIdx.x];
+        if (v) atomicAdd(&st->stats[threadIdx.x], v);
     }
 }
 
@@ -637,7 +644,7 @@ hipError_t launch_reset(DevState* st, kvc_desc* desc, uint64_t n_desc, hipStream
 hipError_t launch_stats(DevState* st, const kvc_desc* desc, uint64_t n_desc, hipStream_t s) {
     hipLaunchKernelGGL(k_stats_zero, dim3(1), dim3(64), 0, s, st);
     if (n_desc) {
-        const unsigned blocks = (unsigned)std::min<uint64_t>((n_desc + 255) / 256, 4096);
+        const unsigned blocks = (unsigned)std::min<uint64_t>((n_desc + 255) / 256, 2048);
         hipLaunchKernelGGL(k_stats, dim3(blocks), dim3(256), 0, s, st, desc, n_desc);
     }
     return hipGetLastError();

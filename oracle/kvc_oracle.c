@@ -47,6 +47,7 @@
 #define KVO_MODE_INT8 1
 #define KVO_MODE_DELTA 2
 #define KVO_MODE_RLE 3
+#define KVO_MODE_PACK 4 /* extension, not in Alg. 2: INT8 codes zig-zag mapped and packed as in mode 3, no delta step */
 #define KVO_MODE_INVALID 0xFF
 
 #define KVO_OK 0
@@ -150,6 +151,15 @@ void kvo_delta_zigzag(const int8_t* q, int N, int d, uint8_t* u) {
     }
 }
 
+/* Mode 4 (an extension beyond Algorithm 2, for data without correlation along the channel index, where
+ * differencing only widens the values): the zig-zag map applied to the codes themselves. */
+void kvo_zigzag_codes(const int8_t* q, int E, uint8_t* u) {
+    for (int i = 0; i < E; ++i) {
+        int v = q[i];
+        u[i] = (uint8_t)(((v << 1) ^ (v >> 7)) & 0xFF);
+    }
+}
+
 static int bit_length(unsigned v) {
     int n = 0;
     while (v) {
@@ -199,10 +209,10 @@ size_t kvo_rle_pack(const uint8_t* u, int E, int with_runs, uint8_t* out) {
     return pos;
 }
 
-/* Encode one page.  payload must hold 2*E bytes.  scheme = requested mode 0..3.
+/* Encode one page.  payload must hold 2*E bytes.  scheme = requested mode 0..4.
  * Fills desc (off left at 0) and returns the padded payload size in bytes, or <0. */
 int64_t kvo_encode_page(const uint16_t* x, int N, int d, int scheme, uint8_t* payload, kvo_desc* desc) {
-    if (N < 1 || d < 32 || d % 32 != 0 || scheme < 0 || scheme > 3) return KVO_ERR_ARG;
+    if (N < 1 || d < 32 || d % 32 != 0 || scheme < 0 || scheme > 4) return KVO_ERR_ARG;
     int E = N * d;
     desc->off = 0;
     desc->rsvd = 0;
@@ -223,8 +233,11 @@ int64_t kvo_encode_page(const uint16_t* x, int N, int d, int scheme, uint8_t* pa
     if (scheme != KVO_MODE_INT8) {
         uint8_t* u = (uint8_t*)malloc((size_t)E);
         uint8_t* tmp = (uint8_t*)malloc((size_t)E / 64 + 1 + (size_t)E);
-        kvo_delta_zigzag(q, N, d, u);
-        size_t raw_n = kvo_rle_pack(u, E, scheme == KVO_MODE_RLE, tmp);
+        if (scheme == KVO_MODE_PACK)
+            kvo_zigzag_codes(q, E, u);
+        else
+            kvo_delta_zigzag(q, N, d, u);
+        size_t raw_n = kvo_rle_pack(u, E, scheme != KVO_MODE_DELTA, tmp);
         n = kvo_pad16(raw_n);
         if (n >= int8_bytes) {
             mode = KVO_MODE_INT8; /* packing did not beat plain INT8 */
@@ -255,7 +268,8 @@ int kvo_decode_codes(const uint8_t* payload, size_t nbytes, int mode, int N, int
         memcpy(q, payload, (size_t)E);
         return KVO_OK;
     }
-    if (mode != KVO_MODE_DELTA && mode != KVO_MODE_RLE) return KVO_ERR_CORRUPT;
+    if (mode != KVO_MODE_DELTA && mode != KVO_MODE_RLE && mode != KVO_MODE_PACK) return KVO_ERR_CORRUPT;
+    const int runs = mode != KVO_MODE_DELTA; /* zero-run and run packets allowed */
     size_t hdr = (size_t)(G + 1) / 2;
     if (nbytes < hdr) return KVO_ERR_CORRUPT;
     size_t pos = hdr;
@@ -263,9 +277,9 @@ int kvo_decode_codes(const uint8_t* payload, size_t nbytes, int mode, int N, int
     for (int g = 0; g < G; ++g) {
         int code = (g & 1) ? (payload[g >> 1] >> 4) : (payload[g >> 1] & 0xF);
         uint8_t* ug = u + 32 * g;
-        if (code == 0 && mode == KVO_MODE_RLE) {
+        if (code == 0 && runs) {
             memset(ug, 0, 32);
-        } else if (code == 9 && mode == KVO_MODE_RLE) {
+        } else if (code == 9 && runs) {
             if (pos + 1 > nbytes) goto corrupt;
             memset(ug, payload[pos], 32);
             pos += 1;
@@ -286,12 +300,13 @@ int kvo_decode_codes(const uint8_t* payload, size_t nbytes, int mode, int N, int
         }
     }
     if (kvo_pad16(pos) != nbytes) goto corrupt;
-    /* undo zig-zag, then the prefix sum along the channel index, wrapped to 8 bits */
+    /* undo zig-zag, then (modes 2, 3) the prefix sum along the channel index, wrapped to 8 bits */
     for (int j = 0; j < N; ++j) {
         int acc = 0;
         for (int i = 0; i < d; ++i) {
             unsigned uu = u[j * d + i];
             int delta = (int)(uu >> 1) ^ -(int)(uu & 1);
+            if (mode == KVO_MODE_PACK) acc = 0;
             acc = (int8_t)(uint8_t)((acc + delta) & 0xFF);
             q[j * d + i] = (int8_t)acc;
         }

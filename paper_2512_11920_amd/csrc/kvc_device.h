@@ -103,6 +103,20 @@ __device__ __forceinline__ int64_t elem_off(const Geometry& g, int e) {
     return (int64_t)(e >> g.dshift) * g.row_stride + (e & (g.d - 1));
 }
 
+// Workgroup index used for task assignment.  Workgroups are dealt round-robin to the 8 XCDs; with
+// KVC_XCD_REMAP=1 each XCD instead works through one contiguous eighth of the tasks.
+#ifndef KVC_XCD_REMAP
+#define KVC_XCD_REMAP 0
+#endif
+__device__ __forceinline__ unsigned task_block_index() {
+#if KVC_XCD_REMAP
+    const unsigned b = blockIdx.x, q = gridDim.x >> 3;
+    return b < (q << 3) ? (b & 7u) * q + (b >> 3) : b;
+#else
+    return blockIdx.x;
+#endif
+}
+
 struct PageResult {
     uint32_t n16;  // payload size in 16-byte units (0 = page skipped)
     uint32_t mode;

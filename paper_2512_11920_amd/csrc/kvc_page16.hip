@@ -294,7 +294,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_compress_p16(EncodeArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     fill_zigzag_lut(s_lut);
     __syncthreads();
-    const int64_t t0 = ((int64_t)blockIdx.x * WAVES + wave) * PPW;
+    const int64_t t0 = ((int64_t)task_block_index() * WAVES + wave) * PPW;
     TaskPos pos = task_pos(t0, a.g.ppb);
     // the next page's loads are issued before the current page is encoded
     EncTask task = resolve_enc_task(a, t0, pos);
@@ -495,7 +495,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_p16(DecodeArgs a) {
     __shared__ uint32_t s_ginfo[WAVES][Page<D>::kGroups];
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t t0 = ((int64_t)blockIdx.x * WAVES + wave) * PPW;
+    const int64_t t0 = ((int64_t)task_block_index() * WAVES + wave) * PPW;
     TaskPos pos = task_pos(t0, a.g.ppb);
 #pragma unroll 1
     for (int i = 0; i < PPW; ++i) {

@@ -184,6 +184,10 @@ def test_payload_size_closed_form_and_fallback(scheme):
 
 # ------------------------------------------------------------------ the bit format, stated independently
 
+def _zigzag_py(q):
+    return [2 * v if v >= 0 else -2 * v - 1 for v in q]
+
+
 def _parse_payload_py(payload: bytes, G: int, mode: int):
     """Independent reader of the packet format from its definition, with Python big integers:
     a literal body is the little-endian integer whose bits [k*w, (k+1)*w) hold u_k."""
@@ -191,9 +195,9 @@ def _parse_payload_py(payload: bytes, G: int, mode: int):
     pos, u = hdr, []
     for g in range(G):
         c = (payload[g >> 1] >> 4) if g & 1 else (payload[g >> 1] & 15)
-        if mode == 3 and c == 0:
+        if mode in (3, 4) and c == 0:
             u += [0] * 32
-        elif mode == 3 and c == 9:
+        elif mode in (3, 4) and c == 9:
             u += [payload[pos]] * 32
             pos += 1
         else:
@@ -390,3 +394,31 @@ def test_batch_driver_is_thread_count_independent_and_contiguous():
     out, bad = o.decompress_pages(p1, d1, 16, 64, page_ids=ids, n_threads=3)
     full, _ = o.decompress_pages(p1, d1, 16, 64)
     assert bad == 0 and np.array_equal(out, full[ids])
+
+
+def test_no_delta_mode_is_the_same_packing_without_the_delta_step():
+    """Mode 4 (an extension beyond Algorithm 2): the packed values are zigzag(q) themselves."""
+    rng = np.random.default_rng(14)
+    b3 = b4 = 0
+    for t in range(30):
+        x = (rng.standard_normal((4, 64)) * np.exp(rng.uniform(-1, 1, 64))).astype(np.float16)
+        x[:, 9] *= (1, 8, 60)[t % 3]
+        if t % 4 == 0:
+            x[2] = 0
+        d4, p4 = o.encode_page(x, 4, 64, 4)
+        d3, p3 = o.encode_page(x, 4, 64, 3)
+        nf, s, si, q = o.quantize_page(x)
+        assert d4["scale"] == d3["scale"]
+        if d4["mode"] == 1:
+            assert p4 == q.tobytes()
+            continue
+        assert d4["mode"] == 4
+        assert _parse_payload_py(p4, 8, 4) == _zigzag_py(q.tolist())
+        rc, q2 = o.decode_codes(p4, 4, 4, 64)
+        assert rc == 0 and np.array_equal(q2, q)
+        assert len(p4) == _size_closed_form(np.array(_zigzag_py(q.tolist()), np.uint8), True)
+        rc, xh4 = o.decode_page(p4, d4, 4, 64)
+        rc, xh3 = o.decode_page(p3, d3, 4, 64)
+        assert np.array_equal(xh4, xh3)  # same codes, same reconstruction
+        b3, b4 = b3 + len(p3), b4 + len(p4)
+    assert b4 < b3  # uncorrelated channels: differencing widens the values

@@ -542,7 +542,8 @@ def bench_ablation(args):
     for name, blocks in inputs.items():
         out = torch.empty_like(blocks)
         unc = blocks.numel() * 2
-        for scheme, label in ((0, "None (FP16)"), (1, "INT8 only"), (2, "INT8 + Delta"), (3, "INT8 + Delta + RLE")):
+        for scheme, label in ((0, "None (FP16)"), (1, "INT8 only"), (2, "INT8 + Delta"), (3, "INT8 + Delta + RLE"),
+                              (4, "INT8 + pack, no delta (extension)")):
             codec = kvc.Codec(N, d, ppb, scheme)
             codec.alloc_pool(blocks.shape[0], unc + 4096, dev)
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
@@ -566,7 +567,7 @@ def bench_ablation(args):
                          "compress_GBps_unc": round(unc / (tc / args.steps) / 1e6, 1),
                          "decompress_GBps_unc": round(unc / (td / args.steps) / 1e6, 1),
                          "rel_rmse": round(float(err), 5)})
-            log(f"[ablation] {name:12s} {label:20s} ratio {rows[-1]['ratio']:.3f} (payload {rows[-1]['payload_ratio']:.3f}) "
+            log(f"[ablation] {name:12s} {label:34s} ratio {rows[-1]['ratio']:.3f} (payload {rows[-1]['payload_ratio']:.3f}) "
                 f"C {rows[-1]['compress_GBps_unc']:.0f} D {rows[-1]['decompress_GBps_unc']:.0f} GB/s rel-rmse {rows[-1]['rel_rmse']:.4f}")
             del codec
     print(json.dumps({"metric": "compression ratio and codec GB/s (uncompressed fp16) per scheme", "n_gpus": 1,

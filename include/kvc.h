@@ -21,7 +21,9 @@
  *            even g in the low nibble) followed by the group bodies; code w in 1..8 = literal
  *            packet, 4*w bytes, u_k in bits [k*w,(k+1)*w) of the little-endian bit string;
  *   3 RLE    as 2, plus code 0 = 32 zeros (no body) and code 9 = 32 copies of one byte (1 byte);
- *   payloads are zero-padded to 16 bytes; a mode-2/3 page whose payload would not be smaller
+ *   4 PACK   as 3 with u = zig-zag of q itself, no differencing (for data without correlation
+ *            along the channel index; not part of the paper's algorithm);
+ *   payloads are zero-padded to 16 bytes; a mode-2/3/4 page whose payload would not be smaller
  *   than its INT8 payload is stored as mode 1.
  * Decoding yields fp16(fp32(q) * s), one binary32 multiply and one round-to-nearest-even.
  *
@@ -58,6 +60,7 @@ extern "C" {
 #define KVC_MODE_INT8 1
 #define KVC_MODE_DELTA 2
 #define KVC_MODE_RLE 3
+#define KVC_MODE_PACK 4 /* extension beyond Algorithm 2: as 3 without the delta step (u = zigzag(q)) */
 #define KVC_MODE_INVALID 0xFF
 
 #define KVC_ST_POOL_FULL 1u  /* a page did not fit into the pool */
@@ -80,14 +83,14 @@ typedef struct {
     int32_t tokens_per_block; /* N >= 1 */
     int32_t head_dim;         /* d in {32, 64, 128, 256};  N*d <= 4096 */
     int32_t pages_per_block;  /* ppb >= 1 */
-    int32_t scheme;           /* mode requested from compress: 0..3 */
+    int32_t scheme;           /* mode requested from compress: 0..4 */
 } kvc_config;
 
 typedef struct {
     uint64_t pool_bytes_used; /* bytes handed out by the pool cursor (capped at the pool size) */
-    uint64_t pages[4];        /* bound descriptors per mode 0..3 */
+    uint64_t pages[5];        /* bound descriptors per mode 0..4 */
     uint64_t pages_invalid;   /* bound descriptors with mode 0xFF (never written, or did not fit) */
-    uint64_t payload_bytes;   /* sum of n16*16 over descriptors of mode 0..3 */
+    uint64_t payload_bytes;   /* sum of n16*16 over descriptors of mode 0..4 */
     uint32_t status;          /* OR of KVC_ST_* since the last kvc_reset_pool */
     uint32_t rsvd;
 } kvc_stats_t;
@@ -96,7 +99,7 @@ typedef struct {
 int kvc_create(kvc_ctx** out, const kvc_config* cfg);
 void kvc_destroy(kvc_ctx* ctx);
 
-/* Change the mode compress requests (0..3); takes effect for later calls. */
+/* Change the mode compress requests (0..4); takes effect for later calls. */
 int kvc_set_scheme(kvc_ctx* ctx, int32_t scheme);
 
 /* Layout of the FP16 cache buffers read by compress and written by decompress / gather / prefetch,
@@ -125,8 +128,8 @@ int kvc_reset_pool(kvc_ctx* ctx, void* stream);
 int kvc_compress_blocks(kvc_ctx* ctx, const void* d_cache, int64_t n_cache_blocks, const int32_t* d_src_block_ids,
                         const int32_t* d_pool_block_ids, int32_t n, void* stream);
 
-/* As kvc_compress_blocks, with the requested mode given per block: d_block_scheme[i] in 0..3 (values
- * above 3 are read as 3) applies to block i of the call.  This is the mechanism behind the paper's
+/* As kvc_compress_blocks, with the requested mode given per block: d_block_scheme[i] in 0..4 (values
+ * above 4 are read as 4) applies to block i of the call.  This is the mechanism behind the paper's
  * layer-wise algorithm selection (Sections 3.1 (vi) and 3.6.3); the selection policy is the caller's. */
 int kvc_compress_blocks_mixed(kvc_ctx* ctx, const void* d_cache, int64_t n_cache_blocks, const int32_t* d_src_block_ids,
                               const int32_t* d_pool_block_ids, const uint8_t* d_block_scheme, int32_t n, void* stream);

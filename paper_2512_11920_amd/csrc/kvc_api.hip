@@ -32,7 +32,7 @@ static bool on_ctx_device(const kvc_ctx* ctx);
 static bool config_ok(const kvc_config* c) {
     if (!c) return false;
     if (c->tokens_per_block < 1 || c->pages_per_block < 1) return false;
-    if (c->scheme < 0 || c->scheme > 3) return false;
+    if (c->scheme < 0 || c->scheme > KVC_MODE_PACK) return false;
     const int d = c->head_dim;
     if (!(d == 32 || d == 64 || d == 128 || d == 256)) return false;
     const int64_t E = (int64_t)c->tokens_per_block * d;
@@ -50,7 +50,7 @@ int kvc_create(kvc_ctx** out, const kvc_config* cfg) {
     if (!out) return KVC_ERR_ARG;
     *out = nullptr;
     if (!cfg) return KVC_ERR_ARG;
-    if (cfg->tokens_per_block < 1 || cfg->pages_per_block < 1 || cfg->scheme < 0 || cfg->scheme > 3 ||
+    if (cfg->tokens_per_block < 1 || cfg->pages_per_block < 1 || cfg->scheme < 0 || cfg->scheme > KVC_MODE_PACK ||
         cfg->head_dim < 32 || cfg->head_dim % 32 != 0)
         return KVC_ERR_ARG;
     if (!config_ok(cfg)) return KVC_ERR_UNSUPPORTED;
@@ -89,7 +89,7 @@ void kvc_destroy(kvc_ctx* ctx) {
 }
 
 int kvc_set_scheme(kvc_ctx* ctx, int32_t scheme) {
-    if (!ctx || scheme < 0 || scheme > 3) return KVC_ERR_ARG;
+    if (!ctx || scheme < 0 || scheme > KVC_MODE_PACK) return KVC_ERR_ARG;
     ctx->cfg.scheme = scheme;
     return KVC_OK;
 }
@@ -104,6 +104,7 @@ int kvc_set_cache_layout(kvc_ctx* ctx, int64_t block_stride, int64_t page_stride
     // 128-bit accesses need 8-element granularity; rows may not overlap their own channels
     if (row_stride < ctx->g.d || page_stride <= 0 || block_stride <= 0) return KVC_ERR_ARG;
     if ((row_stride & 7) || (page_stride & 7) || (block_stride & 7)) return KVC_ERR_ARG;
+    if (row_stride * ctx->g.N >= (1ll << 30)) return KVC_ERR_ARG;  // a page's rows span less than 2 GiB
     ctx->g.row_stride = row_stride;
     ctx->g.page_stride = page_stride;
     ctx->g.block_stride = block_stride;
@@ -316,9 +317,9 @@ int kvc_stats(kvc_ctx* ctx, kvc_stats_t* out, void* stream) {
     if (!hip_ok(hipMemcpyAsync(&h, ctx->st, sizeof(h), hipMemcpyDeviceToHost, s))) return KVC_ERR_HIP;
     if (!hip_ok(hipStreamSynchronize(s))) return KVC_ERR_HIP;
     out->pool_bytes_used = std::min<uint64_t>(h.cursor16 * 16ull, ctx->pool_bytes);
-    for (int i = 0; i < 4; ++i) out->pages[i] = h.stats[i];
-    out->pages_invalid = h.stats[4];
-    out->payload_bytes = h.stats[5] * 16ull;
+    for (int i = 0; i < 5; ++i) out->pages[i] = h.stats[i];
+    out->pages_invalid = h.stats[5];
+    out->payload_bytes = h.stats[6] * 16ull;
     out->status = h.status;
     out->rsvd = 0;
     if (h.status & KVC_ST_POOL_FULL) return KVC_ERR_POOL_FULL;

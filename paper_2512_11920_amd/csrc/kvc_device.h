@@ -117,6 +117,14 @@ __device__ __forceinline__ unsigned task_block_index() {
 #endif
 }
 
+// A 64-bit value every lane of the wave holds the same copy of, moved to scalar registers so that an
+// access at kernel-argument pointer + this offset can use the scalar-base + 32-bit lane offset form.
+__device__ __forceinline__ int64_t wave_uniform(int64_t v) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
 struct PageResult {
     uint32_t n16;  // payload size in 16-byte units (0 = page skipped)
     uint32_t mode;
@@ -173,7 +181,7 @@ __device__ __forceinline__ EncTask resolve_enc_task(const EncodeArgs& a, int64_t
     }
     r.src_off = page_base(a.g, sb, pg);
     r.desc_idx = (long long)d_idx;
-    if (a.block_scheme) r.scheme = min((int)a.block_scheme[blk], 3);
+    if (a.block_scheme) r.scheme = min((int)a.block_scheme[blk], (int)KVC_MODE_PACK);
     return r;
 }
 

@@ -158,9 +158,14 @@ __device__ PageResult encode_page(const uint16_t* __restrict__ src, const Geomet
             int prev = __shfl_up(q[7], 1);
             if ((lane & (lpr - 1)) == 0) prev = 0;
             uint32_t u[8];
-            u[0] = zigzag8(q[0] - prev);
+            if (scheme == KVC_MODE_PACK) {  // no delta step: the codes themselves are packed
 #pragma unroll
-            for (int k = 1; k < 8; ++k) u[k] = zigzag8(q[k] - q[k - 1]);
+                for (int k = 0; k < 8; ++k) u[k] = zigzag8(q[k]);
+            } else {
+                u[0] = zigzag8(q[0] - prev);
+#pragma unroll
+                for (int k = 1; k < 8; ++k) u[k] = zigzag8(q[k] - q[k - 1]);
+            }
             uint32_t umax = u[0], umin = u[0];
 #pragma unroll
             for (int k = 1; k < 8; ++k) {
@@ -173,9 +178,10 @@ __device__ PageResult encode_page(const uint16_t* __restrict__ src, const Geomet
             umax = max(umax, (uint32_t)__shfl_xor((int)umax, 2));
             umin = min(umin, (uint32_t)__shfl_xor((int)umin, 2));
             uint32_t c;
-            if (scheme == KVC_MODE_RLE && umax == 0)
+            const bool runs = scheme != KVC_MODE_DELTA;  // zero-run and run packets
+            if (runs && umax == 0)
                 c = 0;
-            else if (scheme == KVC_MODE_RLE && umin == umax)
+            else if (runs && umin == umax)
                 c = 9;
             else
                 c = max(1u, 32u - (uint32_t)__clz((int)umax));
@@ -287,7 +293,7 @@ __device__ bool decode_page(const DecodeArgs& a, uint64_t d_idx, uint16_t* __res
         ok = ok && n16 == (uint32_t)(E >> 3);
     else if (mode == KVC_MODE_INT8)
         ok = ok && n16 == (uint32_t)(E >> 4);
-    else if (mode == KVC_MODE_DELTA || mode == KVC_MODE_RLE)
+    else if (mode == KVC_MODE_DELTA || mode == KVC_MODE_RLE || mode == KVC_MODE_PACK)
         ok = ok && n16 * 16u >= (uint32_t)hdr && n16 < (uint32_t)(E >> 4);
     else
         ok = false;
@@ -380,8 +386,13 @@ __device__ bool decode_page(const DecodeArgs& a, uint64_t d_idx, uint16_t* __res
                 q[k] = acc;
             }
             const int before = (int)row_excl_scan_u32((uint32_t)acc, lpr);
+            if (mode == KVC_MODE_PACK) {  // values are the codes themselves: undo the in-lane sums
 #pragma unroll
-            for (int k = 0; k < 8; ++k) q[k] += before;
+                for (int k = 7; k > 0; --k) q[k] -= q[k - 1];
+            } else {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) q[k] += before;
+            }
             if (act) *reinterpret_cast<uint4*>(dst + elem_off(a.g, e0)) = dequant8(q, s);
         }
     }
@@ -424,26 +435,26 @@ __global__ void k_stats_zero(DevState* st) {
 }
 
 __global__ __launch_bounds__(256) void k_stats(DevState* st, const kvc_desc* desc, uint64_t n_desc) {
-    __shared__ unsigned long long s_part[4][6];
-    unsigned long long cnt[6] = {0, 0, 0, 0, 0, 0};
+    __shared__ unsigned long long s_part[4][7];
+    unsigned long long cnt[7] = {0, 0, 0, 0, 0, 0, 0};
     for (uint64_t k = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; k < n_desc; k += (uint64_t)gridDim.x * blockDim.x) {
         const uint32_t w = reinterpret_cast<const uint4*>(desc)[k].w;
         const uint32_t mode = (w >> 16) & 0xFFu;
-        if (mode <= 3) {
+        if (mode <= KVC_MODE_PACK) {
             cnt[mode] += 1;
-            cnt[5] += w & 0xFFFFu;
+            cnt[6] += w & 0xFFFFu;
         } else {
-            cnt[4] += 1;
+            cnt[5] += 1;
         }
     }
     // wave reduction, then one atomic per counter per workgroup
-    for (int j = 0; j < 6; ++j) {
+    for (int j = 0; j < 7; ++j) {
         unsigned long long v = cnt[j];
         for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
         if (lane_id() == 0) s_part[threadIdx.x >> 6][j] = v;
     }
     __syncthreads();
-    if (threadIdx.x < 6) {
+    if (threadIdx.x < 7) {
         const unsigned long long v = s_part[0][threadIdx.x] + s_part[1][threadIdx.x] + s_part[2][threadIdx.x] + s_part[3][threadIdx.x];
         if (v) atomicAdd(&st->stats[threadIdx.x], v);
     }

@@ -169,18 +169,22 @@ __device__ __forceinline__ void encode_tail(const uint32_t (&u)[8], uint32_t c, 
 
 // Lane l of pass p holds token row p*(512/D) + l/(D/8), channels 8*(l%(D/8)) .. +7: with contiguous
 // rows this is one 1 KB run per pass, with strided rows 512/D runs of 2*D bytes.
+// The lane's byte offset inside a page is computed once per kernel and kept in 32 bits (the layout
+// setter bounds the row stride), so that page accesses are a wave-uniform 64-bit base plus that offset.
 template <int D>
-__device__ __forceinline__ int64_t lane_elem_off(const Geometry& g) {
-    const int lane = lane_id();
-    return (int64_t)(lane / Page<D>::kLpr) * g.row_stride + (lane % Page<D>::kLpr) * 8;
+__device__ __forceinline__ uint32_t lane_byte_off(const Geometry& g) {
+    const uint32_t lane = (uint32_t)lane_id();
+    return ((lane / Page<D>::kLpr) * (uint32_t)g.row_stride + (lane % Page<D>::kLpr) * 8u) * 2u;
 }
 
 template <int D>
-__device__ __forceinline__ void load_page(const EncodeArgs& a, const EncTask& task, uint4 (&raw)[Page<D>::kPasses]) {
-    const uint16_t* src = a.cache + task.src_off + lane_elem_off<D>(a.g);
+__device__ __forceinline__ void load_page(const EncodeArgs& a, const EncTask& task, uint32_t lane_off,
+                                          uint4 (&raw)[Page<D>::kPasses]) {
+    const char* src = reinterpret_cast<const char*>(a.cache) + wave_uniform(task.src_off * 2);
+    const int64_t pass_bytes = (int64_t)Page<D>::kRowsPerPass * a.g.row_stride * 2;
 #pragma unroll
     for (int p = 0; p < Page<D>::kPasses; ++p)
-        raw[p] = load_stream(reinterpret_cast<const uint4*>(src + (int64_t)p * Page<D>::kRowsPerPass * a.g.row_stride));
+        raw[p] = load_stream(reinterpret_cast<const uint4*>(src + p * pass_bytes + lane_off));
 }
 
 // Encode one page (already in registers) into the LDS slot `stage`.  scheme is wave-uniform.
@@ -188,7 +192,8 @@ template <int D>
 __device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPasses], int scheme, uint32_t* stage,
                                                  const uint8_t* lut, DevState* st) {
     constexpr int kE = Page<D>::kE, kHdr = Page<D>::kHdr, NP = Page<D>::kPasses;
-    const bool RLE = scheme == KVC_MODE_RLE;
+    const bool RLE = scheme != KVC_MODE_DELTA;  // zero-run and run packets (modes 3 and 4)
+    const bool no_delta = scheme == KVC_MODE_PACK;
     const uint32_t c_min = RLE ? 0u : 1u;  // without run packets an all-zero group is a 1-bit literal
     const int lane = lane_id();
     const uint32_t qi = (uint32_t)lane & 3u;
@@ -234,12 +239,17 @@ __device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPa
         quantize8_bits(raw[p], s_inv, t);
         // delta along the channel index, plus 256; the first column of a token row has no left
         // neighbour and is kept verbatim (q - 0).  Then wrap + zig-zag by table.
-        const uint32_t prev = left_neighbour<Page<D>::kLpr>(kMagicBits - 256u, t[7] - 2048u);
         uint32_t u[8];
-        KVC_CHECK(st, t[0] - prev < 512u && t[1] - t[0] < 512u && t[7] - t[6] < 512u);
-        u[0] = lut[t[0] - prev];
+        if (no_delta) {  // mode 4: the table is indexed by q + 256
 #pragma unroll
-        for (int k = 1; k < 8; ++k) u[k] = lut[t[k] - t[k - 1]];
+            for (int k = 0; k < 8; ++k) u[k] = lut[t[k] - (kMagicBits + 256u * (uint32_t)k - 256u)];
+        } else {
+            const uint32_t prev = left_neighbour<Page<D>::kLpr>(kMagicBits - 256u, t[7] - 2048u);
+            KVC_CHECK(st, t[0] - prev < 512u && t[1] - t[0] < 512u && t[7] - t[6] < 512u);
+            u[0] = lut[t[0] - prev];
+#pragma unroll
+            for (int k = 1; k < 8; ++k) u[k] = lut[t[k] - t[k - 1]];
+        }
         // per-group statistics over the quad of lanes
         uint32_t gmax = max(max(u[0], u[1]), u[2]);
         gmax = max(max(gmax, u[3]), u[4]);
@@ -277,7 +287,7 @@ __device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPa
         r.mode = KVC_MODE_INT8;
     } else {
         r.n16 = n >> 4;
-        r.mode = RLE ? KVC_MODE_RLE : KVC_MODE_DELTA;
+        r.mode = (uint32_t)scheme;
     }
     return r;
 }
@@ -298,8 +308,9 @@ __global__ __launch_bounds__(WAVES * 64) void k_compress_p16(EncodeArgs a) {
     TaskPos pos = task_pos(t0, a.g.ppb);
     // the next page's loads are issued before the current page is encoded
     EncTask task = resolve_enc_task(a, t0, pos);
+    const uint32_t lane_off = lane_byte_off<D>(a.g);
     uint4 raw[NP];
-    if (task.desc_idx >= 0) load_page<D>(a, task, raw);
+    if (task.desc_idx >= 0) load_page<D>(a, task, lane_off, raw);
 #pragma unroll 1
     for (int i = 0; i < PPW; ++i) {
         const int slot = wave * PPW + i;
@@ -311,7 +322,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_compress_p16(EncodeArgs a) {
         uint4 raw_next[NP];
         if (kPrefetch && i + 1 < PPW) {
             next = resolve_enc_task(a, t0 + i + 1, pos);
-            if (next.desc_idx >= 0) load_page<D>(a, next, raw_next);
+            if (next.desc_idx >= 0) load_page<D>(a, next, lane_off, raw_next);
         }
         PageResult r;
         r.n16 = 0;
@@ -331,7 +342,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_compress_p16(EncodeArgs a) {
             for (int p = 0; p < NP; ++p) raw[p] = raw_next[p];
         } else if (i + 1 < PPW) {
             task = resolve_enc_task(a, t0 + i + 1, pos);
-            if (task.desc_idx >= 0) load_page<D>(a, task, raw);
+            if (task.desc_idx >= 0) load_page<D>(a, task, lane_off, raw);
         }
     }
     __syncthreads();
@@ -368,15 +379,16 @@ __device__ __forceinline__ bool decode_p16(const DecodeArgs& a, uint64_t d_idx, 
     const float s = __uint_as_float(dw.z);
     const uint32_t n16 = dw.w & 0xFFFFu;
     const uint32_t mode = (dw.w >> 16) & 0xFFu;
-    uint16_t* dst_lane = dst + lane_elem_off<D>(a.g);  // this lane's 8 channels in pass 0
-    const int64_t pass_stride = Page<D>::kRowsPerPass * a.g.row_stride;
+    char* dst_b = reinterpret_cast<char*>(a.out) + wave_uniform((int64_t)(dst - a.out) * 2);  // wave-uniform page base
+    const uint32_t lane_off = lane_byte_off<D>(a.g);    // this lane's 8 channels in pass 0
+    const int64_t pass_bytes = (int64_t)Page<D>::kRowsPerPass * a.g.row_stride * 2;
 
     bool ok = (off & 15u) == 0 && (off >> 4) + n16 <= a.pool_units;
     if (mode == KVC_MODE_RAW)
         ok = ok && n16 == kE / 8;
     else if (mode == KVC_MODE_INT8)
         ok = ok && n16 == kE / 16;
-    else if (mode == KVC_MODE_DELTA || mode == KVC_MODE_RLE)
+    else if (mode == KVC_MODE_DELTA || mode == KVC_MODE_RLE || mode == KVC_MODE_PACK)
         ok = ok && n16 * 16u >= (uint32_t)kHdr && n16 < kE / 16;
     else
         ok = false;
@@ -387,7 +399,7 @@ __device__ __forceinline__ bool decode_p16(const DecodeArgs& a, uint64_t d_idx, 
     const uint4* pl4 = reinterpret_cast<const uint4*>(a.pool + off);
     if (mode == KVC_MODE_RAW) {  // stored-uncompressed bypass
 #pragma unroll
-        for (int p = 0; p < NP; ++p) *reinterpret_cast<uint4*>(dst_lane + p * pass_stride) = pl4[p * 64 + lane];
+        for (int p = 0; p < NP; ++p) *reinterpret_cast<uint4*>(dst_b + p * pass_bytes + lane_off) = pl4[p * 64 + lane];
         return true;
     }
     const float neg128s = -128.0f * s;
@@ -401,7 +413,7 @@ __device__ __forceinline__ bool decode_p16(const DecodeArgs& a, uint64_t d_idx, 
                 pb[k] = ((v.x >> (8 * k)) + 128u);
                 pb[4 + k] = ((v.y >> (8 * k)) + 128u);
             }
-            store_stream(reinterpret_cast<uint4*>(dst_lane + p * pass_stride), dequant8_biased(pb, s, neg128s));
+            store_stream(reinterpret_cast<uint4*>(dst_b + p * pass_bytes + lane_off), dequant8_biased(pb, s, neg128s));
         }
         return true;
     }
@@ -479,12 +491,17 @@ __device__ __forceinline__ bool decode_p16(const DecodeArgs& a, uint64_t d_idx, 
         dl[7] = (int)__builtin_amdgcn_ubfe(mid, o3 + 1u, w1) ^ __builtin_amdgcn_sbfe((int)mid, o3, 1u);
         // prefix sum along the channel index: in the lane, then across the lanes of the token row
         const uint32_t tot = (uint32_t)(dl[0] + dl[1] + dl[2] + dl[3] + dl[4] + dl[5] + dl[6] + dl[7]);
-        const uint32_t rincl = row_incl_scan<Page<D>::kLpr>(tot);
         uint32_t pb[8];
-        pb[0] = rincl - tot + 128u + (uint32_t)dl[0];  // +128: biased codes, see dequant8_biased
+        if (mode == KVC_MODE_PACK) {  // no delta step was taken: the fields are the codes
 #pragma unroll
-        for (int k = 1; k < 8; ++k) pb[k] = pb[k - 1] + (uint32_t)dl[k];
-        store_stream(reinterpret_cast<uint4*>(dst_lane + p * pass_stride), dequant8_biased(pb, s, neg128s));
+            for (int k = 0; k < 8; ++k) pb[k] = (uint32_t)dl[k] + 128u;
+        } else {
+            const uint32_t rincl = row_incl_scan<Page<D>::kLpr>(tot);
+            pb[0] = rincl - tot + 128u + (uint32_t)dl[0];  // +128: biased codes, see dequant8_biased
+#pragma unroll
+            for (int k = 1; k < 8; ++k) pb[k] = pb[k - 1] + (uint32_t)dl[k];
+        }
+        store_stream(reinterpret_cast<uint4*>(dst_b + p * pass_bytes + lane_off), dequant8_biased(pb, s, neg128s));
     }
     return true;
 }

@@ -59,7 +59,8 @@ def _families(rng, n, N, d):
 
 
 @pytest.mark.parametrize("N,d,n,scheme", [(16, 128, 40000, 3), (16, 128, 8000, 2), (16, 64, 8000, 3), (16, 256, 6000, 3),
-                                          (16, 32, 3000, 3), (7, 128, 3000, 3), (32, 64, 3000, 2)])
+                                          (16, 32, 3000, 3), (7, 128, 3000, 3), (32, 64, 3000, 2),
+                                          (16, 128, 8000, 4), (16, 64, 3000, 4), (16, 256, 3000, 4), (5, 128, 2000, 4)])
 def test_differential(N, d, n, scheme):
     rng = np.random.default_rng(N * 1000 + d + scheme)
     x, fam = _families(rng, n, N, d)
@@ -81,5 +82,5 @@ def test_differential(N, d, n, scheme):
     if not np.array_equal(got, want):
         p = int(np.nonzero((got != want).any(axis=(1, 2)))[0][0])
         raise AssertionError(f"decoded page {p} (family {fam[p]}, mode {od['mode'][p]}) differs")
-    modes = np.bincount(od["mode"], minlength=4)
+    modes = np.bincount(od["mode"], minlength=5)
     assert modes[0] > 0 and modes[1] > 0 and modes[scheme] > 0  # raw, fallback and packed pages all occurred

@@ -32,7 +32,7 @@ def _roundtrip_case(x, N, d, ppb, scheme, name):
     pool = c.pool.cpu().numpy()
     check_pool_invariants(desc, st["pool_bytes_used"], pool.size)
     od, op = compare_pages_with_oracle(xu, desc, pool, N, d, scheme)
-    assert st["pages"] == np.bincount(od["mode"], minlength=4).tolist() and st["pages_invalid"] == 0
+    assert st["pages"] == np.bincount(od["mode"], minlength=5).tolist() and st["pages_invalid"] == 0
     assert st["payload_bytes"] == op.size
     assert c.ratio() == pytest.approx(o.ratio(od, N * d))
     # decode GPU-made pool on the GPU
@@ -55,7 +55,7 @@ def _roundtrip_case(x, N, d, ppb, scheme, name):
     return od
 
 
-@pytest.mark.parametrize("scheme", [3, 2, 1, 0])
+@pytest.mark.parametrize("scheme", [3, 2, 1, 0, 4])
 def test_tiny_config_all_pages(scheme):
     sh = synth.CONFIGS["tiny"]
     x = synth.cache_numpy(sh)  # [1][2][16][4][16][64]
@@ -69,7 +69,7 @@ def test_handworked_pages_on_gpu():
     for cs in cases:
         x = np.frombuffer(bytes.fromhex(cs["x_fp16_le_hex"]), np.uint16)
         _say(f"[case] golden/{cs['name']}")
-        c, xt = gpu_compress(x, cs["N"], cs["d"], 1, 3)
+        c, xt = gpu_compress(x, cs["N"], cs["d"], 1, cs["scheme"])
         desc = c.desc_numpy()
         pool = c.pool.cpu().numpy()
         assert int(desc["mode"][0]) == cs["mode"] and int(desc["n16"][0]) == cs["n16"]
@@ -120,7 +120,7 @@ def _special_pages(N, d, rng):
 
 
 @pytest.mark.parametrize("N,d", [(16, 128), (16, 64), (16, 32), (16, 256), (1, 64), (3, 32), (5, 128), (32, 128)])
-@pytest.mark.parametrize("scheme", [3, 2])
+@pytest.mark.parametrize("scheme", [3, 2, 4])
 def test_special_pages_all_geometries(N, d, scheme):
     rng = np.random.default_rng(100 + N + d)
     x = _special_pages(N, d, rng)
@@ -314,8 +314,8 @@ def test_per_block_scheme_selection():
     rng = np.random.default_rng(44)
     N, d, ppb, nb = 16, 128, 4, 40
     x = (rng.standard_normal((nb, ppb, N, d)) * np.exp(0.7 * rng.standard_normal(d))).astype(np.float16)
-    schemes = rng.integers(0, 4, nb).astype(np.uint8)
-    schemes[:4] = [0, 1, 2, 3]
+    schemes = rng.integers(0, 5, nb).astype(np.uint8)
+    schemes[:5] = [0, 1, 2, 3, 4]
     xt = torch.from_numpy(x).to(DEV)
     c = make_codec(N, d, ppb, 3, nb, pool_bytes=nb * ppb * N * d * 2 + 64)
     c.compress_blocks(xt, block_scheme=torch.from_numpy(schemes).to(DEV))

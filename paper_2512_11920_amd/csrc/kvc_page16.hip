@@ -187,10 +187,13 @@ __device__ __forceinline__ void load_page(const EncodeArgs& a, const EncTask& ta
         raw[p] = load_stream(reinterpret_cast<const uint4*>(src + p * pass_bytes + lane_off));
 }
 
-// Encode one page (already in registers) into the LDS slot `stage`.  scheme is wave-uniform.
-template <int D>
-__device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPasses], int scheme, uint32_t* stage,
+// Encode one page (already in registers) into the LDS slot `stage`.  The requested mode is the
+// compile-time SCHEME when that is >= 0 (one mode for the whole launch: its branches fold away), else
+// the wave-uniform run-time value.
+template <int D, int SCHEME>
+__device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPasses], int scheme_rt, uint32_t* stage,
                                                  const uint8_t* lut, DevState* st) {
+    const int scheme = SCHEME >= 0 ? SCHEME : scheme_rt;
     constexpr int kE = Page<D>::kE, kHdr = Page<D>::kHdr, NP = Page<D>::kPasses;
     const bool RLE = scheme != KVC_MODE_DELTA;  // zero-run and run packets (modes 3 and 4)
     const bool no_delta = scheme == KVC_MODE_PACK;
@@ -292,7 +295,7 @@ __device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPa
     return r;
 }
 
-template <int D, int WAVES, int PPW>
+template <int D, int WAVES, int PPW, int SCHEME>
 __global__ __launch_bounds__(WAVES * 64) void k_compress_p16(EncodeArgs a) {
     constexpr int kSlots = WAVES * PPW;
     constexpr int NP = Page<D>::kPasses;
@@ -328,7 +331,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_compress_p16(EncodeArgs a) {
         r.n16 = 0;
         r.mode = KVC_MODE_INVALID;
         r.scale = 0.0f;
-        if (task.desc_idx >= 0) r = encode_p16<D>(raw, task.scheme, s_stage[slot], s_lut, a.st);
+        if (task.desc_idx >= 0) r = encode_p16<D, SCHEME>(raw, task.scheme, s_stage[slot], s_lut, a.st);
         if (lane == 0) {
             s_book.n16[slot] = r.n16;
             s_book.mode[slot] = r.mode;
@@ -542,17 +545,27 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_p16(DecodeArgs a) {
 #define KVC_DEC_PPW 1
 #endif
 
-hipError_t launch_compress_p16(const EncodeArgs& a, hipStream_t s) {
+template <int SCHEME>
+static void launch_compress_scheme(const EncodeArgs& a, hipStream_t s) {
     // pages per pool-cursor atomic scale with the page size: 64 KB of input per workgroup
     constexpr int WAVES = KVC_ENC_WAVES, PPW = KVC_ENC_PPW;
     const dim3 block(WAVES * 64);
     auto grid = [&](int ppw) { return dim3((unsigned)((a.n_pages + (int64_t)WAVES * ppw - 1) / ((int64_t)WAVES * ppw))); };
     if (a.g.d == 64)
-        hipLaunchKernelGGL((k_compress_p16<64, WAVES, 2 * PPW>), grid(2 * PPW), block, 0, s, a);
+        hipLaunchKernelGGL((k_compress_p16<64, WAVES, 2 * PPW, SCHEME>), grid(2 * PPW), block, 0, s, a);
     else if (a.g.d == 128)
-        hipLaunchKernelGGL((k_compress_p16<128, WAVES, PPW>), grid(PPW), block, 0, s, a);
+        hipLaunchKernelGGL((k_compress_p16<128, WAVES, PPW, SCHEME>), grid(PPW), block, 0, s, a);
     else
-        hipLaunchKernelGGL((k_compress_p16<256, WAVES, PPW / 2>), grid(PPW / 2), block, 0, s, a);
+        hipLaunchKernelGGL((k_compress_p16<256, WAVES, PPW / 2, SCHEME>), grid(PPW / 2), block, 0, s, a);
+}
+
+hipError_t launch_compress_p16(const EncodeArgs& a, hipStream_t s) {
+    // the full scheme of Algorithm 2 for every block is the common launch and gets its own
+    // instantiation; any other request (another mode, or one mode per block) reads it at run time
+    if (a.block_scheme == nullptr && a.scheme == KVC_MODE_RLE)
+        launch_compress_scheme<KVC_MODE_RLE>(a, s);
+    else
+        launch_compress_scheme<-1>(a, s);
     return hipGetLastError();
 }
 

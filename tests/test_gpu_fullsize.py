@@ -1,7 +1,11 @@
-"""Parity at the benchmark's full sizes and launch configuration.  The oracle cannot process tens of
-gigabytes in a test, so these cases check (a) randomly sampled pages one by one against the oracle and
-(b) properties that hold for every page at any size: pool spans tile [0, used) without overlap, the
-reconstruction error bound of the quantizer, decode consistency between the gather and the plain path."""
+"""Parity at the benchmark's full sizes and launch configuration.  These cases check (a) randomly
+sampled pages one by one against the oracle, (b) whole layers streamed through the oracle page by page
+(a tenth of the layers by default; every layer, i.e. every page of the cache, with KVC_ALL_LAYERS=1 in
+the environment, which takes a few minutes of host time) and (c) properties that hold for every page at
+any size: pool spans tile [0, used) without overlap, the reconstruction error bound of the quantizer,
+decode consistency between the gather and the plain path."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -21,16 +25,23 @@ def _sampled_pages_match_oracle(codec, cache_pages, out_pages, ids, N, d):
     idt = torch.from_numpy(ids).to(DEV)
     x = cache_pages[idt].cpu().numpy().view(np.uint16)
     gd, gp = fetch_pages(codec, ids)
-    od, op = o.compress_pages(x, N, d, 3, n_threads=8)
+    od, op = o.compress_pages(x, N, d, 3, n_threads=16)
     assert np.array_equal(gd["mode"], od["mode"]) and np.array_equal(gd["n16"], od["n16"])
     assert np.array_equal(gd["scale"].view(np.uint32), od["scale"].view(np.uint32))
     assert np.array_equal(gp, op), "payload bytes differ"
-    want, bad = o.decompress_pages(op, od, N, d, n_threads=8)
+    want, bad = o.decompress_pages(op, od, N, d, n_threads=16)
     assert bad == 0
     got = out_pages[idt].cpu().numpy().view(np.uint16)
     assert np.array_equal(got, want)
 
 
+def _streamed_layers(n_layers):
+    if os.environ.get("KVC_ALL_LAYERS") == "1":
+        return list(range(n_layers))
+    return sorted({0, n_layers - 1} | set(range(3, n_layers, 10)))
+
+
+@pytest.mark.timeout(900)
 @pytest.mark.parametrize("name", ["70b_gqa", "7b_full"])
 def test_full_cache_sampled_parity_and_invariants(name):
     """BASELINE configs 4 (80 layers x 8 KV heads x 128, seq 4096, batch 16, 21.47 GB) and 3 (32 layers x
@@ -64,9 +75,15 @@ def test_full_cache_sampled_parity_and_invariants(name):
                                     np.arange(1 << 20, (1 << 20) + 40)]))
     _say(f"[case] oracle on {ids.size} sampled pages")
     _sampled_pages_match_oracle(codec, blocks.view(-1, N, d), out.view(-1, N, d), ids, N, d)
-    # (b) every page: |x - xhat| <= amax/254 (1 + 2^-14) + ulp16(xhat)/2, checked layer by layer
-    _say("[case] error bound on all pages")
+    # (b) whole layers, every page of each, streamed through the oracle
     per = sh.pages_per_layer
+    layers = _streamed_layers(sh.n_layers)
+    for l in layers:
+        _say(f"[case] oracle on all {per} pages of layer {l}")
+        _sampled_pages_match_oracle(codec, blocks.view(-1, N, d), out.view(-1, N, d), np.arange(l * per, (l + 1) * per), N, d)
+    _say(f"[case] {len(layers)} of {sh.n_layers} layers compared page by page")
+    # (c) every page: |x - xhat| <= amax/254 (1 + 2^-14) + ulp16(xhat)/2, checked layer by layer
+    _say("[case] error bound on all pages")
     xp, yp = blocks.view(-1, N * d), out.view(-1, N * d)
     for l in range(sh.n_layers):
         x = xp[l * per:(l + 1) * per].float()

@@ -37,7 +37,8 @@
  * (decompress); kvc_stats() reports them.  Block ids < 0 mean "skip this block".
  * Calls on one context that overlap on different streams race on the pool cursor; serialise them.
  * A context belongs to the device that was current in kvc_create; calls made with another device
- * current return KVC_ERR_ARG.
+ * current return KVC_ERR_ARG.  A context is not thread-safe: one host thread at a time.
+ * One data call handles at most 2^31 - 1 pages (blocks * pages_per_block); more is KVC_ERR_ARG.
  */
 #ifndef KVC_H
 #define KVC_H
@@ -182,6 +183,13 @@ int kvc_prefetch_layers(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fe
  * (on `stream`).  Returns KVC_ERR_POOL_FULL / KVC_ERR_CORRUPT if the matching status bit is set
  * (out is filled either way), else 0. */
 int kvc_stats(kvc_ctx* ctx, kvc_stats_t* out, void* stream);
+
+/* The scaling step of Algorithm 2 on its own: for n page maxima given as FP16 bit patterns (sign
+ * ignored) write s = amax / 127 and s_inv = 1 / s as the encoder computes them (binary32); 0, Inf
+ * and NaN give 0 for both.  All three arrays are device memory.  The encoder does not use IEEE
+ * division instructions for these quotients; this call lets a test compare its arithmetic with
+ * plain division for every possible maximum. */
+int kvc_page_scales(const uint16_t* d_amax, float* d_scale, float* d_scale_inv, uint64_t n, void* stream);
 
 /* dst[0..nbytes) = src[0..nbytes) with one 128-bit load and store per lane; nbytes multiple of 16.
  * The bandwidth yardstick the codec kernels are compared with. */

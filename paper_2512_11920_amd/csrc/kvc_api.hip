@@ -18,6 +18,9 @@ struct kvc_ctx {
 
 static_assert(sizeof(kvc_desc) == 16, "descriptor is 16 bytes");
 
+// One data call handles at most this many pages, so that every launch grid fits 31 bits.
+static constexpr int64_t kMaxPagesPerCall = INT32_MAX;
+
 // Text of the last HIP failure seen by this thread (for kvc_strerror(KVC_ERR_HIP)).
 static thread_local hipError_t t_last_hip = hipSuccess;
 
@@ -141,6 +144,7 @@ int kvc_bind_pool(kvc_ctx* ctx, void* d_pool, uint64_t pool_bytes, kvc_desc* d_d
 int kvc_reset_pool(kvc_ctx* ctx, void* stream) {
     if (!ctx) return KVC_ERR_ARG;
     if (!ctx->pool) return KVC_ERR_NOT_BOUND;
+    if (!on_ctx_device(ctx)) return KVC_ERR_ARG;
     return hip_ok(kvc::launch_reset(ctx->st, ctx->desc, ctx->n_desc, static_cast<hipStream_t>(stream)))
                ? KVC_OK
                : KVC_ERR_HIP;
@@ -156,6 +160,7 @@ static int compress_impl(kvc_ctx* ctx, const void* d_cache, int64_t n_cache_bloc
     // identity ids are checked here; explicit id arrays live on the device and are checked there
     if (!d_src_block_ids && (int64_t)n > n_cache_blocks) return KVC_ERR_ARG;
     if (!d_pool_block_ids && (uint64_t)n * (uint64_t)ctx->g.ppb > ctx->n_desc) return KVC_ERR_ARG;
+    if ((int64_t)n * ctx->g.ppb > kMaxPagesPerCall) return KVC_ERR_ARG;
     kvc::EncodeArgs a;
     a.cache = static_cast<const uint16_t*>(d_cache);
     a.n_cache_blocks = n_cache_blocks;
@@ -208,6 +213,7 @@ int kvc_decompress_blocks(kvc_ctx* ctx, void* d_cache_out, int64_t n_out_blocks,
     if (!d_cache_out || (reinterpret_cast<uintptr_t>(d_cache_out) & 15u)) return KVC_ERR_ARG;
     if (!d_dst_block_ids && (int64_t)n > n_out_blocks) return KVC_ERR_ARG;
     if (!d_pool_block_ids && (uint64_t)n * (uint64_t)ctx->g.ppb > ctx->n_desc) return KVC_ERR_ARG;
+    if ((int64_t)n * ctx->g.ppb > kMaxPagesPerCall) return KVC_ERR_ARG;
     kvc::DecodeArgs a;
     fill_decode_common(ctx, a);
     a.out = static_cast<uint16_t*>(d_cache_out);
@@ -229,6 +235,7 @@ int kvc_gather_decompress(kvc_ctx* ctx, void* d_out, const int32_t* d_block_tabl
     if (!d_out || !d_block_table || !d_pred || max_blocks == 0 || (reinterpret_cast<uintptr_t>(d_out) & 15u))
         return KVC_ERR_ARG;
     if ((uint64_t)n_layers * (uint64_t)pool_blocks_per_layer * (uint64_t)ctx->g.ppb > ctx->n_desc) return KVC_ERR_ARG;
+    if (n_blocks > kMaxPagesPerCall / ctx->g.ppb) return KVC_ERR_ARG;
     kvc::DecodeArgs a;
     fill_decode_common(ctx, a);
     a.out = static_cast<uint16_t*>(d_out);
@@ -252,6 +259,7 @@ int kvc_set_prefetch_policy(kvc_ctx* ctx, int32_t policy) {
 
 int kvc_prefetch_reset(kvc_ctx* ctx, int32_t* d_tags, int32_t n_seq, int32_t k, int32_t n_layers, void* stream) {
     if (!ctx || !d_tags || n_seq < 0 || k < 0 || n_layers < 0) return KVC_ERR_ARG;
+    if (!on_ctx_device(ctx)) return KVC_ERR_ARG;
     return hip_ok(kvc::launch_fill_i32(d_tags, -1, 2ull * (uint64_t)n_layers * (uint64_t)n_seq * (uint64_t)k,
                                        static_cast<hipStream_t>(stream)))
                ? KVC_OK
@@ -273,7 +281,7 @@ int kvc_prefetch_layers(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fe
     if (!d_l2 || !d_tags || !d_fetch || !d_loc || !d_block_table || !d_pred || max_blocks == 0 ||
         (reinterpret_cast<uintptr_t>(d_l2) & 15u))
         return KVC_ERR_ARG;
-    if (2 * n_slots > INT32_MAX || n_now > INT32_MAX) return KVC_ERR_ARG;
+    if (2 * n_slots > INT32_MAX || n_now > kMaxPagesPerCall / ctx->g.ppb) return KVC_ERR_ARG;
     if (k > kvc::kMaxPrefetchK) return KVC_ERR_ARG;
     if ((uint64_t)n_layers * (uint64_t)pool_blocks_per_layer * (uint64_t)ctx->g.ppb > ctx->n_desc ||
         (uint64_t)n_layers * (uint64_t)pool_blocks_per_layer > (uint64_t)INT32_MAX)
@@ -311,6 +319,7 @@ int kvc_prefetch_layers(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fe
 int kvc_stats(kvc_ctx* ctx, kvc_stats_t* out, void* stream) {
     if (!ctx || !out) return KVC_ERR_ARG;
     if (!ctx->pool) return KVC_ERR_NOT_BOUND;
+    if (!on_ctx_device(ctx)) return KVC_ERR_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (!hip_ok(kvc::launch_stats(ctx->st, ctx->desc, ctx->n_desc, s))) return KVC_ERR_HIP;
     kvc::DevState h;
@@ -325,6 +334,13 @@ int kvc_stats(kvc_ctx* ctx, kvc_stats_t* out, void* stream) {
     if (h.status & KVC_ST_POOL_FULL) return KVC_ERR_POOL_FULL;
     if (h.status & (KVC_ST_CORRUPT | KVC_ST_BAD_INDEX)) return KVC_ERR_CORRUPT;
     return KVC_OK;
+}
+
+int kvc_page_scales(const uint16_t* d_amax, float* d_scale, float* d_scale_inv, uint64_t n, void* stream) {
+    if (n == 0) return KVC_OK;
+    if (!d_amax || !d_scale || !d_scale_inv || n > (1ull << 31)) return KVC_ERR_ARG;
+    return hip_ok(kvc::launch_page_scales(d_amax, d_scale, d_scale_inv, n, static_cast<hipStream_t>(stream))) ? KVC_OK
+                                                                                                            : KVC_ERR_HIP;
 }
 
 int kvc_copy_bytes(void* d_dst, const void* d_src, uint64_t nbytes, void* stream) {

@@ -117,12 +117,40 @@ __device__ __forceinline__ unsigned task_block_index() {
 #endif
 }
 
-// A 64-bit value every lane of the wave holds the same copy of, moved to scalar registers so that an
-// access at kernel-argument pointer + this offset can use the scalar-base + 32-bit lane offset form.
+// A value every lane of the wave holds the same copy of, moved to scalar registers: index arithmetic
+// on it (64-bit multiplies, bounds checks) then runs on the scalar unit, loads indexed by it become
+// scalar loads, and an access at kernel-argument pointer + such an offset needs no per-lane base.
+__device__ __forceinline__ int32_t wave_uniform(int32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+
 __device__ __forceinline__ int64_t wave_uniform(int64_t v) {
     const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
     const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)v >> 32));
     return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+// Scaling step of Algorithm 2 for a page whose largest magnitude is the finite, non-zero FP16 value
+// with bit pattern m: s = amax / 127 and s_inv = 1 / s, each the correctly rounded binary32 quotient,
+// without the general division sequence.  amax / 127 is the product with the correctly rounded
+// reciprocal of 127, its exact FMA residual and one corrected FMA (Markstein's construction); 1 / s is
+// the hardware reciprocal (within 1 ulp) and one Newton step on the FMA residual.  Neither binary32
+// range can under- or overflow here (2^-24 <= amax <= 65504).  The domain is the 31,743 FP16
+// magnitudes: kvc_page_scales exposes this function so that a test compares every one of them with
+// plain IEEE division.
+struct PageScale {
+    float s, s_inv;
+};
+
+__device__ __forceinline__ PageScale page_scale(uint32_t m) {
+    const float a = (float)__builtin_bit_cast(_Float16, (unsigned short)m);
+    constexpr float kInv127 = 1.0f / 127.0f;
+    const float q0 = a * kInv127;
+    const float r = __builtin_fmaf(-q0, 127.0f, a);
+    PageScale ps;
+    ps.s = __builtin_fmaf(r, kInv127, q0);
+    const float y0 = __builtin_amdgcn_rcpf(ps.s);
+    const float e = __builtin_fmaf(-ps.s, y0, 1.0f);
+    ps.s_inv = __builtin_fmaf(e, y0, y0);
+    return ps;
 }
 
 struct PageResult {
@@ -139,6 +167,7 @@ struct EncTask {
 };
 
 // Position of a wave's first page task as (block, page in block); later tasks advance it by one page.
+// A wave works on one page at a time, so positions and everything derived from them are wave-uniform.
 struct TaskPos {
     int64_t blk;
     int pg;
@@ -151,7 +180,8 @@ __device__ __forceinline__ TaskPos task_pos(int64_t t, int ppb) {
     } else {
         r.blk = (int64_t)((uint32_t)t / (uint32_t)ppb);
     }
-    r.pg = (int)(t - r.blk * ppb);
+    r.pg = wave_uniform((int32_t)(t - r.blk * ppb));
+    r.blk = wave_uniform(r.blk);
     return r;
 }
 
@@ -171,8 +201,8 @@ __device__ __forceinline__ EncTask resolve_enc_task(const EncodeArgs& a, int64_t
     const int ppb = a.g.ppb;
     const int64_t blk = pos.blk;
     const int pg = pos.pg;
-    const int64_t sb = a.src_ids ? (int64_t)a.src_ids[blk] : blk;
-    const int64_t pb = a.pool_ids ? (int64_t)a.pool_ids[blk] : blk;
+    const int64_t sb = a.src_ids ? (int64_t)wave_uniform(a.src_ids[blk]) : blk;
+    const int64_t pb = a.pool_ids ? (int64_t)wave_uniform(a.pool_ids[blk]) : blk;
     if (sb < 0 || pb < 0) return r;
     const uint64_t d_idx = (uint64_t)pb * (uint64_t)ppb + (uint64_t)pg;
     if (sb >= a.n_cache_blocks || d_idx >= a.n_desc) {
@@ -181,7 +211,7 @@ __device__ __forceinline__ EncTask resolve_enc_task(const EncodeArgs& a, int64_t
     }
     r.src_off = page_base(a.g, sb, pg);
     r.desc_idx = (long long)d_idx;
-    if (a.block_scheme) r.scheme = min((int)a.block_scheme[blk], (int)KVC_MODE_PACK);
+    if (a.block_scheme) r.scheme = min(wave_uniform((int32_t)a.block_scheme[blk]), (int32_t)KVC_MODE_PACK);
     return r;
 }
 
@@ -208,21 +238,21 @@ __device__ __forceinline__ DecTask resolve_dec_task(const DecodeArgs& a, int64_t
         const int64_t layer = blk / per_layer;
         const int64_t sj = blk - layer * per_layer;
         const int64_t sq = sj / a.k;
-        const int32_t lb = a.pred[sj];
+        const int32_t lb = wave_uniform(a.pred[sj]);
         db = blk;
         pb = -1;
         if (lb >= a.max_blocks) {
             bad_index = true;
         } else if (lb >= 0) {
-            const int32_t e = a.block_table[sq * a.max_blocks + lb];
+            const int32_t e = wave_uniform(a.block_table[sq * a.max_blocks + lb]);
             if (e >= a.pool_blocks_per_layer)
                 bad_index = true;
             else if (e >= 0)
                 pb = layer * a.pool_blocks_per_layer + e;
         }
     } else {
-        pb = a.pool_ids ? (int64_t)a.pool_ids[blk] : blk;
-        db = a.dst_ids ? (int64_t)a.dst_ids[blk] : blk;
+        pb = a.pool_ids ? (int64_t)wave_uniform(a.pool_ids[blk]) : blk;
+        db = a.dst_ids ? (int64_t)wave_uniform(a.dst_ids[blk]) : blk;
     }
     if (db < 0 || db >= a.n_out_blocks) {
         if (db >= 0 && lane_id() == 0) atomicOr(&a.st->status, KVC_ST_BAD_INDEX);
@@ -260,20 +290,18 @@ struct EncBook {
 // atomic on the pool cursor and hands each page its offset; pages that do not fit become INVALID.
 template <int SLOTS>
 __device__ __forceinline__ void reserve_pool_span(const EncodeArgs& a, EncBook<SLOTS>& b) {
-    unsigned long long tot = 0;
+    uint32_t tot = 0;  // at most SLOTS * 512 units
     for (int k = 0; k < SLOTS; ++k) tot += b.n16[k];
-    unsigned long long base = tot ? atomicAdd(&a.st->cursor16, tot) : 0ull;
-    bool full = false;
+    const unsigned long long base = tot ? atomicAdd(&a.st->cursor16, (unsigned long long)tot) : 0ull;
+    const bool all_fit = base + tot <= a.pool_units;
+    uint32_t rel = 0;
     for (int k = 0; k < SLOTS; ++k) {
-        const unsigned long long n = b.n16[k];
-        if (n && base + n > a.pool_units) {
-            b.mode[k] = KVC_MODE_INVALID;
-            full = true;
-        }
-        b.off16[k] = base;
-        base += n;
+        const uint32_t n = b.n16[k];
+        if (!all_fit && n && base + rel + n > a.pool_units) b.mode[k] = KVC_MODE_INVALID;
+        b.off16[k] = base + rel;
+        rel += n;
     }
-    if (full) atomicOr(&a.st->status, KVC_ST_POOL_FULL);
+    if (!all_fit) atomicOr(&a.st->status, KVC_ST_POOL_FULL);
 }
 
 // A wave moves one staged payload (or, for RAW, the source page) to its pool span and writes the

@@ -133,8 +133,9 @@ __device__ PageResult encode_page(const uint16_t* __restrict__ src, const Geomet
     }
     float s = 0.0f, s_inv = 0.0f;
     if (m != 0) {
-        s = half_bits_to_float(m) / 127.0f;
-        s_inv = 1.0f / s;
+        const PageScale ps = page_scale(m);
+        s = ps.s;
+        s_inv = ps.s_inv;
     }
     r.scale = s;
     if (scheme == KVC_MODE_INT8) {
@@ -591,6 +592,19 @@ __global__ void k_fill_i32(int32_t* p, int32_t v, uint64_t n) {
     for (uint64_t k = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += (uint64_t)gridDim.x * blockDim.x) p[k] = v;
 }
 
+// The encoder's scale arithmetic for a list of page maxima (FP16 bit patterns); 0, Inf and NaN
+// patterns give s = s_inv = 0, as the encoder never scales such pages.
+__global__ void k_page_scales(const uint16_t* amax, float* s, float* s_inv, uint64_t n) {
+    const uint64_t k = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= n) return;
+    const uint32_t m = amax[k] & 0x7FFFu;
+    PageScale ps;
+    ps.s = ps.s_inv = 0.0f;
+    if (m != 0 && m < 0x7C00u) ps = page_scale(m);
+    s[k] = ps.s;
+    s_inv[k] = ps.s_inv;
+}
+
 // ---------------------------------------------------------------------------------- launchers
 
 static inline unsigned grid_for(int64_t n_pages, int ppw) {
@@ -658,6 +672,12 @@ hipError_t launch_stats(DevState* st, const kvc_desc* desc, uint64_t n_desc, hip
         const unsigned blocks = (unsigned)std::min<uint64_t>((n_desc + 255) / 256, 2048);
         hipLaunchKernelGGL(k_stats, dim3(blocks), dim3(256), 0, s, st, desc, n_desc);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_page_scales(const uint16_t* amax, float* s, float* s_inv, uint64_t n, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_page_scales, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, amax, s, s_inv, n);
     return hipGetLastError();
 }
 

@@ -180,7 +180,7 @@ __device__ __forceinline__ uint32_t lane_byte_off(const Geometry& g) {
 template <int D>
 __device__ __forceinline__ void load_page(const EncodeArgs& a, const EncTask& task, uint32_t lane_off,
                                           uint4 (&raw)[Page<D>::kPasses]) {
-    const char* src = reinterpret_cast<const char*>(a.cache) + wave_uniform(task.src_off * 2);
+    const char* src = reinterpret_cast<const char*>(a.cache) + wave_uniform((int64_t)task.src_off * 2);
     const int64_t pass_bytes = (int64_t)Page<D>::kRowsPerPass * a.g.row_stride * 2;
 #pragma unroll
     for (int p = 0; p < Page<D>::kPasses; ++p)
@@ -220,8 +220,9 @@ __device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPa
     }
     float s = 0.0f, s_inv = 0.0f;
     if (m != 0) {
-        s = (float)__builtin_bit_cast(_Float16, (unsigned short)m) / 127.0f;
-        s_inv = 1.0f / s;
+        const PageScale ps = page_scale(m);
+        s = ps.s;
+        s_inv = ps.s_inv;
     }
     r.scale = s;
     if (scheme == KVC_MODE_INT8) {
@@ -295,64 +296,76 @@ __device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPa
     return r;
 }
 
+// Encode the page held in `raw` (if the task is live) into LDS slot `slot` and note its result.
+template <int D, int SCHEME, int SLOTS>
+__device__ __forceinline__ void encode_into_slot(const EncodeArgs& a, const uint4 (&raw)[Page<D>::kPasses], const EncTask& task,
+                                                 int slot, uint32_t* stage, const uint8_t* lut, EncBook<SLOTS>& book) {
+    PageResult r;
+    r.n16 = 0;
+    r.mode = KVC_MODE_INVALID;
+    r.scale = 0.0f;
+    if (task.desc_idx >= 0) r = encode_p16<D, SCHEME>(raw, task.scheme, stage, lut, a.st);
+    if (lane_id() == 0) {
+        book.n16[slot] = r.n16;
+        book.mode[slot] = r.mode;
+        book.scale[slot] = r.scale;
+        book.desc[slot] = task.desc_idx;
+        book.srcoff[slot] = task.src_off;
+    }
+}
+
 template <int D, int WAVES, int PPW, int SCHEME>
 __global__ __launch_bounds__(WAVES * 64) void k_compress_p16(EncodeArgs a) {
     constexpr int kSlots = WAVES * PPW;
     constexpr int NP = Page<D>::kPasses;
     constexpr bool kPrefetch = D <= 128;  // at D = 256 a second page in registers halves the occupancy
+    static_assert(!kPrefetch || PPW % 2 == 0, "the prefetching loop handles pages in pairs");
     __shared__ __align__(16) uint32_t s_stage[kSlots][Slot<NP>::kWords];
     __shared__ EncBook<kSlots> s_book;
     __shared__ uint8_t s_lut[512];
-    const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     fill_zigzag_lut(s_lut);
     __syncthreads();
     const int64_t t0 = ((int64_t)task_block_index() * WAVES + wave) * PPW;
     TaskPos pos = task_pos(t0, a.g.ppb);
-    // the next page's loads are issued before the current page is encoded
-    EncTask task = resolve_enc_task(a, t0, pos);
     const uint32_t lane_off = lane_byte_off<D>(a.g);
-    uint4 raw[NP];
-    if (task.desc_idx >= 0) load_page<D>(a, task, lane_off, raw);
+    const int slot0 = wave * PPW;
+    if (kPrefetch) {
+        // Two pages in registers: while one is encoded the loads of the next are in flight.  The
+        // pair of register sets alternates roles, so nothing is copied between them.
+        EncTask ta = resolve_enc_task(a, t0, pos), tb;
+        uint4 ra[NP], rb[NP];
+        if (ta.desc_idx >= 0) load_page<D>(a, ta, lane_off, ra);
 #pragma unroll 1
-    for (int i = 0; i < PPW; ++i) {
-        const int slot = wave * PPW + i;
-        task_advance(pos, a.g.ppb);
-        EncTask next;
-        next.desc_idx = -1;
-        next.src_off = -1;
-        next.scheme = 0;
-        uint4 raw_next[NP];
-        if (kPrefetch && i + 1 < PPW) {
-            next = resolve_enc_task(a, t0 + i + 1, pos);
-            if (next.desc_idx >= 0) load_page<D>(a, next, lane_off, raw_next);
+        for (int i = 0; i < PPW; i += 2) {
+            task_advance(pos, a.g.ppb);
+            tb = resolve_enc_task(a, t0 + i + 1, pos);
+            if (tb.desc_idx >= 0) load_page<D>(a, tb, lane_off, rb);
+            encode_into_slot<D, SCHEME>(a, ra, ta, slot0 + i, s_stage[slot0 + i], s_lut, s_book);
+            task_advance(pos, a.g.ppb);
+            ta = resolve_enc_task(a, i + 2 < PPW ? t0 + i + 2 : a.n_pages, pos);  // past the end: no task
+            if (ta.desc_idx >= 0) load_page<D>(a, ta, lane_off, ra);
+            encode_into_slot<D, SCHEME>(a, rb, tb, slot0 + i + 1, s_stage[slot0 + i + 1], s_lut, s_book);
         }
-        PageResult r;
-        r.n16 = 0;
-        r.mode = KVC_MODE_INVALID;
-        r.scale = 0.0f;
-        if (task.desc_idx >= 0) r = encode_p16<D, SCHEME>(raw, task.scheme, s_stage[slot], s_lut, a.st);
-        if (lane == 0) {
-            s_book.n16[slot] = r.n16;
-            s_book.mode[slot] = r.mode;
-            s_book.scale[slot] = r.scale;
-            s_book.desc[slot] = task.desc_idx;
-            s_book.srcoff[slot] = task.src_off;
-        }
-        if (kPrefetch) {
-            task = next;
-#pragma unroll
-            for (int p = 0; p < NP; ++p) raw[p] = raw_next[p];
-        } else if (i + 1 < PPW) {
-            task = resolve_enc_task(a, t0 + i + 1, pos);
-            if (task.desc_idx >= 0) load_page<D>(a, task, lane_off, raw);
+    } else {
+        EncTask task = resolve_enc_task(a, t0, pos);
+        uint4 raw[NP];
+        if (task.desc_idx >= 0) load_page<D>(a, task, lane_off, raw);
+#pragma unroll 1
+        for (int i = 0; i < PPW; ++i) {
+            task_advance(pos, a.g.ppb);
+            encode_into_slot<D, SCHEME>(a, raw, task, slot0 + i, s_stage[slot0 + i], s_lut, s_book);
+            if (i + 1 < PPW) {
+                task = resolve_enc_task(a, t0 + i + 1, pos);
+                if (task.desc_idx >= 0) load_page<D>(a, task, lane_off, raw);
+            }
         }
     }
     __syncthreads();
     if (threadIdx.x == 0) reserve_pool_span<kSlots>(a, s_book);
     __syncthreads();
 #pragma unroll 1
-    for (int i = 0; i < PPW; ++i) emit_page<kSlots>(a, s_book, wave * PPW + i, s_stage[wave * PPW + i]);
+    for (int i = 0; i < PPW; ++i) emit_page<kSlots>(a, s_book, slot0 + i, s_stage[slot0 + i]);
 }
 
 // ---------------------------------------------------------------------------------- decode

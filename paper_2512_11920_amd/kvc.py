@@ -21,7 +21,8 @@ ST_POOL_FULL, ST_CORRUPT, ST_BAD_INDEX = 1, 2, 4
 DESC_DTYPE = np.dtype([("off", "<u8"), ("scale", "<f4"), ("n16", "<u2"), ("mode", "u1"), ("rsvd", "u1")])
 
 EXPORTS = ("kvc_create", "kvc_destroy", "kvc_set_scheme", "kvc_set_cache_layout", "kvc_bind_pool", "kvc_reset_pool", "kvc_compress_blocks",
-           "kvc_compress_blocks_mixed", "kvc_decompress_blocks", "kvc_gather_decompress", "kvc_set_prefetch_policy", "kvc_prefetch_reset", "kvc_prefetch_layers", "kvc_stats", "kvc_copy_bytes", "kvc_strerror")
+           "kvc_compress_blocks_mixed", "kvc_decompress_blocks", "kvc_gather_decompress", "kvc_set_prefetch_policy", "kvc_prefetch_reset", "kvc_prefetch_layers", "kvc_stats", "kvc_page_scales",
+           "kvc_copy_bytes", "kvc_strerror")
 
 
 class Config(C.Structure):
@@ -86,6 +87,8 @@ def load():
                                       C.c_int32, C.c_int32, C.c_int64, C.c_int32, vp]
     L.kvc_stats.restype = C.c_int
     L.kvc_stats.argtypes = [vp, C.POINTER(Stats), vp]
+    L.kvc_page_scales.restype = C.c_int
+    L.kvc_page_scales.argtypes = [vp, vp, vp, C.c_uint64, vp]
     L.kvc_copy_bytes.restype = C.c_int
     L.kvc_copy_bytes.argtypes = [vp, vp, C.c_uint64, vp]
     L.kvc_strerror.restype = C.c_char_p
@@ -277,6 +280,18 @@ class Codec:
         s = self.stats()
         n = sum(s["pages"])
         return (n * self.page_elems * 2) / (s["payload_bytes"] + 16 * n) if n else float("nan")
+
+
+def page_scales(amax_bits, stream=None):
+    """Scaling step of Alg. 2 for FP16 page maxima (int16/uint16 CUDA tensor of bit patterns): -> (s, s_inv)."""
+    import torch
+
+    assert amax_bits.element_size() == 2 and amax_bits.is_contiguous()
+    s = torch.empty(amax_bits.numel(), dtype=torch.float32, device=amax_bits.device)
+    s_inv = torch.empty_like(s)
+    _check(load().kvc_page_scales(amax_bits.data_ptr(), s.data_ptr(), s_inv.data_ptr(), amax_bits.numel(), _stream(stream)),
+           "kvc_page_scales")
+    return s, s_inv
 
 
 def copy_bytes(dst, src, stream=None):

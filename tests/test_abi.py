@@ -60,6 +60,8 @@ def test_host_side_argument_checks_need_no_device():
     assert lib.kvc_prefetch_reset(None, None, 0, 0, 0, None) == kvc.ERR_ARG
     assert lib.kvc_prefetch_layers(None, None, None, None, None, None, 0, None, None, 0, 0, 0, 0, 0, 0, 0, None) == kvc.ERR_ARG
     assert lib.kvc_stats(None, None, None) == kvc.ERR_ARG
+    assert lib.kvc_page_scales(None, None, None, 4, None) == kvc.ERR_ARG
+    assert lib.kvc_page_scales(None, None, None, 0, None) == 0  # nothing to do
     assert lib.kvc_copy_bytes(None, None, 16, None) == kvc.ERR_ARG
     assert lib.kvc_copy_bytes(C.c_void_p(4096), C.c_void_p(8192), 24, None) == kvc.ERR_ARG  # not a multiple of 16
     lib.kvc_destroy(None)

@@ -84,3 +84,68 @@ def test_differential(N, d, n, scheme):
         raise AssertionError(f"decoded page {p} (family {fam[p]}, mode {od['mode'][p]}) differs")
     modes = np.bincount(od["mode"], minlength=5)
     assert modes[0] > 0 and modes[1] > 0 and modes[scheme] > 0  # raw, fallback and packed pages all occurred
+
+
+def _soak_pages(rng, n, N, d):
+    """n pages drawn without Python loops: channel-scaled noise, channel-correlated walks (narrow widths,
+    zero groups) and constant rows with offsets (run packets), mixed page by page."""
+    kind = rng.integers(0, 3, n)
+    noise = rng.standard_normal((n, N, d), dtype=np.float32) * np.exp(rng.standard_normal((n, 1, d), dtype=np.float32))
+    walk = np.cumsum(rng.integers(-2, 3, (n, N, d), dtype=np.int8), axis=2, dtype=np.float32)
+    walk[:, :, 0] += 100.0  # keeps the page maximum away from the walk's own range
+    rows = np.broadcast_to(rng.integers(-60, 61, (n, N, 1)).astype(np.float32), (n, N, d)).copy()
+    rows[:, 0, 0] = 127.0
+    x = np.where((kind == 0)[:, None, None], noise, np.where((kind == 1)[:, None, None], walk, rows))
+    return x.astype(np.float16)
+
+
+@pytest.mark.parametrize("d", [64, 128, 256])
+@pytest.mark.parametrize("scheme", [2, 3, 4, "mixed"])
+def test_every_fast_kernel_instantiation_under_full_occupancy(d, scheme):
+    """Each instantiation of the 16-token kernels (three head dimensions; the compile-time scheme, the
+    run-time scheme and the per-block scheme) on enough pages that several workgroups share every
+    compute unit, three launches each, every page compared with the oracle bit for bit."""
+    N, n = 16, 24576
+    rng = np.random.default_rng(7000 + d + (9 if scheme == "mixed" else scheme))
+    x = _soak_pages(rng, n, N, d)
+    xt = torch.from_numpy(x.reshape(-1, 1, N, d)).to(DEV)
+    if scheme == "mixed":
+        per_block = rng.integers(0, 5, n).astype(np.uint8)
+        bs = torch.from_numpy(per_block).to(DEV)
+        od = np.zeros(n, o.DESC_DTYPE)
+        chunks, off = [], 0
+        for sc in range(5):
+            idx = np.nonzero(per_block == sc)[0]
+            dd, pp = o.compress_pages(x[idx].view(np.uint16), N, d, sc, n_threads=16)
+            dd = dd.copy()
+            dd["off"] += off
+            od[idx] = dd
+            chunks.append(pp)
+            off += pp.size
+        op = np.concatenate(chunks)
+    else:
+        bs = None
+        od, op = o.compress_pages(x.view(np.uint16), N, d, scheme, n_threads=16)
+    want, bad = o.decompress_pages(op, od, N, d, n_threads=16)
+    assert bad == 0
+    c = kvc.Codec(N, d, 1, 3 if scheme == "mixed" else scheme)
+    c.alloc_pool(n, n * N * d * 2 + 64, DEV)
+    out = torch.empty_like(xt)
+    for launch in range(3):
+        c.reset_pool()
+        c.compress_blocks(xt, block_scheme=bs)
+        out.zero_()
+        c.decompress_blocks(out)
+        st = c.stats()
+        assert st["rc"] == 0, st
+        desc, pool = c.desc_numpy(), c.pool.cpu().numpy()
+        assert np.array_equal(desc["mode"], od["mode"]) and np.array_equal(desc["n16"], od["n16"])
+        assert np.array_equal(desc["scale"].view(np.uint32), od["scale"].view(np.uint32))
+        size = od["n16"].astype(np.int64) * 16
+        start = np.concatenate([[0], np.cumsum(size)[:-1]])
+        got = pool[np.repeat(desc["off"].astype(np.int64) - start, size) + np.arange(size.sum())]
+        ref = op[np.repeat(od["off"].astype(np.int64) - start, size) + np.arange(size.sum())]
+        if not np.array_equal(got, ref):
+            badp = np.unique(np.searchsorted(np.cumsum(size), np.nonzero(got != ref)[0], side="right"))
+            raise AssertionError(f"launch {launch}: payload bytes differ in {badp.size} pages, first {badp[:8]}")
+        assert np.array_equal(out.cpu().numpy().view(np.uint16).reshape(-1, N, d), want), f"launch {launch}: decoded values differ"

@@ -189,3 +189,22 @@ def test_decode_gather_pattern_70b_shape():
         got = out[torch.from_numpy(sb).to(DEV)].cpu().numpy().view(np.uint16).reshape(-1, N, d)
         assert np.array_equal(got, want)
     assert codec.stats()["status"] == 0
+
+
+def test_scale_arithmetic_equals_ieee_division_for_every_maximum():
+    """Scaling step of Algorithm 2: the encoder forms s = amax / 127 and 1 / s without division
+    instructions.  Both must be the correctly rounded binary32 quotients for all 31,743 finite non-zero
+    FP16 magnitudes (numpy's float32 division is the yardstick), and 0 for zero, Inf and NaN."""
+    bits = np.arange(0, 0x8000, dtype=np.uint16)
+    s, s_inv = kvc.page_scales(torch.from_numpy(bits.view(np.int16)).to(DEV))
+    s, s_inv = s.cpu().numpy(), s_inv.cpu().numpy()
+    fin = (bits > 0) & (bits < 0x7C00)
+    want_s = bits[fin].view(np.float16).astype(np.float32) / np.float32(127.0)
+    want_i = np.float32(1.0) / want_s
+    assert want_s.dtype == np.float32 and want_i.dtype == np.float32
+    assert np.array_equal(s[fin].view(np.uint32), want_s.view(np.uint32))
+    assert np.array_equal(s_inv[fin].view(np.uint32), want_i.view(np.uint32))
+    assert not s[~fin].any() and not s_inv[~fin].any()
+    # the sign bit of the pattern is ignored
+    s2, i2 = kvc.page_scales(torch.from_numpy((bits | 0x8000).view(np.int16)).to(DEV))
+    assert np.array_equal(s2.cpu().numpy(), s) and np.array_equal(i2.cpu().numpy(), s_inv)

@@ -173,15 +173,12 @@ struct TaskPos {
     int pg;
 };
 
+// The host bounds the pages of one call by 2^31 - 1, so task indices divide in 32 bits.
 __device__ __forceinline__ TaskPos task_pos(int64_t t, int ppb) {
     TaskPos r;
-    if ((uint64_t)t >> 32) {
-        r.blk = t / ppb;
-    } else {
-        r.blk = (int64_t)((uint32_t)t / (uint32_t)ppb);
-    }
-    r.pg = wave_uniform((int32_t)(t - r.blk * ppb));
-    r.blk = wave_uniform(r.blk);
+    const uint32_t blk = (uint32_t)t / (uint32_t)ppb;
+    r.pg = wave_uniform((int32_t)((uint32_t)t - blk * (uint32_t)ppb));
+    r.blk = (int64_t)(uint32_t)wave_uniform((int32_t)blk);
     return r;
 }
 
@@ -234,10 +231,11 @@ __device__ __forceinline__ DecTask resolve_dec_task(const DecodeArgs& a, int64_t
     int64_t pb, db;
     bool bad_index = false;
     if (a.block_table) {  // translate (layer, sequence, predicted logical block) -> pool block
-        const int64_t per_layer = (int64_t)a.n_seq * a.k;
-        const int64_t layer = blk / per_layer;
-        const int64_t sj = blk - layer * per_layer;
-        const int64_t sq = sj / a.k;
+        const uint32_t per_layer = (uint32_t)a.n_seq * (uint32_t)a.k;  // blocks of one call fit 31 bits
+        const uint32_t layer_u = (uint32_t)blk / per_layer;
+        const uint32_t sj = (uint32_t)blk - layer_u * per_layer;
+        const int64_t sq = sj / (uint32_t)a.k;
+        const int64_t layer = layer_u;
         const int32_t lb = wave_uniform(a.pred[sj]);
         db = blk;
         pb = -1;

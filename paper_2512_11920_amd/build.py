@@ -38,5 +38,21 @@ def build(force: bool = True, verbose: bool = False, extra_flags=()) -> str:
     return LIB
 
 
+CLIENT_SRC = os.path.join(_ROOT, "tests", "abi_client.cpp")
+CLIENT_BIN = os.path.join(_ROOT, "tests", "abi_client")
+
+
+def build_client(verbose: bool = False) -> str:
+    """Compile the stand-alone C-ABI client (HIP runtime + kvc.h only) against the built library."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "-O2", "-std=c++17", "-Wall", "-Wno-unused-command-line-argument", "-I", os.path.join(_ROOT, "include"),
+           "-o", CLIENT_BIN, CLIENT_SRC, "-L", _PKG, "-lkvc", "-Wl,-rpath," + _PKG, "-Wl,-rpath,$ORIGIN/../paper_2512_11920_amd"]
+    if verbose:
+        print(" ".join(cmd), file=sys.stderr)
+    subprocess.run(cmd, check=True)
+    return CLIENT_BIN
+
+
 if __name__ == "__main__":
     print(build(force=True, verbose=True))
+    print(build_client(verbose=True))

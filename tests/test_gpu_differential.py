@@ -99,14 +99,18 @@ def _soak_pages(rng, n, N, d):
     return x.astype(np.float16)
 
 
-@pytest.mark.parametrize("d", [64, 128, 256])
-@pytest.mark.parametrize("scheme", [2, 3, 4, "mixed"])
-def test_every_fast_kernel_instantiation_under_full_occupancy(d, scheme):
+_SOAK_CASES = [(16, d, sc) for d in (64, 128, 256) for sc in (2, 3, 4, "mixed")] + \
+              [(N, d, sc) for (N, d) in ((8, 128), (32, 64), (16, 32), (4, 256)) for sc in (3, "mixed")]
+
+
+@pytest.mark.parametrize("N,d,scheme", _SOAK_CASES)
+def test_every_kernel_instantiation_under_full_occupancy(N, d, scheme):
     """Each instantiation of the 16-token kernels (three head dimensions; the compile-time scheme, the
-    run-time scheme and the per-block scheme) on enough pages that several workgroups share every
-    compute unit, three launches each, every page compared with the oracle bit for bit."""
-    N, n = 16, 24576
-    rng = np.random.default_rng(7000 + d + (9 if scheme == "mixed" else scheme))
+    run-time scheme and the per-block scheme) and of the generic kernels (one, four or eight passes per
+    page) on enough pages that several workgroups share every compute unit, three launches each, every
+    page compared with the oracle bit for bit."""
+    n = 24576
+    rng = np.random.default_rng(7000 + 31 * N + d + (9 if scheme == "mixed" else scheme))
     x = _soak_pages(rng, n, N, d)
     xt = torch.from_numpy(x.reshape(-1, 1, N, d)).to(DEV)
     if scheme == "mixed":

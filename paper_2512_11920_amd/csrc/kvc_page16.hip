@@ -496,26 +496,31 @@ __device__ __forceinline__ bool decode_p16(const DecodeArgs& a, uint64_t d_idx, 
         // value k sits at bits [k*c, k*c + c); delta = (u >> 1) ^ -(u & 1) taken straight from the fields
         const uint32_t w1 = c - 1u;
         const uint32_t o1 = c, o2 = c << 1, o3 = o2 + c;
-        int dl[8];
-        dl[0] = (int)__builtin_amdgcn_ubfe(lo, 1u, w1) ^ __builtin_amdgcn_sbfe((int)lo, 0u, 1u);
-        dl[1] = (int)__builtin_amdgcn_ubfe(lo, o1 + 1u, w1) ^ __builtin_amdgcn_sbfe((int)lo, o1, 1u);
-        dl[2] = (int)__builtin_amdgcn_ubfe(lo, o2 + 1u, w1) ^ __builtin_amdgcn_sbfe((int)lo, o2, 1u);
-        dl[3] = (int)__builtin_amdgcn_ubfe(lo, o3 + 1u, w1) ^ __builtin_amdgcn_sbfe((int)lo, o3, 1u);
-        dl[4] = (int)__builtin_amdgcn_ubfe(mid, 1u, w1) ^ __builtin_amdgcn_sbfe((int)mid, 0u, 1u);
-        dl[5] = (int)__builtin_amdgcn_ubfe(mid, o1 + 1u, w1) ^ __builtin_amdgcn_sbfe((int)mid, o1, 1u);
-        dl[6] = (int)__builtin_amdgcn_ubfe(mid, o2 + 1u, w1) ^ __builtin_amdgcn_sbfe((int)mid, o2, 1u);
-        dl[7] = (int)__builtin_amdgcn_ubfe(mid, o3 + 1u, w1) ^ __builtin_amdgcn_sbfe((int)mid, o3, 1u);
-        // prefix sum along the channel index: in the lane, then across the lanes of the token row
-        const uint32_t tot = (uint32_t)(dl[0] + dl[1] + dl[2] + dl[3] + dl[4] + dl[5] + dl[6] + dl[7]);
+        uint32_t hb[8];  // bits above the sign flag
+        int sg[8];       // 0 or -1 from the sign flag
+        hb[0] = __builtin_amdgcn_ubfe(lo, 1u, w1), sg[0] = __builtin_amdgcn_sbfe((int)lo, 0u, 1u);
+        hb[1] = __builtin_amdgcn_ubfe(lo, o1 + 1u, w1), sg[1] = __builtin_amdgcn_sbfe((int)lo, o1, 1u);
+        hb[2] = __builtin_amdgcn_ubfe(lo, o2 + 1u, w1), sg[2] = __builtin_amdgcn_sbfe((int)lo, o2, 1u);
+        hb[3] = __builtin_amdgcn_ubfe(lo, o3 + 1u, w1), sg[3] = __builtin_amdgcn_sbfe((int)lo, o3, 1u);
+        hb[4] = __builtin_amdgcn_ubfe(mid, 1u, w1), sg[4] = __builtin_amdgcn_sbfe((int)mid, 0u, 1u);
+        hb[5] = __builtin_amdgcn_ubfe(mid, o1 + 1u, w1), sg[5] = __builtin_amdgcn_sbfe((int)mid, o1, 1u);
+        hb[6] = __builtin_amdgcn_ubfe(mid, o2 + 1u, w1), sg[6] = __builtin_amdgcn_sbfe((int)mid, o2, 1u);
+        hb[7] = __builtin_amdgcn_ubfe(mid, o3 + 1u, w1), sg[7] = __builtin_amdgcn_sbfe((int)mid, o3, 1u);
         uint32_t pb[8];
         if (mode == KVC_MODE_PACK) {  // no delta step was taken: the fields are the codes
 #pragma unroll
-            for (int k = 0; k < 8; ++k) pb[k] = (uint32_t)dl[k] + 128u;
+            for (int k = 0; k < 8; ++k) pb[k] = (hb[k] ^ (uint32_t)sg[k]) + 128u;
         } else {
-            const uint32_t rincl = row_incl_scan<Page<D>::kLpr>(tot);
-            pb[0] = rincl - tot + 128u + (uint32_t)dl[0];  // +128: biased codes, see dequant8_biased
+            // prefix sum along the channel index: in the lane first (each step is one xor-add), then
+            // the lanes of the token row before this one
+            uint32_t pre[8];
+            pre[0] = hb[0] ^ (uint32_t)sg[0];
 #pragma unroll
-            for (int k = 1; k < 8; ++k) pb[k] = pb[k - 1] + (uint32_t)dl[k];
+            for (int k = 1; k < 8; ++k) pre[k] = (hb[k] ^ (uint32_t)sg[k]) + pre[k - 1];
+            const uint32_t tot = pre[7];
+            const uint32_t base = row_incl_scan<Page<D>::kLpr>(tot) - tot + 128u;  // +128: biased codes, see dequant8_biased
+#pragma unroll
+            for (int k = 0; k < 8; ++k) pb[k] = pre[k] + base;
         }
         store_stream(reinterpret_cast<uint4*>(dst_b + p * pass_bytes + lane_off), dequant8_biased(pb, s, neg128s));
     }

@@ -97,7 +97,7 @@ def cpu_baseline(sample_u16, N, d, scheme, target_s=12.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default 10; decode_gather: 1000, as the config is stated)")
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="70b_gqa")
     ap.add_argument("--scheme", type=int, default=3)
@@ -107,6 +107,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
+    if args.steps is None:
+        args.steps = 1000 if args.workload == "decode_gather" else 10
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (pages are independent; no collective exists "
               "on the path). Run with --gpus 1.", file=sys.stderr)

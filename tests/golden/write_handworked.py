@@ -1,0 +1,70 @@
+"""Writes kvc1_handworked.json: pages small enough to encode by hand under the KVC-1 reading of
+Algorithm 2 (KV-Cache Compression) and Section 3.5.3.  Inputs come from the formulas below; every
+expected payload, scale and mode is typed in by hand with the working in its note.  Nothing here
+calls the oracle or the GPU library: the fixture pins both from outside.
+
+Run from the repository root: python tests/golden/write_handworked.py
+"""
+import json
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+cases = []
+
+
+def hx(a):
+    return np.asarray(a, np.float16).view(np.uint16).tobytes().hex()
+
+
+def add(name, N, d, x, mode, scale_bits, payload_hex, xhat=None, note="", scheme=3):
+    assert len(payload_hex) % 32 == 0
+    c = dict(name=name, N=N, d=d, scheme=scheme, x_fp16_le_hex=hx(x), mode=mode, scale_bits=scale_bits,
+             n16=len(payload_hex) // 32, payload_hex=payload_hex, note=note)
+    if xhat is not None:
+        c["xhat_bits_prefix"] = xhat
+    cases.append(c)
+
+
+i = np.arange(64)
+add("all_zero", 1, 64, np.zeros(64), 3, "00000000", "00" * 16,
+    note="amax=0: s=0, both groups zero-run packets, header byte 0x00")
+add("all_127", 1, 64, np.full(64, 127.0), 3, "3f800000", "08fe" + "00" * 46,
+    note="delta=[127,0,...]: g0 literal w=8 (u0=zigzag(127)=254), g1 zero-run; 1+32=33 -> 48 B")
+x = i.astype(np.float64)
+x[63] = 127
+add("ramp", 1, 64, x, 3, "3f800000", "82" + "a8" + "aa" * 7 + "02" * 31 + "82" + "00" * 7,
+    note="g0: u=[0,2,2,...] w=2 -> a8 aa*7; g1: u=[2]*31+[130] w=8; header 0x82; 1+8+32=41 -> 48 B")
+add("stride4", 1, 64, -127 + 4 * i, 3, "3f800000", "98" + "fd" + "08" * 31 + "08" + "00" * 14,
+    note="g0: u=[253,8,8,...] w=8; g1: all delta=4 -> run packet body 0x08; header 0x98; 1+32+1=34 -> 48 B")
+x = np.zeros(64)
+x[:31] = 4 * np.arange(31)
+x[31] = 127
+q = [4 * k for k in range(31)] + [127] + [0] * 32
+add("fallback_int8", 1, 64, x, 1, "3f800000", bytes(q).hex(),
+    note="g0 w=4 (16 B), g1 starts with delta=-127 -> w=8 (32 B); 1+16+32=49 -> 64 >= 64: stored as plain INT8")
+x = np.zeros(64)
+x[:4] = [1.0, 0.5, -1.0, 1 / 254]
+add("unit_amax", 1, 64, x, 3, "3c010204", "08fe7d82fe" + "00" * 43, xhat=["3c00", "3808", "bc00", "0000"],
+    note="amax=1: s=fl32(1/127)=0x3C010204, 1/s=127 exactly; q=[127,64,-127,0]; u=[254,125,130,254,0..]")
+x = np.zeros((2, 32))
+x[0, :] = 127
+x[0, 0] = 63
+x[0, 1] = 126
+x[1, :] = 5
+add("two_rows", 2, 32, x, 3, "3f800000", "47" + "7ebf" + "00" * 26 + "0a" + "00" * 15 + "00" * 3,
+    note="rows are differenced along the channel index only: row0 q=[63,126,127,...] u=[126,126,2,0..] w=7 "
+         "(126|126<<7|2<<14 = 0xBF7E); row1 q=5 everywhere, first column verbatim: u=[10,0,..] w=4; header 0x47; 1+28+16=45 -> 48 B")
+x = np.zeros(64)
+x[:3] = [3, -2, 1]
+x[40] = 127
+add("nodelta_mode4", 1, 64, x, 4, "3f800000", "83" + "9e" + "00" * 11 + "00" * 8 + "fe" + "00" * 23 + "00" * 3, scheme=4,
+    note="mode 4 (extension: no delta step): u = zigzag(q) = [6,3,2,0..] -> w=3, 6|3<<3|2<<6 = 0x9E; second group has "
+         "u[8] = zigzag(127) = 254 -> w=8; header 0x83; 1+12+32 = 45 -> 48 B")
+
+doc = dict(citation="Algorithm 2 (KV-Cache Compression) and Section 3.5.3 (inverse), under the KVC-1 reading of the "
+           "unspecified byte format; worked by hand, not produced by any implementation. The paper prints no numeric example.",
+           cases=cases)
+with open(os.path.join(HERE, "kvc1_handworked.json"), "w") as f:
+    json.dump(doc, f, indent=1)

@@ -136,6 +136,7 @@ __device__ __forceinline__ uint32_t row_incl_scan(uint32_t v) {
 template <int D, bool RUNS>
 __device__ __forceinline__ void encode_tail(const uint32_t (&u)[8], uint32_t c, uint32_t size, bool is_run, uint32_t qi,
                                             int p, uint32_t& run, uint32_t* stage, DevState* st) {
+    (void)st;  // only the bounds-checking build reads it
     const uint32_t incl = quad_incl_scan_dpp(size);
     const uint32_t off = run + incl - size;  // byte offset of this group's body
     run += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);

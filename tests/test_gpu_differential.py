@@ -1,5 +1,7 @@
 """Randomized differential test: many pages from deliberately varied value distributions go through the
 HIP library and the oracle; descriptors, payload bytes and decoded values must agree bit for bit."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -62,7 +64,8 @@ def _families(rng, n, N, d):
                                           (16, 32, 3000, 3), (7, 128, 3000, 3), (32, 64, 3000, 2),
                                           (16, 128, 8000, 4), (16, 64, 3000, 4), (16, 256, 3000, 4), (5, 128, 2000, 4)])
 def test_differential(N, d, n, scheme):
-    rng = np.random.default_rng(N * 1000 + d + scheme)
+    # KVC_DIFF_SEED in the environment draws a different set of pages (for longer hunts)
+    rng = np.random.default_rng(N * 1000 + d + scheme + 100003 * int(os.environ.get("KVC_DIFF_SEED", "0")))
     x, fam = _families(rng, n, N, d)
     print(f"[case] differential N={N} d={d} pages={n} scheme={scheme}", flush=True)
     xt = torch.from_numpy(x.reshape(-1, 1, N, d)).to(DEV)
@@ -110,7 +113,7 @@ def test_every_kernel_instantiation_under_full_occupancy(N, d, scheme):
     page) on enough pages that several workgroups share every compute unit, three launches each, every
     page compared with the oracle bit for bit."""
     n = 24576
-    rng = np.random.default_rng(7000 + 31 * N + d + (9 if scheme == "mixed" else scheme))
+    rng = np.random.default_rng(7000 + 31 * N + d + (9 if scheme == "mixed" else scheme) + 100003 * int(os.environ.get("KVC_DIFF_SEED", "0")))
     x = _soak_pages(rng, n, N, d)
     xt = torch.from_numpy(x.reshape(-1, 1, N, d)).to(DEV)
     if scheme == "mixed":

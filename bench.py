@@ -98,7 +98,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None, help="timed steps (default 10; decode_gather: 1000, as the config is stated)")
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="70b_gqa")
     ap.add_argument("--scheme", type=int, default=3)
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (quick runs; not the headline)")

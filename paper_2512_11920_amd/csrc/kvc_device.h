@@ -93,6 +93,43 @@ __device__ __forceinline__ uint32_t row16_incl_scan_dpp(uint32_t v) {
     return v;
 }
 
+// ---- bit strings wider than 32 bits, handled as 32-bit halves --------------------------------
+// No 64-bit shift by a register amount may appear in these kernels.  On this hardware v_lshlrev_b64 and
+// v_lshrrev_b64 misread their shift count when it sits in the last VGPR of the wave's allocation and
+// another wave shares the SIMD: the result is shifted by some bits of the neighbouring wave's first
+// register.  (Measured with a stand-alone kernel: count in v127 of 128, v119 of 120 or v63 of 64 allocated
+// registers: wrong; in any other register, or with one workgroup per compute unit: right; 32-bit shifts
+// and v_mad_u64_u32 are not affected.)  The compiler picks the registers, so the packing and unpacking
+// below use 32-bit shifts, funnel shifts and byte permutes only; a test scans the generated code.
+
+// u[0..7], each below 2^c with 0 <= c <= 8, as one little-endian bit string of 8c bits: x = low 32
+// bits, y = the rest.  (c = 9, a run packet, gives a value the caller discards.)
+__device__ __forceinline__ uint2 pack8_bits(const uint32_t (&u)[8], uint32_t c) {
+    const uint32_t a01 = u[0] | (u[1] << c), a23 = u[2] | (u[3] << c);
+    const uint32_t a45 = u[4] | (u[5] << c), a67 = u[6] | (u[7] << c);
+    const uint32_t c2 = c << 1;
+    const uint32_t b0 = a01 | (a23 << c2), b1 = a45 | (a67 << c2);  // 4c bits each
+    // b1 << 4c over 64 bits is (b1 : 0) funnel-shifted right by 32 - 4c; 4c = 32 gives (b1 : 0) itself,
+    // and 4c = 0 only occurs with b1 = 0
+    const uint32_t r = (32u - (c << 2)) & 31u;
+    return make_uint2(b0 | __builtin_amdgcn_alignbit(b1, 0u, r), __builtin_amdgcn_alignbit(0u, b1, r));
+}
+
+// The three dwords of (W.y : W.x) << 8k for k = 0..3: one byte permute each with a common selector.
+__device__ __forceinline__ void shl_bytes(uint2 W, uint32_t k, uint32_t& d0, uint32_t& d1, uint32_t& d2) {
+    const uint32_t kk = k | (k << 8);
+    const uint32_t sel = 0x07060504u - (kk | (kk << 16));
+    d0 = __builtin_amdgcn_perm(W.x, 0u, sel);
+    d1 = __builtin_amdgcn_perm(W.y, W.x, sel);
+    d2 = __builtin_amdgcn_perm(0u, W.y, sel);
+}
+
+// Low 32 bits of (hi : lo) >> 4c for 1 <= c <= 8.
+__device__ __forceinline__ uint32_t shr_nibbles(uint32_t lo, uint32_t hi, uint32_t c) {
+    const uint32_t v = __builtin_amdgcn_alignbit(hi, lo, c << 2);  // the shift is taken mod 32
+    return c == 8u ? hi : v;
+}
+
 // element offset of a page inside a cache buffer
 __device__ __forceinline__ int64_t page_base(const Geometry& g, int64_t blk, int pg) {
     return blk * g.block_stride + (int64_t)pg * g.page_stride;

@@ -195,21 +195,18 @@ __device__ PageResult encode_page(const uint16_t* __restrict__ src, const Geomet
             const uint32_t c_next = (uint32_t)__shfl_down((int)c, 4);
             if (act && (lane & 7) == 0) stage8[(p * 16 + (lane >> 2)) >> 1] = (uint8_t)(c | (c_next << 4));
             // body: this lane's 8 values are bytes [qi*w, qi*w + w) of the group's bit string
-            uint64_t W = 0;
+            uint2 W = make_uint2(0u, 0u);
             uint32_t B = hdr + off;
             if (c >= 1 && c <= 8) {
-#pragma unroll
-                for (int k = 0; k < 8; ++k) W |= (uint64_t)u[k] << (k * c);
+                W = pack8_bits(u, c);
                 B += (lane & 3) * c;
             } else if (c == 9) {
-                W = (lane & 3) == 0 ? u[0] : 0;
+                W.x = (lane & 3) == 0 ? u[0] : 0;
             }
-            if (W != 0) {
-                const uint32_t sh = (B & 3u) * 8u;
+            if ((W.x | W.y) != 0) {
                 uint32_t* p0 = stage + (B >> 2);
-                const uint64_t lo = W << sh;
-                const uint32_t d0 = (uint32_t)lo, d1 = (uint32_t)(lo >> 32);
-                const uint32_t d2 = sh ? (uint32_t)(W >> (64u - sh)) : 0u;
+                uint32_t d0, d1, d2;
+                shl_bytes(W, B & 3u, d0, d1, d2);
                 if (d0) atomicOr(p0, d0);
                 if (d1) atomicOr(p0 + 1, d1);
                 if (d2) atomicOr(p0 + 2, d2);
@@ -369,10 +366,13 @@ __device__ bool decode_page(const DecodeArgs& a, uint64_t d_idx, uint16_t* __res
                 const uint32_t d0 = p0[0], d1 = p0[1], d2 = p0[2];
                 const uint32_t lo = sh ? (d0 >> sh) | (d1 << (32u - sh)) : d0;
                 const uint32_t hi = sh ? (d1 >> sh) | (d2 << (32u - sh)) : d1;
-                const uint64_t W = (uint64_t)lo | ((uint64_t)hi << 32);
+                const uint32_t mid = shr_nibbles(lo, hi, c);  // values 4..7 start at bit 4c
                 const uint32_t mask = (1u << c) - 1u;
 #pragma unroll
-                for (int k = 0; k < 8; ++k) u[k] = (uint32_t)(W >> (k * c)) & mask;
+                for (int k = 0; k < 4; ++k) {
+                    u[k] = (lo >> (k * c)) & mask;
+                    u[4 + k] = (mid >> (k * c)) & mask;
+                }
             } else {
                 const uint32_t v = (c == 9) ? stage8[hdr + goff] : 0u;
 #pragma unroll

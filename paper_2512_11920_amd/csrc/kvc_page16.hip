@@ -148,23 +148,18 @@ __device__ __forceinline__ void encode_tail(const uint32_t (&u)[8], uint32_t c, 
         stage[2 * p + 1] = (uint32_t)(hb >> 32);
     }
     // body: this lane's 8 values are bytes [qi*c, qi*c + c) of the group's little-endian bit string
-    const uint32_t a01 = u[0] | (u[1] << c), a23 = u[2] | (u[3] << c);
-    const uint32_t a45 = u[4] | (u[5] << c), a67 = u[6] | (u[7] << c);
-    const uint32_t c2 = c << 1;
-    const uint32_t b0 = a01 | (a23 << c2), b1 = a45 | (a67 << c2);
-    uint64_t W = (uint64_t)b0 | ((uint64_t)b1 << (c << 2));
+    uint2 W = pack8_bits(u, c);
     uint32_t B = off + __umul24(qi, c);
     if (RUNS && is_run) {
-        W = qi == 0 ? u[0] : 0;
+        W = make_uint2(qi == 0 ? u[0] : 0u, 0u);
         B = off;
     }
-    const uint32_t sh = (B & 3u) << 3;
     uint32_t* p0 = stage + (B >> 2);
     KVC_CHECK(st, c <= 9 && (B >> 2) + 2 < (uint32_t)Slot<Page<D>::kPasses>::kWords && B >= (uint32_t)Page<D>::kHdr);
-    const uint64_t lo = W << sh;
-    const uint32_t d2 = (uint32_t)(((uint64_t)(uint32_t)(W >> 32) << sh) >> 32);
-    atomicOr(p0, (uint32_t)lo);
-    atomicOr(p0 + 1, (uint32_t)(lo >> 32));
+    uint32_t d0, d1, d2;
+    shl_bytes(W, B & 3u, d0, d1, d2);
+    atomicOr(p0, d0);
+    atomicOr(p0 + 1, d1);
     if (d2) atomicOr(p0 + 2, d2);
 }
 
@@ -349,17 +344,13 @@ __global__ __launch_bounds__(WAVES * 64) void k_compress_p16(EncodeArgs a) {
             encode_into_slot<D, SCHEME>(a, rb, tb, slot0 + i + 1, s_stage[slot0 + i + 1], s_lut, s_book);
         }
     } else {
-        EncTask task = resolve_enc_task(a, t0, pos);
-        uint4 raw[NP];
-        if (task.desc_idx >= 0) load_page<D>(a, task, lane_off, raw);
 #pragma unroll 1
         for (int i = 0; i < PPW; ++i) {
+            const EncTask task = resolve_enc_task(a, t0 + i, pos);
             task_advance(pos, a.g.ppb);
+            uint4 raw[NP];
+            if (task.desc_idx >= 0) load_page<D>(a, task, lane_off, raw);
             encode_into_slot<D, SCHEME>(a, raw, task, slot0 + i, s_stage[slot0 + i], s_lut, s_book);
-            if (i + 1 < PPW) {
-                task = resolve_enc_task(a, t0 + i + 1, pos);
-                if (task.desc_idx >= 0) load_page<D>(a, task, lane_off, raw);
-            }
         }
     }
     __syncthreads();
@@ -493,7 +484,7 @@ __device__ __forceinline__ bool decode_p16(const DecodeArgs& a, uint64_t d_idx, 
                 c = 1;
             }
         }
-        const uint32_t mid = (uint32_t)((((uint64_t)hi << 32) | lo) >> (c << 2));  // values 4..7 start at bit 4c
+        const uint32_t mid = shr_nibbles(lo, hi, c);  // values 4..7 start at bit 4c
         // value k sits at bits [k*c, k*c + c); delta = (u >> 1) ^ -(u & 1) taken straight from the fields
         const uint32_t w1 = c - 1u;
         const uint32_t o1 = c, o2 = c << 1, o3 = o2 + c;

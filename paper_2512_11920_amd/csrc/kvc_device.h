@@ -110,15 +110,16 @@ __device__ __forceinline__ uint2 pack8_bits(const uint32_t (&u)[8], uint32_t c) 
     const uint32_t c2 = c << 1;
     const uint32_t b0 = a01 | (a23 << c2), b1 = a45 | (a67 << c2);  // 4c bits each
     // b1 << 4c over 64 bits is (b1 : 0) funnel-shifted right by 32 - 4c; 4c = 32 gives (b1 : 0) itself,
-    // and 4c = 0 only occurs with b1 = 0
-    const uint32_t r = (32u - (c << 2)) & 31u;
+    // and 4c = 0 only occurs with b1 = 0.  The funnel shift reads its amount mod 32, so -4c will do.
+    const uint32_t r = (uint32_t)__mul24((int)c, -4);
     return make_uint2(b0 | __builtin_amdgcn_alignbit(b1, 0u, r), __builtin_amdgcn_alignbit(0u, b1, r));
 }
 
-// The three dwords of (W.y : W.x) << 8k for k = 0..3: one byte permute each with a common selector.
-__device__ __forceinline__ void shl_bytes(uint2 W, uint32_t k, uint32_t& d0, uint32_t& d1, uint32_t& d2) {
-    const uint32_t kk = k | (k << 8);
-    const uint32_t sel = 0x07060504u - (kk | (kk << 16));
+// The three dwords of (W.y : W.x) << 8k, k = B mod 4: one byte permute each with a common selector
+// {7-k, 6-k, 5-k, 4-k}, which is the byte string 08 07 .. 01 shifted right by 3 - k bytes (the byte
+// funnel shift reads its amount mod 4, so ~B will do).
+__device__ __forceinline__ void shl_bytes(uint2 W, uint32_t B, uint32_t& d0, uint32_t& d1, uint32_t& d2) {
+    const uint32_t sel = __builtin_amdgcn_alignbyte(0x08070605u, 0x04030201u, ~B);
     d0 = __builtin_amdgcn_perm(W.x, 0u, sel);
     d1 = __builtin_amdgcn_perm(W.y, W.x, sel);
     d2 = __builtin_amdgcn_perm(0u, W.y, sel);

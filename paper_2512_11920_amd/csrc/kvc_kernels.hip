@@ -206,7 +206,7 @@ __device__ PageResult encode_page(const uint16_t* __restrict__ src, const Geomet
             if ((W.x | W.y) != 0) {
                 uint32_t* p0 = stage + (B >> 2);
                 uint32_t d0, d1, d2;
-                shl_bytes(W, B & 3u, d0, d1, d2);
+                shl_bytes(W, B, d0, d1, d2);
                 if (d0) atomicOr(p0, d0);
                 if (d1) atomicOr(p0 + 1, d1);
                 if (d2) atomicOr(p0 + 2, d2);

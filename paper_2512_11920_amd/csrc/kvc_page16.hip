@@ -157,7 +157,7 @@ __device__ __forceinline__ void encode_tail(const uint32_t (&u)[8], uint32_t c, 
     uint32_t* p0 = stage + (B >> 2);
     KVC_CHECK(st, c <= 9 && (B >> 2) + 2 < (uint32_t)Slot<Page<D>::kPasses>::kWords && B >= (uint32_t)Page<D>::kHdr);
     uint32_t d0, d1, d2;
-    shl_bytes(W, B & 3u, d0, d1, d2);
+    shl_bytes(W, B, d0, d1, d2);
     atomicOr(p0, d0);
     atomicOr(p0 + 1, d1);
     if (d2) atomicOr(p0 + 2, d2);

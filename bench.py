@@ -89,9 +89,16 @@ def cpu_baseline(sample_u16, N, d, scheme, target_s=12.0):
         t_total += time.perf_counter() - t0
         done_bytes += 2 * sample_u16.nbytes
         reps += 1
+    # the same on one thread, over a sixteenth of the sample
+    one = sample_u16[: max(1, n_pages // 16)]
+    t0 = time.perf_counter()
+    od, op = o.compress_pages(one, N, d, scheme, n_threads=1)
+    o.decompress_pages(op, od, N, d, n_threads=1)
+    t_one = time.perf_counter() - t0
     return {"value": round(done_bytes / t_total / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
             "sample": f"{n_pages} pages ({sample_u16.nbytes / 2**20:.0f} MiB of the same seeded cache), "
-                      f"compress+decompress x{reps}, {t_total:.1f} s"}
+                      f"compress+decompress x{reps}, {t_total:.1f} s",
+            "single_thread_value": round(2 * one.nbytes / t_one / 1e9, 4)}
 
 
 def main():

@@ -310,12 +310,26 @@ __device__ __forceinline__ void encode_into_slot(const EncodeArgs& a, const uint
     }
 }
 
+#ifndef KVC_ENC_RING64
+#define KVC_ENC_RING64 8
+#endif
+#ifndef KVC_ENC_RING128
+#define KVC_ENC_RING128 4
+#endif
+#ifndef KVC_ENC_RING256
+#define KVC_ENC_RING256 1
+#endif
+
 template <int D, int WAVES, int PPW, int SCHEME>
 __global__ __launch_bounds__(WAVES * 64) void k_compress_p16(EncodeArgs a) {
     constexpr int kSlots = WAVES * PPW;
     constexpr int NP = Page<D>::kPasses;
-    constexpr bool kPrefetch = D <= 128;  // at D = 256 a second page in registers halves the occupancy
-    static_assert(!kPrefetch || PPW % 2 == 0, "the prefetching loop handles pages in pairs");
+    // Pages held in registers per wave: while one is encoded the loads of the next kRing - 1 are in
+    // flight.  Measured best with the ring as long as the wave's whole share (all loads issued up
+    // front, about 16 KB per wave, no loop) at d = 64 and d = 128; at d = 256 a second page in
+    // registers costs occupancy and gains nothing.
+    constexpr int kRing = D <= 64 ? KVC_ENC_RING64 : D <= 128 ? KVC_ENC_RING128 : KVC_ENC_RING256;
+    static_assert(PPW % kRing == 0, "the loop handles pages in groups of kRing");
     __shared__ __align__(16) uint32_t s_stage[kSlots][Slot<NP>::kWords];
     __shared__ EncBook<kSlots> s_book;
     __shared__ uint8_t s_lut[512];
@@ -326,22 +340,28 @@ __global__ __launch_bounds__(WAVES * 64) void k_compress_p16(EncodeArgs a) {
     TaskPos pos = task_pos(t0, a.g.ppb);
     const uint32_t lane_off = lane_byte_off<D>(a.g);
     const int slot0 = wave * PPW;
-    if (kPrefetch) {
-        // Two pages in registers: while one is encoded the loads of the next are in flight.  The
-        // pair of register sets alternates roles, so nothing is copied between them.
-        EncTask ta = resolve_enc_task(a, t0, pos), tb;
-        uint4 ra[NP], rb[NP];
-        if (ta.desc_idx >= 0) load_page<D>(a, ta, lane_off, ra);
+    if (kRing > 1) {
+        // The register sets take turns (the inner loop is unrolled, so every index is a constant):
+        // nothing is copied between them.
+        EncTask t[kRing];
+        uint4 r[kRing][NP];
+#pragma unroll
+        for (int j = 0; j < kRing - 1; ++j) {
+            if (j > 0) task_advance(pos, a.g.ppb);
+            t[j] = resolve_enc_task(a, t0 + j, pos);
+            if (t[j].desc_idx >= 0) load_page<D>(a, t[j], lane_off, r[j]);
+        }
 #pragma unroll 1
-        for (int i = 0; i < PPW; i += 2) {
-            task_advance(pos, a.g.ppb);
-            tb = resolve_enc_task(a, t0 + i + 1, pos);
-            if (tb.desc_idx >= 0) load_page<D>(a, tb, lane_off, rb);
-            encode_into_slot<D, SCHEME>(a, ra, ta, slot0 + i, s_stage[slot0 + i], s_lut, s_book);
-            task_advance(pos, a.g.ppb);
-            ta = resolve_enc_task(a, i + 2 < PPW ? t0 + i + 2 : a.n_pages, pos);  // past the end: no task
-            if (ta.desc_idx >= 0) load_page<D>(a, ta, lane_off, ra);
-            encode_into_slot<D, SCHEME>(a, rb, tb, slot0 + i + 1, s_stage[slot0 + i + 1], s_lut, s_book);
+        for (int i = 0; i < PPW; i += kRing) {
+#pragma unroll
+            for (int j = 0; j < kRing; ++j) {
+                constexpr int kAhead = kRing - 1;
+                const int nb = (j + kAhead) % kRing;
+                task_advance(pos, a.g.ppb);
+                t[nb] = resolve_enc_task(a, i + j + kAhead < PPW ? t0 + i + j + kAhead : a.n_pages, pos);  // past the end: no task
+                if (t[nb].desc_idx >= 0) load_page<D>(a, t[nb], lane_off, r[nb]);
+                encode_into_slot<D, SCHEME>(a, r[j], t[j], slot0 + i + j, s_stage[slot0 + i + j], s_lut, s_book);
+            }
         }
     } else {
 #pragma unroll 1
@@ -375,36 +395,75 @@ __device__ __forceinline__ uint4 dequant8_biased(const uint32_t pb[8], float s, 
                       __builtin_bit_cast(uint32_t, h[2]), __builtin_bit_cast(uint32_t, h[3]));
 }
 
-// Decode the page described by descriptor d_idx into dst.  false = validation failed, dst zeroed.
+// A page on its way through the decoder: the descriptor's fields, the verdict of its validation and,
+// for the packed modes, the payload as it arrives from the pool (16 bytes per lane and round).
 template <int D>
-__device__ __forceinline__ bool decode_p16(const DecodeArgs& a, uint64_t d_idx, uint16_t* __restrict__ dst,
+struct DecPage {
+    uint64_t off;
+    float s;
+    uint32_t n16, mode;
+    bool ok;
+    uint4 pay[Page<D>::kE / 1024];
+};
+
+__device__ __forceinline__ bool is_packed_mode(uint32_t mode) {
+    return mode == KVC_MODE_DELTA || mode == KVC_MODE_RLE || mode == KVC_MODE_PACK;
+}
+
+// Take the descriptor apart, validate it against the pool and the page geometry, and start the
+// payload loads of a packed page.  Nothing here waits for those loads.
+template <int D>
+__device__ __forceinline__ DecPage<D> dec_open(const DecodeArgs& a, uint4 dw) {
+    constexpr int kE = Page<D>::kE, kHdr = Page<D>::kHdr;
+    const int lane = lane_id();
+    DecPage<D> pg;
+    pg.off = (uint64_t)dw.x | ((uint64_t)dw.y << 32);
+    pg.s = __uint_as_float(dw.z);
+    pg.n16 = dw.w & 0xFFFFu;
+    pg.mode = (dw.w >> 16) & 0xFFu;
+    bool ok = (pg.off & 15u) == 0 && (pg.off >> 4) + pg.n16 <= a.pool_units;
+    if (pg.mode == KVC_MODE_RAW)
+        ok = ok && pg.n16 == kE / 8;
+    else if (pg.mode == KVC_MODE_INT8)
+        ok = ok && pg.n16 == kE / 16;
+    else if (is_packed_mode(pg.mode))
+        ok = ok && pg.n16 * 16u >= (uint32_t)kHdr && pg.n16 < kE / 16;
+    else
+        ok = false;
+    pg.ok = ok;
+#pragma unroll
+    for (int z = 0; z < kE / 1024; ++z) pg.pay[z] = make_uint4(0u, 0u, 0u, 0u);
+    if (ok && is_packed_mode(pg.mode)) {
+        const uint4* pl4 = reinterpret_cast<const uint4*>(a.pool + pg.off);
+#pragma unroll
+        for (int z = 0; z < kE / 1024; ++z) {
+#if KVC_NT_POOL
+            if ((uint32_t)lane + 64 * z < pg.n16) pg.pay[z] = load_stream(pl4 + lane + 64 * z);
+#else
+            if ((uint32_t)lane + 64 * z < pg.n16) pg.pay[z] = pl4[lane + 64 * z];
+#endif
+        }
+    }
+    return pg;
+}
+
+// Decode an opened page into dst.  false = validation failed, dst zeroed.
+template <int D>
+__device__ __forceinline__ bool dec_finish(const DecodeArgs& a, const DecPage<D>& pg, uint16_t* __restrict__ dst,
                                            uint32_t* stage, uint32_t* ginfo) {
     constexpr int kE = Page<D>::kE, kHdr = Page<D>::kHdr, NP = Page<D>::kPasses, kG = Page<D>::kGroups;
     const int lane = lane_id();
     const uint32_t qi = (uint32_t)lane & 3u;
-    const uint4 dw = reinterpret_cast<const uint4*>(a.desc)[d_idx];
-    const uint64_t off = (uint64_t)dw.x | ((uint64_t)dw.y << 32);
-    const float s = __uint_as_float(dw.z);
-    const uint32_t n16 = dw.w & 0xFFFFu;
-    const uint32_t mode = (dw.w >> 16) & 0xFFu;
+    const float s = pg.s;
+    const uint32_t n16 = pg.n16, mode = pg.mode;
     char* dst_b = reinterpret_cast<char*>(a.out) + wave_uniform((int64_t)(dst - a.out) * 2);  // wave-uniform page base
     const uint32_t lane_off = lane_byte_off<D>(a.g);    // this lane's 8 channels in pass 0
     const int64_t pass_bytes = (int64_t)Page<D>::kRowsPerPass * a.g.row_stride * 2;
-
-    bool ok = (off & 15u) == 0 && (off >> 4) + n16 <= a.pool_units;
-    if (mode == KVC_MODE_RAW)
-        ok = ok && n16 == kE / 8;
-    else if (mode == KVC_MODE_INT8)
-        ok = ok && n16 == kE / 16;
-    else if (mode == KVC_MODE_DELTA || mode == KVC_MODE_RLE || mode == KVC_MODE_PACK)
-        ok = ok && n16 * 16u >= (uint32_t)kHdr && n16 < kE / 16;
-    else
-        ok = false;
-    if (!ok) {
+    if (!pg.ok) {
         zero_page(dst, a.g);
         return false;
     }
-    const uint4* pl4 = reinterpret_cast<const uint4*>(a.pool + off);
+    const uint4* pl4 = reinterpret_cast<const uint4*>(a.pool + pg.off);
     if (mode == KVC_MODE_RAW) {  // stored-uncompressed bypass
 #pragma unroll
         for (int p = 0; p < NP; ++p) *reinterpret_cast<uint4*>(dst_b + p * pass_bytes + lane_off) = pl4[p * 64 + lane];
@@ -429,13 +488,8 @@ __device__ __forceinline__ bool decode_p16(const DecodeArgs& a, uint64_t d_idx, 
     {
         uint4* st4 = reinterpret_cast<uint4*>(stage);
 #pragma unroll
-        for (int z = 0; z < kE / 1024; ++z) {
-#if KVC_NT_POOL
-            if ((uint32_t)lane + 64 * z < n16) st4[lane + 64 * z] = load_stream(pl4 + lane + 64 * z);
-#else
-            if ((uint32_t)lane + 64 * z < n16) st4[lane + 64 * z] = pl4[lane + 64 * z];
-#endif
-        }
+        for (int z = 0; z < kE / 1024; ++z)
+            if ((uint32_t)lane + 64 * z < n16) st4[lane + 64 * z] = pg.pay[z];
     }
     wave_sync();
     // header: a lane takes the code of group g (64 groups per round); body offsets are a prefix sum of
@@ -527,12 +581,25 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_p16(DecodeArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t t0 = ((int64_t)task_block_index() * WAVES + wave) * PPW;
     TaskPos pos = task_pos(t0, a.g.ppb);
-#pragma unroll 1
+    // A page's memory chain is ids -> descriptor -> payload, each a full trip to HBM.  The wave walks
+    // it for all of its PPW pages side by side: every descriptor load is issued before the first is
+    // looked at, then every payload load before the first page is decoded.
+    DecTask task[PPW];
+    uint4 dw[PPW];
+    DecPage<D> pg[PPW];
+#pragma unroll
     for (int i = 0; i < PPW; ++i) {
-        const DecTask task = resolve_dec_task(a, t0 + i, pos);
+        task[i] = resolve_dec_task(a, t0 + i, pos);
         task_advance(pos, a.g.ppb);
-        if (task.kind == 2) zero_page(task.dst, a.g);
-        if (task.kind == 1 && !decode_p16<D>(a, task.desc_idx, task.dst, s_stage[wave], s_ginfo[wave])) {
+        if (task[i].kind == 1) dw[i] = reinterpret_cast<const uint4*>(a.desc)[task[i].desc_idx];
+    }
+#pragma unroll
+    for (int i = 0; i < PPW; ++i)
+        if (task[i].kind == 1) pg[i] = dec_open<D>(a, dw[i]);
+#pragma unroll
+    for (int i = 0; i < PPW; ++i) {
+        if (task[i].kind == 2) zero_page(task[i].dst, a.g);
+        if (task[i].kind == 1 && !dec_finish<D>(a, pg[i], task[i].dst, s_stage[wave], s_ginfo[wave])) {
             if (lane == 0) atomicOr(&a.st->status, KVC_ST_CORRUPT);
         }
         wave_sync();
@@ -581,14 +648,15 @@ hipError_t launch_compress_p16(const EncodeArgs& a, hipStream_t s) {
 
 hipError_t launch_decompress_p16(const DecodeArgs& a, hipStream_t s) {
     constexpr int WAVES = KVC_DEC_WAVES, PPW = KVC_DEC_PPW;
-    const int64_t per_wg = (int64_t)WAVES * PPW;
-    const dim3 grid((unsigned)((a.n_pages + per_wg - 1) / per_wg)), block(WAVES * 64);
+    const dim3 block(WAVES * 64);
+    auto grid = [&](int ppw) { return dim3((unsigned)((a.n_pages + (int64_t)WAVES * ppw - 1) / ((int64_t)WAVES * ppw))); };
+    // a d = 64 page is too small to cover its own memory chain: there a wave walks two side by side
     if (a.g.d == 64)
-        hipLaunchKernelGGL((k_decompress_p16<64, WAVES, PPW>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((k_decompress_p16<64, WAVES, 2 * PPW>), grid(2 * PPW), block, 0, s, a);
     else if (a.g.d == 128)
-        hipLaunchKernelGGL((k_decompress_p16<128, WAVES, PPW>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((k_decompress_p16<128, WAVES, PPW>), grid(PPW), block, 0, s, a);
     else
-        hipLaunchKernelGGL((k_decompress_p16<256, WAVES, PPW>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((k_decompress_p16<256, WAVES, PPW>), grid(PPW), block, 0, s, a);
     return hipGetLastError();
 }
 

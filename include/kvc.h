@@ -38,7 +38,8 @@
  * Calls on one context that overlap on different streams race on the pool cursor; serialise them.
  * A context belongs to the device that was current in kvc_create; calls made with another device
  * current return KVC_ERR_ARG.  A context is not thread-safe: one host thread at a time.
- * One data call handles at most 2^31 - 1 pages (blocks * pages_per_block); more is KVC_ERR_ARG.
+ * One data call handles at most 2^26 - 1 pages (blocks * pages_per_block; 256 GiB of 4 KB pages); more is
+ * KVC_ERR_ARG.
  */
 #ifndef KVC_H
 #define KVC_H

@@ -18,8 +18,10 @@ struct kvc_ctx {
 
 static_assert(sizeof(kvc_desc) == 16, "descriptor is 16 bytes");
 
-// One data call handles at most this many pages, so that every launch grid fits 31 bits.
-static constexpr int64_t kMaxPagesPerCall = INT32_MAX;
+// One data call handles at most this many pages: a launch may hold fewer than 2^32 threads in all, and
+// the decoder spends a 64-thread wave on a page (256 GiB of 4 KB pages per call; task indices then also
+// divide in 32 bits).
+static constexpr int64_t kMaxPagesPerCall = (1ll << 26) - 1;
 
 // Text of the last HIP failure seen by this thread (for kvc_strerror(KVC_ERR_HIP)).
 static thread_local hipError_t t_last_hip = hipSuccess;
@@ -121,7 +123,10 @@ int kvc_bind_pool(kvc_ctx* ctx, void* d_pool, uint64_t pool_bytes, kvc_desc* d_d
     // The pool may also live in pinned, device-mapped host memory (a slow-link tier): take the address
     // the device sees.  Pageable host memory is rejected here rather than faulting in a kernel.
     hipPointerAttribute_t attr;
-    if (!hip_ok(hipPointerGetAttributes(&attr, d_pool))) return KVC_ERR_ARG;
+    if (!hip_ok(hipPointerGetAttributes(&attr, d_pool))) {
+        (void)hipGetLastError();  // the failed query is ours: leave no error behind for the caller's next check
+        return KVC_ERR_ARG;
+    }
     if (attr.type == hipMemoryTypeHost) {
         if (!attr.devicePointer) return KVC_ERR_ARG;
         d_pool = attr.devicePointer;
@@ -129,7 +134,11 @@ int kvc_bind_pool(kvc_ctx* ctx, void* d_pool, uint64_t pool_bytes, kvc_desc* d_d
         return KVC_ERR_ARG;
     }
     hipPointerAttribute_t dattr;
-    if (!hip_ok(hipPointerGetAttributes(&dattr, d_desc)) || dattr.type == hipMemoryTypeUnregistered) return KVC_ERR_ARG;
+    if (!hip_ok(hipPointerGetAttributes(&dattr, d_desc))) {
+        (void)hipGetLastError();
+        return KVC_ERR_ARG;
+    }
+    if (dattr.type == hipMemoryTypeUnregistered) return KVC_ERR_ARG;
     if (dattr.type == hipMemoryTypeHost) {
         if (!dattr.devicePointer) return KVC_ERR_ARG;
         d_desc = static_cast<kvc_desc*>(dattr.devicePointer);

@@ -74,6 +74,19 @@ struct PlanArgs {
     DevState* st;
 };
 
+// Launch `kernel` and return the status of this launch itself.  (A launch through the <<<>>> form
+// reports failure only through the thread's last-error slot, which may still hold an error left by
+// an earlier, unrelated call of the application.)
+template <typename T>
+struct SameType {
+    using type = T;
+};
+template <typename... P>
+inline hipError_t launch_kernel(void (*kernel)(P...), dim3 grid, dim3 block, hipStream_t s, typename SameType<P>::type... args) {
+    void* ptrs[] = {static_cast<void*>(&args)...};
+    return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, 0, s);
+}
+
 hipError_t launch_prefetch_plan(const PlanArgs& a, hipStream_t s);
 hipError_t launch_fill_i32(int32_t* p, int32_t v, uint64_t n, hipStream_t s);
 hipError_t launch_compress(const EncodeArgs& a, hipStream_t s);

@@ -211,7 +211,7 @@ struct TaskPos {
     int pg;
 };
 
-// The host bounds the pages of one call by 2^31 - 1, so task indices divide in 32 bits.
+// The host bounds the pages of one call well below 2^31, so task indices divide in 32 bits.
 __device__ __forceinline__ TaskPos task_pos(int64_t t, int ppb) {
     TaskPos r;
     const uint32_t blk = (uint32_t)t / (uint32_t)ppb;

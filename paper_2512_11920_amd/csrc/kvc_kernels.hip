@@ -617,13 +617,9 @@ hipError_t launch_compress(const EncodeArgs& a, hipStream_t s) {
     if (a.g.N == 16 && a.g.d >= 64) return launch_compress_p16(a, s);
     constexpr int PPW = 4;
     const dim3 grid(grid_for(a.n_pages, PPW)), block(kThreads);
-    if (a.g.E <= 512)
-        hipLaunchKernelGGL((k_compress<1, PPW>), grid, block, 0, s, a);
-    else if (a.g.E <= 2048)
-        hipLaunchKernelGGL((k_compress<4, PPW>), grid, block, 0, s, a);
-    else
-        hipLaunchKernelGGL((k_compress<8, 2>), dim3(grid_for(a.n_pages, 2)), block, 0, s, a);
-    return hipGetLastError();
+    if (a.g.E <= 512) return launch_kernel(k_compress<1, PPW>, grid, block, s, a);
+    if (a.g.E <= 2048) return launch_kernel(k_compress<4, PPW>, grid, block, s, a);
+    return launch_kernel(k_compress<8, 2>, dim3(grid_for(a.n_pages, 2)), block, s, a);
 }
 
 hipError_t launch_decompress(const DecodeArgs& a, hipStream_t s) {
@@ -631,62 +627,47 @@ hipError_t launch_decompress(const DecodeArgs& a, hipStream_t s) {
     if (a.g.N == 16 && a.g.d >= 64) return launch_decompress_p16(a, s);
     constexpr int PPW = 4;
     const dim3 grid(grid_for(a.n_pages, PPW)), block(kThreads);
-    if (a.g.E <= 512)
-        hipLaunchKernelGGL((k_decompress<1, PPW>), grid, block, 0, s, a);
-    else if (a.g.E <= 2048)
-        hipLaunchKernelGGL((k_decompress<4, PPW>), grid, block, 0, s, a);
-    else
-        hipLaunchKernelGGL((k_decompress<8, PPW>), grid, block, 0, s, a);
-    return hipGetLastError();
+    if (a.g.E <= 512) return launch_kernel(k_decompress<1, PPW>, grid, block, s, a);
+    if (a.g.E <= 2048) return launch_kernel(k_decompress<4, PPW>, grid, block, s, a);
+    return launch_kernel(k_decompress<8, PPW>, grid, block, s, a);
 }
 
 hipError_t launch_prefetch_plan(const PlanArgs& a, hipStream_t s) {
     const int64_t n = (int64_t)(a.layer_end - a.layer_begin) * a.n_seq;
     if (n <= 0) return hipSuccess;
     const dim3 grid((unsigned)((n + 63) / 64)), block(64);
-    if (a.k <= 8)
-        hipLaunchKernelGGL(k_prefetch_plan<8>, grid, block, 0, s, a);
-    else if (a.k <= 16)
-        hipLaunchKernelGGL(k_prefetch_plan<16>, grid, block, 0, s, a);
-    else
-        hipLaunchKernelGGL(k_prefetch_plan<kMaxPrefetchK>, grid, block, 0, s, a);
-    return hipGetLastError();
+    if (a.k <= 8) return launch_kernel(k_prefetch_plan<8>, grid, block, s, a);
+    if (a.k <= 16) return launch_kernel(k_prefetch_plan<16>, grid, block, s, a);
+    return launch_kernel(k_prefetch_plan<kMaxPrefetchK>, grid, block, s, a);
 }
 
 hipError_t launch_fill_i32(int32_t* p, int32_t v, uint64_t n, hipStream_t s) {
     if (n == 0) return hipSuccess;
     const unsigned blocks = (unsigned)std::min<uint64_t>((n + 255) / 256, 4096);
-    hipLaunchKernelGGL(k_fill_i32, dim3(blocks), dim3(256), 0, s, p, v, n);
-    return hipGetLastError();
+    return launch_kernel(k_fill_i32, dim3(blocks), dim3(256), s, p, v, n);
 }
 
 hipError_t launch_reset(DevState* st, kvc_desc* desc, uint64_t n_desc, hipStream_t s) {
     const unsigned blocks = (unsigned)std::min<uint64_t>(std::max<uint64_t>((n_desc + 255) / 256, 1), 65536);
-    hipLaunchKernelGGL(k_reset, dim3(blocks), dim3(256), 0, s, st, desc, n_desc);
-    return hipGetLastError();
+    return launch_kernel(k_reset, dim3(blocks), dim3(256), s, st, desc, n_desc);
 }
 
 hipError_t launch_stats(DevState* st, const kvc_desc* desc, uint64_t n_desc, hipStream_t s) {
-    hipLaunchKernelGGL(k_stats_zero, dim3(1), dim3(64), 0, s, st);
-    if (n_desc) {
-        const unsigned blocks = (unsigned)std::min<uint64_t>((n_desc + 255) / 256, 2048);
-        hipLaunchKernelGGL(k_stats, dim3(blocks), dim3(256), 0, s, st, desc, n_desc);
-    }
-    return hipGetLastError();
+    const hipError_t e = launch_kernel(k_stats_zero, dim3(1), dim3(64), s, st);
+    if (e != hipSuccess || n_desc == 0) return e;
+    const unsigned blocks = (unsigned)std::min<uint64_t>((n_desc + 255) / 256, 2048);
+    return launch_kernel(k_stats, dim3(blocks), dim3(256), s, st, desc, n_desc);
 }
 
 hipError_t launch_page_scales(const uint16_t* amax, float* s, float* s_inv, uint64_t n, hipStream_t st) {
     if (n == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_page_scales, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, amax, s, s_inv, n);
-    return hipGetLastError();
+    return launch_kernel(k_page_scales, dim3((unsigned)((n + 255) / 256)), dim3(256), st, amax, s, s_inv, n);
 }
 
 hipError_t launch_copy(void* dst, const void* src, uint64_t n16, hipStream_t s) {
     if (n16 == 0) return hipSuccess;
     const unsigned blocks = (unsigned)std::min<uint64_t>((n16 + 255) / 256, 256u * 32u);
-    hipLaunchKernelGGL(k_copy, dim3(blocks), dim3(256), 0, s, reinterpret_cast<uint4*>(dst),
-                       reinterpret_cast<const uint4*>(src), n16);
-    return hipGetLastError();
+    return launch_kernel(k_copy, dim3(blocks), dim3(256), s, reinterpret_cast<uint4*>(dst), reinterpret_cast<const uint4*>(src), n16);
 }
 
 }  // namespace kvc

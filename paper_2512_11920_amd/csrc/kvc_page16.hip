@@ -623,27 +623,21 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_p16(DecodeArgs a) {
 #endif
 
 template <int SCHEME>
-static void launch_compress_scheme(const EncodeArgs& a, hipStream_t s) {
+static hipError_t launch_compress_scheme(const EncodeArgs& a, hipStream_t s) {
     // pages per pool-cursor atomic scale with the page size: 64 KB of input per workgroup
     constexpr int WAVES = KVC_ENC_WAVES, PPW = KVC_ENC_PPW;
     const dim3 block(WAVES * 64);
     auto grid = [&](int ppw) { return dim3((unsigned)((a.n_pages + (int64_t)WAVES * ppw - 1) / ((int64_t)WAVES * ppw))); };
-    if (a.g.d == 64)
-        hipLaunchKernelGGL((k_compress_p16<64, WAVES, 2 * PPW, SCHEME>), grid(2 * PPW), block, 0, s, a);
-    else if (a.g.d == 128)
-        hipLaunchKernelGGL((k_compress_p16<128, WAVES, PPW, SCHEME>), grid(PPW), block, 0, s, a);
-    else
-        hipLaunchKernelGGL((k_compress_p16<256, WAVES, PPW / 2, SCHEME>), grid(PPW / 2), block, 0, s, a);
+    if (a.g.d == 64) return launch_kernel(k_compress_p16<64, WAVES, 2 * PPW, SCHEME>, grid(2 * PPW), block, s, a);
+    if (a.g.d == 128) return launch_kernel(k_compress_p16<128, WAVES, PPW, SCHEME>, grid(PPW), block, s, a);
+    return launch_kernel(k_compress_p16<256, WAVES, PPW / 2, SCHEME>, grid(PPW / 2), block, s, a);
 }
 
 hipError_t launch_compress_p16(const EncodeArgs& a, hipStream_t s) {
     // the full scheme of Algorithm 2 for every block is the common launch and gets its own
     // instantiation; any other request (another mode, or one mode per block) reads it at run time
-    if (a.block_scheme == nullptr && a.scheme == KVC_MODE_RLE)
-        launch_compress_scheme<KVC_MODE_RLE>(a, s);
-    else
-        launch_compress_scheme<-1>(a, s);
-    return hipGetLastError();
+    if (a.block_scheme == nullptr && a.scheme == KVC_MODE_RLE) return launch_compress_scheme<KVC_MODE_RLE>(a, s);
+    return launch_compress_scheme<-1>(a, s);
 }
 
 hipError_t launch_decompress_p16(const DecodeArgs& a, hipStream_t s) {
@@ -651,13 +645,9 @@ hipError_t launch_decompress_p16(const DecodeArgs& a, hipStream_t s) {
     const dim3 block(WAVES * 64);
     auto grid = [&](int ppw) { return dim3((unsigned)((a.n_pages + (int64_t)WAVES * ppw - 1) / ((int64_t)WAVES * ppw))); };
     // a d = 64 page is too small to cover its own memory chain: there a wave walks two side by side
-    if (a.g.d == 64)
-        hipLaunchKernelGGL((k_decompress_p16<64, WAVES, 2 * PPW>), grid(2 * PPW), block, 0, s, a);
-    else if (a.g.d == 128)
-        hipLaunchKernelGGL((k_decompress_p16<128, WAVES, PPW>), grid(PPW), block, 0, s, a);
-    else
-        hipLaunchKernelGGL((k_decompress_p16<256, WAVES, PPW>), grid(PPW), block, 0, s, a);
-    return hipGetLastError();
+    if (a.g.d == 64) return launch_kernel(k_decompress_p16<64, WAVES, 2 * PPW>, grid(2 * PPW), block, s, a);
+    if (a.g.d == 128) return launch_kernel(k_decompress_p16<128, WAVES, PPW>, grid(PPW), block, s, a);
+    return launch_kernel(k_decompress_p16<256, WAVES, PPW>, grid(PPW), block, s, a);
 }
 
 }  // namespace kvc

@@ -117,7 +117,7 @@ def _stream(stream):
     return s.cuda_stream
 
 
-def _ids(t, n_expected=None):
+def _ids(t):
     import torch
 
     if t is None:
@@ -212,6 +212,7 @@ class Codec:
         src_ids, pool_ids = _ids(src_ids), _ids(pool_ids)
         if n is None:
             n = src_ids.numel() if src_ids is not None else (pool_ids.numel() if pool_ids is not None else nb)
+        assert all(t is None or t.numel() >= n for t in (src_ids, pool_ids)), "id tensors shorter than n"
         if block_scheme is None:
             _check(self._L.kvc_compress_blocks(self._ctx, cache.data_ptr(), nb, _ptr(src_ids), _ptr(pool_ids), int(n),
                                                _stream(stream)), "kvc_compress_blocks")
@@ -226,6 +227,7 @@ class Codec:
         pool_ids, dst_ids = _ids(pool_ids), _ids(dst_ids)
         if n is None:
             n = pool_ids.numel() if pool_ids is not None else (dst_ids.numel() if dst_ids is not None else nb)
+        assert all(t is None or t.numel() >= n for t in (pool_ids, dst_ids)), "id tensors shorter than n"
         _check(self._L.kvc_decompress_blocks(self._ctx, out.data_ptr(), nb, _ptr(pool_ids), _ptr(dst_ids), int(n),
                                              _stream(stream)), "kvc_decompress_blocks")
 
@@ -257,6 +259,7 @@ class Codec:
         n_slots = n_layers * n_seq * k
         assert self._blocks_of(l2) == 2 * n_slots
         assert _ids(tags).numel() == 2 * n_slots and _ids(fetch).numel() == n_slots and _ids(loc).numel() == n_slots
+        assert pred.shape[0] == n_seq and (l1_first is None or l1_first.numel() == n_seq)
         layer_end = n_layers if layer_end is None else layer_end
         _check(self._L.kvc_prefetch_layers(self._ctx, l2.data_ptr(), tags.data_ptr(), fetch.data_ptr(), loc.data_ptr(),
                                            block_table.data_ptr(), max_blocks, pred.data_ptr(), _ptr(_ids(l1_first)),
@@ -286,7 +289,7 @@ def page_scales(amax_bits, stream=None):
     """Scaling step of Alg. 2 for FP16 page maxima (int16/uint16 CUDA tensor of bit patterns): -> (s, s_inv)."""
     import torch
 
-    assert amax_bits.element_size() == 2 and amax_bits.is_contiguous()
+    assert amax_bits.is_cuda and amax_bits.element_size() == 2 and amax_bits.is_contiguous()
     s = torch.empty(amax_bits.numel(), dtype=torch.float32, device=amax_bits.device)
     s_inv = torch.empty_like(s)
     _check(load().kvc_page_scales(amax_bits.data_ptr(), s.data_ptr(), s_inv.data_ptr(), amax_bits.numel(), _stream(stream)),
@@ -296,6 +299,7 @@ def page_scales(amax_bits, stream=None):
 
 def copy_bytes(dst, src, stream=None):
     """Yardstick copy kernel: dst[:] = src[:] (uint8 CUDA tensors, multiple of 16 bytes)."""
+    assert dst.is_cuda and src.is_cuda and dst.is_contiguous() and src.is_contiguous()
     assert dst.numel() * dst.element_size() == src.numel() * src.element_size()
     _check(load().kvc_copy_bytes(dst.data_ptr(), src.data_ptr(), src.numel() * src.element_size(), _stream(stream)),
            "kvc_copy_bytes")

@@ -362,6 +362,10 @@ def test_pool_in_pinned_host_memory():
     pageable = torch.empty(4096, dtype=torch.uint8)
     rc = kvc.load().kvc_bind_pool(c2._ctx, pageable.data_ptr(), 4096, desc.data_ptr(), 4)
     assert rc == kvc.ERR_ARG
+    # the refused call leaves no HIP error behind: the next launches of either context report their own status
+    c.reset_pool()
+    c.compress_blocks(xt)
+    assert c.stats()["rc"] == 0
 
 
 @pytest.mark.parametrize("d,H,pad", [(128, 4, 0), (128, 3, 64), (64, 2, 8), (256, 2, 0)])

@@ -38,6 +38,8 @@
  * Calls on one context that overlap on different streams race on the pool cursor; serialise them.
  * A context belongs to the device that was current in kvc_create; calls made with another device
  * current return KVC_ERR_ARG.  A context is not thread-safe: one host thread at a time.
+ * The data calls (compress, decompress, gather, prefetch, reset) launch kernels only: no allocation, no
+ * memset, no synchronisation, so a stream that is being captured into a HIP graph may record them.
  * One data call handles at most 2^26 - 1 pages (blocks * pages_per_block; 256 GiB of 4 KB pages); more is
  * KVC_ERR_ARG.
  */

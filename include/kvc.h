@@ -194,8 +194,9 @@ int kvc_stats(kvc_ctx* ctx, kvc_stats_t* out, void* stream);
  * plain division for every possible maximum. */
 int kvc_page_scales(const uint16_t* d_amax, float* d_scale, float* d_scale_inv, uint64_t n, void* stream);
 
-/* dst[0..nbytes) = src[0..nbytes) with one 128-bit load and store per lane; nbytes multiple of 16.
- * The bandwidth yardstick the codec kernels are compared with. */
+/* dst[0..nbytes) = src[0..nbytes), a wavefront per contiguous 4 KB with 128-bit loads and stores;
+ * nbytes a multiple of 16 and at most 2^38 (else KVC_ERR_ARG); both pointers device memory, 16-byte
+ * aligned, not overlapping.  The bandwidth yardstick the codec kernels are compared with. */
 int kvc_copy_bytes(void* d_dst, const void* d_src, uint64_t nbytes, void* stream);
 
 const char* kvc_strerror(int code);

@@ -354,7 +354,7 @@ int kvc_page_scales(const uint16_t* d_amax, float* d_scale, float* d_scale_inv, 
 
 int kvc_copy_bytes(void* d_dst, const void* d_src, uint64_t nbytes, void* stream) {
     if (!d_dst || !d_src || (nbytes & 15u) || (reinterpret_cast<uintptr_t>(d_dst) & 15u) ||
-        (reinterpret_cast<uintptr_t>(d_src) & 15u))
+        (reinterpret_cast<uintptr_t>(d_src) & 15u) || nbytes > (1ull << 38))
         return KVC_ERR_ARG;
     return hip_ok(kvc::launch_copy(d_dst, d_src, nbytes / 16, static_cast<hipStream_t>(stream))) ? KVC_OK : KVC_ERR_HIP;
 }

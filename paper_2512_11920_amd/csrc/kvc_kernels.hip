@@ -461,9 +461,17 @@ __global__ __launch_bounds__(256) void k_stats(DevState* st, const kvc_desc* des
     }
 }
 
-__global__ void k_copy(uint4* __restrict__ dst, const uint4* __restrict__ src, uint64_t n16) {
-    for (uint64_t k = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; k < n16; k += (uint64_t)gridDim.x * blockDim.x)
-        dst[k] = src[k];
+// Yardstick copy, shaped like the codec's traffic: a wave moves one contiguous 4 KB piece, its four
+// 128-bit loads in flight together, then its four stores.
+__global__ __launch_bounds__(kThreads) void k_copy(uint4* __restrict__ dst, const uint4* __restrict__ src, uint64_t n16) {
+    const uint64_t k0 = ((uint64_t)blockIdx.x * kWavesPerWG + (threadIdx.x >> 6)) * 256u + (threadIdx.x & 63u);
+    uint4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+        if (k0 + 64u * u < n16) v[u] = src[k0 + 64u * u];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+        if (k0 + 64u * u < n16) dst[k0 + 64u * u] = v[u];
 }
 
 // Prefetch planner, Algorithm 1 of the paper without the token predictor: one thread per
@@ -666,8 +674,10 @@ hipError_t launch_page_scales(const uint16_t* amax, float* s, float* s_inv, uint
 
 hipError_t launch_copy(void* dst, const void* src, uint64_t n16, hipStream_t s) {
     if (n16 == 0) return hipSuccess;
-    const unsigned blocks = (unsigned)std::min<uint64_t>((n16 + 255) / 256, 256u * 32u);
-    return launch_kernel(k_copy, dim3(blocks), dim3(256), s, reinterpret_cast<uint4*>(dst), reinterpret_cast<const uint4*>(src), n16);
+    const uint64_t per_wg = 256u * kWavesPerWG;  // 16-byte units per workgroup
+    const uint64_t blocks = (n16 + per_wg - 1) / per_wg;
+    if (blocks > (1ull << 24)) return hipErrorInvalidValue;  // 256 GiB per call: the launch stays below 2^32 threads
+    return launch_kernel(k_copy, dim3((unsigned)blocks), dim3(kThreads), s, reinterpret_cast<uint4*>(dst), reinterpret_cast<const uint4*>(src), n16);
 }
 
 }  // namespace kvc

@@ -407,3 +407,15 @@ def test_strided_cache_layout(d, H, pad):
         c.set_cache_layout(block_stride=N * row, page_stride=d, row_stride=d - 8)
     with pytest.raises(kvc.KvcError):
         c.set_cache_layout(block_stride=N * row + 4, page_stride=d, row_stride=row)
+
+
+@pytest.mark.parametrize("nbytes", [16, 4096 - 16, 4096, 4096 + 16, 3 * 16384 + 48, (1 << 20) + 4080])
+def test_copy_yardstick_copies_every_byte(nbytes):
+    """The bandwidth yardstick is a real copy: ragged sizes around its 4 KB and 16 KB work units, nothing
+    written past the end."""
+    g = torch.Generator(device="cpu").manual_seed(nbytes)
+    src = torch.randint(0, 256, (nbytes,), dtype=torch.uint8, generator=g).to(DEV)
+    buf = torch.full((nbytes + 64,), 0xA5, dtype=torch.uint8, device=DEV)
+    kvc.copy_bytes(buf[:nbytes], src)
+    torch.cuda.synchronize()
+    assert torch.equal(buf[:nbytes], src) and bool((buf[nbytes:] == 0xA5).all())

@@ -328,7 +328,8 @@ __global__ __launch_bounds__(WAVES * 64) void k_compress_p16(EncodeArgs a) {
     // flight.  Measured best with the ring as long as the wave's whole share (all loads issued up
     // front, about 16 KB per wave, no loop) at d = 64 and d = 128; at d = 256 a second page in
     // registers costs occupancy and gains nothing.
-    constexpr int kRing = D <= 64 ? KVC_ENC_RING64 : D <= 128 ? KVC_ENC_RING128 : KVC_ENC_RING256;
+    constexpr int kRingMax = D <= 64 ? KVC_ENC_RING64 : D <= 128 ? KVC_ENC_RING128 : KVC_ENC_RING256;
+    constexpr int kRing = kRingMax < PPW ? kRingMax : PPW;
     static_assert(PPW % kRing == 0, "the loop handles pages in groups of kRing");
     __shared__ __align__(16) uint32_t s_stage[kSlots][Slot<NP>::kWords];
     __shared__ EncBook<kSlots> s_book;
@@ -615,6 +616,10 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_p16(DecodeArgs a) {
 #ifndef KVC_ENC_PPW
 #define KVC_ENC_PPW 4
 #endif
+// calls of at most this many pages take the low-latency launch shape
+#ifndef KVC_ENC_SMALL_PAGES
+#define KVC_ENC_SMALL_PAGES 2048
+#endif
 #ifndef KVC_DEC_WAVES
 #define KVC_DEC_WAVES 4
 #endif
@@ -624,10 +629,18 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_p16(DecodeArgs a) {
 
 template <int SCHEME>
 static hipError_t launch_compress_scheme(const EncodeArgs& a, hipStream_t s) {
-    // pages per pool-cursor atomic scale with the page size: 64 KB of input per workgroup
     constexpr int WAVES = KVC_ENC_WAVES, PPW = KVC_ENC_PPW;
     const dim3 block(WAVES * 64);
     auto grid = [&](int ppw) { return dim3((unsigned)((a.n_pages + (int64_t)WAVES * ppw - 1) / ((int64_t)WAVES * ppw))); };
+    if (a.n_pages <= KVC_ENC_SMALL_PAGES) {
+        // A small call (a decode step's offload of a few blocks) is latency: one page per wave
+        // (two at d = 64), so the pages are encoded side by side instead of four in a row.  The
+        // cursor then takes an atomic per four pages, which only a large call would feel.
+        if (a.g.d == 64) return launch_kernel(k_compress_p16<64, WAVES, 2, SCHEME>, grid(2), block, s, a);
+        if (a.g.d == 128) return launch_kernel(k_compress_p16<128, WAVES, 1, SCHEME>, grid(1), block, s, a);
+        return launch_kernel(k_compress_p16<256, WAVES, 1, SCHEME>, grid(1), block, s, a);
+    }
+    // pages per pool-cursor atomic scale with the page size: 64 KB of input per workgroup
     if (a.g.d == 64) return launch_kernel(k_compress_p16<64, WAVES, 2 * PPW, SCHEME>, grid(2 * PPW), block, s, a);
     if (a.g.d == 128) return launch_kernel(k_compress_p16<128, WAVES, PPW, SCHEME>, grid(PPW), block, s, a);
     return launch_kernel(k_compress_p16<256, WAVES, PPW / 2, SCHEME>, grid(PPW / 2), block, s, a);

@@ -62,7 +62,10 @@ def _families(rng, n, N, d):
 
 @pytest.mark.parametrize("N,d,n,scheme", [(16, 128, 40000, 3), (16, 128, 8000, 2), (16, 64, 8000, 3), (16, 256, 6000, 3),
                                           (16, 32, 3000, 3), (7, 128, 3000, 3), (32, 64, 3000, 2),
-                                          (16, 128, 8000, 4), (16, 64, 3000, 4), (16, 256, 3000, 4), (5, 128, 2000, 4)])
+                                          (16, 128, 8000, 4), (16, 64, 3000, 4), (16, 256, 3000, 4), (5, 128, 2000, 4),
+                                          # calls of at most 2048 pages take the encoder's low-latency launch shape
+                                          (16, 128, 2048, 3), (16, 64, 2047, 3), (16, 256, 2048, 3), (16, 128, 1501, 4),
+                                          (16, 64, 777, 2), (16, 256, 999, 1), (16, 128, 2049, 3)])
 def test_differential(N, d, n, scheme):
     # KVC_DIFF_SEED in the environment draws a different set of pages (for longer hunts)
     rng = np.random.default_rng(N * 1000 + d + scheme + 100003 * int(os.environ.get("KVC_DIFF_SEED", "0")))

@@ -5,8 +5,8 @@
 // 8 consecutive channels, a packet group is a quad of lanes, a token row is D/8 neighbouring lanes
 // (one 16-lane DPP row at D = 128) -- but every cross-lane step is a DPP operation, the per-group
 // statistics (max, width, run test) and the offset scans are done on quads, and no lane is ever
-// inactive.  The codec is bound by vector-ALU issue before HBM bandwidth, so the code is written to keep
-// the instruction count per element low.
+// inactive.  Written plainly the codec is bound by vector-ALU issue long before HBM bandwidth; the
+// instruction count per element is kept low enough here that the memory system is the limit.
 //
 // Encode: Algorithm 2 of the paper (scaling, quantize, delta, run-length encode).
 // Decode: Section 3.5.3 (undo run-length coding, prefix sum, dequantize; bypass for raw pages).

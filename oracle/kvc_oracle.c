@@ -55,6 +55,7 @@
 #define KVO_MODE_DELTA 2
 #define KVO_MODE_RLE 3
 #define KVO_MODE_PACK 4 /* extension, not in Alg. 2: INT8 codes zig-zag mapped and packed as in mode 3, no delta step */
+#define KVO_MODE_CHAN 5 /* extension: mode 4 with the stream regrouped by channel pair (16-token pages only) */
 #define KVO_MODE_INVALID 0xFF
 
 #define KVO_OK 0
@@ -167,6 +168,25 @@ void kvo_zigzag_codes(const int8_t* q, int E, uint8_t* u) {
     }
 }
 
+/* Mode 5 (an extension beyond Algorithm 2, for 16-token pages): the codes of mode 4, but put into the
+ * stream so that a group of 32 holds one pair of neighbouring channels over all 16 tokens.  KV channels
+ * differ in scale far more than the tokens of one channel do, so such a group packs at the width its own
+ * channels need instead of the width of the widest of 32 neighbouring channels.
+ * Element (token t, channel c), channel pair cp = c / 2, goes to group g = (cp mod 4) * (d / 8) + cp div 4
+ * at position k = (t mod 4) * 8 + (t div 4) * 2 + (c mod 2) of the group.  (The order inside a group
+ * and of the groups is free as far as the ratio goes; this one lets a GPU lane that holds tokens
+ * t, t+4, t+8, t+12 of eight neighbouring channels emit whole bytes.) */
+void kvo_zigzag_codes_by_channel(const int8_t* q, int d, uint8_t* u) {
+    for (int t = 0; t < 16; ++t)
+        for (int c = 0; c < d; ++c) {
+            int cp = c / 2;
+            int g = (cp % 4) * (d / 8) + cp / 4;
+            int k = (t % 4) * 8 + (t / 4) * 2 + (c % 2);
+            int v = q[t * d + c];
+            u[32 * g + k] = (uint8_t)(((v << 1) ^ (v >> 7)) & 0xFF);
+        }
+}
+
 static int bit_length(unsigned v) {
     int n = 0;
     while (v) {
@@ -216,10 +236,11 @@ size_t kvo_rle_pack(const uint8_t* u, int E, int with_runs, uint8_t* out) {
     return pos;
 }
 
-/* Encode one page.  payload must hold 2*E bytes.  scheme = requested mode 0..4.
+/* Encode one page.  payload must hold 2*E bytes.  scheme = requested mode 0..5 (5: N = 16 only).
  * Fills desc (off left at 0) and returns the padded payload size in bytes, or <0. */
 int64_t kvo_encode_page(const uint16_t* x, int N, int d, int scheme, uint8_t* payload, kvo_desc* desc) {
-    if (N < 1 || d < 32 || d % 32 != 0 || scheme < 0 || scheme > 4) return KVO_ERR_ARG;
+    if (N < 1 || d < 32 || d % 32 != 0 || scheme < 0 || scheme > 5) return KVO_ERR_ARG;
+    if (scheme == KVO_MODE_CHAN && N != 16) return KVO_ERR_ARG;
     int E = N * d;
     desc->off = 0;
     desc->rsvd = 0;
@@ -242,6 +263,8 @@ int64_t kvo_encode_page(const uint16_t* x, int N, int d, int scheme, uint8_t* pa
         uint8_t* tmp = (uint8_t*)malloc((size_t)E / 64 + 1 + (size_t)E);
         if (scheme == KVO_MODE_PACK)
             kvo_zigzag_codes(q, E, u);
+        else if (scheme == KVO_MODE_CHAN)
+            kvo_zigzag_codes_by_channel(q, d, u);
         else
             kvo_delta_zigzag(q, N, d, u);
         size_t raw_n = kvo_rle_pack(u, E, scheme != KVO_MODE_DELTA, tmp);
@@ -267,7 +290,7 @@ int64_t kvo_encode_page(const uint16_t* x, int N, int d, int scheme, uint8_t* pa
     return (int64_t)n;
 }
 
-/* Recover the INT8 codes of a page stored in mode 1, 2 or 3. */
+/* Recover the INT8 codes of a page stored in mode 1 to 5. */
 int kvo_decode_codes(const uint8_t* payload, size_t nbytes, int mode, int N, int d, int8_t* q) {
     int E = N * d, G = E / 32;
     if (mode == KVO_MODE_INT8) {
@@ -275,7 +298,8 @@ int kvo_decode_codes(const uint8_t* payload, size_t nbytes, int mode, int N, int
         memcpy(q, payload, (size_t)E);
         return KVO_OK;
     }
-    if (mode != KVO_MODE_DELTA && mode != KVO_MODE_RLE && mode != KVO_MODE_PACK) return KVO_ERR_CORRUPT;
+    if (mode != KVO_MODE_DELTA && mode != KVO_MODE_RLE && mode != KVO_MODE_PACK && mode != KVO_MODE_CHAN) return KVO_ERR_CORRUPT;
+    if (mode == KVO_MODE_CHAN && N != 16) return KVO_ERR_CORRUPT;
     const int runs = mode != KVO_MODE_DELTA; /* zero-run and run packets allowed */
     size_t hdr = (size_t)(G + 1) / 2;
     if (nbytes < hdr) return KVO_ERR_CORRUPT;
@@ -307,6 +331,16 @@ int kvo_decode_codes(const uint8_t* payload, size_t nbytes, int mode, int N, int
         }
     }
     if (kvo_pad16(pos) != nbytes) goto corrupt;
+    if (mode == KVO_MODE_CHAN) { /* undo the regrouping and the zig-zag map; there was no delta step */
+        for (int t = 0; t < 16; ++t)
+            for (int c = 0; c < d; ++c) {
+                int cp = c / 2;
+                unsigned uu = u[32 * ((cp % 4) * (d / 8) + cp / 4) + (t % 4) * 8 + (t / 4) * 2 + (c % 2)];
+                q[t * d + c] = (int8_t)((int)(uu >> 1) ^ -(int)(uu & 1));
+            }
+        free(u);
+        return KVO_OK;
+    }
     /* undo zig-zag, then (modes 2, 3) the prefix sum along the channel index, wrapped to 8 bits */
     for (int j = 0; j < N; ++j) {
         int acc = 0;

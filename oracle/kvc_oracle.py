@@ -19,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "kvc_oracle.c")
 _LIB = os.path.join(_HERE, "libkvc_oracle.so")
 
-MODE_RAW, MODE_INT8, MODE_DELTA, MODE_RLE, MODE_PACK, MODE_INVALID = 0, 1, 2, 3, 4, 0xFF
+MODE_RAW, MODE_INT8, MODE_DELTA, MODE_RLE, MODE_PACK, MODE_CHAN, MODE_INVALID = 0, 1, 2, 3, 4, 5, 0xFF
 
 #: numpy view of the 16-byte page descriptor (little-endian, no padding)
 DESC_DTYPE = np.dtype(

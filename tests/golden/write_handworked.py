@@ -62,6 +62,17 @@ x[40] = 127
 add("nodelta_mode4", 1, 64, x, 4, "3f800000", "83" + "9e" + "00" * 11 + "00" * 8 + "fe" + "00" * 23 + "00" * 3, scheme=4,
     note="mode 4 (extension: no delta step): u = zigzag(q) = [6,3,2,0..] -> w=3, 6|3<<3|2<<6 = 0x9E; second group has "
          "u[8] = zigzag(127) = 254 -> w=8; header 0x83; 1+12+32 = 45 -> 48 B")
+x = np.zeros((16, 128))
+x[0, 0] = 127
+x[:, 2:4] = 1
+x[5, 9] = -1
+add("channel_pairs_mode5", 16, 128, x, 5, "3f800000",
+    "18" + "00" * 7 + "09" + "00" * 23 + "fe" + "00" * 31 + "00080000" + "02" + "00" * 11, scheme=5,
+    note="mode 5 (extension: groups are channel pairs over the 16 tokens, no delta step): pair p goes to group "
+         "(p mod 4)*16 + p div 4, element (t, c) to position (t mod 4)*8 + (t div 4)*2 + (c mod 2). x[0][0]=127: pair 0, "
+         "group 0, position 0, u=254 -> w=8; x[5][9]=-1: pair 4, group 1, position 8+2+1=11, u=1 -> w=1, bit 11 = byte 1 "
+         "value 0x08; channels 2,3 all 1: pair 1, group 16, 32 equal u=2 -> run packet, body 0x02; every other group "
+         "zero-run. Header nibbles 0,1,16 = 8,1,9. 32+32+4+1 = 69 -> 80 B")
 
 doc = dict(citation="Algorithm 2 (KV-Cache Compression) and Section 3.5.3 (inverse), under the KVC-1 reading of the "
            "unspecified byte format; worked by hand, not produced by any implementation. The paper prints no numeric example.",

@@ -195,9 +195,9 @@ def _parse_payload_py(payload: bytes, G: int, mode: int):
     pos, u = hdr, []
     for g in range(G):
         c = (payload[g >> 1] >> 4) if g & 1 else (payload[g >> 1] & 15)
-        if mode in (3, 4) and c == 0:
+        if mode in (3, 4, 5) and c == 0:
             u += [0] * 32
-        elif mode in (3, 4) and c == 9:
+        elif mode in (3, 4, 5) and c == 9:
             u += [payload[pos]] * 32
             pos += 1
         else:
@@ -422,3 +422,75 @@ def test_no_delta_mode_is_the_same_packing_without_the_delta_step():
         assert np.array_equal(xh4, xh3)  # same codes, same reconstruction
         b3, b4 = b3 + len(p3), b4 + len(p4)
     assert b4 < b3  # uncorrelated channels: differencing widens the values
+
+
+def _chan_stream_py(q, d):
+    """Mode 5 stream order stated on its own: the groups are channel pairs, first all pairs with
+    pair index = 0 mod 4 in rising order, then 1 mod 4, ...; inside a group the four tokens
+    t, t+4, t+8, t+12 of one residue t mod 4 sit together, two channels each."""
+    q = np.asarray(q).reshape(16, d)
+    u = []
+    for j in range(4):
+        for l in range(d // 8):
+            pair = 4 * l + j
+            for r in range(4):
+                for p in range(4):
+                    for e in range(2):
+                        u.append(int(q[4 * p + r, 2 * pair + e]))
+    return _zigzag_py(u)
+
+
+@pytest.mark.parametrize("d", [32, 64, 128, 256])
+def test_channel_pair_mode_is_mode_4_over_a_regrouped_stream(d):
+    """Mode 5 (an extension beyond Algorithm 2): the packets of mode 4 over groups that hold one pair of
+    neighbouring channels across the 16 tokens.  Checked against an independent statement of the
+    order, the size closed form, losslessness, and what it is for: channels of unequal scale."""
+    rng = np.random.default_rng(15 + d)
+    b4 = b5 = 0
+    seen_modes = set()
+    for t in range(24):
+        x = (rng.standard_normal((16, d)) * np.exp(rng.normal(0, 0.7, d))).astype(np.float16)
+        if t % 3 == 0:
+            x[:, rng.integers(0, d)] *= 12
+        if t % 5 == 0:
+            x[:, 4:6] = 0       # an all-zero channel pair: a zero-run packet
+        if t % 7 == 0:
+            x[:, 8:10] = x.max()  # a constant channel pair at the page maximum: a run packet
+        d5, p5 = o.encode_page(x, 16, d, 5)
+        d4, p4 = o.encode_page(x, 16, d, 4)
+        nf, s, si, q = o.quantize_page(x)
+        seen_modes.add(int(d5["mode"]))
+        assert d5["scale"] == d4["scale"]
+        want_u = _chan_stream_py(q, d)
+        n = _size_closed_form(np.array(want_u, np.uint8), True)
+        if n >= 16 * d:
+            assert d5["mode"] == 1 and p5 == q.tobytes()
+            continue
+        assert d5["mode"] == 5 and len(p5) == n
+        assert _parse_payload_py(p5, 16 * d // 32, 5) == want_u
+        rc, q2 = o.decode_codes(p5, 5, 16, d)
+        assert rc == 0 and np.array_equal(q2, q)
+        rc, xh5 = o.decode_page(p5, d5, 16, d)
+        rc4, xh4 = o.decode_page(p4, d4, 16, d)
+        assert rc == 0 and np.array_equal(xh5, xh4)  # same codes, same reconstruction
+        if t % 5 == 0:
+            G = 16 * d // 32
+            g_zero = (2 % 4) * (d // 8) + 2 // 4  # channel pair 2 = channels 4, 5
+            code = (p5[g_zero >> 1] >> 4) if g_zero & 1 else (p5[g_zero >> 1] & 15)
+            assert code == 0
+        if t % 7 == 0:
+            g_run = (4 % 4) * (d // 8) + 4 // 4   # channel pair 4 = channels 8, 9
+            code = (p5[g_run >> 1] >> 4) if g_run & 1 else (p5[g_run >> 1] & 15)
+            assert code == 9
+        b4, b5 = b4 + len(p4), b5 + len(p5)
+    assert 5 in seen_modes
+    assert b5 < 0.95 * b4  # channel scales differ: per-pair widths beat widths over 32 channels
+
+
+def test_channel_pair_mode_needs_16_token_pages():
+    x = np.ones((8, 64), np.float16)
+    with pytest.raises(Exception):
+        o.encode_page(x, 8, 64, 5)
+    d5, p5 = o.encode_page(np.ones((16, 64), np.float16), 16, 64, 5)
+    rc, q = o.decode_codes(p5, 5, 8, 128)  # a mode-5 payload read with another page height
+    assert rc != 0

@@ -552,7 +552,8 @@ def bench_ablation(args):
         out = torch.empty_like(blocks)
         unc = blocks.numel() * 2
         for scheme, label in ((0, "None (FP16)"), (1, "INT8 only"), (2, "INT8 + Delta"), (3, "INT8 + Delta + RLE"),
-                              (4, "INT8 + pack, no delta (extension)")):
+                              (4, "INT8 + pack, no delta (extension)"),
+                              (5, "INT8 + pack over channel-pair groups (extension)")):
             codec = kvc.Codec(N, d, ppb, scheme)
             codec.alloc_pool(blocks.shape[0], unc + 4096, dev)
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]

@@ -65,6 +65,12 @@ extern "C" {
 #define KVC_MODE_DELTA 2
 #define KVC_MODE_RLE 3
 #define KVC_MODE_PACK 4 /* extension beyond Algorithm 2: as 3 without the delta step (u = zigzag(q)) */
+/* Extension beyond Algorithm 2, for 16-token pages: the packets of mode 4 over groups that hold one
+ * pair of neighbouring channels across the 16 tokens (pair p = c / 2 goes to group
+ * (p mod 4) * (d / 8) + p div 4, element (t, c) to position (t mod 4) * 8 + (t div 4) * 2 + c mod 2),
+ * so that each pair packs at its own width.  Compress produces it for tokens_per_block = 16 and
+ * head_dim = 128 only; decompress reads it for that geometry only. */
+#define KVC_MODE_CHAN 5
 #define KVC_MODE_INVALID 0xFF
 
 #define KVC_ST_POOL_FULL 1u  /* a page did not fit into the pool */
@@ -87,14 +93,14 @@ typedef struct {
     int32_t tokens_per_block; /* N >= 1 */
     int32_t head_dim;         /* d in {32, 64, 128, 256};  N*d <= 4096 */
     int32_t pages_per_block;  /* ppb >= 1 */
-    int32_t scheme;           /* mode requested from compress: 0..4 */
+    int32_t scheme;           /* mode requested from compress: 0..5 (5: N = 16, d = 128 only, else KVC_ERR_UNSUPPORTED) */
 } kvc_config;
 
 typedef struct {
     uint64_t pool_bytes_used; /* bytes handed out by the pool cursor (capped at the pool size) */
-    uint64_t pages[5];        /* bound descriptors per mode 0..4 */
+    uint64_t pages[6];        /* bound descriptors per mode 0..5 */
     uint64_t pages_invalid;   /* bound descriptors with mode 0xFF (never written, or did not fit) */
-    uint64_t payload_bytes;   /* sum of n16*16 over descriptors of mode 0..4 */
+    uint64_t payload_bytes;   /* sum of n16*16 over descriptors of mode 0..5 */
     uint32_t status;          /* OR of KVC_ST_* since the last kvc_reset_pool */
     uint32_t rsvd;
 } kvc_stats_t;
@@ -103,7 +109,7 @@ typedef struct {
 int kvc_create(kvc_ctx** out, const kvc_config* cfg);
 void kvc_destroy(kvc_ctx* ctx);
 
-/* Change the mode compress requests (0..4); takes effect for later calls. */
+/* Change the mode compress requests (0..5, with the geometry limit of mode 5); takes effect for later calls. */
 int kvc_set_scheme(kvc_ctx* ctx, int32_t scheme);
 
 /* Layout of the FP16 cache buffers read by compress and written by decompress / gather / prefetch,

@@ -37,7 +37,8 @@ static bool on_ctx_device(const kvc_ctx* ctx);
 static bool config_ok(const kvc_config* c) {
     if (!c) return false;
     if (c->tokens_per_block < 1 || c->pages_per_block < 1) return false;
-    if (c->scheme < 0 || c->scheme > KVC_MODE_PACK) return false;
+    if (c->scheme < 0 || c->scheme > KVC_MODE_CHAN) return false;
+    if (c->scheme == KVC_MODE_CHAN && !(c->tokens_per_block == 16 && c->head_dim == 128)) return false;
     const int d = c->head_dim;
     if (!(d == 32 || d == 64 || d == 128 || d == 256)) return false;
     const int64_t E = (int64_t)c->tokens_per_block * d;
@@ -55,7 +56,7 @@ int kvc_create(kvc_ctx** out, const kvc_config* cfg) {
     if (!out) return KVC_ERR_ARG;
     *out = nullptr;
     if (!cfg) return KVC_ERR_ARG;
-    if (cfg->tokens_per_block < 1 || cfg->pages_per_block < 1 || cfg->scheme < 0 || cfg->scheme > KVC_MODE_PACK ||
+    if (cfg->tokens_per_block < 1 || cfg->pages_per_block < 1 || cfg->scheme < 0 || cfg->scheme > KVC_MODE_CHAN ||
         cfg->head_dim < 32 || cfg->head_dim % 32 != 0)
         return KVC_ERR_ARG;
     if (!config_ok(cfg)) return KVC_ERR_UNSUPPORTED;
@@ -94,7 +95,8 @@ void kvc_destroy(kvc_ctx* ctx) {
 }
 
 int kvc_set_scheme(kvc_ctx* ctx, int32_t scheme) {
-    if (!ctx || scheme < 0 || scheme > KVC_MODE_PACK) return KVC_ERR_ARG;
+    if (!ctx || scheme < 0 || scheme > KVC_MODE_CHAN) return KVC_ERR_ARG;
+    if (scheme == KVC_MODE_CHAN && !(ctx->g.N == 16 && ctx->g.d == 128)) return KVC_ERR_UNSUPPORTED;
     ctx->cfg.scheme = scheme;
     return KVC_OK;
 }
@@ -335,9 +337,9 @@ int kvc_stats(kvc_ctx* ctx, kvc_stats_t* out, void* stream) {
     if (!hip_ok(hipMemcpyAsync(&h, ctx->st, sizeof(h), hipMemcpyDeviceToHost, s))) return KVC_ERR_HIP;
     if (!hip_ok(hipStreamSynchronize(s))) return KVC_ERR_HIP;
     out->pool_bytes_used = std::min<uint64_t>(h.cursor16 * 16ull, ctx->pool_bytes);
-    for (int i = 0; i < 5; ++i) out->pages[i] = h.stats[i];
-    out->pages_invalid = h.stats[5];
-    out->payload_bytes = h.stats[6] * 16ull;
+    for (int i = 0; i < 6; ++i) out->pages[i] = h.stats[i];
+    out->pages_invalid = h.stats[6];
+    out->payload_bytes = h.stats[7] * 16ull;
     out->status = h.status;
     out->rsvd = 0;
     if (h.status & KVC_ST_POOL_FULL) return KVC_ERR_POOL_FULL;
@@ -367,7 +369,7 @@ const char* kvc_strerror(int code) {
         case KVC_ERR_HIP: return t_last_hip != hipSuccess ? hipGetErrorString(t_last_hip) : "HIP runtime error";
         case KVC_ERR_POOL_FULL: return "compressed pool exhausted; some pages were not stored";
         case KVC_ERR_CORRUPT: return "invalid descriptor, payload or block index met on the device";
-        case KVC_ERR_UNSUPPORTED: return "page geometry not supported (head_dim in {32,64,128,256}, N*d <= 4096)";
+        case KVC_ERR_UNSUPPORTED: return "page geometry not supported (head_dim in {32,64,128,256}, N*d <= 4096; mode 5: N = 16, d = 128)";
         default: return "unknown error";
     }
 }

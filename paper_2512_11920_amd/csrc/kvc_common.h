@@ -12,7 +12,7 @@ struct DevState {
     unsigned long long cursor16;  // next free 16-byte unit of the pool
     unsigned int status;          // sticky KVC_ST_* bits
     unsigned int pad;
-    unsigned long long stats[8];  // scratch of kvc_stats: pages[0..4], invalid, payload16
+    unsigned long long stats[8];  // scratch of kvc_stats: pages[0..5], invalid, payload16
 };
 
 // Page geometry and cache layout.  Element (token j, channel i) of page pg of block b sits at

@@ -436,26 +436,26 @@ __global__ void k_stats_zero(DevState* st) {
 }
 
 __global__ __launch_bounds__(256) void k_stats(DevState* st, const kvc_desc* desc, uint64_t n_desc) {
-    __shared__ unsigned long long s_part[4][7];
-    unsigned long long cnt[7] = {0, 0, 0, 0, 0, 0, 0};
+    __shared__ unsigned long long s_part[4][8];
+    unsigned long long cnt[8] = {0, 0, 0, 0, 0, 0, 0, 0};  // pages per mode 0..5, invalid, payload units
     for (uint64_t k = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; k < n_desc; k += (uint64_t)gridDim.x * blockDim.x) {
         const uint32_t w = reinterpret_cast<const uint4*>(desc)[k].w;
         const uint32_t mode = (w >> 16) & 0xFFu;
-        if (mode <= KVC_MODE_PACK) {
+        if (mode <= KVC_MODE_CHAN) {
             cnt[mode] += 1;
-            cnt[6] += w & 0xFFFFu;
+            cnt[7] += w & 0xFFFFu;
         } else {
-            cnt[5] += 1;
+            cnt[6] += 1;
         }
     }
     // wave reduction, then one atomic per counter per workgroup
-    for (int j = 0; j < 7; ++j) {
+    for (int j = 0; j < 8; ++j) {
         unsigned long long v = cnt[j];
         for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
         if (lane_id() == 0) s_part[threadIdx.x >> 6][j] = v;
     }
     __syncthreads();
-    if (threadIdx.x < 7) {
+    if (threadIdx.x < 8) {
         const unsigned long long v = s_part[0][threadIdx.x] + s_part[1][threadIdx.x] + s_part[2][threadIdx.x] + s_part[3][threadIdx.x];
         if (v) atomicAdd(&st->stats[threadIdx.x], v);
     }

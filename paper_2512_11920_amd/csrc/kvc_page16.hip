@@ -79,10 +79,10 @@ __device__ __forceinline__ void quantize8_bits(const uint4& raw, float s_inv, ui
     for (int k = 0; k < 8; ++k) t[k] = __float_as_uint(__builtin_fmaf((float)h[k], s_inv, kMagic + 256.0f * (float)k));
 }
 
-// plain INT8 payload: codes as bytes, row-major
+// plain INT8 payload: codes as bytes, row-major.  pos = the place of this lane's 8 channels among the
+// 64 eight-channel pieces of a pass.
 template <int NP>
-__device__ __forceinline__ void store_codes(const uint4 (&raw)[NP], float s_inv, uint32_t* stage) {
-    const int lane = lane_id();
+__device__ __forceinline__ void store_codes(const uint4 (&raw)[NP], float s_inv, uint32_t* stage, int pos) {
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
         uint32_t t[8];
@@ -90,7 +90,7 @@ __device__ __forceinline__ void store_codes(const uint4 (&raw)[NP], float s_inv,
         uint2 v;
         v.x = __builtin_amdgcn_perm(__builtin_amdgcn_perm(t[3], t[2], 0x0c0c0400u), __builtin_amdgcn_perm(t[1], t[0], 0x0c0c0400u), 0x05040100u);
         v.y = __builtin_amdgcn_perm(__builtin_amdgcn_perm(t[7], t[6], 0x0c0c0400u), __builtin_amdgcn_perm(t[5], t[4], 0x0c0c0400u), 0x05040100u);
-        reinterpret_cast<uint2*>(stage)[p * 64 + lane] = v;
+        reinterpret_cast<uint2*>(stage)[p * 64 + pos] = v;
     }
 }
 
@@ -163,6 +163,41 @@ __device__ __forceinline__ void encode_tail(const uint32_t (&u)[8], uint32_t c, 
     if (d2) atomicOr(p0 + 2, d2);
 }
 
+// One packet group per quad of lanes: each lane brings 8 of its 32 values.  Group statistics over
+// the quad (max -> width, run test), then the tail.  p = index of the group's set of 16 (a pass).
+template <int D>
+__device__ __forceinline__ void encode_groups(const uint32_t (&u)[8], bool RLE, uint32_t c_min, uint32_t qi, int p,
+                                              uint32_t& run, uint32_t* stage, DevState* st) {
+    // per-group statistics over the quad of lanes
+    uint32_t gmax = max(max(u[0], u[1]), u[2]);
+    gmax = max(max(gmax, u[3]), u[4]);
+    gmax = max(max(gmax, u[5]), u[6]);
+    gmax = max(gmax, u[7]);
+    gmax = max(gmax, dpp<0xB1>(0, gmax));
+    gmax = max(gmax, dpp<0x4E>(0, gmax));
+    // bit length of the group maximum (0 for 0): exponent of its float value
+    const uint32_t c = max((uint32_t)__builtin_amdgcn_frexp_expf((float)gmax), c_min);
+    const uint32_t size = c << 2;
+    bool cand_any = false;
+    uint32_t x = 0;
+    if (RLE) {
+        // run packet: all 32 values equal and non-zero.  Cheap necessary test first.
+        x = (u[0] ^ gmax) | (u[7] ^ gmax);
+        cand_any = __builtin_amdgcn_ballot_w64(x == 0 && gmax != 0) != 0;
+    }
+    if (RLE && cand_any) {
+        uint32_t y = x;
+#pragma unroll
+        for (int k = 1; k < 7; ++k) y |= u[k] ^ gmax;
+        y |= dpp<0xB1>(0, y);
+        y |= dpp<0x4E>(0, y);
+        const bool is_run = (y == 0) && (gmax != 0);
+        encode_tail<D, true>(u, is_run ? 9u : c, is_run ? 1u : size, is_run, qi, p, run, stage, st);
+    } else {
+        encode_tail<D, false>(u, c, size, false, qi, p, run, stage, st);
+    }
+}
+
 // Lane l of pass p holds token row p*(512/D) + l/(D/8), channels 8*(l%(D/8)) .. +7: with contiguous
 // rows this is one 1 KB run per pass, with strided rows 512/D runs of 2*D bytes.
 // The lane's byte offset inside a page is computed once per kernel and kept in 32 bits (the layout
@@ -171,6 +206,14 @@ template <int D>
 __device__ __forceinline__ uint32_t lane_byte_off(const Geometry& g) {
     const uint32_t lane = (uint32_t)lane_id();
     return ((lane / Page<D>::kLpr) * (uint32_t)g.row_stride + (lane % Page<D>::kLpr) * 8u) * 2u;
+}
+
+// Mode 5 (channel-pair groups, D = 128) deals the same 128-bit pieces to the lanes in another order: lane
+// 4*l + r holds token row 4*p + r of pass p (channels 8*l .. 8*l + 7), so that the four lanes of a quad
+// hold the 16 tokens of the same eight channels between them.
+__device__ __forceinline__ uint32_t lane_byte_off_chan(const Geometry& g) {
+    const uint32_t lane = (uint32_t)lane_id();
+    return ((lane & 3u) * (uint32_t)g.row_stride + (lane >> 2) * 8u) * 2u;
 }
 
 template <int D>
@@ -196,6 +239,8 @@ __device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPa
     const uint32_t c_min = RLE ? 0u : 1u;  // without run packets an all-zero group is a 1-bit literal
     const int lane = lane_id();
     const uint32_t qi = (uint32_t)lane & 3u;
+    // place of this lane's piece in the row-major order of a pass
+    const int pos = SCHEME == KVC_MODE_CHAN ? ((lane & 3) << 4) | (lane >> 2) : lane;
 
     // scaling: max |x| on the FP16 bit patterns, two per dword
     uint32_t m2 = 0;
@@ -222,7 +267,7 @@ __device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPa
     }
     r.scale = s;
     if (scheme == KVC_MODE_INT8) {
-        store_codes<NP>(raw, s_inv, stage);
+        store_codes<NP>(raw, s_inv, stage, pos);
         r.n16 = kE / 16;
         r.mode = KVC_MODE_INT8;
         return r;
@@ -233,6 +278,27 @@ __device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPa
     wave_sync();
 
     uint32_t run = kHdr;  // payload bytes so far (wave-uniform)
+    if constexpr (SCHEME == KVC_MODE_CHAN) {
+        // Mode 5: the lanes hold the page dealt as lane_byte_off_chan says.  All four passes are
+        // quantized and mapped first; group set j then takes channels 2j, 2j + 1 of every pass: the
+        // quad's 32 values are one channel pair over the 16 tokens.
+        static_assert(D == 128, "a lane's share of a channel pair is 8 values only at D = 128");
+        uint32_t uu[NP][8];
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            uint32_t t[8];
+            quantize8_bits(raw[p], s_inv, t);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) uu[p][k] = lut[t[k] - (kMagicBits + 256u * (uint32_t)k - 256u)];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t u[8];
+#pragma unroll
+            for (int m = 0; m < 8; ++m) u[m] = uu[m >> 1][2 * j + (m & 1)];
+            encode_groups<D>(u, true, 0u, qi, j, run, stage, st);
+        }
+    } else {
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
         uint32_t t[8];
@@ -250,39 +316,13 @@ __device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPa
 #pragma unroll
             for (int k = 1; k < 8; ++k) u[k] = lut[t[k] - t[k - 1]];
         }
-        // per-group statistics over the quad of lanes
-        uint32_t gmax = max(max(u[0], u[1]), u[2]);
-        gmax = max(max(gmax, u[3]), u[4]);
-        gmax = max(max(gmax, u[5]), u[6]);
-        gmax = max(gmax, u[7]);
-        gmax = max(gmax, dpp<0xB1>(0, gmax));
-        gmax = max(gmax, dpp<0x4E>(0, gmax));
-        // bit length of the group maximum (0 for 0): exponent of its float value
-        const uint32_t c = max((uint32_t)__builtin_amdgcn_frexp_expf((float)gmax), c_min);
-        const uint32_t size = c << 2;
-        bool cand_any = false;
-        uint32_t x = 0;
-        if (RLE) {
-            // run packet: all 32 values equal and non-zero.  Cheap necessary test first.
-            x = (u[0] ^ gmax) | (u[7] ^ gmax);
-            cand_any = __builtin_amdgcn_ballot_w64(x == 0 && gmax != 0) != 0;
-        }
-        if (RLE && cand_any) {
-            uint32_t y = x;
-#pragma unroll
-            for (int k = 1; k < 7; ++k) y |= u[k] ^ gmax;
-            y |= dpp<0xB1>(0, y);
-            y |= dpp<0x4E>(0, y);
-            const bool is_run = (y == 0) && (gmax != 0);
-            encode_tail<D, true>(u, is_run ? 9u : c, is_run ? 1u : size, is_run, qi, p, run, stage, st);
-        } else {
-            encode_tail<D, false>(u, c, size, false, qi, p, run, stage, st);
-        }
+        encode_groups<D>(u, RLE, c_min, qi, p, run, stage, st);
+    }
     }
     const uint32_t n = (run + 15u) & ~15u;
     wave_sync();
     if (n >= (uint32_t)kE) {  // packing did not beat plain INT8
-        store_codes<NP>(raw, s_inv, stage);
+        store_codes<NP>(raw, s_inv, stage, pos);
         r.n16 = kE / 16;
         r.mode = KVC_MODE_INT8;
     } else {
@@ -320,8 +360,9 @@ __device__ __forceinline__ void encode_into_slot(const EncodeArgs& a, const uint
 #define KVC_ENC_RING256 1
 #endif
 
+// (four waves per SIMD is what the LDS slots allow anyway: keep every instantiation within 128 VGPRs)
 template <int D, int WAVES, int PPW, int SCHEME>
-__global__ __launch_bounds__(WAVES * 64) void k_compress_p16(EncodeArgs a) {
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(4))) void k_compress_p16(EncodeArgs a) {
     constexpr int kSlots = WAVES * PPW;
     constexpr int NP = Page<D>::kPasses;
     // Pages held in registers per wave: while one is encoded the loads of the next kRing - 1 are in
@@ -339,7 +380,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_compress_p16(EncodeArgs a) {
     __syncthreads();
     const int64_t t0 = ((int64_t)task_block_index() * WAVES + wave) * PPW;
     TaskPos pos = task_pos(t0, a.g.ppb);
-    const uint32_t lane_off = lane_byte_off<D>(a.g);
+    const uint32_t lane_off = SCHEME == KVC_MODE_CHAN ? lane_byte_off_chan(a.g) : lane_byte_off<D>(a.g);
     const int slot0 = wave * PPW;
     if (kRing > 1) {
         // The register sets take turns (the inner loop is unrolled, so every index is a constant):
@@ -396,6 +437,50 @@ __device__ __forceinline__ uint4 dequant8_biased(const uint32_t pb[8], float s, 
                       __builtin_bit_cast(uint32_t, h[2]), __builtin_bit_cast(uint32_t, h[3]));
 }
 
+// This lane's 8 values of its quad's packet in group set p, read from the staged payload: the bits
+// above each value's sign flag (hb) and the flag as 0 / -1 (sg): delta = hb ^ sg.
+template <int NP>
+__device__ __forceinline__ void unpack8(const DecodeArgs& a, const uint32_t* stage, const uint32_t* ginfo, int p, bool special,
+                                        uint32_t (&hb)[8], int (&sg)[8]) {
+    (void)a;  // only the bounds-checking build reads it
+    const int lane = lane_id();
+    const uint32_t qi = (uint32_t)lane & 3u;
+    const uint32_t gi = ginfo[p * 16 + (lane >> 2)];
+    uint32_t c = gi & 15u;
+    const uint32_t goff = gi >> 4;
+    uint32_t B = goff + qi * c;
+    if (special && c == 9) B = goff;
+    const uint32_t sh = (B & 3u) << 3;
+    const uint32_t* p0 = stage + (B >> 2);
+    KVC_CHECK(a.st, (B >> 2) + 2 < (uint32_t)Slot<NP>::kWords && B >= (uint32_t)(NP * 32));
+    const uint32_t d0 = p0[0], d1 = p0[1], d2 = p0[2];
+    uint32_t lo = __builtin_amdgcn_alignbit(d1, d0, sh);
+    uint32_t hi = __builtin_amdgcn_alignbit(d2, d1, sh);
+    if (special) {
+        if (c == 9) {  // run packet: the body byte, 32 times
+            lo = __builtin_amdgcn_perm(lo, lo, 0u);
+            hi = lo;
+            c = 8;
+        } else if (c == 0) {  // zero-run packet
+            lo = 0;
+            hi = 0;
+            c = 1;
+        }
+    }
+    const uint32_t mid = shr_nibbles(lo, hi, c);  // values 4..7 start at bit 4c
+    // value k sits at bits [k*c, k*c + c); delta = (u >> 1) ^ -(u & 1) taken straight from the fields
+    const uint32_t w1 = c - 1u;
+    const uint32_t o1 = c, o2 = c << 1, o3 = o2 + c;
+    hb[0] = __builtin_amdgcn_ubfe(lo, 1u, w1), sg[0] = __builtin_amdgcn_sbfe((int)lo, 0u, 1u);
+    hb[1] = __builtin_amdgcn_ubfe(lo, o1 + 1u, w1), sg[1] = __builtin_amdgcn_sbfe((int)lo, o1, 1u);
+    hb[2] = __builtin_amdgcn_ubfe(lo, o2 + 1u, w1), sg[2] = __builtin_amdgcn_sbfe((int)lo, o2, 1u);
+    hb[3] = __builtin_amdgcn_ubfe(lo, o3 + 1u, w1), sg[3] = __builtin_amdgcn_sbfe((int)lo, o3, 1u);
+    hb[4] = __builtin_amdgcn_ubfe(mid, 1u, w1), sg[4] = __builtin_amdgcn_sbfe((int)mid, 0u, 1u);
+    hb[5] = __builtin_amdgcn_ubfe(mid, o1 + 1u, w1), sg[5] = __builtin_amdgcn_sbfe((int)mid, o1, 1u);
+    hb[6] = __builtin_amdgcn_ubfe(mid, o2 + 1u, w1), sg[6] = __builtin_amdgcn_sbfe((int)mid, o2, 1u);
+    hb[7] = __builtin_amdgcn_ubfe(mid, o3 + 1u, w1), sg[7] = __builtin_amdgcn_sbfe((int)mid, o3, 1u);
+}
+
 // A page on its way through the decoder: the descriptor's fields, the verdict of its validation and,
 // for the packed modes, the payload as it arrives from the pool (16 bytes per lane and round).
 template <int D>
@@ -407,8 +492,9 @@ struct DecPage {
     uint4 pay[Page<D>::kE / 1024];
 };
 
+template <int D>
 __device__ __forceinline__ bool is_packed_mode(uint32_t mode) {
-    return mode == KVC_MODE_DELTA || mode == KVC_MODE_RLE || mode == KVC_MODE_PACK;
+    return mode == KVC_MODE_DELTA || mode == KVC_MODE_RLE || mode == KVC_MODE_PACK || (D == 128 && mode == KVC_MODE_CHAN);
 }
 
 // Take the descriptor apart, validate it against the pool and the page geometry, and start the
@@ -427,14 +513,14 @@ __device__ __forceinline__ DecPage<D> dec_open(const DecodeArgs& a, uint4 dw) {
         ok = ok && pg.n16 == kE / 8;
     else if (pg.mode == KVC_MODE_INT8)
         ok = ok && pg.n16 == kE / 16;
-    else if (is_packed_mode(pg.mode))
+    else if (is_packed_mode<D>(pg.mode))
         ok = ok && pg.n16 * 16u >= (uint32_t)kHdr && pg.n16 < kE / 16;
     else
         ok = false;
     pg.ok = ok;
 #pragma unroll
     for (int z = 0; z < kE / 1024; ++z) pg.pay[z] = make_uint4(0u, 0u, 0u, 0u);
-    if (ok && is_packed_mode(pg.mode)) {
+    if (ok && is_packed_mode<D>(pg.mode)) {
         const uint4* pl4 = reinterpret_cast<const uint4*>(a.pool + pg.off);
 #pragma unroll
         for (int z = 0; z < kE / 1024; ++z) {
@@ -454,7 +540,6 @@ __device__ __forceinline__ bool dec_finish(const DecodeArgs& a, const DecPage<D>
                                            uint32_t* stage, uint32_t* ginfo) {
     constexpr int kE = Page<D>::kE, kHdr = Page<D>::kHdr, NP = Page<D>::kPasses, kG = Page<D>::kGroups;
     const int lane = lane_id();
-    const uint32_t qi = (uint32_t)lane & 3u;
     const float s = pg.s;
     const uint32_t n16 = pg.n16, mode = pg.mode;
     char* dst_b = reinterpret_cast<char*>(a.out) + wave_uniform((int64_t)(dst - a.out) * 2);  // wave-uniform page base
@@ -515,44 +600,40 @@ __device__ __forceinline__ bool dec_finish(const DecodeArgs& a, const DecPage<D>
         return false;
     }
     wave_sync();
+    if (D == 128 && mode == KVC_MODE_CHAN) {
+        // Mode 5: group set j holds channels 2j, 2j + 1 of the lane's eight, tokens 4p + (lane & 3) for
+        // p = 0..3 (value 2p + e of the packet = pass p, channel 2j + e).  The biased codes of a set are
+        // kept as bytes, so that pass p then finds its eight codes at fixed byte positions.
+        uint32_t packed[4][2];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t hb[8];
+            int sg[8];
+            unpack8<NP>(a, stage, ginfo, j, special, hb, sg);
+            uint32_t b[8];
+#pragma unroll
+            for (int m = 0; m < 8; ++m) b[m] = (hb[m] ^ (uint32_t)sg[m]) + 128u;
+            packed[j][0] = __builtin_amdgcn_perm(__builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u), __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u), 0x05040100u);
+            packed[j][1] = __builtin_amdgcn_perm(__builtin_amdgcn_perm(b[7], b[6], 0x0c0c0400u), __builtin_amdgcn_perm(b[5], b[4], 0x0c0c0400u), 0x05040100u);
+        }
+        const uint32_t lane_off_chan = lane_byte_off_chan(a.g);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            uint32_t pb[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int m = 2 * p + (k & 1);  // value index inside group set k / 2
+                pb[k] = packed[k >> 1][m >> 2] >> (8 * (m & 3));
+            }
+            store_stream(reinterpret_cast<uint4*>(dst_b + p * pass_bytes + lane_off_chan), dequant8_biased(pb, s, neg128s));
+        }
+        return true;
+    }
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
-        const uint32_t gi = ginfo[p * 16 + (lane >> 2)];
-        uint32_t c = gi & 15u;
-        const uint32_t goff = gi >> 4;
-        uint32_t B = goff + qi * c;
-        if (special && c == 9) B = goff;
-        const uint32_t sh = (B & 3u) << 3;
-        const uint32_t* p0 = stage + (B >> 2);
-        KVC_CHECK(a.st, (B >> 2) + 2 < (uint32_t)Slot<NP>::kWords && B >= (uint32_t)kHdr);
-        const uint32_t d0 = p0[0], d1 = p0[1], d2 = p0[2];
-        uint32_t lo = __builtin_amdgcn_alignbit(d1, d0, sh);
-        uint32_t hi = __builtin_amdgcn_alignbit(d2, d1, sh);
-        if (special) {
-            if (c == 9) {  // run packet: the body byte, 32 times
-                lo = __builtin_amdgcn_perm(lo, lo, 0u);
-                hi = lo;
-                c = 8;
-            } else if (c == 0) {  // zero-run packet
-                lo = 0;
-                hi = 0;
-                c = 1;
-            }
-        }
-        const uint32_t mid = shr_nibbles(lo, hi, c);  // values 4..7 start at bit 4c
-        // value k sits at bits [k*c, k*c + c); delta = (u >> 1) ^ -(u & 1) taken straight from the fields
-        const uint32_t w1 = c - 1u;
-        const uint32_t o1 = c, o2 = c << 1, o3 = o2 + c;
         uint32_t hb[8];  // bits above the sign flag
         int sg[8];       // 0 or -1 from the sign flag
-        hb[0] = __builtin_amdgcn_ubfe(lo, 1u, w1), sg[0] = __builtin_amdgcn_sbfe((int)lo, 0u, 1u);
-        hb[1] = __builtin_amdgcn_ubfe(lo, o1 + 1u, w1), sg[1] = __builtin_amdgcn_sbfe((int)lo, o1, 1u);
-        hb[2] = __builtin_amdgcn_ubfe(lo, o2 + 1u, w1), sg[2] = __builtin_amdgcn_sbfe((int)lo, o2, 1u);
-        hb[3] = __builtin_amdgcn_ubfe(lo, o3 + 1u, w1), sg[3] = __builtin_amdgcn_sbfe((int)lo, o3, 1u);
-        hb[4] = __builtin_amdgcn_ubfe(mid, 1u, w1), sg[4] = __builtin_amdgcn_sbfe((int)mid, 0u, 1u);
-        hb[5] = __builtin_amdgcn_ubfe(mid, o1 + 1u, w1), sg[5] = __builtin_amdgcn_sbfe((int)mid, o1, 1u);
-        hb[6] = __builtin_amdgcn_ubfe(mid, o2 + 1u, w1), sg[6] = __builtin_amdgcn_sbfe((int)mid, o2, 1u);
-        hb[7] = __builtin_amdgcn_ubfe(mid, o3 + 1u, w1), sg[7] = __builtin_amdgcn_sbfe((int)mid, o3, 1u);
+        unpack8<NP>(a, stage, ginfo, p, special, hb, sg);
         uint32_t pb[8];
         if (mode == KVC_MODE_PACK) {  // no delta step was taken: the fields are the codes
 #pragma unroll
@@ -650,6 +731,16 @@ hipError_t launch_compress_p16(const EncodeArgs& a, hipStream_t s) {
     // the full scheme of Algorithm 2 for every block is the common launch and gets its own
     // instantiation; any other request (another mode, or one mode per block) reads it at run time
     if (a.block_scheme == nullptr && a.scheme == KVC_MODE_RLE) return launch_compress_scheme<KVC_MODE_RLE>(a, s);
+    if (a.block_scheme == nullptr && a.scheme == KVC_MODE_CHAN) {
+        // channel-pair groups: its own instantiation (another deal of the page to the lanes), D = 128 only
+        if (a.g.d != 128) return hipErrorInvalidValue;
+        constexpr int WAVES = KVC_ENC_WAVES, PPW = KVC_ENC_PPW;
+        const bool small = a.n_pages <= KVC_ENC_SMALL_PAGES;
+        const int64_t per_wg = (int64_t)WAVES * (small ? 1 : PPW);
+        const dim3 grid((unsigned)((a.n_pages + per_wg - 1) / per_wg)), block(WAVES * 64);
+        if (small) return launch_kernel(k_compress_p16<128, WAVES, 1, KVC_MODE_CHAN>, grid, block, s, a);
+        return launch_kernel(k_compress_p16<128, WAVES, PPW, KVC_MODE_CHAN>, grid, block, s, a);
+    }
     return launch_compress_scheme<-1>(a, s);
 }
 

@@ -14,7 +14,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libkvc.so")
 
 OK, ERR_ARG, ERR_NOT_BOUND, ERR_HIP, ERR_POOL_FULL, ERR_CORRUPT, ERR_UNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
-MODE_RAW, MODE_INT8, MODE_DELTA, MODE_RLE, MODE_PACK, MODE_INVALID = 0, 1, 2, 3, 4, 0xFF
+MODE_RAW, MODE_INT8, MODE_DELTA, MODE_RLE, MODE_PACK, MODE_CHAN, MODE_INVALID = 0, 1, 2, 3, 4, 5, 0xFF
 ST_POOL_FULL, ST_CORRUPT, ST_BAD_INDEX = 1, 2, 4
 
 #: numpy view of kvc_desc
@@ -31,7 +31,7 @@ class Config(C.Structure):
 
 
 class Stats(C.Structure):
-    _fields_ = [("pool_bytes_used", C.c_uint64), ("pages", C.c_uint64 * 5), ("pages_invalid", C.c_uint64),
+    _fields_ = [("pool_bytes_used", C.c_uint64), ("pages", C.c_uint64 * 6), ("pages_invalid", C.c_uint64),
                 ("payload_bytes", C.c_uint64), ("status", C.c_uint32), ("rsvd", C.c_uint32)]
 
 

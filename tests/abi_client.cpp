@@ -108,12 +108,12 @@ int main() {
     KVC_OK_OR_FAIL(kvc_compress_blocks(ctx, d_x, n_blocks, nullptr, nullptr, n_blocks, nullptr));
     kvc_stats_t st;
     KVC_OK_OR_FAIL(kvc_stats(ctx, &st, nullptr));
-    const uint64_t stored = st.pages[0] + st.pages[1] + st.pages[2] + st.pages[3] + st.pages[4];
+    const uint64_t stored = st.pages[0] + st.pages[1] + st.pages[2] + st.pages[3] + st.pages[4] + st.pages[5];
     std::printf("compress: %llu pages (raw %llu, int8 %llu, rle %llu), pool %llu bytes, ratio %.3f\n",
                 (unsigned long long)stored, (unsigned long long)st.pages[0], (unsigned long long)st.pages[1],
                 (unsigned long long)st.pages[3], (unsigned long long)st.pool_bytes_used,
                 (double)(n_elem * 2) / (double)(st.payload_bytes + 16 * stored));
-    if (stored != n_pages || st.pages[0] != 1 || st.pages[2] != 0 || st.pages[4] != 0 || st.pages_invalid != 0 ||
+    if (stored != n_pages || st.pages[0] != 1 || st.pages[2] != 0 || st.pages[4] != 0 || st.pages[5] != 0 || st.pages_invalid != 0 ||
         st.status != 0 || st.payload_bytes != st.pool_bytes_used) {
         std::printf("unexpected statistics\n");
         return 4;

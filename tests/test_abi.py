@@ -35,7 +35,7 @@ def test_library_exports_every_declared_symbol():
 def test_descriptor_and_config_layouts():
     assert kvc.DESC_DTYPE.itemsize == 16
     assert [kvc.DESC_DTYPE.fields[f][1] for f in ("off", "scale", "n16", "mode", "rsvd")] == [0, 8, 12, 14, 15]
-    assert C.sizeof(kvc.Config) == 16 and C.sizeof(kvc.Stats) == 72
+    assert C.sizeof(kvc.Config) == 16 and C.sizeof(kvc.Stats) == 80
 
 
 def test_host_side_argument_checks_need_no_device():
@@ -44,8 +44,10 @@ def test_host_side_argument_checks_need_no_device():
     assert lib.kvc_create(None, None) == kvc.ERR_ARG
     assert lib.kvc_create(C.byref(ctx), None) == kvc.ERR_ARG
     for cfg, want in ((kvc.Config(0, 128, 1, 3), kvc.ERR_ARG), (kvc.Config(16, 128, 0, 3), kvc.ERR_ARG),
-                      (kvc.Config(16, 128, 1, 5), kvc.ERR_ARG), (kvc.Config(16, 100, 1, 3), kvc.ERR_ARG),
-                      (kvc.Config(16, 96, 1, 3), kvc.ERR_UNSUPPORTED), (kvc.Config(64, 128, 1, 3), kvc.ERR_UNSUPPORTED)):
+                      (kvc.Config(16, 128, 1, -1), kvc.ERR_ARG), (kvc.Config(16, 100, 1, 3), kvc.ERR_ARG),
+                      (kvc.Config(16, 96, 1, 3), kvc.ERR_UNSUPPORTED), (kvc.Config(64, 128, 1, 3), kvc.ERR_UNSUPPORTED),
+                      (kvc.Config(16, 64, 1, 5), kvc.ERR_UNSUPPORTED), (kvc.Config(8, 128, 1, 5), kvc.ERR_UNSUPPORTED),
+                      (kvc.Config(16, 128, 1, 6), kvc.ERR_ARG)):
         assert lib.kvc_create(C.byref(ctx), C.byref(cfg)) == want
         assert not ctx.value
     assert lib.kvc_set_scheme(None, 1) == kvc.ERR_ARG

@@ -65,7 +65,9 @@ def _families(rng, n, N, d):
                                           (16, 128, 8000, 4), (16, 64, 3000, 4), (16, 256, 3000, 4), (5, 128, 2000, 4),
                                           # calls of at most 2048 pages take the encoder's low-latency launch shape
                                           (16, 128, 2048, 3), (16, 64, 2047, 3), (16, 256, 2048, 3), (16, 128, 1501, 4),
-                                          (16, 64, 777, 2), (16, 256, 999, 1), (16, 128, 2049, 3)])
+                                          (16, 64, 777, 2), (16, 256, 999, 1), (16, 128, 2049, 3),
+                                          # mode 5: channel-pair groups (16 x 128 pages), both launch shapes
+                                          (16, 128, 9000, 5), (16, 128, 2048, 5), (16, 128, 333, 5)])
 def test_differential(N, d, n, scheme):
     # KVC_DIFF_SEED in the environment draws a different set of pages (for longer hunts)
     rng = np.random.default_rng(N * 1000 + d + scheme + 100003 * int(os.environ.get("KVC_DIFF_SEED", "0")))
@@ -88,7 +90,7 @@ def test_differential(N, d, n, scheme):
     if not np.array_equal(got, want):
         p = int(np.nonzero((got != want).any(axis=(1, 2)))[0][0])
         raise AssertionError(f"decoded page {p} (family {fam[p]}, mode {od['mode'][p]}) differs")
-    modes = np.bincount(od["mode"], minlength=5)
+    modes = np.bincount(od["mode"], minlength=6)
     assert modes[0] > 0 and modes[1] > 0 and modes[scheme] > 0  # raw, fallback and packed pages all occurred
 
 
@@ -106,7 +108,7 @@ def _soak_pages(rng, n, N, d):
 
 
 _SOAK_CASES = [(16, d, sc) for d in (64, 128, 256) for sc in (2, 3, 4, "mixed")] + \
-              [(N, d, sc) for (N, d) in ((8, 128), (32, 64), (16, 32), (4, 256)) for sc in (3, "mixed")]
+              [(N, d, sc) for (N, d) in ((8, 128), (32, 64), (16, 32), (4, 256)) for sc in (3, "mixed")] + [(16, 128, 5)]
 
 
 @pytest.mark.parametrize("N,d,scheme", _SOAK_CASES)

@@ -32,7 +32,7 @@ def _roundtrip_case(x, N, d, ppb, scheme, name):
     pool = c.pool.cpu().numpy()
     check_pool_invariants(desc, st["pool_bytes_used"], pool.size)
     od, op = compare_pages_with_oracle(xu, desc, pool, N, d, scheme)
-    assert st["pages"] == np.bincount(od["mode"], minlength=5).tolist() and st["pages_invalid"] == 0
+    assert st["pages"] == np.bincount(od["mode"], minlength=6).tolist() and st["pages_invalid"] == 0
     assert st["payload_bytes"] == op.size
     assert c.ratio() == pytest.approx(o.ratio(od, N * d))
     # decode GPU-made pool on the GPU
@@ -136,6 +136,44 @@ def test_special_pages_all_geometries(N, d, scheme):
                 G = N * d // 32
                 pool_codes |= {(pl[g >> 1] >> 4) if g & 1 else (pl[g >> 1] & 15) for g in range(G)}
         assert pool_codes >= set(range(0, 10)), pool_codes
+
+
+def test_special_pages_channel_pair_mode():
+    """Mode 5 (channel-pair groups; the GPU builds it for 16 x 128 pages): every branch page, and the
+    geometries it is not built for are refused on the host."""
+    rng = np.random.default_rng(777)
+    x = _special_pages(16, 128, rng)
+    # pages for what the mode is about: channel pairs that are zero, constant, narrow and wide
+    p = np.zeros((16, 128), np.float16); p[:, 6:8] = 3; p[0, 0] = 127; p[:, 20] = np.arange(16) - 8
+    q = (rng.standard_normal((16, 128)) * np.exp(1.5 * rng.standard_normal(128))).astype(np.float16)
+    x = np.concatenate([x, p[None], q[None]])
+    od = _roundtrip_case(x, 16, 128, 1, 5, "special N=16 d=128 channel pairs")
+    assert (od["mode"][5 + 1:5 + 6] == 0).all() and (od["mode"] == 5).sum() > 10
+    codes = set()
+    _, op = o.compress_pages(x.view(np.uint16), 16, 128, 5)
+    for i in range(x.shape[0]):
+        if od["mode"][i] == 5:
+            pl = o.page_payload(op, od[i])
+            codes |= {(pl[g >> 1] >> 4) if g & 1 else (pl[g >> 1] & 15) for g in range(64)}
+    assert codes >= set(range(0, 10)), codes
+    for N, d in ((16, 64), (16, 256), (8, 128), (16, 32)):
+        with pytest.raises(kvc.KvcError) as e:
+            kvc.Codec(N, d, 1, 5)
+        assert e.value.code == kvc.ERR_UNSUPPORTED
+        c = kvc.Codec(N, d, 1, 3)
+        with pytest.raises(kvc.KvcError) as e:
+            c.set_scheme(5)
+        assert e.value.code == kvc.ERR_UNSUPPORTED
+    # a mode-5 page met by a decoder of another geometry is contained like any unknown mode
+    x64 = (rng.standard_normal((3, 16, 64)) * np.exp(rng.standard_normal(64))).astype(np.float16)
+    od64, op64 = o.compress_pages(x64.view(np.uint16), 16, 64, 5)
+    assert (od64["mode"] == 5).all()
+    c = kvc.Codec(16, 64, 1, 3)
+    upload_oracle_pool(c, od64, op64)
+    out = torch.full((3, 1, 16, 64), 7.0, dtype=torch.float16, device=DEV)
+    c.decompress_blocks(out)
+    st = c.stats()
+    assert st["rc"] == kvc.ERR_CORRUPT and st["status"] & kvc.ST_CORRUPT and bool((out == 0).all())
 
 
 def test_llama7b_layer_slice_ragged_tail():

@@ -21,11 +21,11 @@ def _say(msg):
     print(msg, flush=True)
 
 
-def _sampled_pages_match_oracle(codec, cache_pages, out_pages, ids, N, d):
+def _sampled_pages_match_oracle(codec, cache_pages, out_pages, ids, N, d, scheme=3):
     idt = torch.from_numpy(ids).to(DEV)
     x = cache_pages[idt].cpu().numpy().view(np.uint16)
     gd, gp = fetch_pages(codec, ids)
-    od, op = o.compress_pages(x, N, d, 3, n_threads=16)
+    od, op = o.compress_pages(x, N, d, scheme, n_threads=16)
     assert np.array_equal(gd["mode"], od["mode"]) and np.array_equal(gd["n16"], od["n16"])
     assert np.array_equal(gd["scale"].view(np.uint32), od["scale"].view(np.uint32))
     assert np.array_equal(gp, op), "payload bytes differ"
@@ -95,6 +95,39 @@ def test_full_cache_sampled_parity_and_invariants(name):
         ok = (x - y.float()).abs() <= amax / 254 * (1 + 2.0 ** -14) + ulp / 2
         assert bool(ok.all()), f"layer {l}"
         del x, y, ya, ulp, ok
+
+
+@pytest.mark.timeout(600)
+def test_full_cache_channel_pair_mode():
+    """Config 4 (21.47 GB) through mode 5, the packets over channel-pair groups: one launch per direction,
+    sampled pages and two whole layers against the oracle, spans, counts and the ratio it is for."""
+    sh = synth.CONFIGS["70b_gqa"]
+    N, d, ppb = 16, 128, sh.n_kv_heads
+    _say(f"[case] building {sh.name}: {sh.n_pages} pages, scheme 5")
+    cache = synth.cache_torch(sh, DEV)
+    blocks = cache.view(-1, ppb, N, d)
+    codec = kvc.Codec(N, d, ppb, kvc.MODE_CHAN)
+    codec.alloc_pool(blocks.shape[0], sh.n_pages * N * d + 4096, DEV)
+    codec.compress_blocks(blocks)
+    st = codec.stats()
+    assert st["rc"] == 0 and st["status"] == 0 and sum(st["pages"]) == sh.n_pages
+    assert st["pages"][0] == 0 and st["pages"][5] > 0.95 * sh.n_pages and st["pages"][2] == st["pages"][3] == st["pages"][4] == 0
+    ratio = codec.ratio()
+    _say(f"[case] ratio {ratio:.4f} modes {st['pages']}")
+    assert 2.45 < ratio < 2.60  # the oracle gives 2.52 on this distribution (2.23 with Algorithm 2's delta + RLE)
+    check_pool_invariants(codec.desc_numpy(), st["pool_bytes_used"], codec.pool.numel())
+    out = torch.empty_like(blocks)
+    codec.decompress_blocks(out)
+    torch.cuda.synchronize()
+    assert codec.stats()["status"] == 0
+    rng = np.random.default_rng(2025)
+    ids = np.unique(np.concatenate([rng.integers(0, sh.n_pages, 3000), np.arange(0, 40), np.arange(sh.n_pages - 40, sh.n_pages)]))
+    _say(f"[case] oracle on {ids.size} sampled pages")
+    _sampled_pages_match_oracle(codec, blocks.view(-1, N, d), out.view(-1, N, d), ids, N, d, scheme=5)
+    per = sh.pages_per_layer
+    for l in (0, 41):
+        _say(f"[case] oracle on all {per} pages of layer {l}")
+        _sampled_pages_match_oracle(codec, blocks.view(-1, N, d), out.view(-1, N, d), np.arange(l * per, (l + 1) * per), N, d, scheme=5)
 
 
 def test_7b_layer_all_pages():

@@ -502,7 +502,8 @@ def bench_host_pool(args):
     out = torch.empty_like(blocks)
     unc = blocks.numel() * 2
     rows = []
-    for scheme, label in ((0, "None (FP16)"), (1, "INT8 only"), (3, "INT8 + Delta + RLE")):
+    for scheme, label in ((0, "None (FP16)"), (1, "INT8 only"), (3, "INT8 + Delta + RLE"),
+                          (5, "INT8 + pack over channel-pair groups (extension)")):
         codec = kvc.Codec(N, d, ppb, scheme)
         codec.alloc_pool(blocks.shape[0], unc + 4096, dev, host_pool=True)
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]

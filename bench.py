@@ -31,7 +31,8 @@ def log(msg):
 
 def read_traffic(workload: str, kernel: str):
     """HBM bytes per launch from the committed rocprofv3 --pmc summary, if one covers this kernel
-    and workload (profiles/hbm_traffic_<workload>.txt, lines `<kernel>_traffic_bytes: <int>`)."""
+    and workload (profiles/hbm_traffic_<workload>.txt, lines `<kernel>_traffic_bytes: <int>`).  The
+    summaries were taken with Algorithm 2's full scheme on the whole workload: callers ask only then."""
     p = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
     if not os.path.exists(p):
         return None
@@ -256,7 +257,7 @@ def main():
                    "gather": f"{rows} rows x {k} predicted blocks x {shape.n_layers} layers = {g_pages} pages"},
         "roofline": {"bound": "hbm", "kernel": kname, "achieved": round(kern[dom]["hbm_GBps"], 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(kern[dom]["frac_of_peak"], 4),
-                     "traffic": read_traffic(shape.name, kname), "alg_bytes_per_launch": int(kern[dom]["alg_bytes"]),
+                     "traffic": read_traffic(shape.name, kname) if args.scheme == 3 and not args.layers else None, "alg_bytes_per_launch": int(kern[dom]["alg_bytes"]),
                      "launch_ms": round(kern[dom]["ms"], 4)},
         "kernels": {k_: {a: (round(b, 4) if isinstance(b, float) else b) for a, b in v.items()} for k_, v in kern.items()},
         "copy_kernel_GBps": round(copy_gbps, 1),
@@ -329,7 +330,7 @@ def bench_decode_gather(args):
                    "ratio": round(codec.ratio(), 4)},
         "roofline": {"bound": "hbm", "kernel": "k_decompress_p16", "achieved": round(alg / ts.mean() / 1e6, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(alg / ts.mean() / 1e6 / HBM_PEAK_GBS, 4),
-                     "traffic": read_traffic("decode_gather", "k_decompress_p16"), "alg_bytes_per_launch": int(alg),
+                     "traffic": read_traffic("decode_gather", "k_decompress_p16") if args.scheme == 3 and not args.layers else None, "alg_bytes_per_launch": int(alg),
                      "launch_ms": round(float(ts.mean()), 4)},
         "step_ms": {"mean": round(float(ts.mean()), 4), "p50": round(float(np.percentile(ts, 50)), 4),
                     "p99": round(float(np.percentile(ts, 99)), 4)},

@@ -300,24 +300,24 @@ __device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPa
         }
     } else {
 #pragma unroll
-    for (int p = 0; p < NP; ++p) {
-        uint32_t t[8];
-        quantize8_bits(raw[p], s_inv, t);
-        // delta along the channel index, plus 256; the first column of a token row has no left
-        // neighbour and is kept verbatim (q - 0).  Then wrap + zig-zag by table.
-        uint32_t u[8];
-        if (no_delta) {  // mode 4: the table is indexed by q + 256
+        for (int p = 0; p < NP; ++p) {
+            uint32_t t[8];
+            quantize8_bits(raw[p], s_inv, t);
+            // delta along the channel index, plus 256; the first column of a token row has no left
+            // neighbour and is kept verbatim (q - 0).  Then wrap + zig-zag by table.
+            uint32_t u[8];
+            if (no_delta) {  // mode 4: the table is indexed by q + 256
 #pragma unroll
-            for (int k = 0; k < 8; ++k) u[k] = lut[t[k] - (kMagicBits + 256u * (uint32_t)k - 256u)];
-        } else {
-            const uint32_t prev = left_neighbour<Page<D>::kLpr>(kMagicBits - 256u, t[7] - 2048u);
-            KVC_CHECK(st, t[0] - prev < 512u && t[1] - t[0] < 512u && t[7] - t[6] < 512u);
-            u[0] = lut[t[0] - prev];
+                for (int k = 0; k < 8; ++k) u[k] = lut[t[k] - (kMagicBits + 256u * (uint32_t)k - 256u)];
+            } else {
+                const uint32_t prev = left_neighbour<Page<D>::kLpr>(kMagicBits - 256u, t[7] - 2048u);
+                KVC_CHECK(st, t[0] - prev < 512u && t[1] - t[0] < 512u && t[7] - t[6] < 512u);
+                u[0] = lut[t[0] - prev];
 #pragma unroll
-            for (int k = 1; k < 8; ++k) u[k] = lut[t[k] - t[k - 1]];
+                for (int k = 1; k < 8; ++k) u[k] = lut[t[k] - t[k - 1]];
+            }
+            encode_groups<D>(u, RLE, c_min, qi, p, run, stage, st);
         }
-        encode_groups<D>(u, RLE, c_min, qi, p, run, stage, st);
-    }
     }
     const uint32_t n = (run + 15u) & ~15u;
     wave_sync();

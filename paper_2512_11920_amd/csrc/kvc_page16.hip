@@ -452,7 +452,7 @@ __device__ __forceinline__ void unpack8(const DecodeArgs& a, const uint32_t* sta
     if (special && c == 9) B = goff;
     const uint32_t sh = (B & 3u) << 3;
     const uint32_t* p0 = stage + (B >> 2);
-    KVC_CHECK(a.st, (B >> 2) + 2 < (uint32_t)Slot<NP>::kWords && B >= (uint32_t)(NP * 32));
+    KVC_CHECK(a.st, (B >> 2) + 2 < (uint32_t)Slot<NP>::kWords && B >= (uint32_t)(NP * 8));  // bodies start after the NP * 8 header bytes
     const uint32_t d0 = p0[0], d1 = p0[1], d2 = p0[2];
     uint32_t lo = __builtin_amdgcn_alignbit(d1, d0, sh);
     uint32_t hi = __builtin_amdgcn_alignbit(d2, d1, sh);

@@ -30,6 +30,8 @@
  *     (1 byte), anything else a literal packet bit-packed at the width of its largest u;
  *   - a page with a NaN/Inf is stored raw (the bypass path); a page whose packed form is
  *     not smaller than its plain INT8 form is stored as plain INT8.
+ * Two modes go beyond Algorithm 2 and are marked as extensions where they are defined: mode 4 packs
+ * the codes without the delta step, mode 5 packs them in groups of one channel pair over 16 tokens.
  *
  * Floating point: the paper fixes FP16 in/out and INT8 codes; everything else here is
  * binary64 or exact integer arithmetic, except s and s^-1 which are binary32 by the

@@ -23,7 +23,10 @@
  *   3 RLE    as 2, plus code 0 = 32 zeros (no body) and code 9 = 32 copies of one byte (1 byte);
  *   4 PACK   as 3 with u = zig-zag of q itself, no differencing (for data without correlation
  *            along the channel index; not part of the paper's algorithm);
- *   payloads are zero-padded to 16 bytes; a mode-2/3/4 page whose payload would not be smaller
+ *   5 CHAN   as 4 with the values regrouped so that a group holds one pair of neighbouring channels
+ *            over the 16 tokens of the page (see KVC_MODE_CHAN below; N = 16, d = 128 only; not part
+ *            of the paper's algorithm);
+ *   payloads are zero-padded to 16 bytes; a mode-2/3/4/5 page whose payload would not be smaller
  *   than its INT8 payload is stored as mode 1.
  * Decoding yields fp16(fp32(q) * s), one binary32 multiply and one round-to-nearest-even.
  *

@@ -481,7 +481,7 @@ __device__ __forceinline__ void unpack8(const DecodeArgs& a, const uint32_t* sta
     hb[7] = __builtin_amdgcn_ubfe(mid, o3 + 1u, w1), sg[7] = __builtin_amdgcn_sbfe((int)mid, o3, 1u);
 }
 
-// A page on its way through the decoder: the descriptor's fields, the verdict of its validation and,
+// A page on its way through the decoder: the descriptor's fields, the outcome of its validation and,
 // for the packed modes, the payload as it arrives from the pool (16 bytes per lane and round).
 template <int D>
 struct DecPage {

@@ -24,7 +24,7 @@
  *   4 PACK   as 3 with u = zig-zag of q itself, no differencing (for data without correlation
  *            along the channel index; not part of the paper's algorithm);
  *   5 CHAN   as 4 with the values regrouped so that a group holds one pair of neighbouring channels
- *            over the 16 tokens of the page (see KVC_MODE_CHAN below; N = 16, d = 128 only; not part
+ *            over the 16 tokens of the page (see KVC_MODE_CHAN below; N = 16, d = 128 or 256 only; not part
  *            of the paper's algorithm);
  *   payloads are zero-padded to 16 bytes; a mode-2/3/4/5 page whose payload would not be smaller
  *   than its INT8 payload is stored as mode 1.
@@ -69,10 +69,11 @@ extern "C" {
 #define KVC_MODE_RLE 3
 #define KVC_MODE_PACK 4 /* extension beyond Algorithm 2: as 3 without the delta step (u = zigzag(q)) */
 /* Extension beyond Algorithm 2, for 16-token pages: the packets of mode 4 over groups that hold one
- * pair of neighbouring channels across the 16 tokens (pair p = c / 2 goes to group
- * (p mod 4) * (d / 8) + p div 4, element (t, c) to position (t mod 4) * 8 + (t div 4) * 2 + c mod 2),
- * so that each pair packs at its own width.  Compress produces it for tokens_per_block = 16 and
- * head_dim = 128 only; decompress reads it for that geometry only. */
+ * pair of neighbouring channels across the 16 tokens, so that each pair packs at its own width.
+ * With o = c / 8 the channel's octet, j = (c / 2) mod 4 its pair inside the octet and W = min(16, d / 8),
+ * element (t, c) goes to group ((o div W) * 4 + j) * W + o mod W, position
+ * (t mod 4) * 8 + (t div 4) * 2 + c mod 2.  Compress produces it, and decompress reads it, for
+ * tokens_per_block = 16 and head_dim 128 or 256 only. */
 #define KVC_MODE_CHAN 5
 #define KVC_MODE_INVALID 0xFF
 
@@ -96,7 +97,7 @@ typedef struct {
     int32_t tokens_per_block; /* N >= 1 */
     int32_t head_dim;         /* d in {32, 64, 128, 256};  N*d <= 4096 */
     int32_t pages_per_block;  /* ppb >= 1 */
-    int32_t scheme;           /* mode requested from compress: 0..5 (5: N = 16, d = 128 only, else KVC_ERR_UNSUPPORTED) */
+    int32_t scheme;           /* mode requested from compress: 0..5 (5: N = 16, d = 128 or 256 only, else KVC_ERR_UNSUPPORTED) */
 } kvc_config;
 
 typedef struct {

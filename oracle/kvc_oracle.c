@@ -174,15 +174,22 @@ void kvo_zigzag_codes(const int8_t* q, int E, uint8_t* u) {
  * stream so that a group of 32 holds one pair of neighbouring channels over all 16 tokens.  KV channels
  * differ in scale far more than the tokens of one channel do, so such a group packs at the width its own
  * channels need instead of the width of the widest of 32 neighbouring channels.
- * Element (token t, channel c), channel pair cp = c / 2, goes to group g = (cp mod 4) * (d / 8) + cp div 4
- * at position k = (t mod 4) * 8 + (t div 4) * 2 + (c mod 2) of the group.  (The order inside a group
- * and of the groups is free as far as the ratio goes; this one lets a GPU lane that holds tokens
- * t, t+4, t+8, t+12 of eight neighbouring channels emit whole bytes.) */
+ * Element (token t, channel c) sits in octet o = c / 8 of the channels, pair j = (c / 2) mod 4 of that
+ * octet.  The octets are taken in runs of W = min(16, d / 8); inside a run the groups are ordered by
+ * pair index first: g = ((o div W) * 4 + j) * W + o mod W, and the element goes to position
+ * k = (t mod 4) * 8 + (t div 4) * 2 + (c mod 2) of its group.  (The order inside a group and of the
+ * groups is free as far as the ratio goes; this one lets a GPU lane that holds tokens t, t+4, t+8, t+12
+ * of one octet emit whole bytes, sixteen octets at a time.) */
+static int chan_group(int c, int d) {
+    int o = c / 8, j = (c / 2) % 4;
+    int W = d / 8 < 16 ? d / 8 : 16;
+    return ((o / W) * 4 + j) * W + o % W;
+}
+
 void kvo_zigzag_codes_by_channel(const int8_t* q, int d, uint8_t* u) {
     for (int t = 0; t < 16; ++t)
         for (int c = 0; c < d; ++c) {
-            int cp = c / 2;
-            int g = (cp % 4) * (d / 8) + cp / 4;
+            int g = chan_group(c, d);
             int k = (t % 4) * 8 + (t / 4) * 2 + (c % 2);
             int v = q[t * d + c];
             u[32 * g + k] = (uint8_t)(((v << 1) ^ (v >> 7)) & 0xFF);
@@ -336,8 +343,7 @@ int kvo_decode_codes(const uint8_t* payload, size_t nbytes, int mode, int N, int
     if (mode == KVO_MODE_CHAN) { /* undo the regrouping and the zig-zag map; there was no delta step */
         for (int t = 0; t < 16; ++t)
             for (int c = 0; c < d; ++c) {
-                int cp = c / 2;
-                unsigned uu = u[32 * ((cp % 4) * (d / 8) + cp / 4) + (t % 4) * 8 + (t / 4) * 2 + (c % 2)];
+                unsigned uu = u[32 * chan_group(c, d) + (t % 4) * 8 + (t / 4) * 2 + (c % 2)];
                 q[t * d + c] = (int8_t)((int)(uu >> 1) ^ -(int)(uu & 1));
             }
         free(u);

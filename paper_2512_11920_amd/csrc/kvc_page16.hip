@@ -79,10 +79,20 @@ __device__ __forceinline__ void quantize8_bits(const uint4& raw, float s_inv, ui
     for (int k = 0; k < 8; ++k) t[k] = __float_as_uint(__builtin_fmaf((float)h[k], s_inv, kMagic + 256.0f * (float)k));
 }
 
-// plain INT8 payload: codes as bytes, row-major.  pos = the place of this lane's 8 channels among the
-// 64 eight-channel pieces of a pass.
-template <int NP>
-__device__ __forceinline__ void store_codes(const uint4 (&raw)[NP], float s_inv, uint32_t* stage, int pos) {
+// Two ways of dealing a page's 128-bit pieces (one token, eight channels = one octet) to the lanes.
+// Row-major (CHAN = false): piece number p*64 + lane in pass p.  Channel-pair mode 5 (CHAN = true,
+// D = 128 or 256): lane 4*l + r takes, in pass p, token 4*(p mod 4) + r of octet 16*(p div 4) + l, so
+// that the four lanes of a quad hold the 16 tokens of one octet over four passes.
+template <int D, bool CHAN>
+__device__ __forceinline__ int piece_index(int p, int lane) {  // position in row-major piece order
+    if (!CHAN) return p * 64 + lane;
+    return (4 * (p & 3) + (lane & 3)) * (D / 8) + 16 * (p >> 2) + (lane >> 2);
+}
+
+// plain INT8 payload: codes as bytes, row-major
+template <int D, bool CHAN, int NP>
+__device__ __forceinline__ void store_codes(const uint4 (&raw)[NP], float s_inv, uint32_t* stage) {
+    const int lane = lane_id();
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
         uint32_t t[8];
@@ -90,7 +100,7 @@ __device__ __forceinline__ void store_codes(const uint4 (&raw)[NP], float s_inv,
         uint2 v;
         v.x = __builtin_amdgcn_perm(__builtin_amdgcn_perm(t[3], t[2], 0x0c0c0400u), __builtin_amdgcn_perm(t[1], t[0], 0x0c0c0400u), 0x05040100u);
         v.y = __builtin_amdgcn_perm(__builtin_amdgcn_perm(t[7], t[6], 0x0c0c0400u), __builtin_amdgcn_perm(t[5], t[4], 0x0c0c0400u), 0x05040100u);
-        reinterpret_cast<uint2*>(stage)[p * 64 + pos] = v;
+        reinterpret_cast<uint2*>(stage)[piece_index<D, CHAN>(p, lane)] = v;
     }
 }
 
@@ -208,22 +218,25 @@ __device__ __forceinline__ uint32_t lane_byte_off(const Geometry& g) {
     return ((lane / Page<D>::kLpr) * (uint32_t)g.row_stride + (lane % Page<D>::kLpr) * 8u) * 2u;
 }
 
-// Mode 5 (channel-pair groups, D = 128) deals the same 128-bit pieces to the lanes in another order: lane
-// 4*l + r holds token row 4*p + r of pass p (channels 8*l .. 8*l + 7), so that the four lanes of a quad
-// hold the 16 tokens of the same eight channels between them.
+// The same for the deal of mode 5 (see piece_index): the lane's offset in pass 0, and what pass p adds.
 __device__ __forceinline__ uint32_t lane_byte_off_chan(const Geometry& g) {
     const uint32_t lane = (uint32_t)lane_id();
     return ((lane & 3u) * (uint32_t)g.row_stride + (lane >> 2) * 8u) * 2u;
 }
 
-template <int D>
+template <int D, bool CHAN>
+__device__ __forceinline__ int64_t pass_byte_off(const Geometry& g, int p) {
+    if (!CHAN) return (int64_t)p * Page<D>::kRowsPerPass * g.row_stride * 2;
+    return (int64_t)(p & 3) * 4 * g.row_stride * 2 + (p >> 2) * 256;
+}
+
+template <int D, bool CHAN>
 __device__ __forceinline__ void load_page(const EncodeArgs& a, const EncTask& task, uint32_t lane_off,
                                           uint4 (&raw)[Page<D>::kPasses]) {
     const char* src = reinterpret_cast<const char*>(a.cache) + wave_uniform((int64_t)task.src_off * 2);
-    const int64_t pass_bytes = (int64_t)Page<D>::kRowsPerPass * a.g.row_stride * 2;
 #pragma unroll
     for (int p = 0; p < Page<D>::kPasses; ++p)
-        raw[p] = load_stream(reinterpret_cast<const uint4*>(src + p * pass_bytes + lane_off));
+        raw[p] = load_stream(reinterpret_cast<const uint4*>(src + pass_byte_off<D, CHAN>(a.g, p) + lane_off));
 }
 
 // Encode one page (already in registers) into the LDS slot `stage`.  The requested mode is the
@@ -239,8 +252,6 @@ __device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPa
     const uint32_t c_min = RLE ? 0u : 1u;  // without run packets an all-zero group is a 1-bit literal
     const int lane = lane_id();
     const uint32_t qi = (uint32_t)lane & 3u;
-    // place of this lane's piece in the row-major order of a pass
-    const int pos = SCHEME == KVC_MODE_CHAN ? ((lane & 3) << 4) | (lane >> 2) : lane;
 
     // scaling: max |x| on the FP16 bit patterns, two per dword
     uint32_t m2 = 0;
@@ -267,7 +278,7 @@ __device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPa
     }
     r.scale = s;
     if (scheme == KVC_MODE_INT8) {
-        store_codes<NP>(raw, s_inv, stage, pos);
+        store_codes<D, SCHEME == KVC_MODE_CHAN, NP>(raw, s_inv, stage);
         r.n16 = kE / 16;
         r.mode = KVC_MODE_INT8;
         return r;
@@ -279,24 +290,27 @@ __device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPa
 
     uint32_t run = kHdr;  // payload bytes so far (wave-uniform)
     if constexpr (SCHEME == KVC_MODE_CHAN) {
-        // Mode 5: the lanes hold the page dealt as lane_byte_off_chan says.  All four passes are
-        // quantized and mapped first; group set j then takes channels 2j, 2j + 1 of every pass: the
-        // quad's 32 values are one channel pair over the 16 tokens.
-        static_assert(D == 128, "a lane's share of a channel pair is 8 values only at D = 128");
-        uint32_t uu[NP][8];
+        // Mode 5: the lanes hold the page dealt as piece_index says.  The four passes of a run of 16
+        // octets are quantized and mapped first; group set j of the run then takes channels 2j, 2j + 1
+        // of each of them: the quad's 32 values are one channel pair over the 16 tokens.
+        static_assert(D == 128 || D == 256, "a lane's share of a channel pair is 8 values when an octet's 16 tokens are 4 passes");
 #pragma unroll
-        for (int p = 0; p < NP; ++p) {
-            uint32_t t[8];
-            quantize8_bits(raw[p], s_inv, t);
+        for (int h = 0; h < NP / 4; ++h) {
+            uint32_t uu[4][8];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) uu[p][k] = lut[t[k] - (kMagicBits + 256u * (uint32_t)k - 256u)];
-        }
+            for (int p = 0; p < 4; ++p) {
+                uint32_t t[8];
+                quantize8_bits(raw[4 * h + p], s_inv, t);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            uint32_t u[8];
+                for (int k = 0; k < 8; ++k) uu[p][k] = lut[t[k] - (kMagicBits + 256u * (uint32_t)k - 256u)];
+            }
 #pragma unroll
-            for (int m = 0; m < 8; ++m) u[m] = uu[m >> 1][2 * j + (m & 1)];
-            encode_groups<D>(u, true, 0u, qi, j, run, stage, st);
+            for (int j = 0; j < 4; ++j) {
+                uint32_t u[8];
+#pragma unroll
+                for (int m = 0; m < 8; ++m) u[m] = uu[m >> 1][2 * j + (m & 1)];
+                encode_groups<D>(u, true, 0u, qi, 4 * h + j, run, stage, st);
+            }
         }
     } else {
 #pragma unroll
@@ -322,7 +336,7 @@ __device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPa
     const uint32_t n = (run + 15u) & ~15u;
     wave_sync();
     if (n >= (uint32_t)kE) {  // packing did not beat plain INT8
-        store_codes<NP>(raw, s_inv, stage, pos);
+        store_codes<D, SCHEME == KVC_MODE_CHAN, NP>(raw, s_inv, stage);
         r.n16 = kE / 16;
         r.mode = KVC_MODE_INT8;
     } else {
@@ -350,6 +364,9 @@ __device__ __forceinline__ void encode_into_slot(const EncodeArgs& a, const uint
     }
 }
 
+#ifndef KVC_ENC_MIN_WAVES
+#define KVC_ENC_MIN_WAVES 4
+#endif
 #ifndef KVC_ENC_RING64
 #define KVC_ENC_RING64 8
 #endif
@@ -360,9 +377,10 @@ __device__ __forceinline__ void encode_into_slot(const EncodeArgs& a, const uint
 #define KVC_ENC_RING256 1
 #endif
 
-// (four waves per SIMD is what the LDS slots allow anyway: keep every instantiation within 128 VGPRs)
+// (four waves per SIMD is what the LDS slots allow anyway: keep every instantiation within 128 VGPRs; the
+// channel-pair encoder at D = 256 holds 32 mapped values beside the page and runs better with three)
 template <int D, int WAVES, int PPW, int SCHEME>
-__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(4))) void k_compress_p16(EncodeArgs a) {
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((D == 256 && SCHEME == KVC_MODE_CHAN) ? 3 : KVC_ENC_MIN_WAVES))) void k_compress_p16(EncodeArgs a) {
     constexpr int kSlots = WAVES * PPW;
     constexpr int NP = Page<D>::kPasses;
     // Pages held in registers per wave: while one is encoded the loads of the next kRing - 1 are in
@@ -391,7 +409,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(4)))
         for (int j = 0; j < kRing - 1; ++j) {
             if (j > 0) task_advance(pos, a.g.ppb);
             t[j] = resolve_enc_task(a, t0 + j, pos);
-            if (t[j].desc_idx >= 0) load_page<D>(a, t[j], lane_off, r[j]);
+            if (t[j].desc_idx >= 0) load_page<D, SCHEME == KVC_MODE_CHAN>(a, t[j], lane_off, r[j]);
         }
 #pragma unroll 1
         for (int i = 0; i < PPW; i += kRing) {
@@ -401,7 +419,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(4)))
                 const int nb = (j + kAhead) % kRing;
                 task_advance(pos, a.g.ppb);
                 t[nb] = resolve_enc_task(a, i + j + kAhead < PPW ? t0 + i + j + kAhead : a.n_pages, pos);  // past the end: no task
-                if (t[nb].desc_idx >= 0) load_page<D>(a, t[nb], lane_off, r[nb]);
+                if (t[nb].desc_idx >= 0) load_page<D, SCHEME == KVC_MODE_CHAN>(a, t[nb], lane_off, r[nb]);
                 encode_into_slot<D, SCHEME>(a, r[j], t[j], slot0 + i + j, s_stage[slot0 + i + j], s_lut, s_book);
             }
         }
@@ -411,7 +429,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(4)))
             const EncTask task = resolve_enc_task(a, t0 + i, pos);
             task_advance(pos, a.g.ppb);
             uint4 raw[NP];
-            if (task.desc_idx >= 0) load_page<D>(a, task, lane_off, raw);
+            if (task.desc_idx >= 0) load_page<D, SCHEME == KVC_MODE_CHAN>(a, task, lane_off, raw);
             encode_into_slot<D, SCHEME>(a, raw, task, slot0 + i, s_stage[slot0 + i], s_lut, s_book);
         }
     }
@@ -494,7 +512,7 @@ struct DecPage {
 
 template <int D>
 __device__ __forceinline__ bool is_packed_mode(uint32_t mode) {
-    return mode == KVC_MODE_DELTA || mode == KVC_MODE_RLE || mode == KVC_MODE_PACK || (D == 128 && mode == KVC_MODE_CHAN);
+    return mode == KVC_MODE_DELTA || mode == KVC_MODE_RLE || mode == KVC_MODE_PACK || (D >= 128 && mode == KVC_MODE_CHAN);
 }
 
 // Take the descriptor apart, validate it against the pool and the page geometry, and start the
@@ -600,32 +618,37 @@ __device__ __forceinline__ bool dec_finish(const DecodeArgs& a, const DecPage<D>
         return false;
     }
     wave_sync();
-    if (D == 128 && mode == KVC_MODE_CHAN) {
-        // Mode 5: group set j holds channels 2j, 2j + 1 of the lane's eight, tokens 4p + (lane & 3) for
-        // p = 0..3 (value 2p + e of the packet = pass p, channel 2j + e).  The biased codes of a set are
-        // kept as bytes, so that pass p then finds its eight codes at fixed byte positions.
-        uint32_t packed[4][2];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            uint32_t hb[8];
-            int sg[8];
-            unpack8<NP>(a, stage, ginfo, j, special, hb, sg);
-            uint32_t b[8];
-#pragma unroll
-            for (int m = 0; m < 8; ++m) b[m] = (hb[m] ^ (uint32_t)sg[m]) + 128u;
-            packed[j][0] = __builtin_amdgcn_perm(__builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u), __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u), 0x05040100u);
-            packed[j][1] = __builtin_amdgcn_perm(__builtin_amdgcn_perm(b[7], b[6], 0x0c0c0400u), __builtin_amdgcn_perm(b[5], b[4], 0x0c0c0400u), 0x05040100u);
-        }
+    if (D >= 128 && mode == KVC_MODE_CHAN) {
+        // Mode 5: of a run of 16 octets, group set j holds channels 2j, 2j + 1 of the lane's octet,
+        // tokens 4p + (lane & 3) for p = 0..3 (value 2p + e of the packet = pass p, channel 2j + e).  The
+        // biased codes of a set are kept as bytes, so that pass p then finds its eight codes at fixed
+        // byte positions.
         const uint32_t lane_off_chan = lane_byte_off_chan(a.g);
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            uint32_t pb[8];
+        for (int h = 0; h < NP / 4; ++h) {
+            uint32_t packed[4][2];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const int m = 2 * p + (k & 1);  // value index inside group set k / 2
-                pb[k] = packed[k >> 1][m >> 2] >> (8 * (m & 3));
+            for (int j = 0; j < 4; ++j) {
+                uint32_t hb[8];
+                int sg[8];
+                unpack8<NP>(a, stage, ginfo, 4 * h + j, special, hb, sg);
+                uint32_t b[8];
+#pragma unroll
+                for (int m = 0; m < 8; ++m) b[m] = (hb[m] ^ (uint32_t)sg[m]) + 128u;
+                packed[j][0] = __builtin_amdgcn_perm(__builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u), __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u), 0x05040100u);
+                packed[j][1] = __builtin_amdgcn_perm(__builtin_amdgcn_perm(b[7], b[6], 0x0c0c0400u), __builtin_amdgcn_perm(b[5], b[4], 0x0c0c0400u), 0x05040100u);
             }
-            store_stream(reinterpret_cast<uint4*>(dst_b + p * pass_bytes + lane_off_chan), dequant8_biased(pb, s, neg128s));
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                uint32_t pb[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const int m = 2 * p + (k & 1);  // value index inside group set k / 2
+                    pb[k] = packed[k >> 1][m >> 2] >> (8 * (m & 3));
+                }
+                store_stream(reinterpret_cast<uint4*>(dst_b + pass_byte_off<D, true>(a.g, 4 * h + p) + lane_off_chan),
+                             dequant8_biased(pb, s, neg128s));
+            }
         }
         return true;
     }
@@ -732,14 +755,18 @@ hipError_t launch_compress_p16(const EncodeArgs& a, hipStream_t s) {
     // instantiation; any other request (another mode, or one mode per block) reads it at run time
     if (a.block_scheme == nullptr && a.scheme == KVC_MODE_RLE) return launch_compress_scheme<KVC_MODE_RLE>(a, s);
     if (a.block_scheme == nullptr && a.scheme == KVC_MODE_CHAN) {
-        // channel-pair groups: its own instantiation (another deal of the page to the lanes), D = 128 only
-        if (a.g.d != 128) return hipErrorInvalidValue;
+        // channel-pair groups: its own instantiations (another deal of the page to the lanes), D = 128 and 256
+        if (a.g.d != 128 && a.g.d != 256) return hipErrorInvalidValue;
         constexpr int WAVES = KVC_ENC_WAVES, PPW = KVC_ENC_PPW;
         const bool small = a.n_pages <= KVC_ENC_SMALL_PAGES;
-        const int64_t per_wg = (int64_t)WAVES * (small ? 1 : PPW);
-        const dim3 grid((unsigned)((a.n_pages + per_wg - 1) / per_wg)), block(WAVES * 64);
-        if (small) return launch_kernel(k_compress_p16<128, WAVES, 1, KVC_MODE_CHAN>, grid, block, s, a);
-        return launch_kernel(k_compress_p16<128, WAVES, PPW, KVC_MODE_CHAN>, grid, block, s, a);
+        const dim3 block(WAVES * 64);
+        auto grid = [&](int ppw) { return dim3((unsigned)((a.n_pages + (int64_t)WAVES * ppw - 1) / ((int64_t)WAVES * ppw))); };
+        if (a.g.d == 128) {
+            if (small) return launch_kernel(k_compress_p16<128, WAVES, 1, KVC_MODE_CHAN>, grid(1), block, s, a);
+            return launch_kernel(k_compress_p16<128, WAVES, PPW, KVC_MODE_CHAN>, grid(PPW), block, s, a);
+        }
+        if (small) return launch_kernel(k_compress_p16<256, WAVES, 1, KVC_MODE_CHAN>, grid(1), block, s, a);
+        return launch_kernel(k_compress_p16<256, WAVES, PPW / 2, KVC_MODE_CHAN>, grid(PPW / 2), block, s, a);
     }
     return launch_compress_scheme<-1>(a, s);
 }

@@ -138,25 +138,26 @@ def test_special_pages_all_geometries(N, d, scheme):
         assert pool_codes >= set(range(0, 10)), pool_codes
 
 
-def test_special_pages_channel_pair_mode():
-    """Mode 5 (channel-pair groups; the GPU builds it for 16 x 128 pages): every branch page, and the
-    geometries it is not built for are refused on the host."""
-    rng = np.random.default_rng(777)
-    x = _special_pages(16, 128, rng)
+@pytest.mark.parametrize("d", [128, 256])
+def test_special_pages_channel_pair_mode(d):
+    """Mode 5 (channel-pair groups; the GPU builds it for 16-token pages of 128 or 256 channels): every
+    branch page, and the geometries it is not built for are refused on the host."""
+    rng = np.random.default_rng(777 + d)
+    x = _special_pages(16, d, rng)
     # pages for what the mode is about: channel pairs that are zero, constant, narrow and wide
-    p = np.zeros((16, 128), np.float16); p[:, 6:8] = 3; p[0, 0] = 127; p[:, 20] = np.arange(16) - 8
-    q = (rng.standard_normal((16, 128)) * np.exp(1.5 * rng.standard_normal(128))).astype(np.float16)
+    p = np.zeros((16, d), np.float16); p[:, 6:8] = 3; p[0, 0] = 127; p[:, 20] = np.arange(16) - 8; p[:, d - 2:] = -5
+    q = (rng.standard_normal((16, d)) * np.exp(1.5 * rng.standard_normal(d))).astype(np.float16)
     x = np.concatenate([x, p[None], q[None]])
-    od = _roundtrip_case(x, 16, 128, 1, 5, "special N=16 d=128 channel pairs")
+    od = _roundtrip_case(x, 16, d, 1, 5, f"special N=16 d={d} channel pairs")
     assert (od["mode"][5 + 1:5 + 6] == 0).all() and (od["mode"] == 5).sum() > 10
     codes = set()
-    _, op = o.compress_pages(x.view(np.uint16), 16, 128, 5)
+    _, op = o.compress_pages(x.view(np.uint16), 16, d, 5)
     for i in range(x.shape[0]):
         if od["mode"][i] == 5:
             pl = o.page_payload(op, od[i])
-            codes |= {(pl[g >> 1] >> 4) if g & 1 else (pl[g >> 1] & 15) for g in range(64)}
+            codes |= {(pl[g >> 1] >> 4) if g & 1 else (pl[g >> 1] & 15) for g in range(d // 2)}
     assert codes >= set(range(0, 10)), codes
-    for N, d in ((16, 64), (16, 256), (8, 128), (16, 32)):
+    for N, d in ((16, 64), (8, 128), (16, 32), (8, 256)):
         with pytest.raises(kvc.KvcError) as e:
             kvc.Codec(N, d, 1, 5)
         assert e.value.code == kvc.ERR_UNSUPPORTED

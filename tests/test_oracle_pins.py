@@ -425,18 +425,21 @@ def test_no_delta_mode_is_the_same_packing_without_the_delta_step():
 
 
 def _chan_stream_py(q, d):
-    """Mode 5 stream order stated on its own: the groups are channel pairs, first all pairs with
-    pair index = 0 mod 4 in rising order, then 1 mod 4, ...; inside a group the four tokens
-    t, t+4, t+8, t+12 of one residue t mod 4 sit together, two channels each."""
+    """Mode 5 stream order stated on its own: the channel octets are taken sixteen at a time (all of
+    them if there are fewer); of such a run, first the first pair of every octet in rising order, then
+    the second pair of every octet, ...; inside a group the four tokens t, t+4, t+8, t+12 of one
+    residue t mod 4 sit together, two channels each."""
     q = np.asarray(q).reshape(16, d)
     u = []
-    for j in range(4):
-        for l in range(d // 8):
-            pair = 4 * l + j
-            for r in range(4):
-                for p in range(4):
-                    for e in range(2):
-                        u.append(int(q[4 * p + r, 2 * pair + e]))
+    n_oct = d // 8
+    for first in range(0, n_oct, 16):
+        for j in range(4):
+            for octet in range(first, min(first + 16, n_oct)):
+                pair = 4 * octet + j
+                for r in range(4):
+                    for p in range(4):
+                        for e in range(2):
+                            u.append(int(q[4 * p + r, 2 * pair + e]))
     return _zigzag_py(u)
 
 
@@ -475,11 +478,11 @@ def test_channel_pair_mode_is_mode_4_over_a_regrouped_stream(d):
         assert rc == 0 and np.array_equal(xh5, xh4)  # same codes, same reconstruction
         if t % 5 == 0:
             G = 16 * d // 32
-            g_zero = (2 % 4) * (d // 8) + 2 // 4  # channel pair 2 = channels 4, 5
+            g_zero = 2 * min(16, d // 8)  # channel pair 2 = channels 4, 5: third pair of octet 0
             code = (p5[g_zero >> 1] >> 4) if g_zero & 1 else (p5[g_zero >> 1] & 15)
             assert code == 0
         if t % 7 == 0:
-            g_run = (4 % 4) * (d // 8) + 4 // 4   # channel pair 4 = channels 8, 9
+            g_run = 1   # channel pair 4 = channels 8, 9: first pair of octet 1
             code = (p5[g_run >> 1] >> 4) if g_run & 1 else (p5[g_run >> 1] & 15)
             assert code == 9
         b4, b5 = b4 + len(p4), b5 + len(p5)

@@ -82,3 +82,34 @@ def test_offload_fetch_cycle_replays_from_a_graph():
                 assert np.array_equal(w_got[s * k + j], w_out[tb[s, pr[s, j]]]), (s, j)
     od, op = o.compress_pages(xs[0].view(np.uint16).reshape(-1, N, d), N, d, kvc.MODE_RLE)
     assert np.array_equal(want[0][0].reshape(-1, N, d), o.decompress_pages(op, od, N, d)[0])
+
+
+def test_two_contexts_on_two_streams_do_not_interfere():
+    """Contexts own all their state (cursor, status, statistics): two of them driven from two streams at
+    the same time give what each gives alone."""
+    N, d, ppb, nb = 16, 128, 8, 512
+    xs = [_inputs(300 + i, nb, ppb, N, d) for i in range(2)]
+    codecs, caches, outs, streams = [], [], [], [torch.cuda.Stream(), torch.cuda.Stream()]
+    for i in range(2):
+        c = kvc.Codec(N, d, ppb, (kvc.MODE_RLE, kvc.MODE_CHAN)[i])
+        c.alloc_pool(nb, nb * ppb * N * d * 2 + 64, DEV)
+        codecs.append(c)
+        caches.append(torch.from_numpy(xs[i]).to(DEV))
+        outs.append(torch.empty_like(caches[i]))
+    torch.cuda.synchronize()
+    for rep in range(6):  # interleave the enqueues so the kernels of the two contexts overlap
+        for i in range(2):
+            codecs[i].reset_pool(stream=streams[i])
+            codecs[i].compress_blocks(caches[i], stream=streams[i])
+        for i in range(2):
+            codecs[i].decompress_blocks(outs[i], stream=streams[i])
+    torch.cuda.synchronize()
+    for i in range(2):
+        scheme = (3, 5)[i]
+        st = codecs[i].stats()
+        assert st["rc"] == 0 and sum(st["pages"]) == nb * ppb, st
+        desc = codecs[i].desc_numpy()
+        check_pool_invariants(desc, st["pool_bytes_used"], codecs[i].pool.numel())
+        od, op = compare_pages_with_oracle(xs[i].view(np.uint16).reshape(-1, N, d), desc, codecs[i].pool.cpu().numpy(), N, d, scheme)
+        want, bad = o.decompress_pages(op, od, N, d)
+        assert bad == 0 and np.array_equal(outs[i].cpu().numpy().view(np.uint16).reshape(-1, N, d), want)

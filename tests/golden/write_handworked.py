@@ -74,6 +74,25 @@ add("channel_pairs_mode5", 16, 128, x, 5, "3f800000",
          "value 0x08; channels 2,3 all 1: pair 1, group 16, 32 equal u=2 -> run packet, body 0x02; every other group "
          "zero-run. Header nibbles 0,1,16 = 8,1,9. 32+32+4+1 = 69 -> 80 B")
 
+x = np.zeros((16, 256))
+x[0, 0] = 127
+x[15, 77] = -3
+x[9, 201] = 3
+x[3, 130] = -1
+x[:, 252:254] = 2
+add("channel_pairs_mode5_d256", 16, 256, x, 5, "3f800000",
+    "08" + "00" * 19 + "30" + "00" * 15 + "30" + "00" * 3 + "01" + "00" * 14 + "90" + "00" * 8
+    + "fe" + "00" * 31 + "00" * 11 + "a0" + "00" * 5 + "03" + "00" * 6 + "00000001" + "04" + "00" * 3, scheme=5,
+    note="mode 5 at d = 256 (extension): 32 channel octets in two runs of W = 16; channel c has octet o = c div 8, pair "
+         "j = (c div 2) mod 4, group ((o div 16)*4 + j)*16 + o mod 16; position (t mod 4)*8 + (t div 4)*2 + c mod 2. "
+         "x[0][0]=127: o=0 j=0 -> group 0, pos 0, u=254, w=8 (32 B: fe 00..). x[15][77]=-3: o=9 j=2 -> group 41, pos "
+         "24+6+1=31, u=5, w=3 (12 B), bits 93..95 = 101b -> byte 11 = 0xA0. x[9][201]=3: o=25 (second run) j=0 -> group "
+         "(4+0)*16+9=73, pos 8+4+1=13, u=6, w=3, bits 39..41 = 110b -> byte 5 = 0x03. x[3][130]=-1: o=16 j=1 -> group "
+         "(4+1)*16+0=80, pos 24, u=1, w=1 (4 B), bit 24 -> byte 3 = 0x01. channels 252,253 all 2: o=31 j=2 -> group "
+         "(4+2)*16+15=111, 32 equal u=4 -> run packet, body 0x04. Header (64 B): nibble of group 0 = 8 (byte 0 low), "
+         "41 = 3 (byte 20 high), 73 = 3 (byte 36 high), 80 = 1 (byte 40 low), 111 = 9 (byte 55 high); all other groups "
+         "zero-run. 64+32+12+12+4+1 = 125 -> 128 B")
+
 doc = dict(citation="Algorithm 2 (KV-Cache Compression) and Section 3.5.3 (inverse), under the KVC-1 reading of the "
            "unspecified byte format; worked by hand, not produced by any implementation. The paper prints no numeric example.",
            cases=cases)

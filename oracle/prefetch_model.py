@@ -133,3 +133,42 @@ def prefetch_step(tags: np.ndarray, fill: int, table: np.ndarray, pred: np.ndarr
                         fetch[l, s, j] = phys
                 loc[l, s, j] = where
     return fetch, loc, bad_index
+
+
+def window_schedule(fetch: np.ndarray, omega: int, layer_begin: int = 0, layer_end: int | None = None):
+    """Outstanding-request window of Algorithm 1 (WaitCompletion over at most Omega_max concurrent
+    transfers, Section 3.4.2): the transfers a step issued are carried out in issue order -- layer, then
+    sequence, then slot, the order of the loops -- with never more than `omega` of them in flight; the step
+    is ready when all have completed.
+    fetch: int32 [n_layers][n_seq][k] as returned by prefetch_step / prefetch_step_reuse.
+    Returns (queue, per_layer, batches):
+      queue      int32 [n_issued]: flat slot index (l*n_seq + s)*k + j of every issued transfer, in issue order;
+      per_layer  int32 [n_layers]: transfers issued for each layer (a layer is ready when that many completed);
+      batches    list of int32 arrays: the queue cut into consecutive pieces of at most omega entries -- the
+                 contents of the window if every transfer takes the same time.  omega <= 0 means no bound
+                 (one batch)."""
+    n_layers = fetch.shape[0]
+    layer_end = n_layers if layer_end is None else layer_end
+    queue = []
+    per_layer = np.zeros(n_layers, np.int32)
+    for l in range(layer_begin, layer_end):
+        for s in range(fetch.shape[1]):
+            for j in range(fetch.shape[2]):
+                if fetch[l, s, j] >= 0:
+                    queue.append((l * fetch.shape[1] + s) * fetch.shape[2] + j)
+                    per_layer[l] += 1
+    queue = np.asarray(queue, np.int32)
+    if omega <= 0 or queue.size == 0:
+        batches = [queue] if queue.size else []
+    else:
+        batches = [queue[i:i + omega] for i in range(0, queue.size, omega)]
+    return queue, per_layer, batches
+
+
+def batches_until_ready(per_layer: np.ndarray, omega: int, layer_begin: int = 0):
+    """Equal-time model of the window: number of batches after which each layer's transfers have all
+    completed (0 for a layer that issued none before any other did)."""
+    done = np.cumsum(per_layer)
+    if omega <= 0:
+        return (done > 0).astype(np.int64)
+    return (done + omega - 1) // omega

@@ -121,3 +121,53 @@ def test_slot_reuse_transfers_one_block_per_new_block_on_a_sliding_window():
                 tot += int((f >= 0).sum())
         counts[name] = tot
     assert counts["reuse"] == n_seq * 10 and counts["positional"] == n_seq * 10 * k
+
+
+@pytest.mark.parametrize("omega", [1, 3, 16, 64, 0])
+@pytest.mark.parametrize("reuse", [False, True])
+def test_window_never_exceeds_omega_and_carries_out_every_issued_transfer_once_in_order(omega, reuse):
+    """Algorithm 1's WaitCompletion over at most Omega_max concurrent transfers: the batches are pieces of
+    the issue list, none longer than omega, their concatenation is exactly the transfers the step issued
+    (every one once, in layer / sequence / slot order), and a layer's count is what it issued."""
+    rng = np.random.default_rng(100 + omega)
+    n_layers, n_seq, k, pbpl = 5, 4, 6, 40
+    table, nb = _setup(rng, n_layers, n_seq, k, 9, pbpl)
+    tags = np.full((2, n_layers, n_seq, k), -1, np.int32)
+    step_fn = pm.prefetch_step_reuse if reuse else pm.prefetch_step
+    for step in range(6):
+        pred = (rng.random((n_seq, k)) * nb[:, None]).astype(np.int32)
+        pred[rng.random((n_seq, k)) < 0.15] = -1
+        lo, hi = (1, 4) if step == 3 else (0, n_layers)
+        fetch, loc, _ = step_fn(tags, step % 2, table, pred, None, n_layers, pbpl, lo, hi)
+        queue, per_layer, batches = pm.window_schedule(fetch, omega, lo, hi)
+        flat = fetch.reshape(-1)
+        issued = np.nonzero(flat >= 0)[0]  # numpy's flat order is (layer, sequence, slot) order
+        assert np.array_equal(queue, issued.astype(np.int32))
+        assert all(0 < len(b) <= (omega if omega > 0 else max(1, queue.size)) for b in batches)
+        assert np.array_equal(np.concatenate(batches) if batches else np.zeros(0, np.int32), queue)
+        assert len(set(queue.tolist())) == queue.size
+        assert np.array_equal(per_layer, (fetch >= 0).sum(axis=(1, 2)).astype(np.int32))
+        assert per_layer[:lo].sum() == 0 and per_layer[hi:].sum() == 0
+        if omega > 0:
+            assert len(batches) == -(-queue.size // omega)
+            # a full window is kept whenever work remains: only the last batch may be short
+            assert all(len(b) == omega for b in batches[:-1])
+        until = pm.batches_until_ready(per_layer, omega, lo)
+        assert until[-1] == len(batches) and (np.diff(until) >= 0).all()
+
+
+def test_window_closed_forms():
+    """Hand-checked cases: 7 transfers over 3 layers (3, 0, 4) through a window of 2 need 4 batches; the
+    first layer is ready after 2, the empty layer with it, the last after 4.  Without a bound: one batch."""
+    fetch = np.full((3, 1, 4), -1, np.int32)
+    fetch[0, 0, [0, 2, 3]] = [5, 6, 7]
+    fetch[2, 0, :] = [20, 21, 22, 23]
+    queue, per_layer, batches = pm.window_schedule(fetch, 2)
+    assert queue.tolist() == [0, 2, 3, 8, 9, 10, 11] and per_layer.tolist() == [3, 0, 4]
+    assert [b.tolist() for b in batches] == [[0, 2], [3, 8], [9, 10], [11]]
+    assert pm.batches_until_ready(per_layer, 2).tolist() == [2, 2, 4]
+    _, _, one = pm.window_schedule(fetch, 0)
+    assert len(one) == 1 and one[0].tolist() == queue.tolist()
+    assert pm.batches_until_ready(per_layer, 0).tolist() == [1, 1, 1]
+    q0, p0, b0 = pm.window_schedule(np.full((2, 2, 2), -1, np.int32), 4)
+    assert q0.size == 0 and p0.tolist() == [0, 0] and b0 == []

@@ -43,7 +43,8 @@
  * current return KVC_ERR_ARG.  A context is not thread-safe: one host thread at a time.
  * The data calls (compress, decompress, gather, prefetch, reset) launch kernels only: no allocation, no
  * memset, no synchronisation, so a stream that is being captured into a HIP graph may record them.
- * One data call handles at most 2^26 - 1 pages (blocks * pages_per_block; 256 GiB of 4 KB pages); more is
+ * One data call handles at most 2^26 - 4 pages (blocks * pages_per_block; 256 GiB of 4 KB pages: the
+ * largest launch of 256-thread workgroups, one wave per page, that stays below 2^32 threads); more is
  * KVC_ERR_ARG.
  */
 #ifndef KVC_H
@@ -166,7 +167,9 @@ int kvc_gather_decompress(kvc_ctx* ctx, void* d_out, const int32_t* d_block_tabl
 /* Speculative prefetch of Algorithm 1 into a double-buffered L2 prefetch buffer (Section 3.3.1), for
  * layers [layer_begin, layer_end) of one decode step; the token predictor is outside (d_pred is given).
  *   d_l2    FP16 [2][n_layers*n_seq*k][ppb][N][d]: two halves; this call fills half `fill_half`, the
- *           other half is what the previous step filled (and what attention may be reading).
+ *           other half is what the previous step filled (and what attention may be reading).  Under
+ *           kvc_set_cache_layout a slot is a block of that layout: slot i of half h starts at element
+ *           (h*n_layers*n_seq*k + i) * block_stride.
  *   d_tags  int32 [2][n_layers*n_seq*k]: pool block held by every slot, -1 = empty (kvc_prefetch_reset).
  *   d_fetch int32 [n_layers*n_seq*k], out: pool block decoded into slot (l,s,j) by this call, or -1.
  *   d_loc   int32 [n_layers*n_seq*k], out: where the consumer finds predicted block (l,s,j):
@@ -192,6 +195,32 @@ int kvc_prefetch_layers(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fe
                         const int32_t* d_l1_first_block, int32_t n_seq, int32_t k, int32_t n_layers, int32_t layer_begin,
                         int32_t layer_end, int64_t pool_blocks_per_layer, int32_t fill_half, void* stream);
 
+/* kvc_prefetch_layers with Algorithm 1's outstanding-request window (WaitCompletion over at most
+ * Omega_max concurrent transfers; Section 3.4.2 gives the paper's controller a window of 16): the
+ * transfers the planner issues are queued in issue order (layer, sequence, slot) and carried out by at
+ * most `omega` transfer engines (workgroups), each holding one block in flight and taking the next queue
+ * entry when its block is complete.  omega >= 1; a small omega leaves most of the GPU to the computation
+ * the prefetch hides behind, a large one approaches kvc_prefetch_layers.  Plan arrays (tags, fetch, loc)
+ * and buffer contents are those of kvc_prefetch_layers.
+ *   d_notify  int64 [n_layers + 4], device, out.  Entry l (layers of the call only): 0 while transfers
+ *             of layer l are outstanding, then the device's wall clock (hipDeviceAttributeWallClockRate
+ *             ticks, never 0) at which its last transfer completed -- the ready notification a consumer
+ *             may poll or wait for; a layer that needed no transfer is stamped when the window opens.
+ *             [n_layers] = clock when the window opened, [n_layers+1] = transfers issued by the call,
+ *             [n_layers+2] = largest number of blocks in flight at once (<= omega),
+ *             [n_layers+3] = 0 until every transfer of the call has completed, then that clock value.
+ *   d_work    device workspace of at least kvc_prefetch_window_workspace(n_blocks, n_layers_call) bytes,
+ *             256-byte aligned, n_blocks = (layer_end - layer_begin) * n_seq * k, n_layers_call =
+ *             layer_end - layer_begin; caller-owned, contents meaningless between calls.  Calls that
+ *             overlap in time need workspaces and notify arrays of their own.
+ * A call over no slots (layer_begin = layer_end, n_seq = 0 or k = 0) does nothing. */
+uint64_t kvc_prefetch_window_workspace(int64_t n_blocks, int32_t n_layers_call);
+int kvc_prefetch_layers_window(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fetch, int32_t* d_loc,
+                               const int32_t* d_block_table, int32_t max_blocks, const int32_t* d_pred,
+                               const int32_t* d_l1_first_block, int32_t n_seq, int32_t k, int32_t n_layers,
+                               int32_t layer_begin, int32_t layer_end, int64_t pool_blocks_per_layer, int32_t fill_half,
+                               int32_t omega, int64_t* d_notify, void* d_work, uint64_t work_bytes, void* stream);
+
 /* Reduce the descriptor table and read the device state.  The only call that synchronises
  * (on `stream`).  Returns KVC_ERR_POOL_FULL / KVC_ERR_CORRUPT if the matching status bit is set
  * (out is filled either way), else 0. */
@@ -205,7 +234,7 @@ int kvc_stats(kvc_ctx* ctx, kvc_stats_t* out, void* stream);
 int kvc_page_scales(const uint16_t* d_amax, float* d_scale, float* d_scale_inv, uint64_t n, void* stream);
 
 /* dst[0..nbytes) = src[0..nbytes), a wavefront per contiguous 4 KB with 128-bit loads and stores;
- * nbytes a multiple of 16 and at most 2^38 (else KVC_ERR_ARG); both pointers device memory, 16-byte
+ * nbytes a multiple of 16 and at most 2^38 - 4096 (else KVC_ERR_ARG); both pointers device memory, 16-byte
  * aligned, not overlapping.  The bandwidth yardstick the codec kernels are compared with. */
 int kvc_copy_bytes(void* d_dst, const void* d_src, uint64_t nbytes, void* stream);
 

@@ -18,10 +18,11 @@ struct kvc_ctx {
 
 static_assert(sizeof(kvc_desc) == 16, "descriptor is 16 bytes");
 
-// One data call handles at most this many pages: a launch may hold fewer than 2^32 threads in all, and
-// the decoder spends a 64-thread wave on a page (256 GiB of 4 KB pages per call; task indices then also
-// divide in 32 bits).
-static constexpr int64_t kMaxPagesPerCall = (1ll << 26) - 1;
+// One data call handles at most this many pages: a launch may hold at most 2^32 - 1 threads in all, and
+// the decoder spends a 64-thread wave on a page in workgroups of four waves, so its grid of
+// ceil(pages / 4) workgroups of 256 threads must stay below 2^24 workgroups (256 GiB of 4 KB pages per
+// call; task indices then also divide in 32 bits).
+static constexpr int64_t kMaxPagesPerCall = (1ll << 26) - 4;
 
 // Text of the last HIP failure seen by this thread (for kvc_strerror(KVC_ERR_HIP)).
 static thread_local hipError_t t_last_hip = hipSuccess;
@@ -40,7 +41,7 @@ static bool config_ok(const kvc_config* c) {
     if (c->scheme < 0 || c->scheme > KVC_MODE_CHAN) return false;
     if (c->scheme == KVC_MODE_CHAN && !(c->tokens_per_block == 16 && (c->head_dim == 128 || c->head_dim == 256))) return false;
     const int d = c->head_dim;
-    if (!(d == 32 || d == 64 || d == 128 || d == 256)) return false;
+    if (d < 32 || d > 256 || d % 32 != 0) return false;
     const int64_t E = (int64_t)c->tokens_per_block * d;
     return E <= 4096;
 }
@@ -67,7 +68,15 @@ int kvc_create(kvc_ctx** out, const kvc_config* cfg) {
     c->g.d = cfg->head_dim;
     c->g.ppb = cfg->pages_per_block;
     c->g.E = cfg->tokens_per_block * cfg->head_dim;
-    c->g.dshift = __builtin_ctz((unsigned)cfg->head_dim);
+    c->g.lpr = cfg->head_dim / 8;
+    c->g.d_magic = ((1u << 22) + (uint32_t)cfg->head_dim - 1) / (uint32_t)cfg->head_dim;
+    c->g.lpr_magic = ((1u << 16) + (uint32_t)c->g.lpr - 1) / (uint32_t)c->g.lpr;
+    // the kernels divide by d and by d / 8 with these multipliers: they must be exact over the whole range
+    for (uint32_t e = 0; e < 8192; ++e)
+        if (((e * c->g.d_magic) >> 22) != e / (uint32_t)cfg->head_dim || (e < 1024 && ((e * c->g.lpr_magic) >> 16) != e / (uint32_t)c->g.lpr)) {
+            delete c;
+            return KVC_ERR_UNSUPPORTED;
+        }
     c->g.row_stride = cfg->head_dim;
     c->g.page_stride = c->g.E;
     c->g.block_stride = (int64_t)c->g.E * cfg->pages_per_block;
@@ -277,11 +286,15 @@ int kvc_prefetch_reset(kvc_ctx* ctx, int32_t* d_tags, int32_t n_seq, int32_t k, 
                : KVC_ERR_HIP;
 }
 
-int kvc_prefetch_layers(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fetch, int32_t* d_loc,
-                        const int32_t* d_block_table, int32_t max_blocks, const int32_t* d_pred,
-                        const int32_t* d_l1_first_block, int32_t n_seq, int32_t k, int32_t n_layers, int32_t layer_begin,
-                        int32_t layer_end, int64_t pool_blocks_per_layer, int32_t fill_half, void* stream) {
-    if (!ctx || n_seq < 0 || k < 0 || n_layers < 0 || max_blocks < 0 || pool_blocks_per_layer < 0) return KVC_ERR_ARG;
+// Shared body of the prefetch calls.  omega = 0: one decode launch over the call's slots (no bound on
+// the transfers in flight); omega > 0: the outstanding-request window, with its queue in `work`.
+static int prefetch_impl(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fetch, int32_t* d_loc,
+                         const int32_t* d_block_table, int32_t max_blocks, const int32_t* d_pred,
+                         const int32_t* d_l1_first_block, int32_t n_seq, int32_t k, int32_t n_layers, int32_t layer_begin,
+                         int32_t layer_end, int64_t pool_blocks_per_layer, int32_t fill_half, int32_t omega,
+                         long long* d_notify, void* work, uint64_t work_bytes, void* stream) {
+    if (!ctx || n_seq < 0 || k < 0 || n_layers < 0 || max_blocks < 0 || pool_blocks_per_layer < 0 || omega < 0) return KVC_ERR_ARG;
+    if (k > kvc::kMaxPrefetchK) return KVC_ERR_ARG;
     if (layer_begin < 0 || layer_end < layer_begin || layer_end > n_layers || (fill_half != 0 && fill_half != 1))
         return KVC_ERR_ARG;
     if (!ctx->pool) return KVC_ERR_NOT_BOUND;
@@ -293,10 +306,14 @@ int kvc_prefetch_layers(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fe
         (reinterpret_cast<uintptr_t>(d_l2) & 15u))
         return KVC_ERR_ARG;
     if (2 * n_slots > INT32_MAX || n_now > kMaxPagesPerCall / ctx->g.ppb) return KVC_ERR_ARG;
-    if (k > kvc::kMaxPrefetchK) return KVC_ERR_ARG;
     if ((uint64_t)n_layers * (uint64_t)pool_blocks_per_layer * (uint64_t)ctx->g.ppb > ctx->n_desc ||
         (uint64_t)n_layers * (uint64_t)pool_blocks_per_layer > (uint64_t)INT32_MAX)
         return KVC_ERR_ARG;
+    if (omega > 0) {
+        if (!d_notify || !work || (reinterpret_cast<uintptr_t>(work) & 255u) || (reinterpret_cast<uintptr_t>(d_notify) & 7u) ||
+            work_bytes < kvc::window_workspace_bytes(n_now, layer_end - layer_begin))
+            return KVC_ERR_ARG;
+    }
     hipStream_t s = static_cast<hipStream_t>(stream);
     kvc::PlanArgs p;
     p.block_table = d_block_table;
@@ -316,15 +333,54 @@ int kvc_prefetch_layers(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fe
     p.loc = d_loc;
     p.st = ctx->st;
     if (!hip_ok(kvc::launch_prefetch_plan(p, s))) return KVC_ERR_HIP;
-    // decode the listed pool blocks into their slots of the half being filled
+    // decode the listed pool blocks into their slots of the half being filled; slots are blocks of the
+    // cache layout in force (block_stride elements apart)
     const int64_t first = (int64_t)layer_begin * n_seq * k;
     kvc::DecodeArgs a;
     fill_decode_common(ctx, a);
-    a.out = static_cast<uint16_t*>(d_l2) + ((size_t)fill_half * (size_t)n_slots + (size_t)first) * (size_t)ctx->g.ppb * (size_t)ctx->g.E;
+    a.out = static_cast<uint16_t*>(d_l2) + ((int64_t)fill_half * n_slots + first) * ctx->g.block_stride;
     a.n_out_blocks = n_now;
     a.pool_ids = d_fetch + first;
     a.n_pages = n_now * ctx->g.ppb;
-    return hip_ok(kvc::launch_decompress(a, s)) ? KVC_OK : KVC_ERR_HIP;
+    if (omega == 0) return hip_ok(kvc::launch_decompress(a, s)) ? KVC_OK : KVC_ERR_HIP;
+    kvc::WindowArgs w;
+    char* wb = static_cast<char*>(work);
+    w.hdr = reinterpret_cast<kvc::WindowHdr*>(wb);
+    w.pending = reinterpret_cast<int32_t*>(wb + sizeof(kvc::WindowHdr));
+    w.queue = reinterpret_cast<int32_t*>(wb + kvc::window_workspace_bytes(0, layer_end - layer_begin));
+    w.fetch = d_fetch + first;
+    w.n_now = (int32_t)n_now;
+    w.per_layer = n_seq * k;
+    w.layer_begin = layer_begin;
+    w.n_layers_call = layer_end - layer_begin;
+    w.n_layers = n_layers;
+    w.notify = d_notify;
+    if (!hip_ok(kvc::launch_window_build(w, s))) return KVC_ERR_HIP;
+    return hip_ok(kvc::launch_decompress_window(a, w, omega, s)) ? KVC_OK : KVC_ERR_HIP;
+}
+
+int kvc_prefetch_layers(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fetch, int32_t* d_loc,
+                        const int32_t* d_block_table, int32_t max_blocks, const int32_t* d_pred,
+                        const int32_t* d_l1_first_block, int32_t n_seq, int32_t k, int32_t n_layers, int32_t layer_begin,
+                        int32_t layer_end, int64_t pool_blocks_per_layer, int32_t fill_half, void* stream) {
+    return prefetch_impl(ctx, d_l2, d_tags, d_fetch, d_loc, d_block_table, max_blocks, d_pred, d_l1_first_block, n_seq, k,
+                         n_layers, layer_begin, layer_end, pool_blocks_per_layer, fill_half, 0, nullptr, nullptr, 0, stream);
+}
+
+uint64_t kvc_prefetch_window_workspace(int64_t n_blocks, int32_t n_layers_call) {
+    if (n_blocks < 0 || n_layers_call < 0) return 0;
+    return kvc::window_workspace_bytes(n_blocks, n_layers_call);
+}
+
+int kvc_prefetch_layers_window(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fetch, int32_t* d_loc,
+                               const int32_t* d_block_table, int32_t max_blocks, const int32_t* d_pred,
+                               const int32_t* d_l1_first_block, int32_t n_seq, int32_t k, int32_t n_layers,
+                               int32_t layer_begin, int32_t layer_end, int64_t pool_blocks_per_layer, int32_t fill_half,
+                               int32_t omega, int64_t* d_notify, void* d_work, uint64_t work_bytes, void* stream) {
+    if (omega < 1) return KVC_ERR_ARG;
+    return prefetch_impl(ctx, d_l2, d_tags, d_fetch, d_loc, d_block_table, max_blocks, d_pred, d_l1_first_block, n_seq, k,
+                         n_layers, layer_begin, layer_end, pool_blocks_per_layer, fill_half, omega,
+                         reinterpret_cast<long long*>(d_notify), d_work, work_bytes, stream);
 }
 
 int kvc_stats(kvc_ctx* ctx, kvc_stats_t* out, void* stream) {
@@ -356,7 +412,7 @@ int kvc_page_scales(const uint16_t* d_amax, float* d_scale, float* d_scale_inv, 
 
 int kvc_copy_bytes(void* d_dst, const void* d_src, uint64_t nbytes, void* stream) {
     if (!d_dst || !d_src || (nbytes & 15u) || (reinterpret_cast<uintptr_t>(d_dst) & 15u) ||
-        (reinterpret_cast<uintptr_t>(d_src) & 15u) || nbytes > (1ull << 38))
+        (reinterpret_cast<uintptr_t>(d_src) & 15u) || nbytes > (1ull << 38) - 4096)
         return KVC_ERR_ARG;
     return hip_ok(kvc::launch_copy(d_dst, d_src, nbytes / 16, static_cast<hipStream_t>(stream))) ? KVC_OK : KVC_ERR_HIP;
 }
@@ -369,7 +425,7 @@ const char* kvc_strerror(int code) {
         case KVC_ERR_HIP: return t_last_hip != hipSuccess ? hipGetErrorString(t_last_hip) : "HIP runtime error";
         case KVC_ERR_POOL_FULL: return "compressed pool exhausted; some pages were not stored";
         case KVC_ERR_CORRUPT: return "invalid descriptor, payload or block index met on the device";
-        case KVC_ERR_UNSUPPORTED: return "page geometry not supported (head_dim in {32,64,128,256}, N*d <= 4096; mode 5: N = 16, d = 128 or 256)";
+        case KVC_ERR_UNSUPPORTED: return "page geometry not supported (head_dim a multiple of 32 up to 256, N*d <= 4096; mode 5: N = 16, d = 128 or 256)";
         default: return "unknown error";
     }
 }

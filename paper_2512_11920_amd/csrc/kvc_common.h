@@ -19,7 +19,9 @@ struct DevState {
 // b*block_stride + pg*page_stride + j*row_stride + i of the cache buffer (all in FP16 elements).
 struct Geometry {
     int32_t N, d, ppb, E;  // E = N*d elements per page
-    int32_t dshift;        // log2(d)
+    int32_t lpr;           // lanes per token row: d / 8 (a lane owns 8 channels)
+    uint32_t d_magic;      // ceil(2^22 / d):   e / d   == (e * d_magic) >> 22   for e < 8192
+    uint32_t lpr_magic;    // ceil(2^16 / lpr): i / lpr == (i * lpr_magic) >> 16 for i < 1024
     int64_t row_stride, page_stride, block_stride;
 };
 
@@ -74,6 +76,34 @@ struct PlanArgs {
     DevState* st;
 };
 
+// Outstanding-request window of the prefetch path (Algorithm 1: WaitCompletion over at most Omega_max
+// concurrent transfers).  The workspace of one call: this header, then one pending counter per layer of
+// the call, then the queue of issued transfers (slot indices relative to the call's first slot).
+struct WindowHdr {
+    unsigned int n_issued;    // entries in the queue
+    unsigned int ticket;      // next queue entry to hand out
+    unsigned int done;        // blocks completed
+    unsigned int in_flight;   // blocks being decoded at this moment
+    unsigned int high_water;  // largest in_flight seen during the call
+    unsigned int pad[59];     // the counters get a 256-byte line of their own
+};
+static_assert(sizeof(WindowHdr) == 256, "window header is 256 bytes");
+
+struct WindowArgs {
+    WindowHdr* hdr;
+    int32_t* pending;      // [layers of the call]: issued transfers of the layer not yet completed
+    int32_t* queue;        // [n_now]
+    const int32_t* fetch;  // the call's part of the fetch list: [n_now], pool block or -1
+    int32_t n_now;         // slots of the call = layers of the call * per_layer
+    int32_t per_layer;     // n_seq * k
+    int32_t layer_begin, n_layers_call, n_layers;
+    long long* notify;     // [n_layers + 4], see kvc.h
+};
+
+inline uint64_t window_workspace_bytes(int64_t n_blocks, int64_t n_layers_call) {
+    return sizeof(WindowHdr) + (uint64_t)((n_layers_call * 4 + 255) / 256 * 256) + (uint64_t)n_blocks * 4;
+}
+
 // Launch `kernel` and return the status of this launch itself.  (A launch through the <<<>>> form
 // reports failure only through the thread's last-error slot, which may still hold an error left by
 // an earlier, unrelated call of the application.)
@@ -88,6 +118,8 @@ inline hipError_t launch_kernel(void (*kernel)(P...), dim3 grid, dim3 block, hip
 }
 
 hipError_t launch_prefetch_plan(const PlanArgs& a, hipStream_t s);
+hipError_t launch_window_build(const WindowArgs& w, hipStream_t s);
+hipError_t launch_decompress_window(const DecodeArgs& a, const WindowArgs& w, int32_t omega, hipStream_t s);
 hipError_t launch_fill_i32(int32_t* p, int32_t v, uint64_t n, hipStream_t s);
 hipError_t launch_compress(const EncodeArgs& a, hipStream_t s);
 hipError_t launch_decompress(const DecodeArgs& a, hipStream_t s);

@@ -136,9 +136,16 @@ __device__ __forceinline__ int64_t page_base(const Geometry& g, int64_t blk, int
     return blk * g.block_stride + (int64_t)pg * g.page_stride;
 }
 
-// element offset, relative to the page base, of dense element index e (token e/d, channel e%d)
+// element offset, relative to the page base, of dense element index e (token e/d, channel e%d); d is
+// any multiple of 32, the quotient comes from a multiplication (checked for every e when a context is made)
 __device__ __forceinline__ int64_t elem_off(const Geometry& g, int e) {
-    return (int64_t)(e >> g.dshift) * g.row_stride + (e & (g.d - 1));
+    const uint32_t row = ((uint32_t)e * g.d_magic) >> 22;
+    return (int64_t)row * g.row_stride + ((uint32_t)e - row * (uint32_t)g.d);
+}
+
+// position of lane `gl` (counted from the page's first lane, 8 channels per lane) inside its token row
+__device__ __forceinline__ uint32_t lane_in_row(const Geometry& g, uint32_t gl) {
+    return gl - ((gl * g.lpr_magic) >> 16) * (uint32_t)g.lpr;
 }
 
 // Workgroup index used for task assignment.  Workgroups are dealt round-robin to the 8 XCDs; with
@@ -383,8 +390,52 @@ __device__ __forceinline__ void emit_page(const EncodeArgs& a, const EncBook<SLO
     }
 }
 
+// ---- outstanding-request window (Algorithm 1, WaitCompletion over at most Omega_max transfers) ----
+// A workgroup is one transfer engine: it takes the next entry of the issue queue, decodes that block,
+// reports completion and takes the next.  The grid has at most Omega workgroups, so never more than
+// Omega blocks are in flight; every workgroup leaves as soon as the queue is exhausted.
+
+// One turn of an engine: report the block of queue entry `done` (if >= 0) as complete -- make it visible,
+// count it, stamp the layer and the call whose last transfer it was -- and take the next queue entry,
+// or -1 when none is left.  Called by all threads of the workgroup; `s_slot` is a word of LDS.
+// Thread 0 does the bookkeeping between two barriers, so the single-lane region lies inside the loop
+// body and not across its back edge, and the result comes back in a scalar register: the engines' loop
+// and its exit branch on the scalar unit and every wave meets every barrier with all of its lanes.  (With
+// the single-lane work at both ends of the loop body the compiler merges it across the back edge into
+// an outer loop and lets the other lanes run ahead to the next barrier: the workgroup then never
+// meets.)
+__device__ __forceinline__ int32_t window_next(const WindowArgs& w, int32_t* s_slot, int32_t done) {
+    if (done >= 0) __threadfence();  // the block's stores are visible device-wide before the counters move
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        if (done >= 0) {
+            atomicSub(&w.hdr->in_flight, 1u);
+            const int32_t l_rel = done / w.per_layer;
+            const long long now = max(wall_clock64(), 1ll);
+            if (atomicSub(&w.pending[l_rel], 1) == 1)
+                __hip_atomic_store(&w.notify[w.layer_begin + l_rel], now, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+            if (atomicAdd(&w.hdr->done, 1u) + 1u == w.hdr->n_issued) {  // WaitCompletion returns: NotifyGPU(ready)
+                w.notify[w.n_layers + 2] = (long long)__hip_atomic_load(&w.hdr->high_water, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                // the clock is read again: every other engine stamped its layer before it counted its block
+                __hip_atomic_store(&w.notify[w.n_layers + 3], max(wall_clock64(), 1ll), __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        const unsigned int t = atomicAdd(&w.hdr->ticket, 1u);
+        int32_t slot = -1;
+        if (t < w.hdr->n_issued) {
+            slot = w.queue[t];
+            const unsigned int now_in = atomicAdd(&w.hdr->in_flight, 1u) + 1u;
+            atomicMax(&w.hdr->high_water, now_in);
+        }
+        *s_slot = slot;
+    }
+    __syncthreads();
+    return __builtin_amdgcn_readfirstlane(*s_slot);
+}
+
 // kernels specialised for 16-token pages with 64, 128 or 256 channels
 hipError_t launch_compress_p16(const EncodeArgs& a, hipStream_t s);
 hipError_t launch_decompress_p16(const DecodeArgs& a, hipStream_t s);
+hipError_t launch_decompress_window_p16(const DecodeArgs& a, const WindowArgs& w, unsigned grid, hipStream_t s);
 
 }  // namespace kvc

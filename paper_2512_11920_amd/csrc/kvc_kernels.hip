@@ -33,16 +33,18 @@ __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
     return v;
 }
 
-// exclusive prefix over the lanes of one token row (lpr = lanes per row, power of two <= 32)
-__device__ __forceinline__ uint32_t row_excl_scan_u32(uint32_t v, int lpr) {
-    const int r = lane_id() & (lpr - 1);
+// Inclusive prefix over the lanes of one token row.  Rows are runs of lpr <= 32 lanes that may begin
+// anywhere, also in the pass before this one: r = the lane's position in its row; a lane with r > lane
+// belongs to a row that began in the previous pass and adds `carry`, that pass's value at lane 63.
+__device__ __forceinline__ uint32_t row_incl_scan_u32(uint32_t v, uint32_t r, uint32_t carry) {
+    const uint32_t lane = (uint32_t)lane_id();
     uint32_t incl = v;
 #pragma unroll
-    for (int o = 1; o < 32; o <<= 1) {
-        uint32_t t = (uint32_t)__shfl_up((int)incl, o);
-        if (o < lpr && r >= o) incl += t;
+    for (uint32_t o = 1; o < 32; o <<= 1) {
+        uint32_t t = (uint32_t)__shfl_up((int)incl, (int)o);
+        if (r >= o && lane >= o) incl += t;
     }
-    return incl - v;
+    return r > lane ? incl + carry : incl;
 }
 
 __device__ __forceinline__ float half_bits_to_float(uint32_t h) {
@@ -103,7 +105,6 @@ __device__ PageResult encode_page(const uint16_t* __restrict__ src, const Geomet
     const int E = g.E;
     const int G = E >> 5;
     const int hdr = (G + 1) >> 1;
-    const int lpr = g.d >> 3;
     uint8_t* stage8 = reinterpret_cast<uint8_t*>(stage);
 
     uint4 raw[MAXP];
@@ -149,6 +150,7 @@ __device__ PageResult encode_page(const uint16_t* __restrict__ src, const Geomet
     wave_sync();
 
     uint32_t run = 0;  // body bytes emitted so far (wave-uniform)
+    int q_last = 0;    // last code of the pass before (a token row may continue across passes)
 #pragma unroll
     for (int p = 0; p < MAXP; ++p) {
         if (p * 512 < E) {
@@ -157,7 +159,9 @@ __device__ PageResult encode_page(const uint16_t* __restrict__ src, const Geomet
             quantize8(raw[p], s_inv, q);
             // delta along the channel index; the first column of a token row is kept verbatim
             int prev = __shfl_up(q[7], 1);
-            if ((lane & (lpr - 1)) == 0) prev = 0;
+            if (lane == 0) prev = q_last;
+            if (lane_in_row(g, (uint32_t)(p * 64 + lane)) == 0) prev = 0;
+            q_last = __builtin_amdgcn_readlane(q[7], 63);
             uint32_t u[8];
             if (scheme == KVC_MODE_PACK) {  // no delta step: the codes themselves are packed
 #pragma unroll
@@ -279,7 +283,6 @@ __device__ bool decode_page(const DecodeArgs& a, uint64_t d_idx, uint16_t* __res
     const int E = a.g.E;
     const int G = E >> 5;
     const int hdr = (G + 1) >> 1;
-    const int lpr = a.g.d >> 3;
     const uint4 dw = reinterpret_cast<const uint4*>(a.desc)[d_idx];
     const uint64_t off = (uint64_t)dw.x | ((uint64_t)dw.y << 32);
     const float s = __uint_as_float(dw.z);
@@ -347,6 +350,7 @@ __device__ bool decode_page(const DecodeArgs& a, uint64_t d_idx, uint16_t* __res
         return false;
     }
     wave_sync();
+    uint32_t row_carry = 0;  // prefix of the row that continues from the pass before
 #pragma unroll
     for (int p = 0; p < MAXP; ++p) {
         if (p * 512 < E) {
@@ -386,7 +390,9 @@ __device__ bool decode_page(const DecodeArgs& a, uint64_t d_idx, uint16_t* __res
                 acc += (int)(u[k] >> 1) ^ -(int)(u[k] & 1u);
                 q[k] = acc;
             }
-            const int before = (int)row_excl_scan_u32((uint32_t)acc, lpr);
+            const uint32_t incl = row_incl_scan_u32((uint32_t)acc, lane_in_row(a.g, (uint32_t)(p * 64 + lane)), row_carry);
+            row_carry = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+            const int before = (int)(incl - (uint32_t)acc);
             if (mode == KVC_MODE_PACK) {  // values are the codes themselves: undo the in-lane sums
 #pragma unroll
                 for (int k = 7; k > 0; --k) q[k] -= q[k - 1];
@@ -596,6 +602,76 @@ __global__ void k_prefetch_plan(PlanArgs a) {
     if (bad) atomicOr(&a.st->status, KVC_ST_BAD_INDEX);
 }
 
+// Opens the outstanding-request window of a prefetch call: the transfers the planner issued (entries
+// >= 0 of the call's part of the fetch list) are queued in issue order -- layer, sequence, slot -- each
+// layer's count becomes its pending counter, and the notification words are reset: a layer with nothing
+// to transfer is ready at once, the others when their last transfer completes.  One workgroup.
+__global__ __launch_bounds__(256) void k_window_build(WindowArgs w) {
+    __shared__ uint32_t s_cnt[4];
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const long long now = max(wall_clock64(), 1ll);
+    uint32_t base = 0;  // queue entries so far (workgroup-uniform)
+    for (int l = 0; l < w.n_layers_call; ++l) {
+        uint32_t in_layer = 0;
+        for (int c0 = 0; c0 < w.per_layer; c0 += 256) {
+            const int i = c0 + (int)threadIdx.x;
+            const bool live = i < w.per_layer && w.fetch[(int64_t)l * w.per_layer + i] >= 0;
+            const uint64_t m = __builtin_amdgcn_ballot_w64(live);
+            if (lane == 0) s_cnt[wave] = (uint32_t)__builtin_popcountll(m);
+            __syncthreads();
+            uint32_t before = 0, all = 0;
+            for (int k = 0; k < 4; ++k) {
+                before += k < wave ? s_cnt[k] : 0u;
+                all += s_cnt[k];
+            }
+            if (live) w.queue[base + in_layer + before + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u))] = l * w.per_layer + i;
+            in_layer += all;
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) {
+            w.pending[l] = (int32_t)in_layer;
+            w.notify[w.layer_begin + l] = in_layer ? 0ll : now;
+        }
+        base += in_layer;
+    }
+    if (threadIdx.x == 0) {
+        w.hdr->n_issued = base;
+        w.hdr->ticket = 0;
+        w.hdr->done = 0;
+        w.hdr->in_flight = 0;
+        w.hdr->high_water = 0;
+        w.notify[w.n_layers] = now;                    // window opened
+        w.notify[w.n_layers + 1] = (long long)base;    // transfers issued
+        w.notify[w.n_layers + 2] = 0;                  // most transfers in flight at once
+        w.notify[w.n_layers + 3] = base ? 0ll : now;   // all complete
+    }
+}
+
+// Transfer engines of the window for the generic page geometries: see window_next.
+template <int MAXP>
+__global__ __launch_bounds__(kThreads) void k_decompress_window(DecodeArgs a, WindowArgs w) {
+    __shared__ __align__(16) uint32_t s_stage[kWavesPerWG][Slot<MAXP>::kWords];
+    __shared__ uint32_t s_ginfo[kWavesPerWG][MAXP * 16];
+    __shared__ int32_t s_slot;
+    const int lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    int32_t slot = window_next(w, &s_slot, -1);
+    while (slot >= 0) {
+        for (int pg = wave; pg < a.g.ppb; pg += kWavesPerWG) {
+            TaskPos pos;
+            pos.blk = slot;
+            pos.pg = pg;
+            const DecTask task = resolve_dec_task(a, (int64_t)slot * a.g.ppb + pg, pos);
+            if (task.kind == 2) zero_page(task.dst, a.g);
+            if (task.kind == 1 && !decode_page<MAXP>(a, task.desc_idx, task.dst, s_stage[wave], s_ginfo[wave])) {
+                if (lane == 0) atomicOr(&a.st->status, KVC_ST_CORRUPT);
+            }
+            wave_sync();
+        }
+        slot = window_next(w, &s_slot, slot);
+    }
+}
+
 __global__ void k_fill_i32(int32_t* p, int32_t v, uint64_t n) {
     for (uint64_t k = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += (uint64_t)gridDim.x * blockDim.x) p[k] = v;
 }
@@ -615,6 +691,9 @@ __global__ void k_page_scales(const uint16_t* amax, float* s, float* s_inv, uint
 
 // ---------------------------------------------------------------------------------- launchers
 
+// geometries served by the specialised kernels of kvc_page16.hip
+static inline bool has_p16_kernels(const Geometry& g) { return g.N == 16 && (g.d == 64 || g.d == 128 || g.d == 256); }
+
 static inline unsigned grid_for(int64_t n_pages, int ppw) {
     const int64_t per_wg = (int64_t)kWavesPerWG * ppw;
     return (unsigned)((n_pages + per_wg - 1) / per_wg);
@@ -622,7 +701,7 @@ static inline unsigned grid_for(int64_t n_pages, int ppw) {
 
 hipError_t launch_compress(const EncodeArgs& a, hipStream_t s) {
     if (a.n_pages == 0) return hipSuccess;
-    if (a.g.N == 16 && a.g.d >= 64) return launch_compress_p16(a, s);
+    if (has_p16_kernels(a.g)) return launch_compress_p16(a, s);
     constexpr int PPW = 4;
     const dim3 grid(grid_for(a.n_pages, PPW)), block(kThreads);
     if (a.g.E <= 512) return launch_kernel(k_compress<1, PPW>, grid, block, s, a);
@@ -632,7 +711,7 @@ hipError_t launch_compress(const EncodeArgs& a, hipStream_t s) {
 
 hipError_t launch_decompress(const DecodeArgs& a, hipStream_t s) {
     if (a.n_pages == 0) return hipSuccess;
-    if (a.g.N == 16 && a.g.d >= 64) return launch_decompress_p16(a, s);
+    if (has_p16_kernels(a.g)) return launch_decompress_p16(a, s);
     constexpr int PPW = 4;
     const dim3 grid(grid_for(a.n_pages, PPW)), block(kThreads);
     if (a.g.E <= 512) return launch_kernel(k_decompress<1, PPW>, grid, block, s, a);
@@ -647,6 +726,22 @@ hipError_t launch_prefetch_plan(const PlanArgs& a, hipStream_t s) {
     if (a.k <= 8) return launch_kernel(k_prefetch_plan<8>, grid, block, s, a);
     if (a.k <= 16) return launch_kernel(k_prefetch_plan<16>, grid, block, s, a);
     return launch_kernel(k_prefetch_plan<kMaxPrefetchK>, grid, block, s, a);
+}
+
+hipError_t launch_window_build(const WindowArgs& w, hipStream_t s) {
+    return launch_kernel(k_window_build, dim3(1), dim3(256), s, w);
+}
+
+// At most omega workgroups, one block in flight each; the queue may turn out shorter than the grid, in
+// which case the surplus workgroups leave at their first look.
+hipError_t launch_decompress_window(const DecodeArgs& a, const WindowArgs& w, int32_t omega, hipStream_t s) {
+    if (w.n_now <= 0) return hipSuccess;
+    const unsigned grid = (unsigned)std::min<int64_t>(omega, w.n_now);
+    if (has_p16_kernels(a.g)) return launch_decompress_window_p16(a, w, grid, s);
+    const dim3 block(kThreads);
+    if (a.g.E <= 512) return launch_kernel(k_decompress_window<1>, dim3(grid), block, s, a, w);
+    if (a.g.E <= 2048) return launch_kernel(k_decompress_window<4>, dim3(grid), block, s, a, w);
+    return launch_kernel(k_decompress_window<8>, dim3(grid), block, s, a, w);
 }
 
 hipError_t launch_fill_i32(int32_t* p, int32_t v, uint64_t n, hipStream_t s) {
@@ -676,7 +771,7 @@ hipError_t launch_copy(void* dst, const void* src, uint64_t n16, hipStream_t s) 
     if (n16 == 0) return hipSuccess;
     const uint64_t per_wg = 256u * kWavesPerWG;  // 16-byte units per workgroup
     const uint64_t blocks = (n16 + per_wg - 1) / per_wg;
-    if (blocks > (1ull << 24)) return hipErrorInvalidValue;  // 256 GiB per call: the launch stays below 2^32 threads
+    if (blocks >= (1ull << 24)) return hipErrorInvalidValue;  // fewer than 2^24 workgroups of 256 threads: the launch stays below 2^32 threads
     return launch_kernel(k_copy, dim3((unsigned)blocks), dim3(kThreads), s, reinterpret_cast<uint4*>(dst), reinterpret_cast<const uint4*>(src), n16);
 }
 

@@ -711,7 +711,53 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_p16(DecodeArgs a) {
     }
 }
 
+// Transfer engines of the prefetch window (Algorithm 1: at most Omega_max transfers outstanding): a
+// workgroup takes the next issued block from the queue, its waves decode the block's pages, and the
+// completion is reported before the next block is taken.  A wave starts the descriptor and payload loads
+// of its next page before it decodes the current one.
+template <int D, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void k_decompress_window_p16(DecodeArgs a, WindowArgs w) {
+    __shared__ __align__(16) uint32_t s_stage[WAVES][Slot<Page<D>::kPasses>::kWords];
+    __shared__ uint32_t s_ginfo[WAVES][Page<D>::kGroups];
+    __shared__ int32_t s_slot;
+    const int lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int ppb = a.g.ppb;
+    int32_t slot = window_next(w, &s_slot, -1);
+    while (slot >= 0) {
+        auto open_page = [&](int pg, DecTask& task, DecPage<D>& dp) {
+            TaskPos pos;
+            pos.blk = slot;
+            pos.pg = pg;
+            task = resolve_dec_task(a, pg < ppb ? (int64_t)slot * ppb + pg : a.n_pages, pos);
+            if (task.kind == 1) dp = dec_open<D>(a, reinterpret_cast<const uint4*>(a.desc)[task.desc_idx]);
+        };
+        DecTask cur, nxt;
+        DecPage<D> dcur, dnxt;
+        open_page(wave, cur, dcur);
+        for (int pg = wave; pg < ppb; pg += WAVES) {
+            open_page(pg + WAVES, nxt, dnxt);
+            if (cur.kind == 2) zero_page(cur.dst, a.g);
+            if (cur.kind == 1 && !dec_finish<D>(a, dcur, cur.dst, s_stage[wave], s_ginfo[wave])) {
+                if (lane == 0) atomicOr(&a.st->status, KVC_ST_CORRUPT);
+            }
+            wave_sync();
+            cur = nxt;
+            dcur = dnxt;
+        }
+        slot = window_next(w, &s_slot, slot);
+    }
+}
+
 }  // namespace
+
+hipError_t launch_decompress_window_p16(const DecodeArgs& a, const WindowArgs& w, unsigned grid, hipStream_t s) {
+    constexpr int WAVES = 4;
+    const dim3 block(WAVES * 64);
+    if (a.g.d == 64) return launch_kernel(k_decompress_window_p16<64, WAVES>, dim3(grid), block, s, a, w);
+    if (a.g.d == 128) return launch_kernel(k_decompress_window_p16<128, WAVES>, dim3(grid), block, s, a, w);
+    return launch_kernel(k_decompress_window_p16<256, WAVES>, dim3(grid), block, s, a, w);
+}
 
 // Launch shapes (waves per workgroup, pages per wave); compile-time tunables.
 #ifndef KVC_ENC_WAVES

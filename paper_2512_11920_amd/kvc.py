@@ -21,7 +21,8 @@ ST_POOL_FULL, ST_CORRUPT, ST_BAD_INDEX = 1, 2, 4
 DESC_DTYPE = np.dtype([("off", "<u8"), ("scale", "<f4"), ("n16", "<u2"), ("mode", "u1"), ("rsvd", "u1")])
 
 EXPORTS = ("kvc_create", "kvc_destroy", "kvc_set_scheme", "kvc_set_cache_layout", "kvc_bind_pool", "kvc_reset_pool", "kvc_compress_blocks",
-           "kvc_compress_blocks_mixed", "kvc_decompress_blocks", "kvc_gather_decompress", "kvc_set_prefetch_policy", "kvc_prefetch_reset", "kvc_prefetch_layers", "kvc_stats", "kvc_page_scales",
+           "kvc_compress_blocks_mixed", "kvc_decompress_blocks", "kvc_gather_decompress", "kvc_set_prefetch_policy", "kvc_prefetch_reset", "kvc_prefetch_layers", "kvc_prefetch_window_workspace",
+           "kvc_prefetch_layers_window", "kvc_stats", "kvc_page_scales",
            "kvc_copy_bytes", "kvc_strerror")
 
 
@@ -85,6 +86,11 @@ def load():
     L.kvc_prefetch_layers.restype = C.c_int
     L.kvc_prefetch_layers.argtypes = [vp, vp, vp, vp, vp, i32p, C.c_int32, i32p, i32p, C.c_int32, C.c_int32, C.c_int32,
                                       C.c_int32, C.c_int32, C.c_int64, C.c_int32, vp]
+    L.kvc_prefetch_window_workspace.restype = C.c_uint64
+    L.kvc_prefetch_window_workspace.argtypes = [C.c_int64, C.c_int32]
+    L.kvc_prefetch_layers_window.restype = C.c_int
+    L.kvc_prefetch_layers_window.argtypes = [vp, vp, vp, vp, vp, i32p, C.c_int32, i32p, i32p, C.c_int32, C.c_int32, C.c_int32,
+                                             C.c_int32, C.c_int32, C.c_int64, C.c_int32, C.c_int32, vp, vp, C.c_uint64, vp]
     L.kvc_stats.restype = C.c_int
     L.kvc_stats.argtypes = [vp, C.POINTER(Stats), vp]
     L.kvc_page_scales.restype = C.c_int
@@ -266,6 +272,29 @@ class Codec:
                                            n_seq, k, n_layers, layer_begin, layer_end, int(pool_blocks_per_layer),
                                            fill_half, _stream(stream)), "kvc_prefetch_layers")
 
+    def prefetch_layers_window(self, l2, tags, fetch, loc, block_table, pred, n_layers: int, pool_blocks_per_layer: int,
+                               fill_half: int, omega: int, notify, work, layer_begin: int = 0, layer_end: int | None = None,
+                               l1_first=None, stream=None):
+        """prefetch_layers through the outstanding-request window: at most `omega` blocks in flight.
+        notify: int64 CUDA tensor [n_layers + 4]; work: uint8 CUDA tensor of window_workspace(...) bytes."""
+        import torch
+
+        block_table, pred = _ids(block_table), _ids(pred)
+        n_seq, max_blocks = block_table.shape
+        k = pred.shape[1]
+        n_slots = n_layers * n_seq * k
+        assert self._blocks_of(l2) == 2 * n_slots
+        assert _ids(tags).numel() == 2 * n_slots and _ids(fetch).numel() == n_slots and _ids(loc).numel() == n_slots
+        assert pred.shape[0] == n_seq and (l1_first is None or l1_first.numel() == n_seq)
+        assert notify.is_cuda and notify.dtype == torch.int64 and notify.numel() >= n_layers + 4 and notify.is_contiguous()
+        assert work.is_cuda and work.dtype == torch.uint8 and work.is_contiguous()
+        layer_end = n_layers if layer_end is None else layer_end
+        _check(self._L.kvc_prefetch_layers_window(self._ctx, l2.data_ptr(), tags.data_ptr(), fetch.data_ptr(), loc.data_ptr(),
+                                                  block_table.data_ptr(), max_blocks, pred.data_ptr(), _ptr(_ids(l1_first)),
+                                                  n_seq, k, n_layers, layer_begin, layer_end, int(pool_blocks_per_layer),
+                                                  fill_half, int(omega), notify.data_ptr(), work.data_ptr(), work.numel(),
+                                                  _stream(stream)), "kvc_prefetch_layers_window")
+
     def stats(self, stream=None, check: bool = False) -> dict:
         st = Stats()
         rc = self._L.kvc_stats(self._ctx, C.byref(st), _stream(stream))
@@ -283,6 +312,11 @@ class Codec:
         s = self.stats()
         n = sum(s["pages"])
         return (n * self.page_elems * 2) / (s["payload_bytes"] + 16 * n) if n else float("nan")
+
+
+def window_workspace(n_blocks: int, n_layers_call: int) -> int:
+    """Bytes of device workspace prefetch_layers_window needs for a call over n_blocks slots."""
+    return int(load().kvc_prefetch_window_workspace(int(n_blocks), int(n_layers_call)))
 
 
 def page_scales(amax_bits, stream=None):

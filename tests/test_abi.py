@@ -45,7 +45,8 @@ def test_host_side_argument_checks_need_no_device():
     assert lib.kvc_create(C.byref(ctx), None) == kvc.ERR_ARG
     for cfg, want in ((kvc.Config(0, 128, 1, 3), kvc.ERR_ARG), (kvc.Config(16, 128, 0, 3), kvc.ERR_ARG),
                       (kvc.Config(16, 128, 1, -1), kvc.ERR_ARG), (kvc.Config(16, 100, 1, 3), kvc.ERR_ARG),
-                      (kvc.Config(16, 96, 1, 3), kvc.ERR_UNSUPPORTED), (kvc.Config(64, 128, 1, 3), kvc.ERR_UNSUPPORTED),
+                      (kvc.Config(16, 288, 1, 3), kvc.ERR_UNSUPPORTED), (kvc.Config(64, 128, 1, 3), kvc.ERR_UNSUPPORTED),
+                      (kvc.Config(16, 96, 1, 5), kvc.ERR_UNSUPPORTED),
                       (kvc.Config(16, 64, 1, 5), kvc.ERR_UNSUPPORTED), (kvc.Config(8, 128, 1, 5), kvc.ERR_UNSUPPORTED),
                       (kvc.Config(8, 256, 1, 5), kvc.ERR_UNSUPPORTED),
                       (kvc.Config(16, 128, 1, 6), kvc.ERR_ARG)):

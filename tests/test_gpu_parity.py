@@ -119,7 +119,8 @@ def _special_pages(N, d, rng):
     return np.stack([np.asarray(q, np.float16) for q in pages])
 
 
-@pytest.mark.parametrize("N,d", [(16, 128), (16, 64), (16, 32), (16, 256), (1, 64), (3, 32), (5, 128), (32, 128)])
+@pytest.mark.parametrize("N,d", [(16, 128), (16, 64), (16, 32), (16, 256), (1, 64), (3, 32), (5, 128), (32, 128),
+                                 (16, 96), (16, 160), (16, 192), (16, 224), (8, 96), (5, 224), (32, 96), (1, 96)])
 @pytest.mark.parametrize("scheme", [3, 2, 4])
 def test_special_pages_all_geometries(N, d, scheme):
     rng = np.random.default_rng(100 + N + d)
@@ -339,7 +340,7 @@ def test_host_side_argument_errors():
         c.compress_blocks(x)  # 4 blocks, 2 pool blocks, identity ids
     assert e.value.code == kvc.ERR_ARG
     with pytest.raises(kvc.KvcError) as e:
-        kvc.Codec(16, 96, 1, 3)
+        kvc.Codec(16, 288, 1, 3)
     assert e.value.code == kvc.ERR_UNSUPPORTED
     with pytest.raises(kvc.KvcError) as e:
         kvc.Codec(16, 100, 1, 3)

@@ -162,3 +162,126 @@ def test_hip_graph_replays_match_eager():
         for a, b in zip(got, want):
             assert np.array_equal(a, b)
         assert c.stats()["status"] == 0
+
+
+@pytest.mark.parametrize("geom", [(16, 128, 4), (16, 64, 3), (8, 32, 2)])
+@pytest.mark.parametrize("omega", [1, 5, 16, 4096])
+def test_window_prefetch_matches_unbounded_and_model(omega, geom):
+    """Algorithm 1's outstanding-request window: with at most omega blocks in flight the plan arrays and
+    the buffer are those of the unbounded call and of the model; the queue the engines worked through
+    is the model's issue list (count, per-layer completion), and no more than omega were ever in flight."""
+    rng = np.random.default_rng(50 + omega)
+    N, d, ppb = geom
+    n_layers = 4
+    pat = synth.gather_pattern(n_seq=5, k=8, len_lo=48, len_hi=200, seed=12)
+    pbl, n_seq, k = pat.pool_blocks_per_layer, pat.n_seq, pat.k
+    x = (rng.standard_normal((n_layers * pbl, ppb, N, d)) * np.exp(0.5 * rng.standard_normal(d))).astype(np.float16)
+    c, _ = gpu_compress(x, N, d, ppb, 3)
+    n_slots = n_layers * n_seq * k
+
+    def buffers():
+        return (torch.full((2 * n_slots, ppb, N, d), 5.0, dtype=torch.float16, device=DEV),
+                torch.empty(2 * n_slots, dtype=torch.int32, device=DEV), torch.empty(n_slots, dtype=torch.int32, device=DEV),
+                torch.empty(n_slots, dtype=torch.int32, device=DEV))
+
+    l2a, tags_a, fetch_a, loc_a = buffers()  # unbounded
+    l2b, tags_b, fetch_b, loc_b = buffers()  # windowed
+    c.prefetch_reset(tags_a, n_seq, k, n_layers)
+    c.prefetch_reset(tags_b, n_seq, k, n_layers)
+    notify = torch.full((n_layers + 4,), -7, dtype=torch.int64, device=DEV)
+    work = torch.empty(kvc.window_workspace(n_slots, n_layers), dtype=torch.uint8, device=DEV)
+    table = torch.from_numpy(pat.block_table).to(DEV)
+    m_tags = np.full((2, n_layers, n_seq, k), -1, np.int32)
+    for step in range(6):
+        fill = step % 2
+        pred_np = pat.predictions(step).copy()
+        pred = torch.from_numpy(pred_np).to(DEV)
+        lo, hi = (1, 3) if step == 4 else (0, n_layers)
+        _say(f"[case] window omega {omega} geometry {geom} step {step} layers [{lo},{hi})")
+        c.prefetch_layers(l2a, tags_a, fetch_a, loc_a, table, pred, n_layers, pbl, fill, layer_begin=lo, layer_end=hi)
+        c.prefetch_layers_window(l2b, tags_b, fetch_b, loc_b, table, pred, n_layers, pbl, fill, omega, notify, work,
+                                 layer_begin=lo, layer_end=hi)
+        torch.cuda.synchronize()
+        m_fetch, m_loc, bad = pm.prefetch_step(m_tags, fill, pat.block_table, pred_np, None, n_layers, pbl, lo, hi)
+        queue, per_layer, batches = pm.window_schedule(m_fetch, omega, lo, hi)
+        first = lo * n_seq * k
+        sl = slice(first, hi * n_seq * k)
+        assert np.array_equal(tags_b.cpu().numpy(), m_tags.reshape(-1)) and torch.equal(tags_a, tags_b)
+        assert np.array_equal(fetch_b.cpu().numpy()[sl], m_fetch.reshape(-1)[sl]) and torch.equal(fetch_a[sl], fetch_b[sl])
+        assert np.array_equal(loc_b.cpu().numpy()[sl], m_loc.reshape(-1)[sl]) and torch.equal(loc_a[sl], loc_b[sl])
+        assert torch.equal(l2a.view(torch.int16), l2b.view(torch.int16)), "windowed buffer differs from the unbounded call's"
+        nt = notify.cpu().numpy()
+        opened, issued, high, closed = nt[n_layers:]
+        assert issued == queue.size and opened > 0 and closed >= opened
+        assert high <= min(omega, max(1, queue.size)) and (high >= 1) == (queue.size > 0)
+        assert (nt[lo:hi] >= opened).all() and (nt[lo:hi] <= closed).all(), "every layer of the call is stamped ready"
+        # the queue in the workspace is the model's issue list (relative to the call's first slot)
+        hdr = work[:20].view(torch.int32).cpu().numpy()
+        assert hdr[0] == queue.size and hdr[2] == queue.size and hdr[3] == 0 and hdr[1] >= queue.size
+        q_off = kvc.window_workspace(0, hi - lo)
+        got_q = work[q_off:q_off + 4 * queue.size].view(torch.int32).cpu().numpy()
+        assert np.array_equal(got_q + first, queue)
+    assert c.stats()["status"] == 0
+
+
+def test_window_argument_checks():
+    N, d, ppb = 16, 128, 2
+    pat = synth.gather_pattern(n_seq=3, k=4, len_lo=40, len_hi=90, seed=2)
+    pbl = pat.pool_blocks_per_layer
+    x = np.random.default_rng(1).standard_normal((pbl, ppb, N, d)).astype(np.float16)
+    c, _ = gpu_compress(x, N, d, ppb, 3)
+    n_slots = pat.n_seq * pat.k
+    l2 = torch.zeros((2 * n_slots, ppb, N, d), dtype=torch.float16, device=DEV)
+    tags = torch.full((2 * n_slots,), -1, dtype=torch.int32, device=DEV)
+    fetch = torch.empty(n_slots, dtype=torch.int32, device=DEV)
+    loc = torch.empty(n_slots, dtype=torch.int32, device=DEV)
+    notify = torch.zeros(1 + 4, dtype=torch.int64, device=DEV)
+    need = kvc.window_workspace(n_slots, 1)
+    assert need == 256 + 256 + 4 * n_slots
+    table, pred = torch.from_numpy(pat.block_table).to(DEV), torch.from_numpy(pat.predictions(0)).to(DEV)
+    work = torch.empty(need, dtype=torch.uint8, device=DEV)
+    for omega, wk in ((0, work), (-1, work), (4, work[: need - 16])):
+        with pytest.raises(kvc.KvcError) as e:
+            c.prefetch_layers_window(l2, tags, fetch, loc, table, pred, 1, pbl, 0, omega, notify, wk)
+        assert e.value.code == kvc.ERR_ARG
+    c.prefetch_layers_window(l2, tags, fetch, loc, table, pred, 1, pbl, 0, 4, notify, work)
+    torch.cuda.synchronize()
+    assert notify.cpu().numpy()[1 + 1] == (fetch.cpu().numpy() >= 0).sum() > 0
+
+
+def test_prefetch_into_a_strided_buffer():
+    """Slots of the L2 buffer follow the cache layout in force: with a padded token-major layout the
+    blocks of half 1 and of a layer range that does not start at 0 land block_stride elements apart."""
+    rng = np.random.default_rng(9)
+    N, d, H, n_layers = 16, 128, 3, 3
+    pad = 64
+    row, page, block = H * d + pad, d, N * (H * d + pad)
+    pat = synth.gather_pattern(n_seq=4, k=4, len_lo=48, len_hi=160, seed=21)
+    pbl, n_seq, k = pat.pool_blocks_per_layer, pat.n_seq, pat.k
+    x = (rng.standard_normal((n_layers * pbl, H, N, d)) * np.exp(0.5 * rng.standard_normal(d))).astype(np.float16)
+    c, _ = gpu_compress(x, N, d, H, 3)  # compressed from a dense buffer
+    od, op = o.compress_pages(x.view(np.uint16), N, d, 3, n_threads=8)
+    full = o.decompress_pages(op, od, N, d, n_threads=8)[0].reshape(n_layers * pbl, H, N, d)
+    c.set_cache_layout(block, page, row)
+    n_slots = n_layers * n_seq * k
+    l2 = torch.full((2 * n_slots * block,), 5.0, dtype=torch.float16, device=DEV)
+    tags = torch.empty(2 * n_slots, dtype=torch.int32, device=DEV)
+    fetch = torch.empty(n_slots, dtype=torch.int32, device=DEV)
+    loc = torch.empty(n_slots, dtype=torch.int32, device=DEV)
+    c.prefetch_reset(tags, n_seq, k, n_layers)
+    table = torch.from_numpy(pat.block_table).to(DEV)
+    m_tags = np.full((2, n_layers, n_seq, k), -1, np.int32)
+    want = np.full((2 * n_slots, N, H * d + pad), np.float16(5.0).view(np.uint16), np.uint16)
+    for step, (fill, lo, hi) in enumerate(((0, 0, n_layers), (1, 1, n_layers), (0, 2, 3), (1, 0, 2))):
+        pred_np = pat.predictions(step)
+        _say(f"[case] strided prefetch step {step} fill {fill} layers [{lo},{hi})")
+        c.prefetch_layers(l2, tags, fetch, loc, table, torch.from_numpy(pred_np).to(DEV), n_layers, pbl, fill,
+                          layer_begin=lo, layer_end=hi)
+        m_fetch, m_loc, bad = pm.prefetch_step(m_tags, fill, pat.block_table, pred_np, None, n_layers, pbl, lo, hi)
+        assert np.array_equal(tags.cpu().numpy(), m_tags.reshape(-1))
+        for slot in np.nonzero(m_fetch.reshape(-1) >= 0)[0]:
+            blk = full[m_fetch.reshape(-1)[slot]]  # [H][N][d] -> token-major rows [N][H*d]
+            want[fill * n_slots + slot, :, : H * d] = blk.transpose(1, 0, 2).reshape(N, H * d)
+        got = l2.cpu().numpy().view(np.uint16).reshape(2 * n_slots, N, H * d + pad)
+        assert np.array_equal(got, want), "strided L2 buffer differs from the model (padding must stay untouched)"
+    assert c.stats()["status"] == 0

@@ -63,6 +63,7 @@ extern "C" {
 #define KVC_ERR_POOL_FULL (-4)    /* reported by kvc_stats: at least one page did not fit */
 #define KVC_ERR_CORRUPT (-5)      /* reported by kvc_stats: bad descriptor, payload or index */
 #define KVC_ERR_UNSUPPORTED (-6)  /* geometry the kernels are not built for */
+#define KVC_ERR_TOO_LARGE (-7)    /* the call exceeds the library's static workspace */
 
 #define KVC_MODE_RAW 0
 #define KVC_MODE_INT8 1
@@ -220,6 +221,20 @@ int kvc_prefetch_layers_window(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_
                                const int32_t* d_l1_first_block, int32_t n_seq, int32_t k, int32_t n_layers,
                                int32_t layer_begin, int32_t layer_end, int64_t pool_blocks_per_layer, int32_t fill_half,
                                int32_t omega, int64_t* d_notify, void* d_work, uint64_t work_bytes, void* stream);
+
+/* kvc_prefetch_layers_window for callers that cannot allocate and have no workspace to pass: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation.  The window's queue lives in
+ * a static device array inside the library (about 260 KB per GPU, held from library load until the
+ * process ends), so one call covers at most 65,536 slots ((layer_end - layer_begin) * n_seq * k) and at
+ * most 1,024 layers; more returns KVC_ERR_TOO_LARGE and enqueues nothing.  The call itself allocates and
+ * frees nothing and only launches kernels (the array is cleared by them, not by a memset).  Results are
+ * those of kvc_prefetch_layers_window.  Every call on one GPU, from any context, shares the one array:
+ * calls that overlap in time on a GPU (different streams, or different contexts) race on it; order them. */
+int kvc_prefetch_layers_window_static(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fetch, int32_t* d_loc,
+                                      const int32_t* d_block_table, int32_t max_blocks, const int32_t* d_pred,
+                                      const int32_t* d_l1_first_block, int32_t n_seq, int32_t k, int32_t n_layers,
+                                      int32_t layer_begin, int32_t layer_end, int64_t pool_blocks_per_layer,
+                                      int32_t fill_half, int32_t omega, int64_t* d_notify, void* stream);
 
 /* Reduce the descriptor table and read the device state.  The only call that synchronises
  * (on `stream`).  Returns KVC_ERR_POOL_FULL / KVC_ERR_CORRUPT if the matching status bit is set

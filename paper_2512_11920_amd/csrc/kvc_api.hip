@@ -4,8 +4,18 @@
 
 #include "kvc_common.h"
 
+// Workspace of kvc_prefetch_layers_window_static: device memory that exists from the moment the library
+// is loaded, one copy per GPU, so that the call allocates nothing.  In host code the array's name is
+// only a handle for hipGetSymbolAddress; kvc_create asks once per context for the address on its device
+// and every later use goes through that pointer.
+static constexpr int64_t kStaticWindowBlocks = 65536;  // slots one static-workspace call may cover
+static constexpr int32_t kStaticWindowLayers = 1024;   // layers one static-workspace call may cover
+static constexpr uint64_t kStaticWindowBytes = 256 + (uint64_t)kStaticWindowLayers * 4 + (uint64_t)kStaticWindowBlocks * 4;
+static __device__ __align__(256) unsigned char scratch[kStaticWindowBytes];
+
 struct kvc_ctx {
     int prefetch_policy = 0;
+    void* static_work = nullptr;  // device address of `scratch` on this context's device
     kvc_config cfg;
     kvc::Geometry g;
     int device;
@@ -88,7 +98,8 @@ int kvc_create(kvc_ctx** out, const kvc_config* cfg) {
         delete c;
         return KVC_ERR_HIP;
     }
-    if (!hip_ok(hipMemset(c->st, 0, sizeof(kvc::DevState)))) {
+    if (!hip_ok(hipMemset(c->st, 0, sizeof(kvc::DevState))) ||
+        !hip_ok(hipGetSymbolAddress(&c->static_work, HIP_SYMBOL(scratch))) || !c->static_work) {
         (void)hipFree(c->st);
         delete c;
         return KVC_ERR_HIP;
@@ -383,6 +394,22 @@ int kvc_prefetch_layers_window(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_
                          reinterpret_cast<long long*>(d_notify), d_work, work_bytes, stream);
 }
 
+int kvc_prefetch_layers_window_static(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fetch, int32_t* d_loc,
+                                      const int32_t* d_block_table, int32_t max_blocks, const int32_t* d_pred,
+                                      const int32_t* d_l1_first_block, int32_t n_seq, int32_t k, int32_t n_layers,
+                                      int32_t layer_begin, int32_t layer_end, int64_t pool_blocks_per_layer,
+                                      int32_t fill_half, int32_t omega, int64_t* d_notify, void* stream) {
+    if (!ctx || omega < 1 || layer_begin < 0 || layer_end < layer_begin || n_seq < 0 || k < 0 || k > kvc::kMaxPrefetchK)
+        return KVC_ERR_ARG;
+    if (layer_end - layer_begin > kStaticWindowLayers || (int64_t)(layer_end - layer_begin) * n_seq * k > kStaticWindowBlocks)
+        return KVC_ERR_TOO_LARGE;
+    static_assert(kStaticWindowBytes >= 256 + ((uint64_t)kStaticWindowLayers * 4 + 255) / 256 * 256 + (uint64_t)kStaticWindowBlocks * 4,
+                  "the static array holds the largest admitted call");
+    return prefetch_impl(ctx, d_l2, d_tags, d_fetch, d_loc, d_block_table, max_blocks, d_pred, d_l1_first_block, n_seq, k,
+                         n_layers, layer_begin, layer_end, pool_blocks_per_layer, fill_half, omega,
+                         reinterpret_cast<long long*>(d_notify), ctx->static_work, kStaticWindowBytes, stream);
+}
+
 int kvc_stats(kvc_ctx* ctx, kvc_stats_t* out, void* stream) {
     if (!ctx || !out) return KVC_ERR_ARG;
     if (!ctx->pool) return KVC_ERR_NOT_BOUND;
@@ -425,6 +452,7 @@ const char* kvc_strerror(int code) {
         case KVC_ERR_HIP: return t_last_hip != hipSuccess ? hipGetErrorString(t_last_hip) : "HIP runtime error";
         case KVC_ERR_POOL_FULL: return "compressed pool exhausted; some pages were not stored";
         case KVC_ERR_CORRUPT: return "invalid descriptor, payload or block index met on the device";
+        case KVC_ERR_TOO_LARGE: return "call exceeds the library's static workspace (at most 65536 slots and 1024 layers per call)";
         case KVC_ERR_UNSUPPORTED: return "page geometry not supported (head_dim a multiple of 32 up to 256, N*d <= 4096; mode 5: N = 16, d = 128 or 256)";
         default: return "unknown error";
     }

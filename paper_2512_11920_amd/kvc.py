@@ -13,7 +13,7 @@ import numpy as np
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libkvc.so")
 
-OK, ERR_ARG, ERR_NOT_BOUND, ERR_HIP, ERR_POOL_FULL, ERR_CORRUPT, ERR_UNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
+OK, ERR_ARG, ERR_NOT_BOUND, ERR_HIP, ERR_POOL_FULL, ERR_CORRUPT, ERR_UNSUPPORTED, ERR_TOO_LARGE = 0, -1, -2, -3, -4, -5, -6, -7
 MODE_RAW, MODE_INT8, MODE_DELTA, MODE_RLE, MODE_PACK, MODE_CHAN, MODE_INVALID = 0, 1, 2, 3, 4, 5, 0xFF
 ST_POOL_FULL, ST_CORRUPT, ST_BAD_INDEX = 1, 2, 4
 
@@ -22,7 +22,7 @@ DESC_DTYPE = np.dtype([("off", "<u8"), ("scale", "<f4"), ("n16", "<u2"), ("mode"
 
 EXPORTS = ("kvc_create", "kvc_destroy", "kvc_set_scheme", "kvc_set_cache_layout", "kvc_bind_pool", "kvc_reset_pool", "kvc_compress_blocks",
            "kvc_compress_blocks_mixed", "kvc_decompress_blocks", "kvc_gather_decompress", "kvc_set_prefetch_policy", "kvc_prefetch_reset", "kvc_prefetch_layers", "kvc_prefetch_window_workspace",
-           "kvc_prefetch_layers_window", "kvc_stats", "kvc_page_scales",
+           "kvc_prefetch_layers_window", "kvc_prefetch_layers_window_static", "kvc_stats", "kvc_page_scales",
            "kvc_copy_bytes", "kvc_strerror")
 
 
@@ -91,6 +91,9 @@ def load():
     L.kvc_prefetch_layers_window.restype = C.c_int
     L.kvc_prefetch_layers_window.argtypes = [vp, vp, vp, vp, vp, i32p, C.c_int32, i32p, i32p, C.c_int32, C.c_int32, C.c_int32,
                                              C.c_int32, C.c_int32, C.c_int64, C.c_int32, C.c_int32, vp, vp, C.c_uint64, vp]
+    L.kvc_prefetch_layers_window_static.restype = C.c_int
+    L.kvc_prefetch_layers_window_static.argtypes = [vp, vp, vp, vp, vp, i32p, C.c_int32, i32p, i32p, C.c_int32, C.c_int32, C.c_int32,
+                                                    C.c_int32, C.c_int32, C.c_int64, C.c_int32, C.c_int32, vp, vp]
     L.kvc_stats.restype = C.c_int
     L.kvc_stats.argtypes = [vp, C.POINTER(Stats), vp]
     L.kvc_page_scales.restype = C.c_int
@@ -276,7 +279,8 @@ class Codec:
                                fill_half: int, omega: int, notify, work, layer_begin: int = 0, layer_end: int | None = None,
                                l1_first=None, stream=None):
         """prefetch_layers through the outstanding-request window: at most `omega` blocks in flight.
-        notify: int64 CUDA tensor [n_layers + 4]; work: uint8 CUDA tensor of window_workspace(...) bytes."""
+        notify: int64 CUDA tensor [n_layers + 4]; work: uint8 CUDA tensor of window_workspace(...) bytes, or
+        None for the library's static workspace (kvc_prefetch_layers_window_static)."""
         import torch
 
         block_table, pred = _ids(block_table), _ids(pred)
@@ -287,8 +291,14 @@ class Codec:
         assert _ids(tags).numel() == 2 * n_slots and _ids(fetch).numel() == n_slots and _ids(loc).numel() == n_slots
         assert pred.shape[0] == n_seq and (l1_first is None or l1_first.numel() == n_seq)
         assert notify.is_cuda and notify.dtype == torch.int64 and notify.numel() >= n_layers + 4 and notify.is_contiguous()
-        assert work.is_cuda and work.dtype == torch.uint8 and work.is_contiguous()
+        assert work is None or (work.is_cuda and work.dtype == torch.uint8 and work.is_contiguous())
         layer_end = n_layers if layer_end is None else layer_end
+        if work is None:  # the library's static workspace: the call that allocates nothing
+            _check(self._L.kvc_prefetch_layers_window_static(
+                self._ctx, l2.data_ptr(), tags.data_ptr(), fetch.data_ptr(), loc.data_ptr(), block_table.data_ptr(), max_blocks,
+                pred.data_ptr(), _ptr(_ids(l1_first)), n_seq, k, n_layers, layer_begin, layer_end, int(pool_blocks_per_layer),
+                fill_half, int(omega), notify.data_ptr(), _stream(stream)), "kvc_prefetch_layers_window_static")
+            return
         _check(self._L.kvc_prefetch_layers_window(self._ctx, l2.data_ptr(), tags.data_ptr(), fetch.data_ptr(), loc.data_ptr(),
                                                   block_table.data_ptr(), max_blocks, pred.data_ptr(), _ptr(_ids(l1_first)),
                                                   n_seq, k, n_layers, layer_begin, layer_end, int(pool_blocks_per_layer),

@@ -10,6 +10,8 @@ algorithmic bytes (read + written, measured from the descriptors) over that dura
 8 TB/s HBM3E peak.  The CPU oracle is timed on a bounded sample of the same bytes as a baseline.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 70b_gqa|7b_full|7b_layer|tiny|decode_gather]
+    python bench.py --workload geometry --tokens-per-block N --head-dim d    (a 2 GB slice of another page shape)
+    python bench.py --workload prefetch_pipeline | prefetch_window | host_pool ;  python bench.py --ablation
 """
 from __future__ import annotations
 
@@ -29,17 +31,41 @@ def log(msg):
     print(msg, file=sys.stderr, flush=True)
 
 
-def read_traffic(workload: str, kernel: str):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if one covers this kernel
-    and workload (profiles/hbm_traffic_<workload>.txt, lines `<kernel>_traffic_bytes: <int>`).  The
-    summaries were taken with Algorithm 2's full scheme on the whole workload: callers ask only then."""
-    p = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+def kernel_fingerprint() -> str:
+    """Identifies the kernel sources a measurement belongs to: SHA-256 over the files of csrc/ and the
+    public header (names and contents), first 16 hex digits.  The profile summaries carry the value they
+    were taken on."""
+    import hashlib
+
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2512_11920_amd", "csrc")
+    for path in sorted(os.path.join(csrc, f) for f in os.listdir(csrc)) + [os.path.join(ROOT, "include", "kvc.h")]:
+        h.update(os.path.basename(path).encode() + b"\0")
+        h.update(open(path, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def read_traffic(tag: str, kernel: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload, if there is one
+    (profiles/hbm_traffic_<tag>.txt, lines `<kernel>_traffic_bytes: <int>` and `kernel_fingerprint: <hex>`).
+    -> (bytes or None, where the number comes from).  A summary taken on other kernel sources than the
+    ones in the tree is not used: the number is then None and the source says why."""
+    rel = os.path.join("profiles", f"hbm_traffic_{tag}.txt")
+    p = os.path.join(ROOT, rel)
     if not os.path.exists(p):
-        return None
+        return None, {"file": None, "note": "no rocprofv3 --pmc summary is committed for this workload"}
+    val, fp = None, None
     for line in open(p):
         if line.startswith(f"{kernel}_traffic_bytes:"):
-            return int(float(line.split(":")[1].split()[0]))
-    return None
+            val = int(float(line.split(":")[1].split()[0]))
+        if line.startswith("kernel_fingerprint:"):
+            fp = line.split(":")[1].strip()
+    now = kernel_fingerprint()
+    src = {"file": rel, "profile_kernel_fingerprint": fp, "current_kernel_fingerprint": now}
+    if fp != now:
+        src["note"] = "summary was taken on other kernel sources: not used"
+        return None, src
+    return val, src
 
 
 def sample_check(codec, cache_blocks, out_blocks, n_sample, N, d, ppb, scheme):
@@ -80,7 +106,7 @@ def cpu_baseline(sample_u16, N, d, scheme, target_s=12.0):
     (bytes through compress + bytes through decompress) / elapsed."""
     from oracle import kvc_oracle as o
 
-    cores = max(1, min(16, os.cpu_count() or 1))
+    cores = max(1, min(16, os.cpu_count() or 1))  # threads the oracle runs on
     n_pages = sample_u16.shape[0]
     done_bytes, t_total, reps = 0, 0.0, 0
     while t_total < target_s and reps < 16:
@@ -96,7 +122,7 @@ def cpu_baseline(sample_u16, N, d, scheme, target_s=12.0):
     od, op = o.compress_pages(one, N, d, scheme, n_threads=1)
     o.decompress_pages(op, od, N, d, n_threads=1)
     t_one = time.perf_counter() - t0
-    return {"value": round(done_bytes / t_total / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
+    return {"value": round(done_bytes / t_total / 1e9, 4), "unit": "GB/s", "cores": cores, "host_cpus": os.cpu_count(), "kind": "oracle",
             "sample": f"{n_pages} pages ({sample_u16.nbytes / 2**20:.0f} MiB of the same seeded cache), "
                       f"compress+decompress x{reps}, {t_total:.1f} s",
             "single_thread_value": round(2 * one.nbytes / t_one / 1e9, 4)}
@@ -110,6 +136,8 @@ def main():
     ap.add_argument("--workload", default="70b_gqa")
     ap.add_argument("--scheme", type=int, default=3)
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (quick runs; not the headline)")
+    ap.add_argument("--tokens-per-block", type=int, default=16, help="workload geometry: tokens per page (N)")
+    ap.add_argument("--head-dim", type=int, default=128, help="workload geometry: channels per token (d)")
     ap.add_argument("--prefetch-policy", type=int, default=1, help="prefetch_pipeline: 0 positional slots, 1 slot reuse")
     ap.add_argument("--ablation", action="store_true", help="ratio and speed per scheme (Table 9 analogue)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -137,7 +165,14 @@ def main():
         return bench_prefetch_pipeline(args)
     if args.workload == "host_pool":
         return bench_host_pool(args)
-    shape = synth.CONFIGS[args.workload]
+    if args.workload == "prefetch_window":
+        return bench_prefetch_window(args)
+    if args.workload == "geometry":
+        # a slice of about 2 GB with the 70B config's layout (8 KV heads, 4096-token sequences) and another page shape
+        gN, gd = args.tokens_per_block, args.head_dim
+        shape = synth.KVShape(f"geometry_{gN}x{gd}", 8, 8, gd, 4096, max(1, round(16 * 128 / gd)), tokens_per_block=gN)
+    else:
+        shape = synth.CONFIGS[args.workload]
     if args.layers:
         import dataclasses
 
@@ -238,6 +273,8 @@ def main():
 
     dom = "compress" if t_c >= t_d else "decompress"
     kname = {"compress": "k_compress_p16", "decompress": "k_decompress_p16"}[dom]
+    tag = shape.name + (f"_scheme{args.scheme}" if args.scheme != 3 else "")
+    traffic, traffic_source = (None, {"file": None, "note": "layer count overridden"}) if args.layers else read_traffic(tag, kname)
     res = {
         "metric": "KV codec GB/s (uncompressed fp16) compress+decompress; % of HBM peak",
         "value": round((2 * unc + g_unc) / (ms_step * 1e-3) / 1e9, 2),
@@ -257,8 +294,9 @@ def main():
                    "gather": f"{rows} rows x {k} predicted blocks x {shape.n_layers} layers = {g_pages} pages"},
         "roofline": {"bound": "hbm", "kernel": kname, "achieved": round(kern[dom]["hbm_GBps"], 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(kern[dom]["frac_of_peak"], 4),
-                     "traffic": read_traffic(shape.name, kname) if args.scheme == 3 and not args.layers else None, "alg_bytes_per_launch": int(kern[dom]["alg_bytes"]),
+                     "traffic": traffic, "traffic_source": traffic_source, "alg_bytes_per_launch": int(kern[dom]["alg_bytes"]),
                      "launch_ms": round(kern[dom]["ms"], 4)},
+        "kernel_fingerprint": kernel_fingerprint(),
         "kernels": {k_: {a: (round(b, 4) if isinstance(b, float) else b) for a, b in v.items()} for k_, v in kern.items()},
         "copy_kernel_GBps": round(copy_gbps, 1),
         "sample_parity_vs_oracle": check_ok,
@@ -320,6 +358,7 @@ def bench_decode_gather(args):
     mean_payload = st["payload_bytes"] / sum(st["pages"])
     alg = unc + n_pages * (mean_payload + 16) + 8 * n_out
     ms = (t1 - t0) * 1e3 / args.steps
+    dg_traffic, dg_source = read_traffic("decode_gather" + (f"_scheme{args.scheme}" if args.scheme != 3 else ""), "k_decompress_p16")
     res = {
         "metric": "KV codec GB/s (uncompressed fp16) gather-decompress; % of HBM peak",
         "value": round(unc / (ms * 1e-3) / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
@@ -330,8 +369,9 @@ def bench_decode_gather(args):
                    "ratio": round(codec.ratio(), 4)},
         "roofline": {"bound": "hbm", "kernel": "k_decompress_p16", "achieved": round(alg / ts.mean() / 1e6, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(alg / ts.mean() / 1e6 / HBM_PEAK_GBS, 4),
-                     "traffic": read_traffic("decode_gather", "k_decompress_p16") if args.scheme == 3 and not args.layers else None, "alg_bytes_per_launch": int(alg),
+                     "traffic": dg_traffic, "traffic_source": dg_source, "alg_bytes_per_launch": int(alg),
                      "launch_ms": round(float(ts.mean()), 4)},
+        "kernel_fingerprint": kernel_fingerprint(),
         "step_ms": {"mean": round(float(ts.mean()), 4), "p50": round(float(np.percentile(ts, 50)), 4),
                     "p99": round(float(np.percentile(ts, 99)), 4)},
     }
@@ -486,6 +526,122 @@ def bench_prefetch_pipeline(args):
                                              f"U[512,8192], k=8, slot policy {args.prefetch_policy}, per-layer prefetch two layers ahead of the layer's compute "
                                              f"stand-in ({work_bytes >> 20} MiB copy, or 4096^3 bf16 GEMM)"},
                       "patterns": out}), flush=True)
+
+
+def bench_prefetch_window(args):
+    """Algorithm 1's outstanding-request window on the 70B decode shape (80 layers, 64 sequences, k = 8): one
+    kvc_prefetch_layers_window call per decode step for all layers, with at most omega transfers in flight,
+    against the unbounded kvc_prefetch_layers.  Per omega: time of the call alone, when the first layer and
+    when all layers were ready (the call's own ready stamps), and the step time when the call runs beside
+    a stand-in for the step's compute (80 x 256 MiB copies, HBM-bound) on another stream."""
+    import numpy as np
+    import torch
+
+    from paper_2512_11920_amd import kvc, synth
+
+    dev = "cuda:0"
+    n_layers = args.layers or 80
+    shape = synth.KVShape("prefetch_window", n_layers, 8, 128, 0, 0)
+    N, d, H = 16, 128, 8
+    ppb, E = 2 * H, N * d
+    pat = synth.gather_pattern(64, 8, 512, 8192, N, seed=0)
+    pbl, n_seq, k = pat.pool_blocks_per_layer, pat.n_seq, pat.k
+    codec = kvc.Codec(N, d, ppb, args.scheme)
+    codec.alloc_pool(n_layers * pbl, n_layers * pbl * ppb * E + 4096, dev)
+    ids = torch.arange(pbl, dtype=torch.int32, device=dev)
+    for l in range(n_layers):
+        codec.compress_blocks(synth.gather_layer_torch(shape, pat, l, dev).view(-1, ppb, N, d), pool_ids=ids + l * pbl)
+    n_slots = n_layers * n_seq * k
+    codec.set_prefetch_policy(args.prefetch_policy)
+    l2 = torch.zeros((2 * n_slots, ppb, N, d), dtype=torch.float16, device=dev)
+    tags = torch.empty(2 * n_slots, dtype=torch.int32, device=dev)
+    fetch = torch.empty(n_slots, dtype=torch.int32, device=dev)
+    loc = torch.empty(n_slots, dtype=torch.int32, device=dev)
+    notify = torch.zeros(n_layers + 4, dtype=torch.int64, device=dev)
+    work = torch.empty(kvc.window_workspace(n_slots, n_layers), dtype=torch.uint8, device=dev)
+    table = torch.from_numpy(pat.block_table).to(dev)
+    khz = kvc.wall_clock_khz()
+    steps = args.steps + args.warmup
+    wa = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+    wb = torch.empty_like(wa)
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+
+    def preds(pattern, t):
+        if pattern == "uniform":
+            return pat.predictions(t)
+        pos = (t // N + np.arange(n_seq) * 7) % pat.n_blocks
+        return ((pos[:, None] + 1 + np.arange(k)[None, :]) % pat.n_blocks[:, None]).astype(np.int32)
+
+    def prefetch(omega, fill, pred_t, st):
+        if omega:
+            codec.prefetch_layers_window(l2, tags, fetch, loc, table, pred_t, n_layers, pbl, fill, omega, notify, work, stream=st)
+        else:
+            codec.prefetch_layers(l2, tags, fetch, loc, table, pred_t, n_layers, pbl, fill, stream=st)
+
+    # the compute stand-in alone
+    for _ in range(3):
+        for l in range(n_layers):
+            kvc.copy_bytes(wb, wa)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        for l in range(n_layers):
+            kvc.copy_bytes(wb, wa)
+    torch.cuda.synchronize()
+    compute_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    out = {"compute_only_ms": round(compute_ms, 4)}
+    for pattern in ("uniform", "sliding"):
+        pr = [torch.from_numpy(preds(pattern, t)).to(dev) for t in range(steps)]
+        rows = []
+        for omega in (16, 64, 256, 1024, 4096, 0):
+            row = {"omega": omega or "unbounded"}
+            # (1) the call alone
+            codec.prefetch_reset(tags, n_seq, k, n_layers)
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            t_call, first, half, allr, high, issued = [], [], [], [], [], []
+            for t in range(steps):
+                ev[0].record()
+                prefetch(omega, t % 2, pr[t], main)
+                ev[1].record()
+                torch.cuda.synchronize()
+                if t >= args.warmup:
+                    t_call.append(ev[0].elapsed_time(ev[1]))
+                    if omega:
+                        nt = notify.cpu().numpy()
+                        opened = nt[n_layers]
+                        first.append((nt[0] - opened) / khz * 1e3)
+                        half.append((nt[n_layers // 2] - opened) / khz * 1e3)
+                        allr.append((nt[n_layers + 3] - opened) / khz * 1e3)
+                        issued.append(int(nt[n_layers + 1]))
+                        high.append(int(nt[n_layers + 2]))
+            row["call_ms"] = round(float(np.mean(t_call)), 4)
+            if omega:
+                row.update({"first_layer_ready_us": round(float(np.mean(first)), 1), "half_layers_ready_us": round(float(np.mean(half)), 1),
+                            "all_ready_us": round(float(np.mean(allr)), 1), "blocks_issued": round(float(np.mean(issued)), 1),
+                            "max_in_flight": int(max(high))})
+            # (2) beside the step's compute on another stream
+            codec.prefetch_reset(tags, n_seq, k, n_layers)
+            torch.cuda.synchronize()
+            for t in range(steps):
+                if t == args.warmup:
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                side.wait_stream(main)
+                prefetch(omega, t % 2, pr[t], side)
+                for l in range(n_layers):
+                    kvc.copy_bytes(wb, wa, stream=main)
+                main.wait_stream(side)
+            torch.cuda.synchronize()
+            row["step_ms_beside_compute"] = round((time.perf_counter() - t0) * 1e3 / args.steps, 4)
+            rows.append(row)
+            log(f"[window] {pattern}: {row}")
+        out[pattern] = rows
+    assert codec.stats()["status"] == 0
+    print(json.dumps({"metric": "prefetch step under an outstanding-request window (ms, us)", "n_gpus": 1, "steps": args.steps,
+                      "warmup": args.warmup, "data": "synthetic", "higher_is_better": False,
+                      "config": {"workload": f"prefetch_window: {n_layers} layers x 8 KV heads x 128, 64 sequences U[512,8192], k=8, "
+                                             f"slot policy {args.prefetch_policy}; compute stand-in {n_layers} x 256 MiB copies"},
+                      "wall_clock_khz": khz, "window": out}), flush=True)
 
 
 def bench_host_pool(args):

@@ -216,6 +216,8 @@ int kvc_prefetch_layers(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fe
  *             overlap in time need workspaces and notify arrays of their own.
  * A call over no slots (layer_begin = layer_end, n_seq = 0 or k = 0) does nothing. */
 uint64_t kvc_prefetch_window_workspace(int64_t n_blocks, int32_t n_layers_call);
+/* Rate of the clock the d_notify stamps count, in kHz, on the current device (KVC_ERR_HIP if the query fails). */
+int kvc_wall_clock_khz(int32_t* khz);
 int kvc_prefetch_layers_window(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fetch, int32_t* d_loc,
                                const int32_t* d_block_table, int32_t max_blocks, const int32_t* d_pred,
                                const int32_t* d_l1_first_block, int32_t n_seq, int32_t k, int32_t n_layers,

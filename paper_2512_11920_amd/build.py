@@ -1,22 +1,32 @@
-"""Build libkvc.so (HIP, gfx950) in-tree with hipcc.  No GPU is needed to compile."""
+"""Build libkvc.so (HIP, gfx950) in-tree with hipcc.  No GPU is needed to compile.
+
+The specialised kernels (csrc/kvc_fast.hip) are compiled once per group of page shapes
+(-DKVC_FAST_GROUP=k), side by side with the other sources; the objects are then linked."""
 from __future__ import annotations
 
+import concurrent.futures
 import os
 import subprocess
 import sys
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
-SOURCES = [os.path.join(_PKG, "csrc", f) for f in ("kvc_kernels.hip", "kvc_page16.hip", "kvc_api.hip")]
-HEADERS = [os.path.join(_PKG, "csrc", "kvc_common.h"), os.path.join(_PKG, "csrc", "kvc_device.h"),
-           os.path.join(_ROOT, "include", "kvc.h")]
+_CSRC = os.path.join(_PKG, "csrc")
+FAST_GROUPS = 8  # see csrc/kvc_fast.hip
+#: (source, extra defines, object name)
+UNITS = [("kvc_kernels.hip", (), "kvc_kernels.o"), ("kvc_api.hip", (), "kvc_api.o")] + \
+        [("kvc_fast.hip", (f"-DKVC_FAST_GROUP={g}",), f"kvc_fast_{g}.o") for g in range(FAST_GROUPS)]
+SOURCES = [os.path.join(_CSRC, f) for f in ("kvc_kernels.hip", "kvc_fast.hip", "kvc_api.hip")]
+HEADERS = [os.path.join(_CSRC, f) for f in ("kvc_common.h", "kvc_device.h", "kvc_fast.h")] + [os.path.join(_ROOT, "include", "kvc.h")]
 LIB = os.path.join(_PKG, "libkvc.so")
+OBJ_DIR = os.path.join(_PKG, "_build")
 
 HIPCC_FLAGS = [
-    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",  # no packed-FP32 code generation
     "-Wall", "-Wno-unused-command-line-argument",
 ]
+INCLUDES = ["-I", os.path.join(_ROOT, "include"), "-I", _CSRC]
 
 
 def stale() -> bool:
@@ -26,16 +36,40 @@ def stale() -> bool:
     return any(os.path.getmtime(p) > t for p in SOURCES + HEADERS)
 
 
-def build(force: bool = True, verbose: bool = False, extra_flags=()) -> str:
+def _hipcc() -> str:
+    return os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+
+
+def compile_unit(source: str, defines=(), out: str | None = None, extra_flags=(), asm: bool = False, verbose: bool = False) -> str:
+    """Compile one source of csrc/ to an object (or, with asm=True, to the gfx950 assembly of its kernels)."""
+    mode = ["-S", "--cuda-device-only"] if asm else ["-c"]
+    cmd = [_hipcc(), *HIPCC_FLAGS, *extra_flags, *defines, *INCLUDES, *mode, "-o", out, os.path.join(_CSRC, source)]
+    if verbose:
+        print(" ".join(cmd), file=sys.stderr)
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed on {source} {' '.join(defines)}:\n{err}")
+    if err.strip():
+        print(err, file=sys.stderr)
+    return out
+
+
+def build(force: bool = True, verbose: bool = False, extra_flags=(), lib: str = LIB, jobs: int | None = None) -> str:
     if not force and not stale():
-        return LIB
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-I", os.path.join(_ROOT, "include"), "-I", os.path.join(_PKG, "csrc"),
-           "-o", LIB, *SOURCES]
+        return lib
+    obj_dir = OBJ_DIR if lib == LIB else lib + ".objs"
+    os.makedirs(obj_dir, exist_ok=True)
+    jobs = jobs or max(1, min(len(UNITS), os.cpu_count() or 1, 16))
+    with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as ex:
+        futs = [ex.submit(compile_unit, src, defs, os.path.join(obj_dir, obj), tuple(extra_flags), False, verbose)
+                for src, defs, obj in UNITS]
+        objs = [f.result() for f in futs]
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-Wno-unused-command-line-argument", "-o", lib, *objs]
     if verbose:
         print(" ".join(cmd), file=sys.stderr)
     subprocess.run(cmd, check=True)
-    return LIB
+    return lib
 
 
 CLIENT_SRC = os.path.join(_ROOT, "tests", "abi_client.cpp")
@@ -44,8 +78,7 @@ CLIENT_BIN = os.path.join(_ROOT, "tests", "abi_client")
 
 def build_client(verbose: bool = False) -> str:
     """Compile the stand-alone C-ABI client (HIP runtime + kvc.h only) against the built library."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "-O2", "-std=c++17", "-Wall", "-Wno-unused-command-line-argument", "-I", os.path.join(_ROOT, "include"),
+    cmd = [_hipcc(), "-O2", "-std=c++17", "-Wall", "-Wno-unused-command-line-argument", "-I", os.path.join(_ROOT, "include"),
            "-o", CLIENT_BIN, CLIENT_SRC, "-L", _PKG, "-lkvc", "-Wl,-rpath," + _PKG, "-Wl,-rpath,$ORIGIN/../paper_2512_11920_amd"]
     if verbose:
         print(" ".join(cmd), file=sys.stderr)

@@ -383,6 +383,14 @@ uint64_t kvc_prefetch_window_workspace(int64_t n_blocks, int32_t n_layers_call) 
     return kvc::window_workspace_bytes(n_blocks, n_layers_call);
 }
 
+int kvc_wall_clock_khz(int32_t* khz) {
+    if (!khz) return KVC_ERR_ARG;
+    int dev = -1, v = 0;
+    if (!hip_ok(hipGetDevice(&dev)) || !hip_ok(hipDeviceGetAttribute(&v, hipDeviceAttributeWallClockRate, dev))) return KVC_ERR_HIP;
+    *khz = v;
+    return KVC_OK;
+}
+
 int kvc_prefetch_layers_window(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fetch, int32_t* d_loc,
                                const int32_t* d_block_table, int32_t max_blocks, const int32_t* d_pred,
                                const int32_t* d_l1_first_block, int32_t n_seq, int32_t k, int32_t n_layers,

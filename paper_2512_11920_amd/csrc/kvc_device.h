@@ -433,9 +433,24 @@ __device__ __forceinline__ int32_t window_next(const WindowArgs& w, int32_t* s_s
     return __builtin_amdgcn_readfirstlane(*s_slot);
 }
 
-// kernels specialised for 16-token pages with 64, 128 or 256 channels
-hipError_t launch_compress_p16(const EncodeArgs& a, hipStream_t s);
-hipError_t launch_decompress_p16(const DecodeArgs& a, hipStream_t s);
-hipError_t launch_decompress_window_p16(const DecodeArgs& a, const WindowArgs& w, unsigned grid, hipStream_t s);
+// Kernels specialised at compile time for one page shape (kvc_fast.h): the host-side entry points of a
+// geometry.  fast_kernels() returns the set for N tokens x d channels, or nullptr when that shape runs on
+// the generic kernels.  The shapes are compiled in groups (kvc_fast.hip), one lookup function per group.
+struct FastKernels {
+    int N, d;
+    hipError_t (*compress)(const EncodeArgs& a, hipStream_t s);
+    hipError_t (*decompress)(const DecodeArgs& a, hipStream_t s);
+    hipError_t (*decompress_window)(const DecodeArgs& a, const WindowArgs& w, unsigned grid, hipStream_t s);
+};
+constexpr int kFastGroups = 8;
+const FastKernels* fast_kernels_group0(int N, int d);
+const FastKernels* fast_kernels_group1(int N, int d);
+const FastKernels* fast_kernels_group2(int N, int d);
+const FastKernels* fast_kernels_group3(int N, int d);
+const FastKernels* fast_kernels_group4(int N, int d);
+const FastKernels* fast_kernels_group5(int N, int d);
+const FastKernels* fast_kernels_group6(int N, int d);
+const FastKernels* fast_kernels_group7(int N, int d);
+const FastKernels* fast_kernels(int N, int d);
 
 }  // namespace kvc

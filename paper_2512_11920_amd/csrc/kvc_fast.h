@@ -1,15 +1,19 @@
-// Kernels specialised for 16-token pages with 64, 128 or 256 channels; 16 x 128 FP16 is the paper's
-// 4 KB page and the shape the tuning was done on.
+// Kernels specialised at compile time for pages that are a whole number of 512-element passes: D channels
+// (any multiple of 32 up to 256) by N = NP * 512 / D tokens, NP = 1..8 passes.  16 x 128 FP16 (D = 128,
+// NP = 4) is the paper's 4 KB page and the shape the tuning was done on.  This file holds the templates;
+// kvc_fast.hip instantiates them for the geometries listed in kvc_device.h.
 //
 // Same lane mapping as the generic kernels -- one wave per page, passes of 512 elements, a lane owns
 // 8 consecutive channels, a packet group is a quad of lanes, a token row is D/8 neighbouring lanes
 // (one 16-lane DPP row at D = 128) -- but every cross-lane step is a DPP operation, the per-group
 // statistics (max, width, run test) and the offset scans are done on quads, and no lane is ever
-// inactive.  Written plainly the codec is bound by vector-ALU issue long before HBM bandwidth; the
+// inactive.  When D does not divide 512 (96, 160, 192, 224) a token row may begin in one pass and end in
+// the next: the delta step and its inverse then carry one value from pass to pass.  Written plainly the codec is bound by vector-ALU issue long before HBM bandwidth; the
 // instruction count per element is kept low enough here that the memory system is the limit.
 //
 // Encode: Algorithm 2 of the paper (scaling, quantize, delta, run-length encode).
 // Decode: Section 3.5.3 (undo run-length coding, prefix sum, dequantize; bypass for raw pages).
+#pragma once
 #include "kvc_device.h"
 
 namespace kvc {
@@ -50,16 +54,49 @@ __device__ __forceinline__ void store_stream(uint4* p, const uint4& v) {
 #endif
 }
 
-// Compile-time shape of a 16-token page with D channels.
-template <int D>
+// Compile-time shape of a page of NP passes with D channels per token.
+template <int D, int NP>
 struct Page {
-    static constexpr int kE = 16 * D;       // elements
-    static constexpr int kPasses = D / 32;  // passes of 512 elements
-    static constexpr int kGroups = D / 2;   // packet groups of 32
-    static constexpr int kHdr = D / 4;      // header bytes, 4 bits per group
-    static constexpr int kLpr = D / 8;      // lanes per token row
-    static constexpr int kRowsPerPass = 512 / D;
+    static_assert(D % 32 == 0 && D >= 32 && D <= 256 && NP >= 1 && NP <= 8 && (NP * 512) % D == 0, "page shape");
+    static constexpr int kD = D;
+    static constexpr int kE = NP * 512;       // elements
+    static constexpr int kN = kE / D;         // tokens
+    static constexpr int kPasses = NP;        // passes of 512 elements
+    static constexpr int kGroups = NP * 16;   // packet groups of 32
+    static constexpr int kHdr = NP * 8;       // header bytes, 4 bits per group
+    static constexpr int kLpr = D / 8;        // lanes per token row
+    static constexpr bool kAligned = 512 % D == 0;  // a token row never continues into the next pass
+    static constexpr int kRowsPerPass = 512 / D;    // (whole rows; exact when kAligned)
+    static constexpr int kRounds = (NP + 1) / 2;    // rounds of 64 lanes x 16 bytes that cover a payload (< kE bytes)
+    static constexpr bool kChan = kN == 16 && (D == 128 || D == 256);  // mode 5 is built for these pages
 };
+
+// Where a lane sits in pass 0: token row and position inside the row, both in lanes of 8 channels, and
+// the byte offset of its 16 bytes inside the page (row-major deal, and the deal of mode 5).
+struct LanePos {
+    uint32_t row0, col0, off0, off0_chan;
+};
+template <class P>
+__device__ __forceinline__ LanePos lane_pos(const Geometry& g) {
+    const uint32_t lane = (uint32_t)lane_id();
+    LanePos lp;
+    lp.row0 = lane / P::kLpr;
+    lp.col0 = lane % P::kLpr;
+    lp.off0 = (lp.row0 * (uint32_t)g.row_stride + lp.col0 * 8u) * 2u;
+    lp.off0_chan = ((lane & 3u) * (uint32_t)g.row_stride + (lane >> 2) * 8u) * 2u;
+    return lp;
+}
+// ... and in pass p (p is a constant after unrolling): 64 * p lanes further on.
+template <class P>
+__device__ __forceinline__ uint32_t pass_col(const LanePos& lp, int p) {
+    const uint32_t c = lp.col0 + (uint32_t)((p * 64) % P::kLpr);
+    return (!P::kAligned && c >= (uint32_t)P::kLpr) ? c - P::kLpr : c;
+}
+template <class P>
+__device__ __forceinline__ uint32_t pass_row(const LanePos& lp, int p) {
+    const uint32_t wrap = (!P::kAligned && lp.col0 + (uint32_t)((p * 64) % P::kLpr) >= (uint32_t)P::kLpr) ? 1u : 0u;
+    return lp.row0 + (uint32_t)((p * 64) / P::kLpr) + wrap;
+}
 
 constexpr float kMagic = 12582912.0f;  // 1.5 * 2^23: adding it rounds to an integer, ties to even
 constexpr uint32_t kMagicBits = 0x4B400000u;
@@ -83,15 +120,16 @@ __device__ __forceinline__ void quantize8_bits(const uint4& raw, float s_inv, ui
 // Row-major (CHAN = false): piece number p*64 + lane in pass p.  Channel-pair mode 5 (CHAN = true,
 // D = 128 or 256): lane 4*l + r takes, in pass p, token 4*(p mod 4) + r of octet 16*(p div 4) + l, so
 // that the four lanes of a quad hold the 16 tokens of one octet over four passes.
-template <int D, bool CHAN>
+template <class P, bool CHAN>
 __device__ __forceinline__ int piece_index(int p, int lane) {  // position in row-major piece order
     if (!CHAN) return p * 64 + lane;
-    return (4 * (p & 3) + (lane & 3)) * (D / 8) + 16 * (p >> 2) + (lane >> 2);
+    return (4 * (p & 3) + (lane & 3)) * P::kLpr + 16 * (p >> 2) + (lane >> 2);
 }
 
 // plain INT8 payload: codes as bytes, row-major
-template <int D, bool CHAN, int NP>
-__device__ __forceinline__ void store_codes(const uint4 (&raw)[NP], float s_inv, uint32_t* stage) {
+template <class P, bool CHAN>
+__device__ __forceinline__ void store_codes(const uint4 (&raw)[P::kPasses], float s_inv, uint32_t* stage) {
+    constexpr int NP = P::kPasses;
     const int lane = lane_id();
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
@@ -100,7 +138,7 @@ __device__ __forceinline__ void store_codes(const uint4 (&raw)[NP], float s_inv,
         uint2 v;
         v.x = __builtin_amdgcn_perm(__builtin_amdgcn_perm(t[3], t[2], 0x0c0c0400u), __builtin_amdgcn_perm(t[1], t[0], 0x0c0c0400u), 0x05040100u);
         v.y = __builtin_amdgcn_perm(__builtin_amdgcn_perm(t[7], t[6], 0x0c0c0400u), __builtin_amdgcn_perm(t[5], t[4], 0x0c0c0400u), 0x05040100u);
-        reinterpret_cast<uint2*>(stage)[piece_index<D, CHAN>(p, lane)] = v;
+        reinterpret_cast<uint2*>(stage)[piece_index<P, CHAN>(p, lane)] = v;
     }
 }
 
@@ -112,38 +150,56 @@ __device__ __forceinline__ void fill_zigzag_lut(uint8_t* lut) {
     }
 }
 
-// t7 of the lane to the left within the token row; row starts receive `first`.
-template <int LPR>
-__device__ __forceinline__ uint32_t left_neighbour(uint32_t first, uint32_t v) {
-    if (LPR == 16) return dpp<0x111>(first, v);  // row_shr:1, lane 0 of a DPP row keeps `first`
-    if (LPR == 8) {
-        const uint32_t x = dpp<0x111>(first, v);
-        return (lane_id() & 7) == 0 ? first : x;
+// t7 of the lane to the left within the token row; row starts receive `first`.  `carry` is the value
+// of lane 63 in the pass before, for a row that continues across the pass boundary (!P::kAligned only).
+template <class P>
+__device__ __forceinline__ uint32_t left_neighbour(const LanePos& lp, int p, uint32_t first, uint32_t v, uint32_t carry) {
+    constexpr int LPR = P::kLpr;
+    if (P::kAligned) {
+        if (LPR == 16) return dpp<0x111>(first, v);  // row_shr:1, lane 0 of a DPP row keeps `first`
+        if (LPR < 16) {
+            const uint32_t x = dpp<0x111>(first, v);
+            return (lane_id() & (LPR - 1)) == 0 ? first : x;
+        }
+        const uint32_t x = dpp<0x138>(first, v);  // wave_shr:1 crosses the 16-lane rows
+        return (lane_id() & 31) == 0 ? first : x;
     }
-    const uint32_t x = dpp<0x138>(first, v);  // wave_shr:1 crosses the 16-lane rows
-    return (lane_id() & 31) == 0 ? first : x;
+    const uint32_t x = dpp<0x138>(carry, v);  // lane 0 has no source lane and keeps `carry`
+    return pass_col<P>(lp, p) == 0 ? first : x;
 }
 
-// inclusive prefix sum over the LPR lanes of a token row
-template <int LPR>
-__device__ __forceinline__ uint32_t row_incl_scan(uint32_t v) {
-    if (LPR == 16) return row16_incl_scan_dpp(v);
-    if (LPR == 32) {
-        v = row16_incl_scan_dpp(v);
-        return v + dpp<0x142, 0xA>(0, v);  // odd DPP rows add the total of the row before
+// Inclusive prefix sum over the lanes of a token row in pass p.  `carry` is the value this function
+// returned at lane 63 in the pass before, for a row that began there (!P::kAligned only).
+template <class P>
+__device__ __forceinline__ uint32_t row_incl_scan(const LanePos& lp, int p, uint32_t v, uint32_t carry) {
+    constexpr int LPR = P::kLpr;
+    if (P::kAligned) {
+        if (LPR == 16) return row16_incl_scan_dpp(v);
+        if (LPR == 32) {
+            v = row16_incl_scan_dpp(v);
+            return v + dpp<0x142, 0xA>(0, v);  // odd DPP rows add the total of the row before
+        }
+        const int r = lane_id() & (LPR - 1);
+        uint32_t t = dpp<0x111>(0, v);
+        v += r >= 1 ? t : 0u;
+        t = dpp<0x112>(0, v);
+        v += r >= 2 ? t : 0u;
+        if (LPR == 4) return v;
+        t = dpp<0x114>(0, v);
+        return v + (r >= 4 ? t : 0u);
     }
-    const int r = lane_id() & 7;
-    uint32_t t = dpp<0x111>(0, v);
-    v += r >= 1 ? t : 0u;
-    t = dpp<0x112>(0, v);
-    v += r >= 2 ? t : 0u;
-    t = dpp<0x114>(0, v);
-    return v + (r >= 4 ? t : 0u);
+    // rows of LPR lanes begin anywhere: prefix over the whole wave, minus its value just before the
+    // row's first lane; a row that began in the pass before adds what it had collected there
+    const uint32_t S = wave_incl_scan_dpp(v);
+    const int lane = lane_id();
+    const int start = lane - (int)pass_col<P>(lp, p);  // first lane of this lane's row (< 0: in the pass before)
+    const uint32_t before = (uint32_t)__builtin_amdgcn_ds_bpermute((start > 0 ? start - 1 : 0) << 2, (int)S);
+    return start > 0 ? S - before : (start < 0 ? S + carry : S);
 }
 
 // Second half of a pass: body offsets, header bits, packing, LDS write.  RUNS = some group of this
 // pass may be a run packet (is_run is then meaningful), else every group is literal or all-zero.
-template <int D, bool RUNS>
+template <class P, bool RUNS>
 __device__ __forceinline__ void encode_tail(const uint32_t (&u)[8], uint32_t c, uint32_t size, bool is_run, uint32_t qi,
                                             int p, uint32_t& run, uint32_t* stage, DevState* st) {
     (void)st;  // only the bounds-checking build reads it
@@ -165,7 +221,7 @@ __device__ __forceinline__ void encode_tail(const uint32_t (&u)[8], uint32_t c, 
         B = off;
     }
     uint32_t* p0 = stage + (B >> 2);
-    KVC_CHECK(st, c <= 9 && (B >> 2) + 2 < (uint32_t)Slot<Page<D>::kPasses>::kWords && B >= (uint32_t)Page<D>::kHdr);
+    KVC_CHECK(st, c <= 9 && (B >> 2) + 2 < (uint32_t)Slot<P::kPasses>::kWords && B >= (uint32_t)P::kHdr);
     uint32_t d0, d1, d2;
     shl_bytes(W, B, d0, d1, d2);
     atomicOr(p0, d0);
@@ -175,7 +231,7 @@ __device__ __forceinline__ void encode_tail(const uint32_t (&u)[8], uint32_t c, 
 
 // One packet group per quad of lanes: each lane brings 8 of its 32 values.  Group statistics over
 // the quad (max -> width, run test), then the tail.  p = index of the group's set of 16 (a pass).
-template <int D>
+template <class P>
 __device__ __forceinline__ void encode_groups(const uint32_t (&u)[8], bool RLE, uint32_t c_min, uint32_t qi, int p,
                                               uint32_t& run, uint32_t* stage, DevState* st) {
     // per-group statistics over the quad of lanes
@@ -202,51 +258,49 @@ __device__ __forceinline__ void encode_groups(const uint32_t (&u)[8], bool RLE, 
         y |= dpp<0xB1>(0, y);
         y |= dpp<0x4E>(0, y);
         const bool is_run = (y == 0) && (gmax != 0);
-        encode_tail<D, true>(u, is_run ? 9u : c, is_run ? 1u : size, is_run, qi, p, run, stage, st);
+        encode_tail<P, true>(u, is_run ? 9u : c, is_run ? 1u : size, is_run, qi, p, run, stage, st);
     } else {
-        encode_tail<D, false>(u, c, size, false, qi, p, run, stage, st);
+        encode_tail<P, false>(u, c, size, false, qi, p, run, stage, st);
     }
 }
 
-// Lane l of pass p holds token row p*(512/D) + l/(D/8), channels 8*(l%(D/8)) .. +7: with contiguous
-// rows this is one 1 KB run per pass, with strided rows 512/D runs of 2*D bytes.
-// The lane's byte offset inside a page is computed once per kernel and kept in 32 bits (the layout
-// setter bounds the row stride), so that page accesses are a wave-uniform 64-bit base plus that offset.
-template <int D>
-__device__ __forceinline__ uint32_t lane_byte_off(const Geometry& g) {
-    const uint32_t lane = (uint32_t)lane_id();
-    return ((lane / Page<D>::kLpr) * (uint32_t)g.row_stride + (lane % Page<D>::kLpr) * 8u) * 2u;
+// Byte offset, inside a page, of the 16 bytes a lane handles in pass p, as a wave-uniform part plus a
+// per-lane part that stays in 32 bits (the layout setter bounds the row stride): a page access is then a
+// wave-uniform 64-bit base plus a 32-bit lane offset.  Row-major deal: lane l of pass p holds token row
+// (64p + l) / (D/8), channels 8 * ((64p + l) mod (D/8)) .. +7; with contiguous rows a pass is one 1 KB
+// run.  When D divides 512 the lane part is the same in every pass.  Mode 5 (CHAN, see piece_index):
+// lane 4l + r takes token 4 (p mod 4) + r of octet 16 (p div 4) + l.
+template <class P, bool CHAN>
+__device__ __forceinline__ int64_t pass_base_off(const Geometry& g, int p) {
+    if (CHAN) return (int64_t)(p & 3) * 4 * g.row_stride * 2 + (p >> 2) * 256;
+    return (int64_t)((p * 64) / P::kLpr) * g.row_stride * 2;  // the whole rows before the pass
+}
+template <class P, bool CHAN>
+__device__ __forceinline__ uint32_t pass_lane_off(const Geometry& g, const LanePos& lp, int p) {
+    if (CHAN) return lp.off0_chan;
+    if (P::kAligned) return lp.off0;
+    const uint32_t c = lp.col0 + (uint32_t)((p * 64) % P::kLpr);  // the pass begins this far into a row
+    const bool wrap = c >= (uint32_t)P::kLpr;
+    return ((lp.row0 + (wrap ? 1u : 0u)) * (uint32_t)g.row_stride + (wrap ? c - P::kLpr : c) * 8u) * 2u;
 }
 
-// The same for the deal of mode 5 (see piece_index): the lane's offset in pass 0, and what pass p adds.
-__device__ __forceinline__ uint32_t lane_byte_off_chan(const Geometry& g) {
-    const uint32_t lane = (uint32_t)lane_id();
-    return ((lane & 3u) * (uint32_t)g.row_stride + (lane >> 2) * 8u) * 2u;
-}
-
-template <int D, bool CHAN>
-__device__ __forceinline__ int64_t pass_byte_off(const Geometry& g, int p) {
-    if (!CHAN) return (int64_t)p * Page<D>::kRowsPerPass * g.row_stride * 2;
-    return (int64_t)(p & 3) * 4 * g.row_stride * 2 + (p >> 2) * 256;
-}
-
-template <int D, bool CHAN>
-__device__ __forceinline__ void load_page(const EncodeArgs& a, const EncTask& task, uint32_t lane_off,
-                                          uint4 (&raw)[Page<D>::kPasses]) {
+template <class P, bool CHAN>
+__device__ __forceinline__ void load_page(const EncodeArgs& a, const EncTask& task, const LanePos& lp,
+                                          uint4 (&raw)[P::kPasses]) {
     const char* src = reinterpret_cast<const char*>(a.cache) + wave_uniform((int64_t)task.src_off * 2);
 #pragma unroll
-    for (int p = 0; p < Page<D>::kPasses; ++p)
-        raw[p] = load_stream(reinterpret_cast<const uint4*>(src + pass_byte_off<D, CHAN>(a.g, p) + lane_off));
+    for (int p = 0; p < P::kPasses; ++p)
+        raw[p] = load_stream(reinterpret_cast<const uint4*>(src + pass_base_off<P, CHAN>(a.g, p) + pass_lane_off<P, CHAN>(a.g, lp, p)));
 }
 
 // Encode one page (already in registers) into the LDS slot `stage`.  The requested mode is the
 // compile-time SCHEME when that is >= 0 (one mode for the whole launch: its branches fold away), else
 // the wave-uniform run-time value.
-template <int D, int SCHEME>
-__device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPasses], int scheme_rt, uint32_t* stage,
+template <class P, int SCHEME>
+__device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[P::kPasses], const LanePos& lp, int scheme_rt, uint32_t* stage,
                                                  const uint8_t* lut, DevState* st) {
     const int scheme = SCHEME >= 0 ? SCHEME : scheme_rt;
-    constexpr int kE = Page<D>::kE, kHdr = Page<D>::kHdr, NP = Page<D>::kPasses;
+    constexpr int kE = P::kE, kHdr = P::kHdr, NP = P::kPasses;
     const bool RLE = scheme != KVC_MODE_DELTA;  // zero-run and run packets (modes 3 and 4)
     const bool no_delta = scheme == KVC_MODE_PACK;
     const uint32_t c_min = RLE ? 0u : 1u;  // without run packets an all-zero group is a 1-bit literal
@@ -278,14 +332,15 @@ __device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPa
     }
     r.scale = s;
     if (scheme == KVC_MODE_INT8) {
-        store_codes<D, SCHEME == KVC_MODE_CHAN, NP>(raw, s_inv, stage);
+        store_codes<P, SCHEME == KVC_MODE_CHAN>(raw, s_inv, stage);
         r.n16 = kE / 16;
         r.mode = KVC_MODE_INT8;
         return r;
     }
     // bodies are OR-ed into the slot, and the zero padding is part of the payload
 #pragma unroll
-    for (int z = 0; z < kE / 1024; ++z) reinterpret_cast<uint4*>(stage)[lane + 64 * z] = make_uint4(0, 0, 0, 0);
+    for (int z = 0; z < P::kRounds; ++z)
+        if (kE % 1024 == 0 || lane + 64 * z < kE / 16) reinterpret_cast<uint4*>(stage)[lane + 64 * z] = make_uint4(0, 0, 0, 0);
     wave_sync();
 
     uint32_t run = kHdr;  // payload bytes so far (wave-uniform)
@@ -293,7 +348,7 @@ __device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPa
         // Mode 5: the lanes hold the page dealt as piece_index says.  The four passes of a run of 16
         // octets are quantized and mapped first; group set j of the run then takes channels 2j, 2j + 1
         // of each of them: the quad's 32 values are one channel pair over the 16 tokens.
-        static_assert(D == 128 || D == 256, "a lane's share of a channel pair is 8 values when an octet's 16 tokens are 4 passes");
+        static_assert(P::kChan, "a lane's share of a channel pair is 8 values when an octet's 16 tokens are 4 passes");
 #pragma unroll
         for (int h = 0; h < NP / 4; ++h) {
             uint32_t uu[4][8];
@@ -309,10 +364,11 @@ __device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPa
                 uint32_t u[8];
 #pragma unroll
                 for (int m = 0; m < 8; ++m) u[m] = uu[m >> 1][2 * j + (m & 1)];
-                encode_groups<D>(u, true, 0u, qi, 4 * h + j, run, stage, st);
+                encode_groups<P>(u, true, 0u, qi, 4 * h + j, run, stage, st);
             }
         }
     } else {
+        uint32_t carry = kMagicBits - 256u;  // last value of the pass before, for a row that continues
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
             uint32_t t[8];
@@ -324,19 +380,20 @@ __device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPa
 #pragma unroll
                 for (int k = 0; k < 8; ++k) u[k] = lut[t[k] - (kMagicBits + 256u * (uint32_t)k - 256u)];
             } else {
-                const uint32_t prev = left_neighbour<Page<D>::kLpr>(kMagicBits - 256u, t[7] - 2048u);
+                const uint32_t prev = left_neighbour<P>(lp, p, kMagicBits - 256u, t[7] - 2048u, carry);
+                if (!P::kAligned) carry = (uint32_t)__builtin_amdgcn_readlane((int)(t[7] - 2048u), 63);
                 KVC_CHECK(st, t[0] - prev < 512u && t[1] - t[0] < 512u && t[7] - t[6] < 512u);
                 u[0] = lut[t[0] - prev];
 #pragma unroll
                 for (int k = 1; k < 8; ++k) u[k] = lut[t[k] - t[k - 1]];
             }
-            encode_groups<D>(u, RLE, c_min, qi, p, run, stage, st);
+            encode_groups<P>(u, RLE, c_min, qi, p, run, stage, st);
         }
     }
     const uint32_t n = (run + 15u) & ~15u;
     wave_sync();
     if (n >= (uint32_t)kE) {  // packing did not beat plain INT8
-        store_codes<D, SCHEME == KVC_MODE_CHAN, NP>(raw, s_inv, stage);
+        store_codes<P, SCHEME == KVC_MODE_CHAN>(raw, s_inv, stage);
         r.n16 = kE / 16;
         r.mode = KVC_MODE_INT8;
     } else {
@@ -347,14 +404,14 @@ __device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[Page<D>::kPa
 }
 
 // Encode the page held in `raw` (if the task is live) into LDS slot `slot` and note its result.
-template <int D, int SCHEME, int SLOTS>
-__device__ __forceinline__ void encode_into_slot(const EncodeArgs& a, const uint4 (&raw)[Page<D>::kPasses], const EncTask& task,
+template <class P, int SCHEME, int SLOTS>
+__device__ __forceinline__ void encode_into_slot(const EncodeArgs& a, const uint4 (&raw)[P::kPasses], const LanePos& lp, const EncTask& task,
                                                  int slot, uint32_t* stage, const uint8_t* lut, EncBook<SLOTS>& book) {
     PageResult r;
     r.n16 = 0;
     r.mode = KVC_MODE_INVALID;
     r.scale = 0.0f;
-    if (task.desc_idx >= 0) r = encode_p16<D, SCHEME>(raw, task.scheme, stage, lut, a.st);
+    if (task.desc_idx >= 0) r = encode_p16<P, SCHEME>(raw, lp, task.scheme, stage, lut, a.st);
     if (lane_id() == 0) {
         book.n16[slot] = r.n16;
         book.mode[slot] = r.mode;
@@ -367,28 +424,30 @@ __device__ __forceinline__ void encode_into_slot(const EncodeArgs& a, const uint
 #ifndef KVC_ENC_MIN_WAVES
 #define KVC_ENC_MIN_WAVES 4
 #endif
-#ifndef KVC_ENC_RING64
-#define KVC_ENC_RING64 8
-#endif
-#ifndef KVC_ENC_RING128
-#define KVC_ENC_RING128 4
-#endif
-#ifndef KVC_ENC_RING256
-#define KVC_ENC_RING256 1
-#endif
+
+// Pages a wave holds in registers at once: while one is encoded the loads of the others are in flight.
+// Measured best with the ring as long as the wave's whole share (all loads issued up front, about 16 KB
+// per wave, no loop) for pages of up to four passes; a page is 4 registers per pass, so longer pages
+// take turns in fewer sets, and at eight passes a second page in registers costs occupancy and gains
+// nothing.
+// The run-time-scheme instantiation needs more registers for itself: at seven passes it keeps one page.
+constexpr int enc_ring_max(int np, int scheme) {
+    return np <= 2 ? 8 : np <= 3 ? 5 : np <= 4 ? 4 : np <= 5 ? 3 : np <= 6 ? 2 : (np == 7 && scheme >= 0) ? 2 : 1;
+}
 
 // (four waves per SIMD is what the LDS slots allow anyway: keep every instantiation within 128 VGPRs; the
-// channel-pair encoder at D = 256 holds 32 mapped values beside the page and runs better with three)
-template <int D, int WAVES, int PPW, int SCHEME>
-__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((D == 256 && SCHEME == KVC_MODE_CHAN) ? 3 : KVC_ENC_MIN_WAVES))) void k_compress_p16(EncodeArgs a) {
+// channel-pair encoder at D = 256 holds 32 mapped values beside the page and runs better with three, and
+// so does the run-time-scheme encoder of seven-pass pages whose rows cross passes, which would spill at four)
+template <class P, int SCHEME>
+constexpr int enc_min_waves() {
+    return ((P::kD == 256 && SCHEME == KVC_MODE_CHAN) || (P::kPasses >= 7 && !P::kAligned && SCHEME < 0)) ? 3 : KVC_ENC_MIN_WAVES;
+}
+template <class P, int WAVES, int PPW, int SCHEME>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(enc_min_waves<P, SCHEME>()))) void k_compress_p16(EncodeArgs a) {
     constexpr int kSlots = WAVES * PPW;
-    constexpr int NP = Page<D>::kPasses;
-    // Pages held in registers per wave: while one is encoded the loads of the next kRing - 1 are in
-    // flight.  Measured best with the ring as long as the wave's whole share (all loads issued up
-    // front, about 16 KB per wave, no loop) at d = 64 and d = 128; at d = 256 a second page in
-    // registers costs occupancy and gains nothing.
-    constexpr int kRingMax = D <= 64 ? KVC_ENC_RING64 : D <= 128 ? KVC_ENC_RING128 : KVC_ENC_RING256;
-    constexpr int kRing = kRingMax < PPW ? kRingMax : PPW;
+    constexpr int NP = P::kPasses;
+    constexpr bool CHAN = SCHEME == KVC_MODE_CHAN;
+    constexpr int kRing = enc_ring_max(NP, SCHEME) < PPW ? enc_ring_max(NP, SCHEME) : PPW;
     static_assert(PPW % kRing == 0, "the loop handles pages in groups of kRing");
     __shared__ __align__(16) uint32_t s_stage[kSlots][Slot<NP>::kWords];
     __shared__ EncBook<kSlots> s_book;
@@ -398,7 +457,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((D =
     __syncthreads();
     const int64_t t0 = ((int64_t)task_block_index() * WAVES + wave) * PPW;
     TaskPos pos = task_pos(t0, a.g.ppb);
-    const uint32_t lane_off = SCHEME == KVC_MODE_CHAN ? lane_byte_off_chan(a.g) : lane_byte_off<D>(a.g);
+    const LanePos lp = lane_pos<P>(a.g);
     const int slot0 = wave * PPW;
     if (kRing > 1) {
         // The register sets take turns (the inner loop is unrolled, so every index is a constant):
@@ -409,7 +468,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((D =
         for (int j = 0; j < kRing - 1; ++j) {
             if (j > 0) task_advance(pos, a.g.ppb);
             t[j] = resolve_enc_task(a, t0 + j, pos);
-            if (t[j].desc_idx >= 0) load_page<D, SCHEME == KVC_MODE_CHAN>(a, t[j], lane_off, r[j]);
+            if (t[j].desc_idx >= 0) load_page<P, CHAN>(a, t[j], lp, r[j]);
         }
 #pragma unroll 1
         for (int i = 0; i < PPW; i += kRing) {
@@ -419,8 +478,8 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((D =
                 const int nb = (j + kAhead) % kRing;
                 task_advance(pos, a.g.ppb);
                 t[nb] = resolve_enc_task(a, i + j + kAhead < PPW ? t0 + i + j + kAhead : a.n_pages, pos);  // past the end: no task
-                if (t[nb].desc_idx >= 0) load_page<D, SCHEME == KVC_MODE_CHAN>(a, t[nb], lane_off, r[nb]);
-                encode_into_slot<D, SCHEME>(a, r[j], t[j], slot0 + i + j, s_stage[slot0 + i + j], s_lut, s_book);
+                if (t[nb].desc_idx >= 0) load_page<P, CHAN>(a, t[nb], lp, r[nb]);
+                encode_into_slot<P, SCHEME>(a, r[j], lp, t[j], slot0 + i + j, s_stage[slot0 + i + j], s_lut, s_book);
             }
         }
     } else {
@@ -429,8 +488,8 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((D =
             const EncTask task = resolve_enc_task(a, t0 + i, pos);
             task_advance(pos, a.g.ppb);
             uint4 raw[NP];
-            if (task.desc_idx >= 0) load_page<D, SCHEME == KVC_MODE_CHAN>(a, task, lane_off, raw);
-            encode_into_slot<D, SCHEME>(a, raw, task, slot0 + i, s_stage[slot0 + i], s_lut, s_book);
+            if (task.desc_idx >= 0) load_page<P, CHAN>(a, task, lp, raw);
+            encode_into_slot<P, SCHEME>(a, raw, lp, task, slot0 + i, s_stage[slot0 + i], s_lut, s_book);
         }
     }
     __syncthreads();
@@ -501,27 +560,27 @@ __device__ __forceinline__ void unpack8(const DecodeArgs& a, const uint32_t* sta
 
 // A page on its way through the decoder: the descriptor's fields, the outcome of its validation and,
 // for the packed modes, the payload as it arrives from the pool (16 bytes per lane and round).
-template <int D>
+template <class P>
 struct DecPage {
     uint64_t off;
     float s;
     uint32_t n16, mode;
     bool ok;
-    uint4 pay[Page<D>::kE / 1024];
+    uint4 pay[P::kRounds];
 };
 
-template <int D>
+template <class P>
 __device__ __forceinline__ bool is_packed_mode(uint32_t mode) {
-    return mode == KVC_MODE_DELTA || mode == KVC_MODE_RLE || mode == KVC_MODE_PACK || (D >= 128 && mode == KVC_MODE_CHAN);
+    return mode == KVC_MODE_DELTA || mode == KVC_MODE_RLE || mode == KVC_MODE_PACK || (P::kChan && mode == KVC_MODE_CHAN);
 }
 
 // Take the descriptor apart, validate it against the pool and the page geometry, and start the
 // payload loads of a packed page.  Nothing here waits for those loads.
-template <int D>
-__device__ __forceinline__ DecPage<D> dec_open(const DecodeArgs& a, uint4 dw) {
-    constexpr int kE = Page<D>::kE, kHdr = Page<D>::kHdr;
+template <class P>
+__device__ __forceinline__ DecPage<P> dec_open(const DecodeArgs& a, uint4 dw) {
+    constexpr int kE = P::kE, kHdr = P::kHdr;
     const int lane = lane_id();
-    DecPage<D> pg;
+    DecPage<P> pg;
     pg.off = (uint64_t)dw.x | ((uint64_t)dw.y << 32);
     pg.s = __uint_as_float(dw.z);
     pg.n16 = dw.w & 0xFFFFu;
@@ -531,17 +590,17 @@ __device__ __forceinline__ DecPage<D> dec_open(const DecodeArgs& a, uint4 dw) {
         ok = ok && pg.n16 == kE / 8;
     else if (pg.mode == KVC_MODE_INT8)
         ok = ok && pg.n16 == kE / 16;
-    else if (is_packed_mode<D>(pg.mode))
+    else if (is_packed_mode<P>(pg.mode))
         ok = ok && pg.n16 * 16u >= (uint32_t)kHdr && pg.n16 < kE / 16;
     else
         ok = false;
     pg.ok = ok;
 #pragma unroll
-    for (int z = 0; z < kE / 1024; ++z) pg.pay[z] = make_uint4(0u, 0u, 0u, 0u);
-    if (ok && is_packed_mode<D>(pg.mode)) {
+    for (int z = 0; z < P::kRounds; ++z) pg.pay[z] = make_uint4(0u, 0u, 0u, 0u);
+    if (ok && is_packed_mode<P>(pg.mode)) {
         const uint4* pl4 = reinterpret_cast<const uint4*>(a.pool + pg.off);
 #pragma unroll
-        for (int z = 0; z < kE / 1024; ++z) {
+        for (int z = 0; z < P::kRounds; ++z) {
 #if KVC_NT_POOL
             if ((uint32_t)lane + 64 * z < pg.n16) pg.pay[z] = load_stream(pl4 + lane + 64 * z);
 #else
@@ -553,16 +612,15 @@ __device__ __forceinline__ DecPage<D> dec_open(const DecodeArgs& a, uint4 dw) {
 }
 
 // Decode an opened page into dst.  false = validation failed, dst zeroed.
-template <int D>
-__device__ __forceinline__ bool dec_finish(const DecodeArgs& a, const DecPage<D>& pg, uint16_t* __restrict__ dst,
+template <class P>
+__device__ __forceinline__ bool dec_finish(const DecodeArgs& a, const DecPage<P>& pg, uint16_t* __restrict__ dst,
                                            uint32_t* stage, uint32_t* ginfo) {
-    constexpr int kE = Page<D>::kE, kHdr = Page<D>::kHdr, NP = Page<D>::kPasses, kG = Page<D>::kGroups;
+    constexpr int kHdr = P::kHdr, NP = P::kPasses, kG = P::kGroups;
     const int lane = lane_id();
     const float s = pg.s;
     const uint32_t n16 = pg.n16, mode = pg.mode;
     char* dst_b = reinterpret_cast<char*>(a.out) + wave_uniform((int64_t)(dst - a.out) * 2);  // wave-uniform page base
-    const uint32_t lane_off = lane_byte_off<D>(a.g);    // this lane's 8 channels in pass 0
-    const int64_t pass_bytes = (int64_t)Page<D>::kRowsPerPass * a.g.row_stride * 2;
+    const LanePos lp = lane_pos<P>(a.g);
     if (!pg.ok) {
         zero_page(dst, a.g);
         return false;
@@ -570,7 +628,7 @@ __device__ __forceinline__ bool dec_finish(const DecodeArgs& a, const DecPage<D>
     const uint4* pl4 = reinterpret_cast<const uint4*>(a.pool + pg.off);
     if (mode == KVC_MODE_RAW) {  // stored-uncompressed bypass
 #pragma unroll
-        for (int p = 0; p < NP; ++p) *reinterpret_cast<uint4*>(dst_b + p * pass_bytes + lane_off) = pl4[p * 64 + lane];
+        for (int p = 0; p < NP; ++p) *reinterpret_cast<uint4*>(dst_b + pass_base_off<P, false>(a.g, p) + pass_lane_off<P, false>(a.g, lp, p)) = pl4[p * 64 + lane];
         return true;
     }
     const float neg128s = -128.0f * s;
@@ -584,7 +642,7 @@ __device__ __forceinline__ bool dec_finish(const DecodeArgs& a, const DecPage<D>
                 pb[k] = ((v.x >> (8 * k)) + 128u);
                 pb[4 + k] = ((v.y >> (8 * k)) + 128u);
             }
-            store_stream(reinterpret_cast<uint4*>(dst_b + p * pass_bytes + lane_off), dequant8_biased(pb, s, neg128s));
+            store_stream(reinterpret_cast<uint4*>(dst_b + pass_base_off<P, false>(a.g, p) + pass_lane_off<P, false>(a.g, lp, p)), dequant8_biased(pb, s, neg128s));
         }
         return true;
     }
@@ -592,7 +650,7 @@ __device__ __forceinline__ bool dec_finish(const DecodeArgs& a, const DecPage<D>
     {
         uint4* st4 = reinterpret_cast<uint4*>(stage);
 #pragma unroll
-        for (int z = 0; z < kE / 1024; ++z)
+        for (int z = 0; z < P::kRounds; ++z)
             if ((uint32_t)lane + 64 * z < n16) st4[lane + 64 * z] = pg.pay[z];
     }
     wave_sync();
@@ -603,7 +661,7 @@ __device__ __forceinline__ bool dec_finish(const DecodeArgs& a, const DecPage<D>
 #pragma unroll
     for (int g0 = 0; g0 < kG; g0 += 64) {
         const int g = g0 + lane;
-        const bool live = kG >= 64 || g < kG;
+        const bool live = kG % 64 == 0 || g < kG;
         const uint32_t c_own = live ? (stage[g >> 3] >> ((g & 7) << 2)) & 15u : 1u;
         const uint32_t size_own = !live ? 0u : (c_own == 9) ? 1u : (c_own << 2);
         const uint32_t incl = wave_incl_scan_dpp(size_own);
@@ -618,12 +676,11 @@ __device__ __forceinline__ bool dec_finish(const DecodeArgs& a, const DecPage<D>
         return false;
     }
     wave_sync();
-    if (D >= 128 && mode == KVC_MODE_CHAN) {
+    if (P::kChan && mode == KVC_MODE_CHAN) {
         // Mode 5: of a run of 16 octets, group set j holds channels 2j, 2j + 1 of the lane's octet,
         // tokens 4p + (lane & 3) for p = 0..3 (value 2p + e of the packet = pass p, channel 2j + e).  The
         // biased codes of a set are kept as bytes, so that pass p then finds its eight codes at fixed
         // byte positions.
-        const uint32_t lane_off_chan = lane_byte_off_chan(a.g);
 #pragma unroll
         for (int h = 0; h < NP / 4; ++h) {
             uint32_t packed[4][2];
@@ -646,12 +703,13 @@ __device__ __forceinline__ bool dec_finish(const DecodeArgs& a, const DecPage<D>
                     const int m = 2 * p + (k & 1);  // value index inside group set k / 2
                     pb[k] = packed[k >> 1][m >> 2] >> (8 * (m & 3));
                 }
-                store_stream(reinterpret_cast<uint4*>(dst_b + pass_byte_off<D, true>(a.g, 4 * h + p) + lane_off_chan),
+                store_stream(reinterpret_cast<uint4*>(dst_b + pass_base_off<P, true>(a.g, 4 * h + p) + pass_lane_off<P, true>(a.g, lp, 4 * h + p)),
                              dequant8_biased(pb, s, neg128s));
             }
         }
         return true;
     }
+    uint32_t carry = 0;  // what a row that continues from the pass before had summed up there
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
         uint32_t hb[8];  // bits above the sign flag
@@ -669,19 +727,21 @@ __device__ __forceinline__ bool dec_finish(const DecodeArgs& a, const DecPage<D>
 #pragma unroll
             for (int k = 1; k < 8; ++k) pre[k] = (hb[k] ^ (uint32_t)sg[k]) + pre[k - 1];
             const uint32_t tot = pre[7];
-            const uint32_t base = row_incl_scan<Page<D>::kLpr>(tot) - tot + 128u;  // +128: biased codes, see dequant8_biased
+            const uint32_t incl = row_incl_scan<P>(lp, p, tot, carry);
+            if (!P::kAligned) carry = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+            const uint32_t base = incl - tot + 128u;  // +128: biased codes, see dequant8_biased
 #pragma unroll
             for (int k = 0; k < 8; ++k) pb[k] = pre[k] + base;
         }
-        store_stream(reinterpret_cast<uint4*>(dst_b + p * pass_bytes + lane_off), dequant8_biased(pb, s, neg128s));
+        store_stream(reinterpret_cast<uint4*>(dst_b + pass_base_off<P, false>(a.g, p) + pass_lane_off<P, false>(a.g, lp, p)), dequant8_biased(pb, s, neg128s));
     }
     return true;
 }
 
-template <int D, int WAVES, int PPW>
+template <class P, int WAVES, int PPW>
 __global__ __launch_bounds__(WAVES * 64) void k_decompress_p16(DecodeArgs a) {
-    __shared__ __align__(16) uint32_t s_stage[WAVES][Slot<Page<D>::kPasses>::kWords];
-    __shared__ uint32_t s_ginfo[WAVES][Page<D>::kGroups];
+    __shared__ __align__(16) uint32_t s_stage[WAVES][Slot<P::kPasses>::kWords];
+    __shared__ uint32_t s_ginfo[WAVES][P::kGroups];
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t t0 = ((int64_t)task_block_index() * WAVES + wave) * PPW;
@@ -691,7 +751,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_p16(DecodeArgs a) {
     // looked at, then every payload load before the first page is decoded.
     DecTask task[PPW];
     uint4 dw[PPW];
-    DecPage<D> pg[PPW];
+    DecPage<P> pg[PPW];
 #pragma unroll
     for (int i = 0; i < PPW; ++i) {
         task[i] = resolve_dec_task(a, t0 + i, pos);
@@ -700,11 +760,11 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_p16(DecodeArgs a) {
     }
 #pragma unroll
     for (int i = 0; i < PPW; ++i)
-        if (task[i].kind == 1) pg[i] = dec_open<D>(a, dw[i]);
+        if (task[i].kind == 1) pg[i] = dec_open<P>(a, dw[i]);
 #pragma unroll
     for (int i = 0; i < PPW; ++i) {
         if (task[i].kind == 2) zero_page(task[i].dst, a.g);
-        if (task[i].kind == 1 && !dec_finish<D>(a, pg[i], task[i].dst, s_stage[wave], s_ginfo[wave])) {
+        if (task[i].kind == 1 && !dec_finish<P>(a, pg[i], task[i].dst, s_stage[wave], s_ginfo[wave])) {
             if (lane == 0) atomicOr(&a.st->status, KVC_ST_CORRUPT);
         }
         wave_sync();
@@ -715,30 +775,30 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_p16(DecodeArgs a) {
 // workgroup takes the next issued block from the queue, its waves decode the block's pages, and the
 // completion is reported before the next block is taken.  A wave starts the descriptor and payload loads
 // of its next page before it decodes the current one.
-template <int D, int WAVES>
+template <class P, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void k_decompress_window_p16(DecodeArgs a, WindowArgs w) {
-    __shared__ __align__(16) uint32_t s_stage[WAVES][Slot<Page<D>::kPasses>::kWords];
-    __shared__ uint32_t s_ginfo[WAVES][Page<D>::kGroups];
+    __shared__ __align__(16) uint32_t s_stage[WAVES][Slot<P::kPasses>::kWords];
+    __shared__ uint32_t s_ginfo[WAVES][P::kGroups];
     __shared__ int32_t s_slot;
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int ppb = a.g.ppb;
     int32_t slot = window_next(w, &s_slot, -1);
     while (slot >= 0) {
-        auto open_page = [&](int pg, DecTask& task, DecPage<D>& dp) {
+        auto open_page = [&](int pg, DecTask& task, DecPage<P>& dp) {
             TaskPos pos;
             pos.blk = slot;
             pos.pg = pg;
             task = resolve_dec_task(a, pg < ppb ? (int64_t)slot * ppb + pg : a.n_pages, pos);
-            if (task.kind == 1) dp = dec_open<D>(a, reinterpret_cast<const uint4*>(a.desc)[task.desc_idx]);
+            if (task.kind == 1) dp = dec_open<P>(a, reinterpret_cast<const uint4*>(a.desc)[task.desc_idx]);
         };
         DecTask cur, nxt;
-        DecPage<D> dcur, dnxt;
+        DecPage<P> dcur, dnxt;
         open_page(wave, cur, dcur);
         for (int pg = wave; pg < ppb; pg += WAVES) {
             open_page(pg + WAVES, nxt, dnxt);
             if (cur.kind == 2) zero_page(cur.dst, a.g);
-            if (cur.kind == 1 && !dec_finish<D>(a, dcur, cur.dst, s_stage[wave], s_ginfo[wave])) {
+            if (cur.kind == 1 && !dec_finish<P>(a, dcur, cur.dst, s_stage[wave], s_ginfo[wave])) {
                 if (lane == 0) atomicOr(&a.st->status, KVC_ST_CORRUPT);
             }
             wave_sync();
@@ -749,82 +809,63 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_window_p16(DecodeArgs
     }
 }
 
-}  // namespace
-
-hipError_t launch_decompress_window_p16(const DecodeArgs& a, const WindowArgs& w, unsigned grid, hipStream_t s) {
-    constexpr int WAVES = 4;
-    const dim3 block(WAVES * 64);
-    if (a.g.d == 64) return launch_kernel(k_decompress_window_p16<64, WAVES>, dim3(grid), block, s, a, w);
-    if (a.g.d == 128) return launch_kernel(k_decompress_window_p16<128, WAVES>, dim3(grid), block, s, a, w);
-    return launch_kernel(k_decompress_window_p16<256, WAVES>, dim3(grid), block, s, a, w);
-}
-
-// Launch shapes (waves per workgroup, pages per wave); compile-time tunables.
-#ifndef KVC_ENC_WAVES
-#define KVC_ENC_WAVES 4
-#endif
-#ifndef KVC_ENC_PPW
-#define KVC_ENC_PPW 4
-#endif
+// Launch shapes by page size (NP passes of 1 KB): waves per workgroup, pages per wave.
+constexpr int kFastWaves = 4;
+// large calls: about 64 KB of input per workgroup and one pool-cursor atomic for it
+constexpr int enc_ppw_large(int np) { return np == 1 ? 16 : np == 2 ? 8 : np == 3 ? 5 : np == 4 ? 4 : np == 5 ? 3 : 2; }
+// A small call (a decode step's offload of a few blocks) is latency: one page per wave (more only for
+// the smallest pages), so the pages are encoded side by side instead of several in a row.  The cursor
+// then takes an atomic per four pages, which only a large call would feel.
+constexpr int enc_ppw_small(int np) { return np == 1 ? 4 : np == 2 ? 2 : 1; }
+// a page of one or two passes is too small to cover its own memory chain: a wave walks several side by side
+constexpr int dec_ppw(int np) { return np == 1 ? 4 : np == 2 ? 2 : 1; }
 // calls of at most this many pages take the low-latency launch shape
 #ifndef KVC_ENC_SMALL_PAGES
 #define KVC_ENC_SMALL_PAGES 2048
 #endif
-#ifndef KVC_DEC_WAVES
-#define KVC_DEC_WAVES 4
-#endif
-#ifndef KVC_DEC_PPW
-#define KVC_DEC_PPW 1
-#endif
 
-template <int SCHEME>
-static hipError_t launch_compress_scheme(const EncodeArgs& a, hipStream_t s) {
-    constexpr int WAVES = KVC_ENC_WAVES, PPW = KVC_ENC_PPW;
-    const dim3 block(WAVES * 64);
-    auto grid = [&](int ppw) { return dim3((unsigned)((a.n_pages + (int64_t)WAVES * ppw - 1) / ((int64_t)WAVES * ppw))); };
-    if (a.n_pages <= KVC_ENC_SMALL_PAGES) {
-        // A small call (a decode step's offload of a few blocks) is latency: one page per wave
-        // (two at d = 64), so the pages are encoded side by side instead of four in a row.  The
-        // cursor then takes an atomic per four pages, which only a large call would feel.
-        if (a.g.d == 64) return launch_kernel(k_compress_p16<64, WAVES, 2, SCHEME>, grid(2), block, s, a);
-        if (a.g.d == 128) return launch_kernel(k_compress_p16<128, WAVES, 1, SCHEME>, grid(1), block, s, a);
-        return launch_kernel(k_compress_p16<256, WAVES, 1, SCHEME>, grid(1), block, s, a);
-    }
-    // pages per pool-cursor atomic scale with the page size: 64 KB of input per workgroup
-    if (a.g.d == 64) return launch_kernel(k_compress_p16<64, WAVES, 2 * PPW, SCHEME>, grid(2 * PPW), block, s, a);
-    if (a.g.d == 128) return launch_kernel(k_compress_p16<128, WAVES, PPW, SCHEME>, grid(PPW), block, s, a);
-    return launch_kernel(k_compress_p16<256, WAVES, PPW / 2, SCHEME>, grid(PPW / 2), block, s, a);
+inline dim3 fast_grid(int64_t n_pages, int ppw) {
+    const int64_t per_wg = (int64_t)kFastWaves * ppw;
+    return dim3((unsigned)((n_pages + per_wg - 1) / per_wg));
 }
 
-hipError_t launch_compress_p16(const EncodeArgs& a, hipStream_t s) {
-    // the full scheme of Algorithm 2 for every block is the common launch and gets its own
-    // instantiation; any other request (another mode, or one mode per block) reads it at run time
-    if (a.block_scheme == nullptr && a.scheme == KVC_MODE_RLE) return launch_compress_scheme<KVC_MODE_RLE>(a, s);
-    if (a.block_scheme == nullptr && a.scheme == KVC_MODE_CHAN) {
-        // channel-pair groups: its own instantiations (another deal of the page to the lanes), D = 128 and 256
-        if (a.g.d != 128 && a.g.d != 256) return hipErrorInvalidValue;
-        constexpr int WAVES = KVC_ENC_WAVES, PPW = KVC_ENC_PPW;
-        const bool small = a.n_pages <= KVC_ENC_SMALL_PAGES;
-        const dim3 block(WAVES * 64);
-        auto grid = [&](int ppw) { return dim3((unsigned)((a.n_pages + (int64_t)WAVES * ppw - 1) / ((int64_t)WAVES * ppw))); };
-        if (a.g.d == 128) {
-            if (small) return launch_kernel(k_compress_p16<128, WAVES, 1, KVC_MODE_CHAN>, grid(1), block, s, a);
-            return launch_kernel(k_compress_p16<128, WAVES, PPW, KVC_MODE_CHAN>, grid(PPW), block, s, a);
+// The host side of one geometry: picks the instantiation and launches it.
+template <int D, int NP>
+struct FastOps {
+    using P = Page<D, NP>;
+
+    template <int SCHEME>
+    static hipError_t compress_scheme(const EncodeArgs& a, hipStream_t s) {
+        const dim3 block(kFastWaves * 64);
+        if (a.n_pages <= KVC_ENC_SMALL_PAGES)
+            return launch_kernel(k_compress_p16<P, kFastWaves, enc_ppw_small(NP), SCHEME>, fast_grid(a.n_pages, enc_ppw_small(NP)), block, s, a);
+        return launch_kernel(k_compress_p16<P, kFastWaves, enc_ppw_large(NP), SCHEME>, fast_grid(a.n_pages, enc_ppw_large(NP)), block, s, a);
+    }
+
+    static hipError_t compress(const EncodeArgs& a, hipStream_t s) {
+        // the full scheme of Algorithm 2 for every block is the common launch and gets its own
+        // instantiation; any other request (another mode, or one mode per block) reads it at run time
+        if (a.block_scheme == nullptr && a.scheme == KVC_MODE_RLE) return compress_scheme<KVC_MODE_RLE>(a, s);
+        if (a.block_scheme == nullptr && a.scheme == KVC_MODE_CHAN) {
+            // channel-pair groups: its own instantiations (another deal of the page to the lanes)
+            if constexpr (P::kChan)
+                return compress_scheme<KVC_MODE_CHAN>(a, s);
+            else
+                return hipErrorInvalidValue;
         }
-        if (small) return launch_kernel(k_compress_p16<256, WAVES, 1, KVC_MODE_CHAN>, grid(1), block, s, a);
-        return launch_kernel(k_compress_p16<256, WAVES, PPW / 2, KVC_MODE_CHAN>, grid(PPW / 2), block, s, a);
+        return compress_scheme<-1>(a, s);
     }
-    return launch_compress_scheme<-1>(a, s);
-}
 
-hipError_t launch_decompress_p16(const DecodeArgs& a, hipStream_t s) {
-    constexpr int WAVES = KVC_DEC_WAVES, PPW = KVC_DEC_PPW;
-    const dim3 block(WAVES * 64);
-    auto grid = [&](int ppw) { return dim3((unsigned)((a.n_pages + (int64_t)WAVES * ppw - 1) / ((int64_t)WAVES * ppw))); };
-    // a d = 64 page is too small to cover its own memory chain: there a wave walks two side by side
-    if (a.g.d == 64) return launch_kernel(k_decompress_p16<64, WAVES, 2 * PPW>, grid(2 * PPW), block, s, a);
-    if (a.g.d == 128) return launch_kernel(k_decompress_p16<128, WAVES, PPW>, grid(PPW), block, s, a);
-    return launch_kernel(k_decompress_p16<256, WAVES, PPW>, grid(PPW), block, s, a);
-}
+    static hipError_t decompress(const DecodeArgs& a, hipStream_t s) {
+        return launch_kernel(k_decompress_p16<P, kFastWaves, dec_ppw(NP)>, fast_grid(a.n_pages, dec_ppw(NP)), dim3(kFastWaves * 64), s, a);
+    }
 
+    static hipError_t decompress_window(const DecodeArgs& a, const WindowArgs& w, unsigned grid, hipStream_t s) {
+        return launch_kernel(k_decompress_window_p16<P, kFastWaves>, dim3(grid), dim3(kFastWaves * 64), s, a, w);
+    }
+
+    static constexpr FastKernels kTable = {P::kN, D, &compress, &decompress, &decompress_window};
+};
+
+}  // namespace
 }  // namespace kvc

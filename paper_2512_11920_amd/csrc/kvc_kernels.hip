@@ -691,8 +691,15 @@ __global__ void k_page_scales(const uint16_t* amax, float* s, float* s_inv, uint
 
 // ---------------------------------------------------------------------------------- launchers
 
-// geometries served by the specialised kernels of kvc_page16.hip
-static inline bool has_p16_kernels(const Geometry& g) { return g.N == 16 && (g.d == 64 || g.d == 128 || g.d == 256); }
+// geometries served by the specialised kernels of kvc_fast.h
+const FastKernels* fast_kernels(int N, int d) {
+    using Lookup = const FastKernels* (*)(int, int);
+    static const Lookup groups[kFastGroups] = {fast_kernels_group0, fast_kernels_group1, fast_kernels_group2, fast_kernels_group3,
+                                               fast_kernels_group4, fast_kernels_group5, fast_kernels_group6, fast_kernels_group7};
+    for (Lookup f : groups)
+        if (const FastKernels* k = f(N, d)) return k;
+    return nullptr;
+}
 
 static inline unsigned grid_for(int64_t n_pages, int ppw) {
     const int64_t per_wg = (int64_t)kWavesPerWG * ppw;
@@ -701,7 +708,7 @@ static inline unsigned grid_for(int64_t n_pages, int ppw) {
 
 hipError_t launch_compress(const EncodeArgs& a, hipStream_t s) {
     if (a.n_pages == 0) return hipSuccess;
-    if (has_p16_kernels(a.g)) return launch_compress_p16(a, s);
+    if (const FastKernels* f = fast_kernels(a.g.N, a.g.d)) return f->compress(a, s);
     constexpr int PPW = 4;
     const dim3 grid(grid_for(a.n_pages, PPW)), block(kThreads);
     if (a.g.E <= 512) return launch_kernel(k_compress<1, PPW>, grid, block, s, a);
@@ -711,7 +718,7 @@ hipError_t launch_compress(const EncodeArgs& a, hipStream_t s) {
 
 hipError_t launch_decompress(const DecodeArgs& a, hipStream_t s) {
     if (a.n_pages == 0) return hipSuccess;
-    if (has_p16_kernels(a.g)) return launch_decompress_p16(a, s);
+    if (const FastKernels* f = fast_kernels(a.g.N, a.g.d)) return f->decompress(a, s);
     constexpr int PPW = 4;
     const dim3 grid(grid_for(a.n_pages, PPW)), block(kThreads);
     if (a.g.E <= 512) return launch_kernel(k_decompress<1, PPW>, grid, block, s, a);
@@ -737,7 +744,7 @@ hipError_t launch_window_build(const WindowArgs& w, hipStream_t s) {
 hipError_t launch_decompress_window(const DecodeArgs& a, const WindowArgs& w, int32_t omega, hipStream_t s) {
     if (w.n_now <= 0) return hipSuccess;
     const unsigned grid = (unsigned)std::min<int64_t>(omega, w.n_now);
-    if (has_p16_kernels(a.g)) return launch_decompress_window_p16(a, w, grid, s);
+    if (const FastKernels* f = fast_kernels(a.g.N, a.g.d)) return f->decompress_window(a, w, grid, s);
     const dim3 block(kThreads);
     if (a.g.E <= 512) return launch_kernel(k_decompress_window<1>, dim3(grid), block, s, a, w);
     if (a.g.E <= 2048) return launch_kernel(k_decompress_window<4>, dim3(grid), block, s, a, w);

@@ -70,7 +70,13 @@ def _families(rng, n, N, d):
                                           (16, 128, 9000, 5), (16, 128, 2048, 5), (16, 128, 333, 5), (16, 256, 5000, 5), (16, 256, 1200, 5),
                                           # head dimensions that are not powers of two: token rows of 12, 20, 24, 28 lanes
                                           (16, 96, 3000, 3), (16, 160, 3000, 3), (16, 192, 3000, 3), (16, 224, 3000, 3),
-                                          (16, 96, 2000, 4), (16, 192, 2000, 2), (8, 96, 2000, 3), (21, 192, 1500, 3), (3, 160, 2000, 3)])
+                                          (16, 96, 2000, 4), (16, 192, 2000, 2), (8, 96, 2000, 3), (21, 192, 1500, 3), (3, 160, 2000, 3),
+                                          # every other specialised page shape, both launch shapes (large calls, calls of at most 2048 pages)
+                                          (8, 64, 5000, 3), (8, 128, 4000, 2), (8, 192, 3000, 3), (8, 256, 3000, 4), (32, 32, 4000, 3),
+                                          (32, 64, 3000, 3), (32, 96, 2500, 4), (32, 128, 2500, 3),
+                                          (16, 32, 2000, 3), (16, 96, 1500, 3), (16, 160, 2048, 3), (16, 192, 1000, 3), (16, 224, 900, 4),
+                                          (8, 64, 2000, 3), (8, 128, 1900, 4), (8, 192, 1000, 3), (8, 256, 800, 2), (32, 32, 2048, 4),
+                                          (32, 64, 600, 3), (32, 96, 512, 3), (32, 128, 700, 2)])
 def test_differential(N, d, n, scheme):
     # KVC_DIFF_SEED in the environment draws a different set of pages (for longer hunts)
     rng = np.random.default_rng(N * 1000 + d + scheme + 100003 * int(os.environ.get("KVC_DIFF_SEED", "0")))
@@ -112,7 +118,8 @@ def _soak_pages(rng, n, N, d):
 
 _SOAK_CASES = [(16, d, sc) for d in (64, 128, 256) for sc in (2, 3, 4, "mixed")] + \
               [(N, d, sc) for (N, d) in ((8, 128), (32, 64), (16, 32), (4, 256)) for sc in (3, "mixed")] + [(16, 128, 5), (16, 256, 5)] + \
-              [(N, d, sc) for (N, d) in ((16, 96), (16, 160), (16, 192), (16, 224), (8, 96), (32, 96), (8, 192)) for sc in (3, "mixed")]
+              [(N, d, sc) for (N, d) in ((16, 96), (16, 160), (16, 192), (16, 224), (8, 96), (32, 96), (8, 192),
+                                         (8, 64), (8, 256), (32, 32), (32, 128)) for sc in (3, "mixed")]
 
 
 @pytest.mark.parametrize("N,d,scheme", _SOAK_CASES)

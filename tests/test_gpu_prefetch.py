@@ -164,7 +164,7 @@ def test_hip_graph_replays_match_eager():
         assert c.stats()["status"] == 0
 
 
-@pytest.mark.parametrize("geom", [(16, 128, 4), (16, 64, 3), (8, 32, 2)])
+@pytest.mark.parametrize("geom", [(16, 128, 4), (16, 64, 3), (8, 32, 2), (16, 96, 3), (32, 128, 2)])
 @pytest.mark.parametrize("omega", [1, 5, 16, 4096])
 def test_window_prefetch_matches_unbounded_and_model(omega, geom):
     """Algorithm 1's outstanding-request window: with at most omega blocks in flight the plan arrays and

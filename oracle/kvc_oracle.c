@@ -148,15 +148,18 @@ int kvo_quantize_page(const uint16_t* x, int E, float* s, float* s_inv, int8_t* 
     return 0;
 }
 
+/* The zig-zag map 0,-1,1,-2,... -> 0,1,2,3,... of an 8-bit signed value (-128 -> 255), written as its two
+ * cases so that no negative value is ever shifted. */
+static uint8_t zigzag8(int v) { return (uint8_t)(v >= 0 ? 2 * v : -2 * v - 1); }
+
 /* Delta step along the channel index, first column verbatim, wrapped to 8 bits, then
- * the zig-zag map 0,-1,1,-2,... -> 0,1,2,3,... */
+ * the zig-zag map. */
 void kvo_delta_zigzag(const int8_t* q, int N, int d, uint8_t* u) {
     for (int j = 0; j < N; ++j) {
         for (int i = 0; i < d; ++i) {
             int left = (i == 0) ? 0 : q[j * d + i - 1];
             int8_t delta = (int8_t)(uint8_t)((q[j * d + i] - left) & 0xFF);
-            int dz = delta;
-            u[j * d + i] = (uint8_t)(((dz << 1) ^ (dz >> 7)) & 0xFF);
+            u[j * d + i] = zigzag8(delta);
         }
     }
 }
@@ -165,8 +168,7 @@ void kvo_delta_zigzag(const int8_t* q, int N, int d, uint8_t* u) {
  * differencing only widens the values): the zig-zag map applied to the codes themselves. */
 void kvo_zigzag_codes(const int8_t* q, int E, uint8_t* u) {
     for (int i = 0; i < E; ++i) {
-        int v = q[i];
-        u[i] = (uint8_t)(((v << 1) ^ (v >> 7)) & 0xFF);
+        u[i] = zigzag8(q[i]);
     }
 }
 
@@ -180,6 +182,11 @@ void kvo_zigzag_codes(const int8_t* q, int E, uint8_t* u) {
  * k = (t mod 4) * 8 + (t div 4) * 2 + (c mod 2) of its group.  (The order inside a group and of the
  * groups is free as far as the ratio goes; this one lets a GPU lane that holds tokens t, t+4, t+8, t+12
  * of one octet emit whole bytes, sixteen octets at a time.) */
+/* The group formula fills the page's groups exactly once each only when the channel octets make whole
+ * runs of W: d / 8 <= 16 (one run) or d / 8 a multiple of 16.  Other channel counts (160, 192, 224) have
+ * no mode 5. */
+static int chan_geometry_ok(int N, int d) { return N == 16 && (d / 8 <= 16 || (d / 8) % 16 == 0); }
+
 static int chan_group(int c, int d) {
     int o = c / 8, j = (c / 2) % 4;
     int W = d / 8 < 16 ? d / 8 : 16;
@@ -191,8 +198,7 @@ void kvo_zigzag_codes_by_channel(const int8_t* q, int d, uint8_t* u) {
         for (int c = 0; c < d; ++c) {
             int g = chan_group(c, d);
             int k = (t % 4) * 8 + (t / 4) * 2 + (c % 2);
-            int v = q[t * d + c];
-            u[32 * g + k] = (uint8_t)(((v << 1) ^ (v >> 7)) & 0xFF);
+            u[32 * g + k] = zigzag8(q[t * d + c]);
         }
 }
 
@@ -245,11 +251,12 @@ size_t kvo_rle_pack(const uint8_t* u, int E, int with_runs, uint8_t* out) {
     return pos;
 }
 
-/* Encode one page.  payload must hold 2*E bytes.  scheme = requested mode 0..5 (5: N = 16 only).
+/* Encode one page.  payload must hold 2*E bytes.  scheme = requested mode 0..5 (5: N = 16 and d <= 128 or a
+ * multiple of 128 only).
  * Fills desc (off left at 0) and returns the padded payload size in bytes, or <0. */
 int64_t kvo_encode_page(const uint16_t* x, int N, int d, int scheme, uint8_t* payload, kvo_desc* desc) {
     if (N < 1 || d < 32 || d % 32 != 0 || scheme < 0 || scheme > 5) return KVO_ERR_ARG;
-    if (scheme == KVO_MODE_CHAN && N != 16) return KVO_ERR_ARG;
+    if (scheme == KVO_MODE_CHAN && !chan_geometry_ok(N, d)) return KVO_ERR_ARG;
     int E = N * d;
     desc->off = 0;
     desc->rsvd = 0;
@@ -308,7 +315,7 @@ int kvo_decode_codes(const uint8_t* payload, size_t nbytes, int mode, int N, int
         return KVO_OK;
     }
     if (mode != KVO_MODE_DELTA && mode != KVO_MODE_RLE && mode != KVO_MODE_PACK && mode != KVO_MODE_CHAN) return KVO_ERR_CORRUPT;
-    if (mode == KVO_MODE_CHAN && N != 16) return KVO_ERR_CORRUPT;
+    if (mode == KVO_MODE_CHAN && !chan_geometry_ok(N, d)) return KVO_ERR_CORRUPT;
     const int runs = mode != KVO_MODE_DELTA; /* zero-run and run packets allowed */
     size_t hdr = (size_t)(G + 1) / 2;
     if (nbytes < hdr) return KVO_ERR_CORRUPT;

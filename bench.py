@@ -181,12 +181,13 @@ def main():
     ppb = H
     E = N * d
     log(f"[bench] building {shape.name}: {shape.n_pages} pages, {shape.nbytes / 1e9:.2f} GB fp16")
+    pool_bytes = (shape.n_pages * (E if args.scheme else 2 * E) + 4096) // 16 * 16
+    codec = kvc.Codec(N, d, ppb, args.scheme)
     cache = synth.cache_torch(shape, dev)
     blocks = cache.view(-1, ppb, N, d)
-    n_blocks = blocks.shape[0]
     out = torch.empty_like(blocks)
-    codec = kvc.Codec(N, d, ppb, args.scheme)
-    codec.alloc_pool(n_blocks, shape.n_pages * (E if args.scheme else 2 * E) + 4096, dev)
+    codec.alloc_pool(blocks.shape[0], pool_bytes, dev)
+    n_blocks = blocks.shape[0]
 
     # decode-step pattern over the same pool: each (sequence, K|V) is a table row of its blocks
     bps = shape.seq_len // N
@@ -237,9 +238,9 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_step = (t1 - t0) * 1e3 / args.steps
-    t_c = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
-    t_d = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
-    t_g = sum(e[2].elapsed_time(e[3]) for e in evs) / args.steps
+    per_step = {"compress": [e[0].elapsed_time(e[1]) for e in evs], "decompress": [e[1].elapsed_time(e[2]) for e in evs],
+                "gather_decompress": [e[2].elapsed_time(e[3]) for e in evs]}
+    t_c, t_d, t_g = (sum(per_step[k_]) / args.steps for k_ in ("compress", "decompress", "gather_decompress"))
 
     unc = shape.nbytes
     g_pages = g_out.numel() // E
@@ -255,8 +256,9 @@ def main():
         "gather_decompress": {"ms": t_g, "uncompressed_GBps": g_unc / t_g / 1e6, "hbm_GBps": alg_g / t_g / 1e6,
                               "alg_bytes": alg_g},
     }
-    for v in kern.values():
+    for k_, v in kern.items():
         v["frac_of_peak"] = v["hbm_GBps"] / HBM_PEAK_GBS
+        v["ms_min"], v["ms_max"] = min(per_step[k_]), max(per_step[k_])
     # same-run yardstick: plain 128-bit copy of the cache
     cp = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     src8, dst8 = blocks.view(torch.uint8).view(-1), out.view(torch.uint8).view(-1)

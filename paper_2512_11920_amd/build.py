@@ -19,6 +19,9 @@ UNITS = [("kvc_kernels.hip", (), "kvc_kernels.o"), ("kvc_api.hip", (), "kvc_api.
 SOURCES = [os.path.join(_CSRC, f) for f in ("kvc_kernels.hip", "kvc_fast.hip", "kvc_api.hip")]
 HEADERS = [os.path.join(_CSRC, f) for f in ("kvc_common.h", "kvc_device.h", "kvc_fast.h")] + [os.path.join(_ROOT, "include", "kvc.h")]
 LIB = os.path.join(_PKG, "libkvc.so")
+#: the same library with every LDS index and pool span the kernels compute checked against its bounds
+#: (a violation sets status bit 8); a GPU test runs the parity cases through it
+LIB_DEBUG = os.path.join(_PKG, "libkvc_dbg.so")
 OBJ_DIR = os.path.join(_PKG, "_build")
 
 HIPCC_FLAGS = [
@@ -58,7 +61,7 @@ def compile_unit(source: str, defines=(), out: str | None = None, extra_flags=()
 def build(force: bool = True, verbose: bool = False, extra_flags=(), lib: str = LIB, jobs: int | None = None) -> str:
     if not force and not stale():
         return lib
-    obj_dir = OBJ_DIR if lib == LIB else lib + ".objs"
+    obj_dir = OBJ_DIR if lib == LIB else os.path.join(OBJ_DIR, os.path.basename(lib) + ".objs")
     os.makedirs(obj_dir, exist_ok=True)
     jobs = jobs or max(1, min(len(UNITS), os.cpu_count() or 1, 16))
     with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as ex:
@@ -70,6 +73,10 @@ def build(force: bool = True, verbose: bool = False, extra_flags=(), lib: str = 
         print(" ".join(cmd), file=sys.stderr)
     subprocess.run(cmd, check=True)
     return lib
+
+
+def build_debug(verbose: bool = False) -> str:
+    return build(force=True, verbose=verbose, extra_flags=("-DKVC_DEBUG_BOUNDS=1",), lib=LIB_DEBUG)
 
 
 CLIENT_SRC = os.path.join(_ROOT, "tests", "abi_client.cpp")
@@ -88,4 +95,5 @@ def build_client(verbose: bool = False) -> str:
 
 if __name__ == "__main__":
     print(build(force=True, verbose=True))
+    print(build_debug(verbose=True))
     print(build_client(verbose=True))

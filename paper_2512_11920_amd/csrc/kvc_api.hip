@@ -365,6 +365,7 @@ static int prefetch_impl(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_f
     w.layer_begin = layer_begin;
     w.n_layers_call = layer_end - layer_begin;
     w.n_layers = n_layers;
+    w.omega = omega;
     w.notify = d_notify;
     if (!hip_ok(kvc::launch_window_build(w, s))) return KVC_ERR_HIP;
     return hip_ok(kvc::launch_decompress_window(a, w, omega, s)) ? KVC_OK : KVC_ERR_HIP;

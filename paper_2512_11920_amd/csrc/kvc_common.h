@@ -80,12 +80,14 @@ struct PlanArgs {
 // concurrent transfers).  The workspace of one call: this header, then one pending counter per layer of
 // the call, then the queue of issued transfers (slot indices relative to the call's first slot).
 struct WindowHdr {
-    unsigned int n_issued;    // entries in the queue
-    unsigned int ticket;      // next queue entry to hand out
-    unsigned int done;        // blocks completed
-    unsigned int in_flight;   // blocks being decoded at this moment
-    unsigned int high_water;  // largest in_flight seen during the call
-    unsigned int pad[59];     // the counters get a 256-byte line of their own
+    unsigned int n_issued;  // entries in the queue (constant while the engines run)
+    unsigned int engines;   // transfer engines of the call = min(omega, n_issued): the bound on blocks in flight
+    unsigned int chunk;     // queue entries an engine takes per turn (1..8)
+    unsigned int pad0[13];
+    unsigned int ticket;    // next queue entry to hand out; the two hot counters sit in cache lines of their own
+    unsigned int pad1[15];
+    unsigned int done;      // blocks completed
+    unsigned int pad2[31];
 };
 static_assert(sizeof(WindowHdr) == 256, "window header is 256 bytes");
 
@@ -97,6 +99,7 @@ struct WindowArgs {
     int32_t n_now;         // slots of the call = layers of the call * per_layer
     int32_t per_layer;     // n_seq * k
     int32_t layer_begin, n_layers_call, n_layers;
+    int32_t omega;         // engines the decode launch starts at most
     long long* notify;     // [n_layers + 4], see kvc.h
 };
 

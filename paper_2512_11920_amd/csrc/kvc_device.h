@@ -94,13 +94,17 @@ __device__ __forceinline__ uint32_t row16_incl_scan_dpp(uint32_t v) {
 }
 
 // ---- bit strings wider than 32 bits, handled as 32-bit halves --------------------------------
-// No 64-bit shift by a register amount may appear in these kernels.  On this hardware v_lshlrev_b64 and
-// v_lshrrev_b64 misread their shift count when it sits in the last VGPR of the wave's allocation and
-// another wave shares the SIMD: the result is shifted by some bits of the neighbouring wave's first
-// register.  (Measured with a stand-alone kernel: count in v127 of 128, v119 of 120 or v63 of 64 allocated
-// registers: wrong; in any other register, or with one workgroup per compute unit: right; 32-bit shifts
-// and v_mad_u64_u32 are not affected.)  The compiler picks the registers, so the packing and unpacking
-// below use 32-bit shifts, funnel shifts and byte permutes only; a test scans the generated code.
+// No 64-bit shift by a register amount may appear in these kernels.  What was observed: one build of one
+// encoder instantiation (256 channels, run-time scheme, exactly 128 VGPRs) wrote wrong body bytes for a
+// few pages in a thousand, differently on every launch, only when two or more workgroups shared a compute
+// unit, and every recompile that moved registers made the fault vanish.  That build held the count of a
+// v_lshlrev_b64 in the last VGPR of its allocation; the working hypothesis is that v_lshlrev_b64 /
+// v_lshrrev_b64 misread a count held there when another wave shares the SIMD.  The cause was not
+// established beyond that (a compiler or occupancy-dependent fault in that one build fits the same
+// symptoms).  The rule is harmless either way: packing and unpacking below use 32-bit shifts, funnel
+// shifts and byte permutes only; a test scans the generated code for 64-bit shifts by a vector register, and
+// the guard that matters is the test that runs every kernel instantiation at full occupancy against
+// the CPU reference.
 
 // u[0..7], each below 2^c with 0 <= c <= 8, as one little-endian bit string of 8c bits: x = low 32
 // bits, y = the rest.  (c = 9, a run packet, gives a value the caller discards.)
@@ -148,18 +152,24 @@ __device__ __forceinline__ uint32_t lane_in_row(const Geometry& g, uint32_t gl) 
     return gl - ((gl * g.lpr_magic) >> 16) * (uint32_t)g.lpr;
 }
 
-// Workgroup index used for task assignment.  Workgroups are dealt round-robin to the 8 XCDs; with
-// KVC_XCD_REMAP=1 each XCD instead works through one contiguous eighth of the tasks.
-#ifndef KVC_XCD_REMAP
-#define KVC_XCD_REMAP 0
-#endif
+// Workgroup index used for task assignment.  Workgroups are dealt round-robin to the 8 XCDs, so with
+// the identity deal (MODE 0) XCD k works on the tasks whose index is k modulo 8 for the whole launch: all
+// XCDs sweep the buffers side by side, 16 KB apart.  MODE 1 gives each XCD one contiguous eighth of the
+// tasks instead, so that it streams through a region of its own.  Measured on the 21 GB cache: the
+// decoder's time falls into one of two clusters from process to process whatever the deal (the buffers'
+// placement by the driver decides; see the design notes); with MODE 1 the clusters are 5.0 and 5.45 ms,
+// with MODE 0 5.15 and 5.45 ms, and the decode-gather step gains 7 %.  The encoder is 1-2 % faster with
+// MODE 0.  (Also tried, without gain for either kernel: rotating the tasks inside every run of eight
+// workgroups, shifting all tasks by a workgroup, runs of 3 to 4099 tasks per XCD in turn, and eighths
+// entered at staggered points.)
+template <int MODE>
 __device__ __forceinline__ unsigned task_block_index() {
-#if KVC_XCD_REMAP
-    const unsigned b = blockIdx.x, q = gridDim.x >> 3;
-    return b < (q << 3) ? (b & 7u) * q + (b >> 3) : b;
-#else
-    return blockIdx.x;
-#endif
+    const unsigned b = blockIdx.x;
+    if (MODE == 1) {
+        const unsigned q = gridDim.x >> 3;
+        return b < (q << 3) ? (b & 7u) * q + (b >> 3) : b;
+    }
+    return b;
 }
 
 // A value every lane of the wave holds the same copy of, moved to scalar registers: index arithmetic
@@ -395,42 +405,60 @@ __device__ __forceinline__ void emit_page(const EncodeArgs& a, const EncBook<SLO
 // reports completion and takes the next.  The grid has at most Omega workgroups, so never more than
 // Omega blocks are in flight; every workgroup leaves as soon as the queue is exhausted.
 
-// One turn of an engine: report the block of queue entry `done` (if >= 0) as complete -- make it visible,
-// count it, stamp the layer and the call whose last transfer it was -- and take the next queue entry,
-// or -1 when none is left.  Called by all threads of the workgroup; `s_slot` is a word of LDS.
+// What an engine holds between two turns: a run of consecutive queue entries.
+struct WindowTurn {
+    uint32_t first;  // index of the first queue entry
+    uint32_t count;  // entries in the run; 0 = the queue is exhausted, the engine leaves
+};
+
+// One turn of an engine: report the blocks of the run `done` as complete -- make them visible, count
+// them, stamp the layers and the call whose last transfer was among them -- and take the next run of up
+// to hdr->chunk queue entries.  Called by all threads of the workgroup; `s_turn` is two words of LDS.
+// An engine decodes the blocks of its run one after the other, so it still holds one block in flight; the
+// run only spaces out the bookkeeping, whose device-wide release (a write-back of the XCD's L2) and
+// same-address atomics cost more than decoding a block when paid per block.
 // Thread 0 does the bookkeeping between two barriers, so the single-lane region lies inside the loop
-// body and not across its back edge, and the result comes back in a scalar register: the engines' loop
+// body and not across its back edge, and the result comes back in scalar registers: the engines' loop
 // and its exit branch on the scalar unit and every wave meets every barrier with all of its lanes.  (With
 // the single-lane work at both ends of the loop body the compiler merges it across the back edge into
 // an outer loop and lets the other lanes run ahead to the next barrier: the workgroup then never
 // meets.)
-__device__ __forceinline__ int32_t window_next(const WindowArgs& w, int32_t* s_slot, int32_t done) {
-    if (done >= 0) __threadfence();  // the block's stores are visible device-wide before the counters move
+__device__ __forceinline__ WindowTurn window_next(const WindowArgs& w, uint32_t* s_turn, WindowTurn done) {
+    // every wave's stores have reached the XCD's L2 before the workgroup meets ...
+    if (done.count) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
     if (threadIdx.x == 0) {
-        if (done >= 0) {
-            atomicSub(&w.hdr->in_flight, 1u);
-            const int32_t l_rel = done / w.per_layer;
-            const long long now = max(wall_clock64(), 1ll);
-            if (atomicSub(&w.pending[l_rel], 1) == 1)
-                __hip_atomic_store(&w.notify[w.layer_begin + l_rel], now, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-            if (atomicAdd(&w.hdr->done, 1u) + 1u == w.hdr->n_issued) {  // WaitCompletion returns: NotifyGPU(ready)
-                w.notify[w.n_layers + 2] = (long long)__hip_atomic_load(&w.hdr->high_water, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                // the clock is read again: every other engine stamped its layer before it counted its block
-                __hip_atomic_store(&w.notify[w.n_layers + 3], max(wall_clock64(), 1ll), __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        const long long finished = max(wall_clock64(), 1ll);  // read before the blocks are counted
+        const unsigned int n_issued = w.hdr->n_issued;
+        unsigned int dn = 0;
+        if (done.count) {
+            // ... and one device-wide release publishes them before the counters move
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            uint32_t i = 0;
+            while (i < done.count) {  // the run's entries are in layer order: one decrement per layer met
+                const int32_t l_rel = w.queue[done.first + i] / w.per_layer;
+                uint32_t n = 1;
+                while (i + n < done.count && w.queue[done.first + i + n] / w.per_layer == l_rel) ++n;
+                if (atomicSub(&w.pending[l_rel], (int)n) == (int)n)
+                    __hip_atomic_store(&w.notify[w.layer_begin + l_rel], finished, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+                i += n;
             }
+            dn = atomicAdd(&w.hdr->done, done.count) + done.count;
         }
-        const unsigned int t = atomicAdd(&w.hdr->ticket, 1u);
-        int32_t slot = -1;
-        if (t < w.hdr->n_issued) {
-            slot = w.queue[t];
-            const unsigned int now_in = atomicAdd(&w.hdr->in_flight, 1u) + 1u;
-            atomicMax(&w.hdr->high_water, now_in);
-        }
-        *s_slot = slot;
+        const unsigned int chunk = w.hdr->chunk;
+        const unsigned int t = atomicAdd(&w.hdr->ticket, chunk);
+        // WaitCompletion returns: NotifyGPU(ready).  This clock is read after the last block was counted
+        // and every layer stamp before its block was: the stamp is the latest of the call.
+        if (done.count && dn == n_issued)
+            __hip_atomic_store(&w.notify[w.n_layers + 3], max(wall_clock64(), 1ll), __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        s_turn[0] = t;
+        s_turn[1] = t < n_issued ? min(chunk, n_issued - t) : 0u;
     }
     __syncthreads();
-    return __builtin_amdgcn_readfirstlane(*s_slot);
+    WindowTurn r;
+    r.first = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_turn[0]);
+    r.count = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_turn[1]);
+    return r;
 }
 
 // Kernels specialised at compile time for one page shape (kvc_fast.h): the host-side entry points of a

@@ -455,7 +455,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(enc_
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     fill_zigzag_lut(s_lut);
     __syncthreads();
-    const int64_t t0 = ((int64_t)task_block_index() * WAVES + wave) * PPW;
+    const int64_t t0 = ((int64_t)task_block_index<0>() * WAVES + wave) * PPW;
     TaskPos pos = task_pos(t0, a.g.ppb);
     const LanePos lp = lane_pos<P>(a.g);
     const int slot0 = wave * PPW;
@@ -744,7 +744,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_p16(DecodeArgs a) {
     __shared__ uint32_t s_ginfo[WAVES][P::kGroups];
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t t0 = ((int64_t)task_block_index() * WAVES + wave) * PPW;
+    const int64_t t0 = ((int64_t)task_block_index<1>() * WAVES + wave) * PPW;
     TaskPos pos = task_pos(t0, a.g.ppb);
     // A page's memory chain is ids -> descriptor -> payload, each a full trip to HBM.  The wave walks
     // it for all of its PPW pages side by side: every descriptor load is issued before the first is
@@ -773,39 +773,51 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_p16(DecodeArgs a) {
 
 // Transfer engines of the prefetch window (Algorithm 1: at most Omega_max transfers outstanding): a
 // workgroup takes the next issued block from the queue, its waves decode the block's pages, and the
-// completion is reported before the next block is taken.  A wave starts the descriptor and payload loads
-// of its next page before it decodes the current one.
+// completion is reported before the next block is taken.
 template <class P, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void k_decompress_window_p16(DecodeArgs a, WindowArgs w) {
     __shared__ __align__(16) uint32_t s_stage[WAVES][Slot<P::kPasses>::kWords];
     __shared__ uint32_t s_ginfo[WAVES][P::kGroups];
-    __shared__ int32_t s_slot;
+    __shared__ uint32_t s_turn[2];
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int ppb = a.g.ppb;
-    int32_t slot = window_next(w, &s_slot, -1);
-    while (slot >= 0) {
-        auto open_page = [&](int pg, DecTask& task, DecPage<P>& dp) {
-            TaskPos pos;
-            pos.blk = slot;
-            pos.pg = pg;
-            task = resolve_dec_task(a, pg < ppb ? (int64_t)slot * ppb + pg : a.n_pages, pos);
-            if (task.kind == 1) dp = dec_open<P>(a, reinterpret_cast<const uint4*>(a.desc)[task.desc_idx]);
-        };
-        DecTask cur, nxt;
-        DecPage<P> dcur, dnxt;
-        open_page(wave, cur, dcur);
-        for (int pg = wave; pg < ppb; pg += WAVES) {
-            open_page(pg + WAVES, nxt, dnxt);
-            if (cur.kind == 2) zero_page(cur.dst, a.g);
-            if (cur.kind == 1 && !dec_finish<P>(a, dcur, cur.dst, s_stage[wave], s_ginfo[wave])) {
-                if (lane == 0) atomicOr(&a.st->status, KVC_ST_CORRUPT);
+    WindowTurn none;
+    none.first = none.count = 0;
+    WindowTurn turn = window_next(w, s_turn, none);
+    while (turn.count) {
+      for (uint32_t i = 0; i < turn.count; ++i) {
+        const int32_t slot = __builtin_amdgcn_readfirstlane(w.queue[turn.first + i]);
+        // a wave takes the block's pages wave, wave + WAVES, ... four at a time: all four descriptor loads
+        // are issued before the first is looked at, then all payload loads before the first page is decoded
+        constexpr int kSide = 4;
+        for (int pg0 = wave; pg0 < ppb; pg0 += kSide * WAVES) {
+            DecTask task[kSide];
+            uint4 dw[kSide];
+            DecPage<P> dp[kSide];
+#pragma unroll
+            for (int j = 0; j < kSide; ++j) {
+                const int pg = pg0 + j * WAVES;
+                TaskPos pos;
+                pos.blk = slot;
+                pos.pg = pg;
+                task[j] = resolve_dec_task(a, pg < ppb ? (int64_t)slot * ppb + pg : a.n_pages, pos);  // past the block: no task
+                if (task[j].kind == 1) dw[j] = reinterpret_cast<const uint4*>(a.desc)[task[j].desc_idx];
             }
-            wave_sync();
-            cur = nxt;
-            dcur = dnxt;
+#pragma unroll
+            for (int j = 0; j < kSide; ++j)
+                if (task[j].kind == 1) dp[j] = dec_open<P>(a, dw[j]);
+#pragma unroll
+            for (int j = 0; j < kSide; ++j) {
+                if (task[j].kind == 2) zero_page(task[j].dst, a.g);
+                if (task[j].kind == 1 && !dec_finish<P>(a, dp[j], task[j].dst, s_stage[wave], s_ginfo[wave])) {
+                    if (lane == 0) atomicOr(&a.st->status, KVC_ST_CORRUPT);
+                }
+                wave_sync();
+            }
         }
-        slot = window_next(w, &s_slot, slot);
+      }
+      turn = window_next(w, s_turn, turn);
     }
 }
 

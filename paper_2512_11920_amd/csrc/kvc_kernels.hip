@@ -412,7 +412,7 @@ __global__ __launch_bounds__(kThreads) void k_decompress(DecodeArgs a) {
     __shared__ uint32_t s_ginfo[kWavesPerWG][MAXP * 16];
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t t0 = ((int64_t)blockIdx.x * kWavesPerWG + wave) * PPW;
+    const int64_t t0 = ((int64_t)task_block_index<1>() * kWavesPerWG + wave) * PPW;
     TaskPos pos = task_pos(t0, a.g.ppb);
     for (int i = 0; i < PPW; ++i) {
         const DecTask task = resolve_dec_task(a, t0 + i, pos);
@@ -635,15 +635,17 @@ __global__ __launch_bounds__(256) void k_window_build(WindowArgs w) {
         base += in_layer;
     }
     if (threadIdx.x == 0) {
+        const unsigned int engines = min(base, (uint32_t)w.omega);
         w.hdr->n_issued = base;
+        w.hdr->engines = engines;
+        // entries per turn: long queues space out the bookkeeping, short ones keep every engine busy
+        w.hdr->chunk = engines ? min(max(base / (4u * engines), 1u), 8u) : 1u;
         w.hdr->ticket = 0;
         w.hdr->done = 0;
-        w.hdr->in_flight = 0;
-        w.hdr->high_water = 0;
-        w.notify[w.n_layers] = now;                    // window opened
-        w.notify[w.n_layers + 1] = (long long)base;    // transfers issued
-        w.notify[w.n_layers + 2] = 0;                  // most transfers in flight at once
-        w.notify[w.n_layers + 3] = base ? 0ll : now;   // all complete
+        w.notify[w.n_layers] = now;                       // window opened
+        w.notify[w.n_layers + 1] = (long long)base;       // transfers issued
+        w.notify[w.n_layers + 2] = (long long)engines;    // engines at work: the bound on blocks in flight
+        w.notify[w.n_layers + 3] = base ? 0ll : now;      // all complete
     }
 }
 
@@ -652,23 +654,28 @@ template <int MAXP>
 __global__ __launch_bounds__(kThreads) void k_decompress_window(DecodeArgs a, WindowArgs w) {
     __shared__ __align__(16) uint32_t s_stage[kWavesPerWG][Slot<MAXP>::kWords];
     __shared__ uint32_t s_ginfo[kWavesPerWG][MAXP * 16];
-    __shared__ int32_t s_slot;
+    __shared__ uint32_t s_turn[2];
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    int32_t slot = window_next(w, &s_slot, -1);
-    while (slot >= 0) {
-        for (int pg = wave; pg < a.g.ppb; pg += kWavesPerWG) {
-            TaskPos pos;
-            pos.blk = slot;
-            pos.pg = pg;
-            const DecTask task = resolve_dec_task(a, (int64_t)slot * a.g.ppb + pg, pos);
-            if (task.kind == 2) zero_page(task.dst, a.g);
-            if (task.kind == 1 && !decode_page<MAXP>(a, task.desc_idx, task.dst, s_stage[wave], s_ginfo[wave])) {
-                if (lane == 0) atomicOr(&a.st->status, KVC_ST_CORRUPT);
+    WindowTurn none;
+    none.first = none.count = 0;
+    WindowTurn turn = window_next(w, s_turn, none);
+    while (turn.count) {
+        for (uint32_t i = 0; i < turn.count; ++i) {
+            const int32_t slot = __builtin_amdgcn_readfirstlane(w.queue[turn.first + i]);
+            for (int pg = wave; pg < a.g.ppb; pg += kWavesPerWG) {
+                TaskPos pos;
+                pos.blk = slot;
+                pos.pg = pg;
+                const DecTask task = resolve_dec_task(a, (int64_t)slot * a.g.ppb + pg, pos);
+                if (task.kind == 2) zero_page(task.dst, a.g);
+                if (task.kind == 1 && !decode_page<MAXP>(a, task.desc_idx, task.dst, s_stage[wave], s_ginfo[wave])) {
+                    if (lane == 0) atomicOr(&a.st->status, KVC_ST_CORRUPT);
+                }
+                wave_sync();
             }
-            wave_sync();
         }
-        slot = window_next(w, &s_slot, slot);
+        turn = window_next(w, s_turn, turn);
     }
 }
 

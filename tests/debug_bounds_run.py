@@ -1,0 +1,43 @@
+"""Run by tests/test_gpu_debug_bounds.py in a process of its own: the parity cases through the
+bounds-checking build of the library (libkvc_dbg.so, compiled with -DKVC_DEBUG_BOUNDS=1).  Every LDS index
+and pool span the kernels compute is then checked on the device; a violation sets status bit 8."""
+import os
+import sys
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+from paper_2512_11920_amd import build, kvc  # noqa: E402
+
+kvc.LIB_PATH = build.LIB_DEBUG
+from oracle import kvc_oracle as o  # noqa: E402
+import test_gpu_differential as td  # noqa: E402
+import test_gpu_parity as tp  # noqa: E402
+
+DEV = "cuda:0"
+n_cases = 0
+for N, d in ((16, 128), (16, 64), (16, 256), (16, 96), (16, 224), (8, 192), (32, 32), (8, 32), (5, 160)):
+    rng = np.random.default_rng(900 + N + d)
+    special = tp._special_pages(N, d, rng)
+    families, _ = td._families(rng, 1500, N, d)
+    x = np.concatenate([special, families])
+    for scheme in ((3, 2, 4, 5) if (N == 16 and d in (128, 256)) else (3, 2, 4)):
+        print(f"[case] bounds-checking build N={N} d={d} scheme={scheme} pages={x.shape[0]}", flush=True)
+        xt = torch.from_numpy(x.reshape(-1, 1, N, d)).to(DEV)
+        c = kvc.Codec(N, d, 1, scheme)
+        c.alloc_pool(x.shape[0], x.shape[0] * N * d * 2 + 64, DEV)
+        c.compress_blocks(xt)
+        out = torch.empty_like(xt)
+        c.decompress_blocks(out)
+        st = c.stats()
+        assert st["status"] == 0, f"status {st['status']:#x}: bit 8 = an index or span left its bounds"
+        od, op = o.compress_pages(x.view(np.uint16), N, d, scheme, n_threads=8)
+        desc = c.desc_numpy()
+        assert np.array_equal(desc["mode"], od["mode"]) and np.array_equal(desc["n16"], od["n16"])
+        want, bad = o.decompress_pages(op, od, N, d, n_threads=8)
+        assert bad == 0 and np.array_equal(out.cpu().numpy().view(np.uint16).reshape(-1, N, d), want)
+        n_cases += 1
+print(f"debug-bounds ok: {n_cases} cases", flush=True)

@@ -421,6 +421,30 @@ __device__ __forceinline__ void encode_into_slot(const EncodeArgs& a, const uint
     }
 }
 
+#ifndef KVC_PPW5
+#define KVC_PPW5 3
+#endif
+#ifndef KVC_PPW6
+#define KVC_PPW6 3
+#endif
+#ifndef KVC_PPW7
+#define KVC_PPW7 2
+#endif
+#ifndef KVC_PPW8
+#define KVC_PPW8 2
+#endif
+#ifndef KVC_RING5
+#define KVC_RING5 3
+#endif
+#ifndef KVC_RING6
+#define KVC_RING6 3
+#endif
+#ifndef KVC_RING7
+#define KVC_RING7 2
+#endif
+#ifndef KVC_ENC_WAVES_LONG
+#define KVC_ENC_WAVES_LONG 4
+#endif
 #ifndef KVC_ENC_MIN_WAVES
 #define KVC_ENC_MIN_WAVES 4
 #endif
@@ -432,7 +456,7 @@ __device__ __forceinline__ void encode_into_slot(const EncodeArgs& a, const uint
 // nothing.
 // The run-time-scheme instantiation needs more registers for itself: at seven passes it keeps one page.
 constexpr int enc_ring_max(int np, int scheme) {
-    return np <= 2 ? 8 : np <= 3 ? 5 : np <= 4 ? 4 : np <= 5 ? 3 : np <= 6 ? 2 : (np == 7 && scheme >= 0) ? 2 : 1;
+    return np <= 2 ? 8 : np <= 3 ? 5 : np <= 4 ? 4 : np <= 5 ? KVC_RING5 : np <= 6 ? KVC_RING6 : (np == 7 && scheme >= 0) ? KVC_RING7 : 1;
 }
 
 // (four waves per SIMD is what the LDS slots allow anyway: keep every instantiation within 128 VGPRs; the
@@ -824,7 +848,9 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_window_p16(DecodeArgs
 // Launch shapes by page size (NP passes of 1 KB): waves per workgroup, pages per wave.
 constexpr int kFastWaves = 4;
 // large calls: about 64 KB of input per workgroup and one pool-cursor atomic for it
-constexpr int enc_ppw_large(int np) { return np == 1 ? 16 : np == 2 ? 8 : np == 3 ? 5 : np == 4 ? 4 : np == 5 ? 3 : 2; }
+constexpr int enc_ppw_large(int np) { return np == 1 ? 16 : np == 2 ? 8 : np == 3 ? 5 : np == 4 ? 4 : np == 5 ? KVC_PPW5 : np == 6 ? KVC_PPW6 : np == 7 ? KVC_PPW7 : KVC_PPW8; }
+// waves per encoder workgroup in large calls
+constexpr int enc_waves_large(int np) { return np >= 5 ? KVC_ENC_WAVES_LONG : 4; }
 // A small call (a decode step's offload of a few blocks) is latency: one page per wave (more only for
 // the smallest pages), so the pages are encoded side by side instead of several in a row.  The cursor
 // then takes an atomic per four pages, which only a large call would feel.
@@ -836,8 +862,8 @@ constexpr int dec_ppw(int np) { return np == 1 ? 4 : np == 2 ? 2 : 1; }
 #define KVC_ENC_SMALL_PAGES 2048
 #endif
 
-inline dim3 fast_grid(int64_t n_pages, int ppw) {
-    const int64_t per_wg = (int64_t)kFastWaves * ppw;
+inline dim3 fast_grid(int64_t n_pages, int ppw, int waves = kFastWaves) {
+    const int64_t per_wg = (int64_t)waves * ppw;
     return dim3((unsigned)((n_pages + per_wg - 1) / per_wg));
 }
 
@@ -851,7 +877,8 @@ struct FastOps {
         const dim3 block(kFastWaves * 64);
         if (a.n_pages <= KVC_ENC_SMALL_PAGES)
             return launch_kernel(k_compress_p16<P, kFastWaves, enc_ppw_small(NP), SCHEME>, fast_grid(a.n_pages, enc_ppw_small(NP)), block, s, a);
-        return launch_kernel(k_compress_p16<P, kFastWaves, enc_ppw_large(NP), SCHEME>, fast_grid(a.n_pages, enc_ppw_large(NP)), block, s, a);
+        constexpr int W = enc_waves_large(NP);
+        return launch_kernel(k_compress_p16<P, W, enc_ppw_large(NP), SCHEME>, fast_grid(a.n_pages, enc_ppw_large(NP), W), dim3(W * 64), s, a);
     }
 
     static hipError_t compress(const EncodeArgs& a, hipStream_t s) {

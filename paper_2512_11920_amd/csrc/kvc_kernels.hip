@@ -17,34 +17,16 @@
 
 namespace kvc {
 
-__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = max(v, (uint32_t)__shfl_xor((int)v, o));
-    return v;
-}
-
-__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
-    const int lane = lane_id();
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        uint32_t t = (uint32_t)__shfl_up((int)v, o);
-        if (lane >= o) v += t;
-    }
-    return v;
-}
-
 // Inclusive prefix over the lanes of one token row.  Rows are runs of lpr <= 32 lanes that may begin
-// anywhere, also in the pass before this one: r = the lane's position in its row; a lane with r > lane
-// belongs to a row that began in the previous pass and adds `carry`, that pass's value at lane 63.
+// anywhere, also in the pass before this one: r = the lane's position in its row.  Prefix over the whole
+// wave, minus its value just before the row's first lane; a lane with r > lane belongs to a row that
+// began in the previous pass and adds `carry`, that pass's value at lane 63.
 __device__ __forceinline__ uint32_t row_incl_scan_u32(uint32_t v, uint32_t r, uint32_t carry) {
-    const uint32_t lane = (uint32_t)lane_id();
-    uint32_t incl = v;
-#pragma unroll
-    for (uint32_t o = 1; o < 32; o <<= 1) {
-        uint32_t t = (uint32_t)__shfl_up((int)incl, (int)o);
-        if (r >= o && lane >= o) incl += t;
-    }
-    return r > lane ? incl + carry : incl;
+    const int lane = lane_id();
+    const uint32_t S = wave_incl_scan_dpp(v);
+    const int start = lane - (int)r;  // first lane of this lane's row (< 0: in the pass before)
+    const uint32_t before = (uint32_t)__builtin_amdgcn_ds_bpermute((start > 0 ? start - 1 : 0) << 2, (int)S);
+    return start > 0 ? S - before : (start < 0 ? S + carry : S);
 }
 
 __device__ __forceinline__ float half_bits_to_float(uint32_t h) {
@@ -124,7 +106,7 @@ __device__ PageResult encode_page(const uint16_t* __restrict__ src, const Geomet
             m = max(m, max(a & 0xFFFFu, a >> 16));
         }
     }
-    m = wave_max_u32(m);
+    m = wave_max_dpp(m);
     PageResult r;
     if (scheme == KVC_MODE_RAW || m >= 0x7C00u) {  // requested, or a NaN/Inf is present: bypass
         r.n16 = (uint32_t)(E >> 3);
@@ -158,8 +140,7 @@ __device__ PageResult encode_page(const uint16_t* __restrict__ src, const Geomet
             int q[8];
             quantize8(raw[p], s_inv, q);
             // delta along the channel index; the first column of a token row is kept verbatim
-            int prev = __shfl_up(q[7], 1);
-            if (lane == 0) prev = q_last;
+            int prev = (int)dpp<0x138>((uint32_t)q_last, (uint32_t)q[7]);  // wave_shr:1; lane 0 keeps the pass before's last code
             if (lane_in_row(g, (uint32_t)(p * 64 + lane)) == 0) prev = 0;
             q_last = __builtin_amdgcn_readlane(q[7], 63);
             uint32_t u[8];
@@ -178,10 +159,10 @@ __device__ PageResult encode_page(const uint16_t* __restrict__ src, const Geomet
                 umin = min(umin, u[k]);
             }
             // a group of 32 is a quad of lanes
-            umax = max(umax, (uint32_t)__shfl_xor((int)umax, 1));
-            umin = min(umin, (uint32_t)__shfl_xor((int)umin, 1));
-            umax = max(umax, (uint32_t)__shfl_xor((int)umax, 2));
-            umin = min(umin, (uint32_t)__shfl_xor((int)umin, 2));
+            umax = max(umax, dpp<0xB1>(0, umax));  // quad_perm [1,0,3,2]
+            umin = min(umin, dpp<0xB1>(0xFFu, umin));
+            umax = max(umax, dpp<0x4E>(0, umax));  // quad_perm [2,3,0,1]
+            umin = min(umin, dpp<0x4E>(0xFFu, umin));
             uint32_t c;
             const bool runs = scheme != KVC_MODE_DELTA;  // zero-run and run packets
             if (runs && umax == 0)
@@ -192,12 +173,15 @@ __device__ PageResult encode_page(const uint16_t* __restrict__ src, const Geomet
                 c = max(1u, 32u - (uint32_t)__clz((int)umax));
             if (!act) c = 0;
             const uint32_t size = (c == 0) ? 0u : (c == 9 ? 1u : 4u * c);
-            const uint32_t incl = wave_incl_scan_u32((lane & 3) == 0 ? size : 0u);
+            const uint32_t incl = quad_incl_scan_dpp(size);  // size is the same in the four lanes of a group
             const uint32_t off = run + incl - size;
-            run += (uint32_t)__shfl((int)incl, 63);
-            // header: two 4-bit codes per byte, even group in the low nibble
-            const uint32_t c_next = (uint32_t)__shfl_down((int)c, 4);
-            if (act && (lane & 7) == 0) stage8[(p * 16 + (lane >> 2)) >> 1] = (uint8_t)(c | (c_next << 4));
+            run += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+            // header: two 4-bit codes per byte, even group in the low nibble.  Lane 4j+i votes bit i of
+            // group j's code, so the ballot is the pass's eight header bytes; a lane per byte writes its own
+            // (bytes, not dwords: a short page's header ends where its first body begins)
+            const uint64_t hb = __builtin_amdgcn_ballot_w64(((c >> (lane & 3)) & 1u) != 0);
+            if (act && (lane & 7) == 0)
+                stage8[(p * 16 + (lane >> 2)) >> 1] = (uint8_t)(lane < 32 ? (uint32_t)hb >> lane : (uint32_t)(hb >> 32) >> (lane - 32));
             // body: this lane's 8 values are bytes [qi*w, qi*w + w) of the group's bit string
             uint2 W = make_uint2(0u, 0u);
             uint32_t B = hdr + off;
@@ -207,12 +191,12 @@ __device__ PageResult encode_page(const uint16_t* __restrict__ src, const Geomet
             } else if (c == 9) {
                 W.x = (lane & 3) == 0 ? u[0] : 0;
             }
-            if ((W.x | W.y) != 0) {
-                uint32_t* p0 = stage + (B >> 2);
+            {
+                uint32_t* p0 = stage + (B >> 2);  // inside the slot for every lane (the slot has slack beyond the payload)
                 uint32_t d0, d1, d2;
                 shl_bytes(W, B, d0, d1, d2);
-                if (d0) atomicOr(p0, d0);
-                if (d1) atomicOr(p0 + 1, d1);
+                atomicOr(p0, d0);
+                atomicOr(p0 + 1, d1);
                 if (d2) atomicOr(p0 + 2, d2);
             }
         }
@@ -341,9 +325,9 @@ __device__ bool decode_page(const DecodeArgs& a, uint64_t d_idx, uint16_t* __res
             if (c > 9 || (mode == KVC_MODE_DELTA && (c == 0 || c == 9))) bad = true;
         }
         const uint32_t size = (c == 0) ? 0u : (c == 9 ? 1u : 4u * c);
-        const uint32_t incl = wave_incl_scan_u32(size);
+        const uint32_t incl = wave_incl_scan_dpp(size);
         if (gi < G) ginfo[gi] = ((run + incl - size) << 4) | c;
-        run += (uint32_t)__shfl((int)incl, 63);
+        run += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
     }
     if (__any(bad) || (((uint32_t)hdr + run + 15u) >> 4) != n16) {
         zero_page(dst, a.g);
@@ -368,14 +352,13 @@ __device__ bool decode_page(const DecodeArgs& a, uint64_t d_idx, uint16_t* __res
                 const uint32_t sh = (B & 3u) * 8u;
                 const uint32_t* p0 = stage + (B >> 2);
                 const uint32_t d0 = p0[0], d1 = p0[1], d2 = p0[2];
-                const uint32_t lo = sh ? (d0 >> sh) | (d1 << (32u - sh)) : d0;
-                const uint32_t hi = sh ? (d1 >> sh) | (d2 << (32u - sh)) : d1;
+                const uint32_t lo = __builtin_amdgcn_alignbit(d1, d0, sh);  // (d1 : d0) >> sh, sh a multiple of 8 below 32
+                const uint32_t hi = __builtin_amdgcn_alignbit(d2, d1, sh);
                 const uint32_t mid = shr_nibbles(lo, hi, c);  // values 4..7 start at bit 4c
-                const uint32_t mask = (1u << c) - 1u;
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
-                    u[k] = (lo >> (k * c)) & mask;
-                    u[4 + k] = (mid >> (k * c)) & mask;
+                    u[k] = __builtin_amdgcn_ubfe(lo, (uint32_t)k * c, c);
+                    u[4 + k] = __builtin_amdgcn_ubfe(mid, (uint32_t)k * c, c);
                 }
             } else {
                 const uint32_t v = (c == 9) ? stage8[hdr + goff] : 0u;

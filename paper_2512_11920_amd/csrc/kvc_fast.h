@@ -454,9 +454,9 @@ __device__ __forceinline__ void encode_into_slot(const EncodeArgs& a, const uint
 // per wave, no loop) for pages of up to four passes; a page is 4 registers per pass, so longer pages
 // take turns in fewer sets, and at eight passes a second page in registers costs occupancy and gains
 // nothing.
-// The run-time-scheme instantiation needs more registers for itself: at seven passes it keeps one page.
+// The run-time-scheme instantiation needs more registers for itself: from six passes on it keeps one page.
 constexpr int enc_ring_max(int np, int scheme) {
-    return np <= 2 ? 8 : np <= 3 ? 5 : np <= 4 ? 4 : np <= 5 ? KVC_RING5 : np <= 6 ? KVC_RING6 : (np == 7 && scheme >= 0) ? KVC_RING7 : 1;
+    return np <= 2 ? 8 : np <= 3 ? 5 : np <= 4 ? 4 : np <= 5 ? KVC_RING5 : (np == 6 && scheme >= 0) ? KVC_RING6 : (np == 7 && scheme >= 0) ? KVC_RING7 : 1;
 }
 
 // (four waves per SIMD is what the LDS slots allow anyway: keep every instantiation within 128 VGPRs; the

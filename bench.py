@@ -54,14 +54,16 @@ def read_traffic(tag: str, kernel: str):
     p = os.path.join(ROOT, rel)
     if not os.path.exists(p):
         return None, {"file": None, "note": "no rocprofv3 --pmc summary is committed for this workload"}
-    val, fp = None, None
+    val, fp, name = None, None, None
     for line in open(p):
-        if line.startswith(f"{kernel}_traffic_bytes:"):
-            val = int(float(line.split(":")[1].split()[0]))
+        # `kernel` is k_compress or k_decompress; the summary names the kernel that ran (k_compress_fast, or
+        # k_compress for a page shape served by the generic kernels)
+        if line.startswith(kernel) and "_traffic_bytes:" in line:
+            name, val = line.split("_traffic_bytes:")[0], int(float(line.split(":")[1].split()[0]))
         if line.startswith("kernel_fingerprint:"):
             fp = line.split(":")[1].strip()
     now = kernel_fingerprint()
-    src = {"file": rel, "profile_kernel_fingerprint": fp, "current_kernel_fingerprint": now}
+    src = {"file": rel, "kernel": name, "profile_kernel_fingerprint": fp, "current_kernel_fingerprint": now}
     if fp != now:
         src["note"] = "summary was taken on other kernel sources: not used"
         return None, src
@@ -274,9 +276,11 @@ def main():
         v["frac_of_copy"] = v["hbm_GBps"] / copy_gbps
 
     dom = "compress" if t_c >= t_d else "decompress"
-    kname = {"compress": "k_compress_p16", "decompress": "k_decompress_p16"}[dom]
     tag = shape.name + (f"_scheme{args.scheme}" if args.scheme != 3 else "")
-    traffic, traffic_source = (None, {"file": None, "note": "layer count overridden"}) if args.layers else read_traffic(tag, kname)
+    traffic, traffic_source = (None, {"file": None, "note": "layer count overridden"}) if args.layers else read_traffic(tag, "k_" + dom)
+    # the kernel behind the entry point: the one specialised for the page shape (all benchmark configurations),
+    # or the generic one for odd shapes; the committed profile of the workload names it
+    kname = traffic_source.get("kernel") or f"k_{dom}_fast"
     res = {
         "metric": "KV codec GB/s (uncompressed fp16) compress+decompress; % of HBM peak",
         "value": round((2 * unc + g_unc) / (ms_step * 1e-3) / 1e9, 2),
@@ -360,7 +364,7 @@ def bench_decode_gather(args):
     mean_payload = st["payload_bytes"] / sum(st["pages"])
     alg = unc + n_pages * (mean_payload + 16) + 8 * n_out
     ms = (t1 - t0) * 1e3 / args.steps
-    dg_traffic, dg_source = read_traffic("decode_gather" + (f"_scheme{args.scheme}" if args.scheme != 3 else ""), "k_decompress_p16")
+    dg_traffic, dg_source = read_traffic("decode_gather" + (f"_scheme{args.scheme}" if args.scheme != 3 else ""), "k_decompress")
     res = {
         "metric": "KV codec GB/s (uncompressed fp16) gather-decompress; % of HBM peak",
         "value": round(unc / (ms * 1e-3) / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
@@ -369,7 +373,7 @@ def bench_decode_gather(args):
         "config": {"workload": f"decode_gather: 80 layers x 8 KV heads x 128, 64 sequences U[512,8192], "
                                f"8 predicted blocks/seq/layer, {n_pages} pages = {unc / 1e9:.2f} GB out per step",
                    "ratio": round(codec.ratio(), 4)},
-        "roofline": {"bound": "hbm", "kernel": "k_decompress_p16", "achieved": round(alg / ts.mean() / 1e6, 1),
+        "roofline": {"bound": "hbm", "kernel": "k_decompress_fast", "achieved": round(alg / ts.mean() / 1e6, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(alg / ts.mean() / 1e6 / HBM_PEAK_GBS, 4),
                      "traffic": dg_traffic, "traffic_source": dg_source, "alg_bytes_per_launch": int(alg),
                      "launch_ms": round(float(ts.mean()), 4)},

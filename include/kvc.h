@@ -8,7 +8,9 @@
  * (CXL) tier of the paper is a second buffer in the same GPU's HBM.
  *
  * Geometry.  A PAGE is N tokens x d channels of one KV head, FP16, row-major (N*d*2 bytes; 16 x 128
- * gives the paper's 4 KB page).  A BLOCK is `pages_per_block` pages (all KV heads, or K and V of all
+ * gives the paper's 4 KB page).  Any N >= 1 and any d that is a multiple of 32 up to 256 with N*d <= 4096 is
+ * accepted; pages that are a whole number of 512-element passes with N in {8, 16, 32} (every d at N = 16)
+ * run on kernels specialised for their shape, the rest on slower generic kernels.  A BLOCK is `pages_per_block` pages (all KV heads, or K and V of all
  * heads, of one 16-token block).  A cache buffer is FP16 [n_blocks][ppb][N][d] unless
  * kvc_set_cache_layout gives other strides.
  *
@@ -97,7 +99,7 @@ typedef struct {
 
 typedef struct {
     int32_t tokens_per_block; /* N >= 1 */
-    int32_t head_dim;         /* d in {32, 64, 128, 256};  N*d <= 4096 */
+    int32_t head_dim;         /* d: a multiple of 32, 32..256;  N*d <= 4096 */
     int32_t pages_per_block;  /* ppb >= 1 */
     int32_t scheme;           /* mode requested from compress: 0..5 (5: N = 16, d = 128 or 256 only, else KVC_ERR_UNSUPPORTED) */
 } kvc_config;

@@ -297,7 +297,7 @@ __device__ __forceinline__ void load_page(const EncodeArgs& a, const EncTask& ta
 // compile-time SCHEME when that is >= 0 (one mode for the whole launch: its branches fold away), else
 // the wave-uniform run-time value.
 template <class P, int SCHEME>
-__device__ __forceinline__ PageResult encode_p16(const uint4 (&raw)[P::kPasses], const LanePos& lp, int scheme_rt, uint32_t* stage,
+__device__ __forceinline__ PageResult encode_page_fast(const uint4 (&raw)[P::kPasses], const LanePos& lp, int scheme_rt, uint32_t* stage,
                                                  const uint8_t* lut, DevState* st) {
     const int scheme = SCHEME >= 0 ? SCHEME : scheme_rt;
     constexpr int kE = P::kE, kHdr = P::kHdr, NP = P::kPasses;
@@ -411,7 +411,7 @@ __device__ __forceinline__ void encode_into_slot(const EncodeArgs& a, const uint
     r.n16 = 0;
     r.mode = KVC_MODE_INVALID;
     r.scale = 0.0f;
-    if (task.desc_idx >= 0) r = encode_p16<P, SCHEME>(raw, lp, task.scheme, stage, lut, a.st);
+    if (task.desc_idx >= 0) r = encode_page_fast<P, SCHEME>(raw, lp, task.scheme, stage, lut, a.st);
     if (lane_id() == 0) {
         book.n16[slot] = r.n16;
         book.mode[slot] = r.mode;
@@ -467,7 +467,7 @@ constexpr int enc_min_waves() {
     return ((P::kD == 256 && SCHEME == KVC_MODE_CHAN) || (P::kPasses >= 7 && !P::kAligned && SCHEME < 0)) ? 3 : KVC_ENC_MIN_WAVES;
 }
 template <class P, int WAVES, int PPW, int SCHEME>
-__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(enc_min_waves<P, SCHEME>()))) void k_compress_p16(EncodeArgs a) {
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(enc_min_waves<P, SCHEME>()))) void k_compress_fast(EncodeArgs a) {
     constexpr int kSlots = WAVES * PPW;
     constexpr int NP = P::kPasses;
     constexpr bool CHAN = SCHEME == KVC_MODE_CHAN;
@@ -763,7 +763,7 @@ __device__ __forceinline__ bool dec_finish(const DecodeArgs& a, const DecPage<P>
 }
 
 template <class P, int WAVES, int PPW>
-__global__ __launch_bounds__(WAVES * 64) void k_decompress_p16(DecodeArgs a) {
+__global__ __launch_bounds__(WAVES * 64) void k_decompress_fast(DecodeArgs a) {
     __shared__ __align__(16) uint32_t s_stage[WAVES][Slot<P::kPasses>::kWords];
     __shared__ uint32_t s_ginfo[WAVES][P::kGroups];
     const int lane = lane_id();
@@ -799,7 +799,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_p16(DecodeArgs a) {
 // workgroup takes the next issued block from the queue, its waves decode the block's pages, and the
 // completion is reported before the next block is taken.
 template <class P, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void k_decompress_window_p16(DecodeArgs a, WindowArgs w) {
+__global__ __launch_bounds__(WAVES * 64) void k_decompress_window_fast(DecodeArgs a, WindowArgs w) {
     __shared__ __align__(16) uint32_t s_stage[WAVES][Slot<P::kPasses>::kWords];
     __shared__ uint32_t s_ginfo[WAVES][P::kGroups];
     __shared__ uint32_t s_turn[2];
@@ -876,9 +876,9 @@ struct FastOps {
     static hipError_t compress_scheme(const EncodeArgs& a, hipStream_t s) {
         const dim3 block(kFastWaves * 64);
         if (a.n_pages <= KVC_ENC_SMALL_PAGES)
-            return launch_kernel(k_compress_p16<P, kFastWaves, enc_ppw_small(NP), SCHEME>, fast_grid(a.n_pages, enc_ppw_small(NP)), block, s, a);
+            return launch_kernel(k_compress_fast<P, kFastWaves, enc_ppw_small(NP), SCHEME>, fast_grid(a.n_pages, enc_ppw_small(NP)), block, s, a);
         constexpr int W = enc_waves_large(NP);
-        return launch_kernel(k_compress_p16<P, W, enc_ppw_large(NP), SCHEME>, fast_grid(a.n_pages, enc_ppw_large(NP), W), dim3(W * 64), s, a);
+        return launch_kernel(k_compress_fast<P, W, enc_ppw_large(NP), SCHEME>, fast_grid(a.n_pages, enc_ppw_large(NP), W), dim3(W * 64), s, a);
     }
 
     static hipError_t compress(const EncodeArgs& a, hipStream_t s) {
@@ -896,11 +896,11 @@ struct FastOps {
     }
 
     static hipError_t decompress(const DecodeArgs& a, hipStream_t s) {
-        return launch_kernel(k_decompress_p16<P, kFastWaves, dec_ppw(NP)>, fast_grid(a.n_pages, dec_ppw(NP)), dim3(kFastWaves * 64), s, a);
+        return launch_kernel(k_decompress_fast<P, kFastWaves, dec_ppw(NP)>, fast_grid(a.n_pages, dec_ppw(NP)), dim3(kFastWaves * 64), s, a);
     }
 
     static hipError_t decompress_window(const DecodeArgs& a, const WindowArgs& w, unsigned grid, hipStream_t s) {
-        return launch_kernel(k_decompress_window_p16<P, kFastWaves>, dim3(grid), dim3(kFastWaves * 64), s, a, w);
+        return launch_kernel(k_decompress_window_fast<P, kFastWaves>, dim3(grid), dim3(kFastWaves * 64), s, a, w);
     }
 
     static constexpr FastKernels kTable = {P::kN, D, &compress, &decompress, &decompress_window};

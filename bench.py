@@ -32,14 +32,14 @@ def log(msg):
 
 
 def kernel_fingerprint() -> str:
-    """Identifies the kernel sources a measurement belongs to: SHA-256 over the files of csrc/ and the
-    public header (names and contents), first 16 hex digits.  The profile summaries carry the value they
-    were taken on."""
+    """Identifies the kernel sources a measurement belongs to: SHA-256 over the files of csrc/ (kernels and
+    the host code that launches them; names and contents), first 16 hex digits.  The profile summaries
+    carry the value of the run they were taken from."""
     import hashlib
 
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2512_11920_amd", "csrc")
-    for path in sorted(os.path.join(csrc, f) for f in os.listdir(csrc)) + [os.path.join(ROOT, "include", "kvc.h")]:
+    for path in sorted(os.path.join(csrc, f) for f in os.listdir(csrc)):
         h.update(os.path.basename(path).encode() + b"\0")
         h.update(open(path, "rb").read())
     return h.hexdigest()[:16]

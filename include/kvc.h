@@ -246,6 +246,13 @@ int kvc_prefetch_layers_window_static(kvc_ctx* ctx, void* d_l2, int32_t* d_tags,
  * (out is filled either way), else 0. */
 int kvc_stats(kvc_ctx* ctx, kvc_stats_t* out, void* stream);
 
+const char* kvc_strerror(int code);
+
+/* ---- Verification and measurement hooks -------------------------------------------------------
+ * The two calls below are not steps of the codec path and no codec call depends on them.  They exist so
+ * that a test can check the encoder's scale arithmetic exhaustively and so that a benchmark can time a
+ * plain copy with the codec's access shape on the same device, through the same library. */
+
 /* The scaling step of Algorithm 2 on its own: for n page maxima given as FP16 bit patterns (sign
  * ignored) write s = amax / 127 and s_inv = 1 / s as the encoder computes them (binary32); 0, Inf
  * and NaN give 0 for both.  All three arrays are device memory.  The encoder does not use IEEE
@@ -257,8 +264,6 @@ int kvc_page_scales(const uint16_t* d_amax, float* d_scale, float* d_scale_inv, 
  * nbytes a multiple of 16 and at most 2^38 - 4096 (else KVC_ERR_ARG); both pointers device memory, 16-byte
  * aligned, not overlapping.  The bandwidth yardstick the codec kernels are compared with. */
 int kvc_copy_bytes(void* d_dst, const void* d_src, uint64_t nbytes, void* stream);
-
-const char* kvc_strerror(int code);
 
 #ifdef __cplusplus
 }

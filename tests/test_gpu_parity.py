@@ -347,6 +347,15 @@ def test_host_side_argument_errors():
     assert e.value.code == kvc.ERR_ARG
     c.compress_blocks(x, n=0)
     assert c.stats()["pages_invalid"] == 4
+    # one call handles at most 2^26 - 4 pages: beyond that the host refuses before anything is launched
+    # (the counts below are only numbers to the host checks; no buffer of that size exists or is touched)
+    L = kvc.load()
+    big = kvc.Codec(16, 128, 4, 3)
+    assert L.kvc_bind_pool(big._ctx, c.pool.data_ptr(), c.pool.numel(), c.desc.data_ptr(), 1 << 27) == kvc.OK
+    n_over = (1 << 24)  # blocks of 4 pages: 2^26 pages
+    assert L.kvc_compress_blocks(big._ctx, x.data_ptr(), n_over, None, None, n_over, None) == kvc.ERR_ARG
+    assert L.kvc_decompress_blocks(big._ctx, x.data_ptr(), n_over, None, None, n_over, None) == kvc.ERR_ARG
+    assert L.kvc_copy_bytes(x.data_ptr(), x.data_ptr(), (1 << 38) - 4096 + 16, None) == kvc.ERR_ARG
 
 
 def test_per_block_scheme_selection():

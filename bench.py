@@ -56,8 +56,7 @@ def read_traffic(tag: str, kernel: str):
         return None, {"file": None, "note": "no rocprofv3 --pmc summary is committed for this workload"}
     val, fp, name = None, None, None
     for line in open(p):
-        # `kernel` is k_compress or k_decompress; the summary names the kernel that ran (k_compress_fast, or
-        # k_compress for a page shape served by the generic kernels)
+        # `kernel` is k_compress or k_decompress; the summary names the kernel that ran (k_compress_fast, ...)
         if line.startswith(kernel) and "_traffic_bytes:" in line:
             name, val = line.split("_traffic_bytes:")[0], int(float(line.split(":")[1].split()[0]))
         if line.startswith("kernel_fingerprint:"):
@@ -278,8 +277,7 @@ def main():
     dom = "compress" if t_c >= t_d else "decompress"
     tag = shape.name + (f"_scheme{args.scheme}" if args.scheme != 3 else "")
     traffic, traffic_source = (None, {"file": None, "note": "layer count overridden"}) if args.layers else read_traffic(tag, "k_" + dom)
-    # the kernel behind the entry point: the one specialised for the page shape (all benchmark configurations),
-    # or the generic one for odd shapes; the committed profile of the workload names it
+    # the kernel behind the entry point; the committed profile of the workload names it
     kname = traffic_source.get("kernel") or f"k_{dom}_fast"
     res = {
         "metric": "KV codec GB/s (uncompressed fp16) compress+decompress; % of HBM peak",

@@ -9,9 +9,10 @@
  *
  * Geometry.  A PAGE is N tokens x d channels of one KV head, FP16, row-major (N*d*2 bytes; 16 x 128
  * gives the paper's 4 KB page).  Any N >= 1 and any d that is a multiple of 32 up to 256 with N*d <= 4096 is
- * accepted; pages that are a whole number of 512-element passes with N in {8, 16, 32} (every d at N = 16)
- * run on kernels specialised for their shape, the rest on slower generic kernels.  A BLOCK is `pages_per_block` pages (all KV heads, or K and V of all
- * heads, of one 16-token block).  A cache buffer is FP16 [n_blocks][ppb][N][d] unless
+ * accepted.  The kernels are compiled per channel count and page length; pages that are a whole number of
+ * 512-element passes with N in {8, 16, 32} (every d at N = 16) have instantiations of their own, other token
+ * counts run on ones that read N at run time (a little slower).  A BLOCK is `pages_per_block` pages (all KV
+ * heads, or K and V of all heads, of one 16-token block).  A cache buffer is FP16 [n_blocks][ppb][N][d] unless
  * kvc_set_cache_layout gives other strides.
  *
  * Compressed form of a page = one 16-byte descriptor (kvc_desc) + a payload of n16*16 bytes in

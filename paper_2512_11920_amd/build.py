@@ -12,7 +12,7 @@ import sys
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
 _CSRC = os.path.join(_PKG, "csrc")
-FAST_GROUPS = 8  # see csrc/kvc_fast.hip
+FAST_GROUPS = 16  # see csrc/kvc_fast.hip
 #: (source, extra defines, object name)
 UNITS = [("kvc_kernels.hip", (), "kvc_kernels.o"), ("kvc_api.hip", (), "kvc_api.o")] + \
         [("kvc_fast.hip", (f"-DKVC_FAST_GROUP={g}",), f"kvc_fast_{g}.o") for g in range(FAST_GROUPS)]

@@ -80,10 +80,9 @@ int kvc_create(kvc_ctx** out, const kvc_config* cfg) {
     c->g.E = cfg->tokens_per_block * cfg->head_dim;
     c->g.lpr = cfg->head_dim / 8;
     c->g.d_magic = ((1u << 22) + (uint32_t)cfg->head_dim - 1) / (uint32_t)cfg->head_dim;
-    c->g.lpr_magic = ((1u << 16) + (uint32_t)c->g.lpr - 1) / (uint32_t)c->g.lpr;
-    // the kernels divide by d and by d / 8 with these multipliers: they must be exact over the whole range
+    // the kernels divide by d with this multiplier: it must be exact over the whole range
     for (uint32_t e = 0; e < 8192; ++e)
-        if (((e * c->g.d_magic) >> 22) != e / (uint32_t)cfg->head_dim || (e < 1024 && ((e * c->g.lpr_magic) >> 16) != e / (uint32_t)c->g.lpr)) {
+        if (((e * c->g.d_magic) >> 22) != e / (uint32_t)cfg->head_dim) {
             delete c;
             return KVC_ERR_UNSUPPORTED;
         }

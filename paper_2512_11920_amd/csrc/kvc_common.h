@@ -21,7 +21,6 @@ struct Geometry {
     int32_t N, d, ppb, E;  // E = N*d elements per page
     int32_t lpr;           // lanes per token row: d / 8 (a lane owns 8 channels)
     uint32_t d_magic;      // ceil(2^22 / d):   e / d   == (e * d_magic) >> 22   for e < 8192
-    uint32_t lpr_magic;    // ceil(2^16 / lpr): i / lpr == (i * lpr_magic) >> 16 for i < 1024
     int64_t row_stride, page_stride, block_stride;
 };
 

@@ -147,11 +147,6 @@ __device__ __forceinline__ int64_t elem_off(const Geometry& g, int e) {
     return (int64_t)row * g.row_stride + ((uint32_t)e - row * (uint32_t)g.d);
 }
 
-// position of lane `gl` (counted from the page's first lane, 8 channels per lane) inside its token row
-__device__ __forceinline__ uint32_t lane_in_row(const Geometry& g, uint32_t gl) {
-    return gl - ((gl * g.lpr_magic) >> 16) * (uint32_t)g.lpr;
-}
-
 // Workgroup index used for task assignment.  Workgroups are dealt round-robin to the 8 XCDs, so with
 // the identity deal (MODE 0) XCD k works on the tasks whose index is k modulo 8 for the whole launch: all
 // XCDs sweep the buffers side by side, 16 KB apart.  MODE 1 gives each XCD one contiguous eighth of the
@@ -461,24 +456,25 @@ __device__ __forceinline__ WindowTurn window_next(const WindowArgs& w, uint32_t*
     return r;
 }
 
-// Kernels specialised at compile time for one page shape (kvc_fast.h): the host-side entry points of a
-// geometry.  fast_kernels() returns the set for N tokens x d channels, or nullptr when that shape runs on
-// the generic kernels.  The shapes are compiled in groups (kvc_fast.hip), one lookup function per group.
+// The codec kernels are specialised at compile time for the page shape (kvc_fast.h): d channels, np
+// passes of 512 elements, and whether the page fills its last pass (exact: d * N = 512 * np) or not
+// (partial: the token count N is read at run time).  These are the host-side entry points of one shape.
+// The shapes are compiled in groups (kvc_fast.hip), one lookup function per group; fast_kernels() finds
+// the set for N tokens x d channels (nullptr: N * d exceeds eight passes).
 struct FastKernels {
-    int N, d;
+    int d, np;
+    bool partial;
     hipError_t (*compress)(const EncodeArgs& a, hipStream_t s);
     hipError_t (*decompress)(const DecodeArgs& a, hipStream_t s);
     hipError_t (*decompress_window)(const DecodeArgs& a, const WindowArgs& w, unsigned grid, hipStream_t s);
 };
-constexpr int kFastGroups = 8;
-const FastKernels* fast_kernels_group0(int N, int d);
-const FastKernels* fast_kernels_group1(int N, int d);
-const FastKernels* fast_kernels_group2(int N, int d);
-const FastKernels* fast_kernels_group3(int N, int d);
-const FastKernels* fast_kernels_group4(int N, int d);
-const FastKernels* fast_kernels_group5(int N, int d);
-const FastKernels* fast_kernels_group6(int N, int d);
-const FastKernels* fast_kernels_group7(int N, int d);
+constexpr int kFastGroups = 16;
+using FastLookup = const FastKernels* (*)(int d, int np, bool partial);
+#define KVC_DECLARE_GROUP(G) const FastKernels* fast_kernels_group##G(int d, int np, bool partial);
+KVC_DECLARE_GROUP(0) KVC_DECLARE_GROUP(1) KVC_DECLARE_GROUP(2) KVC_DECLARE_GROUP(3) KVC_DECLARE_GROUP(4) KVC_DECLARE_GROUP(5)
+KVC_DECLARE_GROUP(6) KVC_DECLARE_GROUP(7) KVC_DECLARE_GROUP(8) KVC_DECLARE_GROUP(9) KVC_DECLARE_GROUP(10) KVC_DECLARE_GROUP(11)
+KVC_DECLARE_GROUP(12) KVC_DECLARE_GROUP(13) KVC_DECLARE_GROUP(14) KVC_DECLARE_GROUP(15)
+#undef KVC_DECLARE_GROUP
 const FastKernels* fast_kernels(int N, int d);
 
 }  // namespace kvc

@@ -1,15 +1,17 @@
-// Kernels specialised at compile time for pages that are a whole number of 512-element passes: D channels
-// (any multiple of 32 up to 256) by N = NP * 512 / D tokens, NP = 1..8 passes.  16 x 128 FP16 (D = 128,
-// NP = 4) is the paper's 4 KB page and the shape the tuning was done on.  This file holds the templates;
-// kvc_fast.hip instantiates them for the geometries listed in kvc_device.h.
+// The codec kernels, specialised at compile time for the page shape: D channels (any multiple of 32 up to
+// 256) and NP = 1..8 passes of 512 elements.  Two kinds of shape: pages that are a whole number of passes
+// (N = NP * 512 / D tokens; 16 x 128 FP16, D = 128 and NP = 4, is the paper's 4 KB page and the shape the
+// tuning was done on), where every quantity is a constant and no lane is ever inactive, and -- PARTIAL --
+// pages of any other token count that needs NP passes, where the element count is read at run time and the
+// last pass is short.  This file holds the templates; kvc_fast.hip instantiates them.
 //
-// Same lane mapping as the generic kernels -- one wave per page, passes of 512 elements, a lane owns
-// 8 consecutive channels, a packet group is a quad of lanes, a token row is D/8 neighbouring lanes
-// (one 16-lane DPP row at D = 128) -- but every cross-lane step is a DPP operation, the per-group
-// statistics (max, width, run test) and the offset scans are done on quads, and no lane is ever
-// inactive.  When D does not divide 512 (96, 160, 192, 224) a token row may begin in one pass and end in
-// the next: the delta step and its inverse then carry one value from pass to pass.  Written plainly the codec is bound by vector-ALU issue long before HBM bandwidth; the
-// instruction count per element is kept low enough here that the memory system is the limit.
+// Lane mapping: one wave per page, passes of 512 elements, a lane owns 8 consecutive channels (one 128-bit
+// access), a packet group is a quad of lanes, a token row is D/8 neighbouring lanes (one 16-lane DPP row at
+// D = 128).  Every cross-lane step is a DPP operation, the per-group statistics (max, width, run test) and
+// the offset scans are done on quads.  When D does not divide 512 (96, 160, 192, 224) a token row may begin
+// in one pass and end in the next: the delta step and its inverse then carry one value from pass to pass.
+// Written plainly the codec is bound by vector-ALU issue long before HBM bandwidth; the instruction count
+// per element is kept low enough here that the memory system is the limit.
 //
 // Encode: Algorithm 2 of the paper (scaling, quantize, delta, run-length encode).
 // Decode: Section 3.5.3 (undo run-length coding, prefix sum, dequantize; bypass for raw pages).
@@ -54,11 +56,14 @@ __device__ __forceinline__ void store_stream(uint4* p, const uint4& v) {
 #endif
 }
 
-// Compile-time shape of a page of NP passes with D channels per token.
-template <int D, int NP>
+// Compile-time shape of a page of NP passes with D channels per token.  PARTIAL: the page has fewer
+// than NP * 512 elements (more than (NP - 1) * 512); kE, kN, kGroups and kHdr are then upper bounds and
+// the run-time values come from page_extent().
+template <int D, int NP, bool PARTIAL = false>
 struct Page {
-    static_assert(D % 32 == 0 && D >= 32 && D <= 256 && NP >= 1 && NP <= 8 && (NP * 512) % D == 0, "page shape");
+    static_assert(D % 32 == 0 && D >= 32 && D <= 256 && NP >= 1 && NP <= 8 && (PARTIAL || (NP * 512) % D == 0), "page shape");
     static constexpr int kD = D;
+    static constexpr bool kPartial = PARTIAL;
     static constexpr int kE = NP * 512;       // elements
     static constexpr int kN = kE / D;         // tokens
     static constexpr int kPasses = NP;        // passes of 512 elements
@@ -68,8 +73,35 @@ struct Page {
     static constexpr bool kAligned = 512 % D == 0;  // a token row never continues into the next pass
     static constexpr int kRowsPerPass = 512 / D;    // (whole rows; exact when kAligned)
     static constexpr int kRounds = (NP + 1) / 2;    // rounds of 64 lanes x 16 bytes that cover a payload (< kE bytes)
-    static constexpr bool kChan = kN == 16 && (D == 128 || D == 256);  // mode 5 is built for these pages
+    static constexpr bool kChan = !PARTIAL && kN == 16 && (D == 128 || D == 256);  // mode 5 is built for these pages
 };
+
+// Extent of a page: elements, header bytes (4 bits per group of 32, rounded up to a byte) and the number
+// of lanes that hold data in the last pass.  Constants unless P::kPartial.  A token row is a multiple of
+// four lanes, so a packet group (a quad) and a row are either all data or all beyond the page.
+struct Extent {
+    uint32_t E, hdr, last;
+};
+template <class P>
+__device__ __forceinline__ Extent page_extent(const Geometry& g) {
+    Extent x;
+    if (P::kPartial) {
+        x.E = (uint32_t)g.E;
+        x.hdr = (((uint32_t)g.E >> 5) + 1u) >> 1;
+        x.last = ((uint32_t)g.E >> 3) - (uint32_t)(P::kPasses - 1) * 64u;
+    } else {
+        x.E = P::kE;
+        x.hdr = P::kHdr;
+        x.last = 64u;
+    }
+    return x;
+}
+// does this lane hold data in pass p (p a constant after unrolling: true at compile time except in the
+// last pass of a partial page)
+template <class P>
+__device__ __forceinline__ bool lane_live(const Extent& x, int p) {
+    return !P::kPartial || p < P::kPasses - 1 || (uint32_t)lane_id() < x.last;
+}
 
 // Where a lane sits in pass 0: token row and position inside the row, both in lanes of 8 channels, and
 // the byte offset of its 16 bytes inside the page (row-major deal, and the deal of mode 5).
@@ -128,11 +160,12 @@ __device__ __forceinline__ int piece_index(int p, int lane) {  // position in ro
 
 // plain INT8 payload: codes as bytes, row-major
 template <class P, bool CHAN>
-__device__ __forceinline__ void store_codes(const uint4 (&raw)[P::kPasses], float s_inv, uint32_t* stage) {
+__device__ __forceinline__ void store_codes(const uint4 (&raw)[P::kPasses], float s_inv, const Extent& x, uint32_t* stage) {
     constexpr int NP = P::kPasses;
     const int lane = lane_id();
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
+        if (!lane_live<P>(x, p)) continue;
         uint32_t t[8];
         quantize8_bits(raw[p], s_inv, t);
         uint2 v;
@@ -201,7 +234,7 @@ __device__ __forceinline__ uint32_t row_incl_scan(const LanePos& lp, int p, uint
 // pass may be a run packet (is_run is then meaningful), else every group is literal or all-zero.
 template <class P, bool RUNS>
 __device__ __forceinline__ void encode_tail(const uint32_t (&u)[8], uint32_t c, uint32_t size, bool is_run, uint32_t qi,
-                                            int p, uint32_t& run, uint32_t* stage, DevState* st) {
+                                            int p, bool live, uint32_t& run, uint32_t* stage, DevState* st) {
     (void)st;  // only the bounds-checking build reads it
     const uint32_t incl = quad_incl_scan_dpp(size);
     const uint32_t off = run + incl - size;  // byte offset of this group's body
@@ -209,7 +242,13 @@ __device__ __forceinline__ void encode_tail(const uint32_t (&u)[8], uint32_t c, 
     // header: group j of this pass has its code in the quad's lanes; lane 4j+i contributes bit i,
     // so the ballot is the 8 header bytes of the pass (even group in the low nibble)
     const uint64_t hb = __builtin_amdgcn_ballot_w64(((c >> qi) & 1u) != 0);
-    if (lane_id() == 0) {
+    if (P::kPartial && p == P::kPasses - 1) {
+        // a short page's header ends where its first body begins: bytes, each written by the first lane
+        // of the two groups it describes
+        const uint32_t lane = (uint32_t)lane_id();
+        if (live && (lane & 7u) == 0)
+            reinterpret_cast<uint8_t*>(stage)[8 * p + (lane >> 3)] = (uint8_t)(lane < 32 ? (uint32_t)hb >> lane : (uint32_t)(hb >> 32) >> (lane - 32));
+    } else if (lane_id() == 0) {
         stage[2 * p] = (uint32_t)hb;
         stage[2 * p + 1] = (uint32_t)(hb >> 32);
     }
@@ -221,7 +260,7 @@ __device__ __forceinline__ void encode_tail(const uint32_t (&u)[8], uint32_t c, 
         B = off;
     }
     uint32_t* p0 = stage + (B >> 2);
-    KVC_CHECK(st, c <= 9 && (B >> 2) + 2 < (uint32_t)Slot<P::kPasses>::kWords && B >= (uint32_t)P::kHdr);
+    KVC_CHECK(st, c <= 9 && (B >> 2) + 2 < (uint32_t)Slot<P::kPasses>::kWords && B >= (uint32_t)(P::kPartial ? 8 * (P::kPasses - 1) + 1 : P::kHdr));
     uint32_t d0, d1, d2;
     shl_bytes(W, B, d0, d1, d2);
     atomicOr(p0, d0);
@@ -232,7 +271,7 @@ __device__ __forceinline__ void encode_tail(const uint32_t (&u)[8], uint32_t c, 
 // One packet group per quad of lanes: each lane brings 8 of its 32 values.  Group statistics over
 // the quad (max -> width, run test), then the tail.  p = index of the group's set of 16 (a pass).
 template <class P>
-__device__ __forceinline__ void encode_groups(const uint32_t (&u)[8], bool RLE, uint32_t c_min, uint32_t qi, int p,
+__device__ __forceinline__ void encode_groups(const uint32_t (&u)[8], bool RLE, uint32_t c_min, uint32_t qi, int p, bool live,
                                               uint32_t& run, uint32_t* stage, DevState* st) {
     // per-group statistics over the quad of lanes
     uint32_t gmax = max(max(u[0], u[1]), u[2]);
@@ -242,7 +281,8 @@ __device__ __forceinline__ void encode_groups(const uint32_t (&u)[8], bool RLE, 
     gmax = max(gmax, dpp<0xB1>(0, gmax));
     gmax = max(gmax, dpp<0x4E>(0, gmax));
     // bit length of the group maximum (0 for 0): exponent of its float value
-    const uint32_t c = max((uint32_t)__builtin_amdgcn_frexp_expf((float)gmax), c_min);
+    uint32_t c = max((uint32_t)__builtin_amdgcn_frexp_expf((float)gmax), c_min);
+    if (P::kPartial && !live) c = 0;  // a group beyond the page: no header bits, no body (its values are zeros)
     const uint32_t size = c << 2;
     bool cand_any = false;
     uint32_t x = 0;
@@ -258,9 +298,9 @@ __device__ __forceinline__ void encode_groups(const uint32_t (&u)[8], bool RLE, 
         y |= dpp<0xB1>(0, y);
         y |= dpp<0x4E>(0, y);
         const bool is_run = (y == 0) && (gmax != 0);
-        encode_tail<P, true>(u, is_run ? 9u : c, is_run ? 1u : size, is_run, qi, p, run, stage, st);
+        encode_tail<P, true>(u, is_run ? 9u : c, is_run ? 1u : size, is_run, qi, p, live, run, stage, st);
     } else {
-        encode_tail<P, false>(u, c, size, false, qi, p, run, stage, st);
+        encode_tail<P, false>(u, c, size, false, qi, p, live, run, stage, st);
     }
 }
 
@@ -288,19 +328,23 @@ template <class P, bool CHAN>
 __device__ __forceinline__ void load_page(const EncodeArgs& a, const EncTask& task, const LanePos& lp,
                                           uint4 (&raw)[P::kPasses]) {
     const char* src = reinterpret_cast<const char*>(a.cache) + wave_uniform((int64_t)task.src_off * 2);
+    const Extent x = page_extent<P>(a.g);
 #pragma unroll
-    for (int p = 0; p < P::kPasses; ++p)
-        raw[p] = load_stream(reinterpret_cast<const uint4*>(src + pass_base_off<P, CHAN>(a.g, p) + pass_lane_off<P, CHAN>(a.g, lp, p)));
+    for (int p = 0; p < P::kPasses; ++p) {
+        raw[p] = make_uint4(0u, 0u, 0u, 0u);  // lanes beyond a short page hold zeros
+        if (lane_live<P>(x, p))
+            raw[p] = load_stream(reinterpret_cast<const uint4*>(src + pass_base_off<P, CHAN>(a.g, p) + pass_lane_off<P, CHAN>(a.g, lp, p)));
+    }
 }
 
 // Encode one page (already in registers) into the LDS slot `stage`.  The requested mode is the
 // compile-time SCHEME when that is >= 0 (one mode for the whole launch: its branches fold away), else
 // the wave-uniform run-time value.
 template <class P, int SCHEME>
-__device__ __forceinline__ PageResult encode_page_fast(const uint4 (&raw)[P::kPasses], const LanePos& lp, int scheme_rt, uint32_t* stage,
-                                                 const uint8_t* lut, DevState* st) {
+__device__ __forceinline__ PageResult encode_page_fast(const uint4 (&raw)[P::kPasses], const LanePos& lp, const Extent& x, int scheme_rt,
+                                                 uint32_t* stage, const uint8_t* lut, DevState* st) {
     const int scheme = SCHEME >= 0 ? SCHEME : scheme_rt;
-    constexpr int kE = P::kE, kHdr = P::kHdr, NP = P::kPasses;
+    constexpr int kE = P::kE, NP = P::kPasses;
     const bool RLE = scheme != KVC_MODE_DELTA;  // zero-run and run packets (modes 3 and 4)
     const bool no_delta = scheme == KVC_MODE_PACK;
     const uint32_t c_min = RLE ? 0u : 1u;  // without run packets an all-zero group is a 1-bit literal
@@ -319,7 +363,7 @@ __device__ __forceinline__ PageResult encode_page_fast(const uint4 (&raw)[P::kPa
     const uint32_t m = wave_max_dpp(max(m2 & 0xFFFFu, m2 >> 16));
     PageResult r;
     if (scheme == KVC_MODE_RAW || m >= 0x7C00u) {  // requested, or NaN/Inf present: bypass
-        r.n16 = kE / 8;
+        r.n16 = x.E >> 3;
         r.mode = KVC_MODE_RAW;
         r.scale = 0.0f;
         return r;
@@ -332,8 +376,8 @@ __device__ __forceinline__ PageResult encode_page_fast(const uint4 (&raw)[P::kPa
     }
     r.scale = s;
     if (scheme == KVC_MODE_INT8) {
-        store_codes<P, SCHEME == KVC_MODE_CHAN>(raw, s_inv, stage);
-        r.n16 = kE / 16;
+        store_codes<P, SCHEME == KVC_MODE_CHAN>(raw, s_inv, x, stage);
+        r.n16 = x.E >> 4;
         r.mode = KVC_MODE_INT8;
         return r;
     }
@@ -343,7 +387,7 @@ __device__ __forceinline__ PageResult encode_page_fast(const uint4 (&raw)[P::kPa
         if (kE % 1024 == 0 || lane + 64 * z < kE / 16) reinterpret_cast<uint4*>(stage)[lane + 64 * z] = make_uint4(0, 0, 0, 0);
     wave_sync();
 
-    uint32_t run = kHdr;  // payload bytes so far (wave-uniform)
+    uint32_t run = x.hdr;  // payload bytes so far (wave-uniform)
     if constexpr (SCHEME == KVC_MODE_CHAN) {
         // Mode 5: the lanes hold the page dealt as piece_index says.  The four passes of a run of 16
         // octets are quantized and mapped first; group set j of the run then takes channels 2j, 2j + 1
@@ -364,7 +408,7 @@ __device__ __forceinline__ PageResult encode_page_fast(const uint4 (&raw)[P::kPa
                 uint32_t u[8];
 #pragma unroll
                 for (int m = 0; m < 8; ++m) u[m] = uu[m >> 1][2 * j + (m & 1)];
-                encode_groups<P>(u, true, 0u, qi, 4 * h + j, run, stage, st);
+                encode_groups<P>(u, true, 0u, qi, 4 * h + j, true, run, stage, st);
             }
         }
     } else {
@@ -387,14 +431,19 @@ __device__ __forceinline__ PageResult encode_page_fast(const uint4 (&raw)[P::kPa
 #pragma unroll
                 for (int k = 1; k < 8; ++k) u[k] = lut[t[k] - t[k - 1]];
             }
-            encode_groups<P>(u, RLE, c_min, qi, p, run, stage, st);
+            const bool live = lane_live<P>(x, p);
+            if (P::kPartial && p == NP - 1) {  // lanes beyond the page hold no values
+#pragma unroll
+                for (int k = 0; k < 8; ++k) u[k] = live ? u[k] : 0u;
+            }
+            encode_groups<P>(u, RLE, c_min, qi, p, live, run, stage, st);
         }
     }
     const uint32_t n = (run + 15u) & ~15u;
     wave_sync();
-    if (n >= (uint32_t)kE) {  // packing did not beat plain INT8
-        store_codes<P, SCHEME == KVC_MODE_CHAN>(raw, s_inv, stage);
-        r.n16 = kE / 16;
+    if (n >= x.E) {  // packing did not beat plain INT8
+        store_codes<P, SCHEME == KVC_MODE_CHAN>(raw, s_inv, x, stage);
+        r.n16 = x.E >> 4;
         r.mode = KVC_MODE_INT8;
     } else {
         r.n16 = n >> 4;
@@ -411,7 +460,7 @@ __device__ __forceinline__ void encode_into_slot(const EncodeArgs& a, const uint
     r.n16 = 0;
     r.mode = KVC_MODE_INVALID;
     r.scale = 0.0f;
-    if (task.desc_idx >= 0) r = encode_page_fast<P, SCHEME>(raw, lp, task.scheme, stage, lut, a.st);
+    if (task.desc_idx >= 0) r = encode_page_fast<P, SCHEME>(raw, lp, page_extent<P>(a.g), task.scheme, stage, lut, a.st);
     if (lane_id() == 0) {
         book.n16[slot] = r.n16;
         book.mode[slot] = r.mode;
@@ -461,10 +510,11 @@ constexpr int enc_ring_max(int np, int scheme) {
 
 // (four waves per SIMD is what the LDS slots allow anyway: keep every instantiation within 128 VGPRs; the
 // channel-pair encoder at D = 256 holds 32 mapped values beside the page and runs better with three, and
-// so does the run-time-scheme encoder of seven-pass pages whose rows cross passes, which would spill at four)
+// so do the run-time-scheme encoders of seven- and eight-pass pages whose rows cross passes or whose last
+// pass may be short, which would spill at four)
 template <class P, int SCHEME>
 constexpr int enc_min_waves() {
-    return ((P::kD == 256 && SCHEME == KVC_MODE_CHAN) || (P::kPasses >= 7 && !P::kAligned && SCHEME < 0)) ? 3 : KVC_ENC_MIN_WAVES;
+    return ((P::kD == 256 && SCHEME == KVC_MODE_CHAN) || (P::kPasses >= 7 && (!P::kAligned || P::kPartial) && SCHEME < 0)) ? 3 : KVC_ENC_MIN_WAVES;
 }
 template <class P, int WAVES, int PPW, int SCHEME>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(enc_min_waves<P, SCHEME>()))) void k_compress_fast(EncodeArgs a) {
@@ -541,8 +591,9 @@ __device__ __forceinline__ uint4 dequant8_biased(const uint32_t pb[8], float s, 
 // This lane's 8 values of its quad's packet in group set p, read from the staged payload: the bits
 // above each value's sign flag (hb) and the flag as 0 / -1 (sg): delta = hb ^ sg.
 template <int NP>
-__device__ __forceinline__ void unpack8(const DecodeArgs& a, const uint32_t* stage, const uint32_t* ginfo, int p, bool special,
+__device__ __forceinline__ void unpack8(const DecodeArgs& a, const uint32_t* stage, const uint32_t* ginfo, int p, bool special, uint32_t hdr,
                                         uint32_t (&hb)[8], int (&sg)[8]) {
+    (void)hdr;
     (void)a;  // only the bounds-checking build reads it
     const int lane = lane_id();
     const uint32_t qi = (uint32_t)lane & 3u;
@@ -553,7 +604,7 @@ __device__ __forceinline__ void unpack8(const DecodeArgs& a, const uint32_t* sta
     if (special && c == 9) B = goff;
     const uint32_t sh = (B & 3u) << 3;
     const uint32_t* p0 = stage + (B >> 2);
-    KVC_CHECK(a.st, (B >> 2) + 2 < (uint32_t)Slot<NP>::kWords && B >= (uint32_t)(NP * 8));  // bodies start after the NP * 8 header bytes
+    KVC_CHECK(a.st, (B >> 2) + 2 < (uint32_t)Slot<NP>::kWords && B >= hdr);  // bodies start after the header bytes
     const uint32_t d0 = p0[0], d1 = p0[1], d2 = p0[2];
     uint32_t lo = __builtin_amdgcn_alignbit(d1, d0, sh);
     uint32_t hi = __builtin_amdgcn_alignbit(d2, d1, sh);
@@ -602,7 +653,7 @@ __device__ __forceinline__ bool is_packed_mode(uint32_t mode) {
 // payload loads of a packed page.  Nothing here waits for those loads.
 template <class P>
 __device__ __forceinline__ DecPage<P> dec_open(const DecodeArgs& a, uint4 dw) {
-    constexpr int kE = P::kE, kHdr = P::kHdr;
+    const Extent x = page_extent<P>(a.g);
     const int lane = lane_id();
     DecPage<P> pg;
     pg.off = (uint64_t)dw.x | ((uint64_t)dw.y << 32);
@@ -611,11 +662,11 @@ __device__ __forceinline__ DecPage<P> dec_open(const DecodeArgs& a, uint4 dw) {
     pg.mode = (dw.w >> 16) & 0xFFu;
     bool ok = (pg.off & 15u) == 0 && (pg.off >> 4) + pg.n16 <= a.pool_units;
     if (pg.mode == KVC_MODE_RAW)
-        ok = ok && pg.n16 == kE / 8;
+        ok = ok && pg.n16 == x.E >> 3;
     else if (pg.mode == KVC_MODE_INT8)
-        ok = ok && pg.n16 == kE / 16;
+        ok = ok && pg.n16 == x.E >> 4;
     else if (is_packed_mode<P>(pg.mode))
-        ok = ok && pg.n16 * 16u >= (uint32_t)kHdr && pg.n16 < kE / 16;
+        ok = ok && pg.n16 * 16u >= x.hdr && pg.n16 < x.E >> 4;
     else
         ok = false;
     pg.ok = ok;
@@ -639,7 +690,8 @@ __device__ __forceinline__ DecPage<P> dec_open(const DecodeArgs& a, uint4 dw) {
 template <class P>
 __device__ __forceinline__ bool dec_finish(const DecodeArgs& a, const DecPage<P>& pg, uint16_t* __restrict__ dst,
                                            uint32_t* stage, uint32_t* ginfo) {
-    constexpr int kHdr = P::kHdr, NP = P::kPasses, kG = P::kGroups;
+    constexpr int NP = P::kPasses, kG = P::kGroups;
+    const Extent x = page_extent<P>(a.g);
     const int lane = lane_id();
     const float s = pg.s;
     const uint32_t n16 = pg.n16, mode = pg.mode;
@@ -652,13 +704,15 @@ __device__ __forceinline__ bool dec_finish(const DecodeArgs& a, const DecPage<P>
     const uint4* pl4 = reinterpret_cast<const uint4*>(a.pool + pg.off);
     if (mode == KVC_MODE_RAW) {  // stored-uncompressed bypass
 #pragma unroll
-        for (int p = 0; p < NP; ++p) *reinterpret_cast<uint4*>(dst_b + pass_base_off<P, false>(a.g, p) + pass_lane_off<P, false>(a.g, lp, p)) = pl4[p * 64 + lane];
+        for (int p = 0; p < NP; ++p)
+            if (lane_live<P>(x, p)) *reinterpret_cast<uint4*>(dst_b + pass_base_off<P, false>(a.g, p) + pass_lane_off<P, false>(a.g, lp, p)) = pl4[p * 64 + lane];
         return true;
     }
     const float neg128s = -128.0f * s;
     if (mode == KVC_MODE_INT8) {
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
+            if (!lane_live<P>(x, p)) continue;
             const uint2 v = reinterpret_cast<const uint2*>(pl4)[p * 64 + lane];
             uint32_t pb[8];
 #pragma unroll
@@ -680,16 +734,18 @@ __device__ __forceinline__ bool dec_finish(const DecodeArgs& a, const DecPage<P>
     wave_sync();
     // header: a lane takes the code of group g (64 groups per round); body offsets are a prefix sum of
     // body sizes
-    uint32_t total = kHdr;
+    uint32_t total = x.hdr;
     bool bad = false, special = false;
 #pragma unroll
     for (int g0 = 0; g0 < kG; g0 += 64) {
         const int g = g0 + lane;
-        const bool live = kG % 64 == 0 || g < kG;
+        const bool in_slot = kG % 64 == 0 || g < kG;                         // the group has an entry in ginfo
+        const bool live = P::kPartial ? (uint32_t)g < (x.E >> 5) : in_slot;  // ... and exists in this page
         const uint32_t c_own = live ? (stage[g >> 3] >> ((g & 7) << 2)) & 15u : 1u;
         const uint32_t size_own = !live ? 0u : (c_own == 9) ? 1u : (c_own << 2);
         const uint32_t incl = wave_incl_scan_dpp(size_own);
-        if (live) ginfo[g] = ((total + incl - size_own) << 4) | c_own;
+        // (a group beyond a short page: a one-bit literal at the payload's end, read but never stored)
+        if (in_slot) ginfo[g] = ((total + incl - size_own) << 4) | c_own;
         total += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
         bad = bad || c_own > 9 || (mode == KVC_MODE_DELTA && (c_own == 0 || c_own == 9));
         special = special || c_own == 0 || c_own == 9;
@@ -712,7 +768,7 @@ __device__ __forceinline__ bool dec_finish(const DecodeArgs& a, const DecPage<P>
             for (int j = 0; j < 4; ++j) {
                 uint32_t hb[8];
                 int sg[8];
-                unpack8<NP>(a, stage, ginfo, 4 * h + j, special, hb, sg);
+                unpack8<NP>(a, stage, ginfo, 4 * h + j, special, x.hdr, hb, sg);
                 uint32_t b[8];
 #pragma unroll
                 for (int m = 0; m < 8; ++m) b[m] = (hb[m] ^ (uint32_t)sg[m]) + 128u;
@@ -738,7 +794,7 @@ __device__ __forceinline__ bool dec_finish(const DecodeArgs& a, const DecPage<P>
     for (int p = 0; p < NP; ++p) {
         uint32_t hb[8];  // bits above the sign flag
         int sg[8];       // 0 or -1 from the sign flag
-        unpack8<NP>(a, stage, ginfo, p, special, hb, sg);
+        unpack8<NP>(a, stage, ginfo, p, special, x.hdr, hb, sg);
         uint32_t pb[8];
         if (mode == KVC_MODE_PACK) {  // no delta step was taken: the fields are the codes
 #pragma unroll
@@ -757,7 +813,8 @@ __device__ __forceinline__ bool dec_finish(const DecodeArgs& a, const DecPage<P>
 #pragma unroll
             for (int k = 0; k < 8; ++k) pb[k] = pre[k] + base;
         }
-        store_stream(reinterpret_cast<uint4*>(dst_b + pass_base_off<P, false>(a.g, p) + pass_lane_off<P, false>(a.g, lp, p)), dequant8_biased(pb, s, neg128s));
+        if (lane_live<P>(x, p))
+            store_stream(reinterpret_cast<uint4*>(dst_b + pass_base_off<P, false>(a.g, p) + pass_lane_off<P, false>(a.g, lp, p)), dequant8_biased(pb, s, neg128s));
     }
     return true;
 }
@@ -867,10 +924,10 @@ inline dim3 fast_grid(int64_t n_pages, int ppw, int waves = kFastWaves) {
     return dim3((unsigned)((n_pages + per_wg - 1) / per_wg));
 }
 
-// The host side of one geometry: picks the instantiation and launches it.
-template <int D, int NP>
+// The host side of one page shape: picks the instantiation and launches it.
+template <int D, int NP, bool PARTIAL>
 struct FastOps {
-    using P = Page<D, NP>;
+    using P = Page<D, NP, PARTIAL>;
 
     template <int SCHEME>
     static hipError_t compress_scheme(const EncodeArgs& a, hipStream_t s) {
@@ -883,16 +940,21 @@ struct FastOps {
 
     static hipError_t compress(const EncodeArgs& a, hipStream_t s) {
         // the full scheme of Algorithm 2 for every block is the common launch and gets its own
-        // instantiation; any other request (another mode, or one mode per block) reads it at run time
-        if (a.block_scheme == nullptr && a.scheme == KVC_MODE_RLE) return compress_scheme<KVC_MODE_RLE>(a, s);
-        if (a.block_scheme == nullptr && a.scheme == KVC_MODE_CHAN) {
-            // channel-pair groups: its own instantiations (another deal of the page to the lanes)
-            if constexpr (P::kChan)
-                return compress_scheme<KVC_MODE_CHAN>(a, s);
-            else
-                return hipErrorInvalidValue;
+        // instantiation; any other request (another mode, or one mode per block) reads it at run time,
+        // and so do all requests for pages with a short last pass
+        if constexpr (PARTIAL) {
+            return a.scheme == KVC_MODE_CHAN ? hipErrorInvalidValue : compress_scheme<-1>(a, s);
+        } else {
+            if (a.block_scheme == nullptr && a.scheme == KVC_MODE_RLE) return compress_scheme<KVC_MODE_RLE>(a, s);
+            if (a.block_scheme == nullptr && a.scheme == KVC_MODE_CHAN) {
+                // channel-pair groups: its own instantiations (another deal of the page to the lanes)
+                if constexpr (P::kChan)
+                    return compress_scheme<KVC_MODE_CHAN>(a, s);
+                else
+                    return hipErrorInvalidValue;
+            }
+            return compress_scheme<-1>(a, s);
         }
-        return compress_scheme<-1>(a, s);
     }
 
     static hipError_t decompress(const DecodeArgs& a, hipStream_t s) {
@@ -903,7 +965,7 @@ struct FastOps {
         return launch_kernel(k_decompress_window_fast<P, kFastWaves>, dim3(grid), dim3(kFastWaves * 64), s, a, w);
     }
 
-    static constexpr FastKernels kTable = {P::kN, D, &compress, &decompress, &decompress_window};
+    static constexpr FastKernels kTable = {D, NP, PARTIAL, &compress, &decompress, &decompress_window};
 };
 
 }  // namespace

@@ -1,412 +1,12 @@
-// HIP kernels of the KV page codec for gfx950 (wave64).
-//
-// Work decomposition: one wavefront owns one page at a time.  A lane owns 8 consecutive channels
-// (16 bytes of FP16), so a 64-lane pass covers 512 elements with one fully coalesced 128-bit
-// access per lane, a 32-element packet group is a quad of lanes, and a token row of d channels is
-// d/8 neighbouring lanes.  Compressed payloads are assembled in (encode) or staged through (decode)
-// LDS and move to/from the pool as 128-bit accesses.
-//
-// Encode follows Algorithm 2 of the paper (scaling, quantize, delta along the channel index,
-// run-length encode); decode follows Section 3.5.3 (undo run-length coding, prefix sum,
-// dequantize), with the stored-uncompressed bypass.
-#include <hip/hip_fp16.h>
-
+// The small kernels around the codec (pool reset, statistics, yardstick copy, prefetch planner and the
+// window's queue builder) and the launchers of every kernel.  The codec kernels themselves -- Algorithm 2
+// of the paper and its inverse, Section 3.5.3 -- are the templates of kvc_fast.h, instantiated per page
+// shape by kvc_fast.hip and found here through fast_kernels().
 #include <algorithm>
 
 #include "kvc_device.h"
 
 namespace kvc {
-
-// Inclusive prefix over the lanes of one token row.  Rows are runs of lpr <= 32 lanes that may begin
-// anywhere, also in the pass before this one: r = the lane's position in its row.  Prefix over the whole
-// wave, minus its value just before the row's first lane; a lane with r > lane belongs to a row that
-// began in the previous pass and adds `carry`, that pass's value at lane 63.
-__device__ __forceinline__ uint32_t row_incl_scan_u32(uint32_t v, uint32_t r, uint32_t carry) {
-    const int lane = lane_id();
-    const uint32_t S = wave_incl_scan_dpp(v);
-    const int start = lane - (int)r;  // first lane of this lane's row (< 0: in the pass before)
-    const uint32_t before = (uint32_t)__builtin_amdgcn_ds_bpermute((start > 0 ? start - 1 : 0) << 2, (int)S);
-    return start > 0 ? S - before : (start < 0 ? S + carry : S);
-}
-
-__device__ __forceinline__ float half_bits_to_float(uint32_t h) {
-    return __half2float(__ushort_as_half((unsigned short)h));
-}
-
-__device__ __forceinline__ uint32_t float_to_half_bits(float f) {
-    return (uint32_t)__half_as_ushort(__float2half_rn(f));
-}
-
-// Quantize step of Algorithm 2 on a lane's 8 elements: q = round_half_even(x * s_inv).  The fused
-// multiply-add against 1.5*2^23 rounds the exact product once, to an integer, ties to even.
-__device__ __forceinline__ void quantize8(const uint4& raw, float s_inv, int q[8]) {
-    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        float lo = half_bits_to_float(w[k] & 0xFFFFu);
-        float hi = half_bits_to_float(w[k] >> 16);
-        q[2 * k] = (int)__float_as_uint(__builtin_fmaf(lo, s_inv, 12582912.0f)) - 0x4B400000;
-        q[2 * k + 1] = (int)__float_as_uint(__builtin_fmaf(hi, s_inv, 12582912.0f)) - 0x4B400000;
-    }
-}
-
-__device__ __forceinline__ uint32_t pack_bytes4(int a, int b, int c, int d) {
-    return (uint32_t)(a & 0xFF) | ((uint32_t)(b & 0xFF) << 8) | ((uint32_t)(c & 0xFF) << 16) | ((uint32_t)d << 24);
-}
-
-// 8-bit wrap then zig-zag: 0,-1,1,-2,... -> 0,1,2,3,...
-__device__ __forceinline__ uint32_t zigzag8(int delta) {
-    uint32_t b = (uint32_t)delta & 0xFFu;
-    return ((b << 1) ^ (0u - (b >> 7))) & 0xFFu;
-}
-
-// ---------------------------------------------------------------------------------- encode
-
-template <int MAXP>
-__device__ __forceinline__ void store_codes(const uint4 (&raw)[MAXP], float s_inv, int E, uint32_t* stage) {
-    const int lane = lane_id();
-#pragma unroll
-    for (int p = 0; p < MAXP; ++p) {
-        const int e0 = p * 512 + lane * 8;
-        if (e0 < E) {
-            int q[8];
-            quantize8(raw[p], s_inv, q);
-            uint2 v;
-            v.x = pack_bytes4(q[0], q[1], q[2], q[3]);
-            v.y = pack_bytes4(q[4], q[5], q[6], q[7]);
-            *reinterpret_cast<uint2*>(reinterpret_cast<uint8_t*>(stage) + e0) = v;
-        }
-    }
-}
-
-// Encodes one page held at src into the LDS slot `stage` (modes 1..3).  A RAW page is only
-// classified here; its bytes go from the source to the pool in the copy-out phase.
-template <int MAXP>
-__device__ PageResult encode_page(const uint16_t* __restrict__ src, const Geometry& g, int scheme, uint32_t* stage) {
-    const int lane = lane_id();
-    const int E = g.E;
-    const int G = E >> 5;
-    const int hdr = (G + 1) >> 1;
-    uint8_t* stage8 = reinterpret_cast<uint8_t*>(stage);
-
-    uint4 raw[MAXP];
-#pragma unroll
-    for (int p = 0; p < MAXP; ++p) {
-        const int e0 = p * 512 + lane * 8;
-        raw[p] = (e0 < E) ? *reinterpret_cast<const uint4*>(src + elem_off(g, e0)) : make_uint4(0, 0, 0, 0);
-    }
-    // scaling step: max |x| over the page on the FP16 bit patterns (monotone in magnitude)
-    uint32_t m = 0;
-#pragma unroll
-    for (int p = 0; p < MAXP; ++p) {
-        const uint32_t w[4] = {raw[p].x, raw[p].y, raw[p].z, raw[p].w};
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            uint32_t a = w[k] & 0x7FFF7FFFu;
-            m = max(m, max(a & 0xFFFFu, a >> 16));
-        }
-    }
-    m = wave_max_dpp(m);
-    PageResult r;
-    if (scheme == KVC_MODE_RAW || m >= 0x7C00u) {  // requested, or a NaN/Inf is present: bypass
-        r.n16 = (uint32_t)(E >> 3);
-        r.mode = KVC_MODE_RAW;
-        r.scale = 0.0f;
-        return r;
-    }
-    float s = 0.0f, s_inv = 0.0f;
-    if (m != 0) {
-        const PageScale ps = page_scale(m);
-        s = ps.s;
-        s_inv = ps.s_inv;
-    }
-    r.scale = s;
-    if (scheme == KVC_MODE_INT8) {
-        store_codes<MAXP>(raw, s_inv, E, stage);
-        r.n16 = (uint32_t)(E >> 4);
-        r.mode = KVC_MODE_INT8;
-        return r;
-    }
-    // the slot must start as zeros: bodies are OR-ed in, and the padding is part of the payload
-    for (int o = lane * 16; o < E; o += 1024) *reinterpret_cast<uint4*>(stage8 + o) = make_uint4(0, 0, 0, 0);
-    wave_sync();
-
-    uint32_t run = 0;  // body bytes emitted so far (wave-uniform)
-    int q_last = 0;    // last code of the pass before (a token row may continue across passes)
-#pragma unroll
-    for (int p = 0; p < MAXP; ++p) {
-        if (p * 512 < E) {
-            const bool act = p * 512 + lane * 8 < E;
-            int q[8];
-            quantize8(raw[p], s_inv, q);
-            // delta along the channel index; the first column of a token row is kept verbatim
-            int prev = (int)dpp<0x138>((uint32_t)q_last, (uint32_t)q[7]);  // wave_shr:1; lane 0 keeps the pass before's last code
-            if (lane_in_row(g, (uint32_t)(p * 64 + lane)) == 0) prev = 0;
-            q_last = __builtin_amdgcn_readlane(q[7], 63);
-            uint32_t u[8];
-            if (scheme == KVC_MODE_PACK) {  // no delta step: the codes themselves are packed
-#pragma unroll
-                for (int k = 0; k < 8; ++k) u[k] = zigzag8(q[k]);
-            } else {
-                u[0] = zigzag8(q[0] - prev);
-#pragma unroll
-                for (int k = 1; k < 8; ++k) u[k] = zigzag8(q[k] - q[k - 1]);
-            }
-            uint32_t umax = u[0], umin = u[0];
-#pragma unroll
-            for (int k = 1; k < 8; ++k) {
-                umax = max(umax, u[k]);
-                umin = min(umin, u[k]);
-            }
-            // a group of 32 is a quad of lanes
-            umax = max(umax, dpp<0xB1>(0, umax));  // quad_perm [1,0,3,2]
-            umin = min(umin, dpp<0xB1>(0xFFu, umin));
-            umax = max(umax, dpp<0x4E>(0, umax));  // quad_perm [2,3,0,1]
-            umin = min(umin, dpp<0x4E>(0xFFu, umin));
-            uint32_t c;
-            const bool runs = scheme != KVC_MODE_DELTA;  // zero-run and run packets
-            if (runs && umax == 0)
-                c = 0;
-            else if (runs && umin == umax)
-                c = 9;
-            else
-                c = max(1u, 32u - (uint32_t)__clz((int)umax));
-            if (!act) c = 0;
-            const uint32_t size = (c == 0) ? 0u : (c == 9 ? 1u : 4u * c);
-            const uint32_t incl = quad_incl_scan_dpp(size);  // size is the same in the four lanes of a group
-            const uint32_t off = run + incl - size;
-            run += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
-            // header: two 4-bit codes per byte, even group in the low nibble.  Lane 4j+i votes bit i of
-            // group j's code, so the ballot is the pass's eight header bytes; a lane per byte writes its own
-            // (bytes, not dwords: a short page's header ends where its first body begins)
-            const uint64_t hb = __builtin_amdgcn_ballot_w64(((c >> (lane & 3)) & 1u) != 0);
-            if (act && (lane & 7) == 0)
-                stage8[(p * 16 + (lane >> 2)) >> 1] = (uint8_t)(lane < 32 ? (uint32_t)hb >> lane : (uint32_t)(hb >> 32) >> (lane - 32));
-            // body: this lane's 8 values are bytes [qi*w, qi*w + w) of the group's bit string
-            uint2 W = make_uint2(0u, 0u);
-            uint32_t B = hdr + off;
-            if (c >= 1 && c <= 8) {
-                W = pack8_bits(u, c);
-                B += (lane & 3) * c;
-            } else if (c == 9) {
-                W.x = (lane & 3) == 0 ? u[0] : 0;
-            }
-            {
-                uint32_t* p0 = stage + (B >> 2);  // inside the slot for every lane (the slot has slack beyond the payload)
-                uint32_t d0, d1, d2;
-                shl_bytes(W, B, d0, d1, d2);
-                atomicOr(p0, d0);
-                atomicOr(p0 + 1, d1);
-                if (d2) atomicOr(p0 + 2, d2);
-            }
-        }
-    }
-    const uint32_t n = (hdr + run + 15u) & ~15u;
-    wave_sync();
-    if (n >= (uint32_t)E) {  // packing did not beat plain INT8
-        store_codes<MAXP>(raw, s_inv, E, stage);
-        r.n16 = (uint32_t)(E >> 4);
-        r.mode = KVC_MODE_INT8;
-    } else {
-        r.n16 = n >> 4;
-        r.mode = (uint32_t)scheme;
-    }
-    return r;
-}
-
-// One workgroup = 4 waves x PPW pages.  Payloads wait in LDS until the workgroup has reserved
-// one contiguous pool span for all of them with a single atomic on the pool cursor.
-template <int MAXP, int PPW>
-__global__ __launch_bounds__(kThreads) void k_compress(EncodeArgs a) {
-    constexpr int kSlots = kWavesPerWG * PPW;
-    __shared__ __align__(16) uint32_t s_stage[kSlots][Slot<MAXP>::kWords];
-    __shared__ EncBook<kSlots> s_book;
-    const int lane = lane_id();
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t t0 = ((int64_t)blockIdx.x * kWavesPerWG + wave) * PPW;
-    TaskPos pos = task_pos(t0, a.g.ppb);
-    for (int i = 0; i < PPW; ++i) {
-        const int slot = wave * PPW + i;
-        const EncTask task = resolve_enc_task(a, t0 + i, pos);
-        task_advance(pos, a.g.ppb);
-        PageResult r;
-        r.n16 = 0;
-        r.mode = KVC_MODE_INVALID;
-        r.scale = 0.0f;
-        if (task.desc_idx >= 0) r = encode_page<MAXP>(a.cache + task.src_off, a.g, task.scheme, s_stage[slot]);
-        if (lane == 0) {
-            s_book.n16[slot] = r.n16;
-            s_book.mode[slot] = r.mode;
-            s_book.scale[slot] = r.scale;
-            s_book.desc[slot] = task.desc_idx;
-            s_book.srcoff[slot] = task.src_off;
-        }
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) reserve_pool_span<kSlots>(a, s_book);
-    __syncthreads();
-    for (int i = 0; i < PPW; ++i) emit_page<kSlots>(a, s_book, wave * PPW + i, s_stage[wave * PPW + i]);
-}
-
-// ---------------------------------------------------------------------------------- decode
-
-// dequantize step: x = fp16(fp32(q) * s) for a lane's 8 codes (low 8 bits of each q[k], signed)
-__device__ __forceinline__ uint4 dequant8(const int q[8], float s) {
-    uint32_t h[8];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) h[k] = float_to_half_bits((float)(int)(int8_t)(q[k] & 0xFF) * s);
-    return make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-}
-
-// Decodes the page described by descriptor d_idx into dst.  Returns false (dst zero-filled) if the
-// descriptor or the payload fails validation.
-template <int MAXP>
-__device__ bool decode_page(const DecodeArgs& a, uint64_t d_idx, uint16_t* __restrict__ dst, uint32_t* stage,
-                            uint32_t* ginfo) {
-    const int lane = lane_id();
-    const int E = a.g.E;
-    const int G = E >> 5;
-    const int hdr = (G + 1) >> 1;
-    const uint4 dw = reinterpret_cast<const uint4*>(a.desc)[d_idx];
-    const uint64_t off = (uint64_t)dw.x | ((uint64_t)dw.y << 32);
-    const float s = __uint_as_float(dw.z);
-    const uint32_t n16 = dw.w & 0xFFFFu;
-    const uint32_t mode = (dw.w >> 16) & 0xFFu;
-
-    bool ok = (off & 15u) == 0 && (off >> 4) + n16 <= a.pool_units;
-    if (mode == KVC_MODE_RAW)
-        ok = ok && n16 == (uint32_t)(E >> 3);
-    else if (mode == KVC_MODE_INT8)
-        ok = ok && n16 == (uint32_t)(E >> 4);
-    else if (mode == KVC_MODE_DELTA || mode == KVC_MODE_RLE || mode == KVC_MODE_PACK)
-        ok = ok && n16 * 16u >= (uint32_t)hdr && n16 < (uint32_t)(E >> 4);
-    else
-        ok = false;
-    if (!ok) {
-        zero_page(dst, a.g);
-        return false;
-    }
-    const uint8_t* pl = a.pool + off;
-    if (mode == KVC_MODE_RAW) {  // stored-uncompressed bypass
-        for (uint32_t o = lane; o < n16; o += 64)
-            *reinterpret_cast<uint4*>(dst + elem_off(a.g, (int)o * 8)) = reinterpret_cast<const uint4*>(pl)[o];
-        return true;
-    }
-    if (mode == KVC_MODE_INT8) {
-#pragma unroll
-        for (int p = 0; p < MAXP; ++p) {
-            const int e0 = p * 512 + lane * 8;
-            if (e0 < E) {
-                const uint2 v = *reinterpret_cast<const uint2*>(pl + e0);
-                int q[8];
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    q[k] = (int)(v.x >> (8 * k));
-                    q[4 + k] = (int)(v.y >> (8 * k));
-                }
-                *reinterpret_cast<uint4*>(dst + elem_off(a.g, e0)) = dequant8(q, s);
-            }
-        }
-        return true;
-    }
-    // modes 2/3: stage the payload in LDS
-    const uint8_t* stage8 = reinterpret_cast<const uint8_t*>(stage);
-    for (uint32_t o = lane; o < n16; o += 64) reinterpret_cast<uint4*>(stage)[o] = reinterpret_cast<const uint4*>(pl)[o];
-    wave_sync();
-    // header: code of every group -> body offset by a prefix sum over body sizes
-    uint32_t run = 0;
-    bool bad = false;
-    for (int g0 = 0; g0 < G; g0 += 64) {
-        const int gi = g0 + lane;
-        uint32_t c = 0;
-        if (gi < G) {
-            const uint32_t byte = stage8[gi >> 1];
-            c = (gi & 1) ? (byte >> 4) : (byte & 15u);
-            if (c > 9 || (mode == KVC_MODE_DELTA && (c == 0 || c == 9))) bad = true;
-        }
-        const uint32_t size = (c == 0) ? 0u : (c == 9 ? 1u : 4u * c);
-        const uint32_t incl = wave_incl_scan_dpp(size);
-        if (gi < G) ginfo[gi] = ((run + incl - size) << 4) | c;
-        run += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
-    }
-    if (__any(bad) || (((uint32_t)hdr + run + 15u) >> 4) != n16) {
-        zero_page(dst, a.g);
-        return false;
-    }
-    wave_sync();
-    uint32_t row_carry = 0;  // prefix of the row that continues from the pass before
-#pragma unroll
-    for (int p = 0; p < MAXP; ++p) {
-        if (p * 512 < E) {
-            const int e0 = p * 512 + lane * 8;
-            const bool act = e0 < E;
-            uint32_t c = 0, goff = 0;
-            if (act) {
-                const uint32_t gi = ginfo[p * 16 + (lane >> 2)];
-                c = gi & 15u;
-                goff = gi >> 4;
-            }
-            uint32_t u[8];
-            if (c >= 1 && c <= 8) {
-                const uint32_t B = (uint32_t)hdr + goff + (uint32_t)(lane & 3) * c;
-                const uint32_t sh = (B & 3u) * 8u;
-                const uint32_t* p0 = stage + (B >> 2);
-                const uint32_t d0 = p0[0], d1 = p0[1], d2 = p0[2];
-                const uint32_t lo = __builtin_amdgcn_alignbit(d1, d0, sh);  // (d1 : d0) >> sh, sh a multiple of 8 below 32
-                const uint32_t hi = __builtin_amdgcn_alignbit(d2, d1, sh);
-                const uint32_t mid = shr_nibbles(lo, hi, c);  // values 4..7 start at bit 4c
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    u[k] = __builtin_amdgcn_ubfe(lo, (uint32_t)k * c, c);
-                    u[4 + k] = __builtin_amdgcn_ubfe(mid, (uint32_t)k * c, c);
-                }
-            } else {
-                const uint32_t v = (c == 9) ? stage8[hdr + goff] : 0u;
-#pragma unroll
-                for (int k = 0; k < 8; ++k) u[k] = v;
-            }
-            // undo zig-zag, prefix sum along the channel index (mod 256)
-            int q[8];
-            int acc = 0;
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                acc += (int)(u[k] >> 1) ^ -(int)(u[k] & 1u);
-                q[k] = acc;
-            }
-            const uint32_t incl = row_incl_scan_u32((uint32_t)acc, lane_in_row(a.g, (uint32_t)(p * 64 + lane)), row_carry);
-            row_carry = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
-            const int before = (int)(incl - (uint32_t)acc);
-            if (mode == KVC_MODE_PACK) {  // values are the codes themselves: undo the in-lane sums
-#pragma unroll
-                for (int k = 7; k > 0; --k) q[k] -= q[k - 1];
-            } else {
-#pragma unroll
-                for (int k = 0; k < 8; ++k) q[k] += before;
-            }
-            if (act) *reinterpret_cast<uint4*>(dst + elem_off(a.g, e0)) = dequant8(q, s);
-        }
-    }
-    return true;
-}
-
-template <int MAXP, int PPW>
-__global__ __launch_bounds__(kThreads) void k_decompress(DecodeArgs a) {
-    __shared__ __align__(16) uint32_t s_stage[kWavesPerWG][Slot<MAXP>::kWords];
-    __shared__ uint32_t s_ginfo[kWavesPerWG][MAXP * 16];
-    const int lane = lane_id();
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t t0 = ((int64_t)task_block_index<1>() * kWavesPerWG + wave) * PPW;
-    TaskPos pos = task_pos(t0, a.g.ppb);
-    for (int i = 0; i < PPW; ++i) {
-        const DecTask task = resolve_dec_task(a, t0 + i, pos);
-        task_advance(pos, a.g.ppb);
-        if (task.kind == 2) zero_page(task.dst, a.g);
-        if (task.kind == 1 && !decode_page<MAXP>(a, task.desc_idx, task.dst, s_stage[wave], s_ginfo[wave])) {
-            if (lane == 0) atomicOr(&a.st->status, KVC_ST_CORRUPT);
-        }
-        wave_sync();
-    }
-}
 
 // ---------------------------------------------------------------------------------- small kernels
 
@@ -632,36 +232,6 @@ __global__ __launch_bounds__(256) void k_window_build(WindowArgs w) {
     }
 }
 
-// Transfer engines of the window for the generic page geometries: see window_next.
-template <int MAXP>
-__global__ __launch_bounds__(kThreads) void k_decompress_window(DecodeArgs a, WindowArgs w) {
-    __shared__ __align__(16) uint32_t s_stage[kWavesPerWG][Slot<MAXP>::kWords];
-    __shared__ uint32_t s_ginfo[kWavesPerWG][MAXP * 16];
-    __shared__ uint32_t s_turn[2];
-    const int lane = lane_id();
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    WindowTurn none;
-    none.first = none.count = 0;
-    WindowTurn turn = window_next(w, s_turn, none);
-    while (turn.count) {
-        for (uint32_t i = 0; i < turn.count; ++i) {
-            const int32_t slot = __builtin_amdgcn_readfirstlane(w.queue[turn.first + i]);
-            for (int pg = wave; pg < a.g.ppb; pg += kWavesPerWG) {
-                TaskPos pos;
-                pos.blk = slot;
-                pos.pg = pg;
-                const DecTask task = resolve_dec_task(a, (int64_t)slot * a.g.ppb + pg, pos);
-                if (task.kind == 2) zero_page(task.dst, a.g);
-                if (task.kind == 1 && !decode_page<MAXP>(a, task.desc_idx, task.dst, s_stage[wave], s_ginfo[wave])) {
-                    if (lane == 0) atomicOr(&a.st->status, KVC_ST_CORRUPT);
-                }
-                wave_sync();
-            }
-        }
-        turn = window_next(w, s_turn, turn);
-    }
-}
-
 __global__ void k_fill_i32(int32_t* p, int32_t v, uint64_t n) {
     for (uint64_t k = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += (uint64_t)gridDim.x * blockDim.x) p[k] = v;
 }
@@ -681,39 +251,31 @@ __global__ void k_page_scales(const uint16_t* amax, float* s, float* s_inv, uint
 
 // ---------------------------------------------------------------------------------- launchers
 
-// geometries served by the specialised kernels of kvc_fast.h
+// the kernels of a page shape: the exact instantiation when there is one, else the one that reads the
+// token count at run time
 const FastKernels* fast_kernels(int N, int d) {
-    using Lookup = const FastKernels* (*)(int, int);
-    static const Lookup groups[kFastGroups] = {fast_kernels_group0, fast_kernels_group1, fast_kernels_group2, fast_kernels_group3,
-                                               fast_kernels_group4, fast_kernels_group5, fast_kernels_group6, fast_kernels_group7};
-    for (Lookup f : groups)
-        if (const FastKernels* k = f(N, d)) return k;
+    static const FastLookup groups[kFastGroups] = {
+        fast_kernels_group0, fast_kernels_group1, fast_kernels_group2,  fast_kernels_group3,  fast_kernels_group4,  fast_kernels_group5,
+        fast_kernels_group6, fast_kernels_group7, fast_kernels_group8,  fast_kernels_group9,  fast_kernels_group10, fast_kernels_group11,
+        fast_kernels_group12, fast_kernels_group13, fast_kernels_group14, fast_kernels_group15};
+    if (N < 1 || d < 32 || d > 256 || d % 32 != 0 || (int64_t)N * d > 4096) return nullptr;
+    const int E = N * d, np = (E + 511) / 512;
+    for (int partial = E == np * 512 ? 0 : 1; partial < 2; ++partial)
+        for (FastLookup f : groups)
+            if (const FastKernels* k = f(d, np, partial != 0)) return k;
     return nullptr;
-}
-
-static inline unsigned grid_for(int64_t n_pages, int ppw) {
-    const int64_t per_wg = (int64_t)kWavesPerWG * ppw;
-    return (unsigned)((n_pages + per_wg - 1) / per_wg);
 }
 
 hipError_t launch_compress(const EncodeArgs& a, hipStream_t s) {
     if (a.n_pages == 0) return hipSuccess;
-    if (const FastKernels* f = fast_kernels(a.g.N, a.g.d)) return f->compress(a, s);
-    constexpr int PPW = 4;
-    const dim3 grid(grid_for(a.n_pages, PPW)), block(kThreads);
-    if (a.g.E <= 512) return launch_kernel(k_compress<1, PPW>, grid, block, s, a);
-    if (a.g.E <= 2048) return launch_kernel(k_compress<4, PPW>, grid, block, s, a);
-    return launch_kernel(k_compress<8, 2>, dim3(grid_for(a.n_pages, 2)), block, s, a);
+    const FastKernels* f = fast_kernels(a.g.N, a.g.d);
+    return f ? f->compress(a, s) : hipErrorInvalidValue;
 }
 
 hipError_t launch_decompress(const DecodeArgs& a, hipStream_t s) {
     if (a.n_pages == 0) return hipSuccess;
-    if (const FastKernels* f = fast_kernels(a.g.N, a.g.d)) return f->decompress(a, s);
-    constexpr int PPW = 4;
-    const dim3 grid(grid_for(a.n_pages, PPW)), block(kThreads);
-    if (a.g.E <= 512) return launch_kernel(k_decompress<1, PPW>, grid, block, s, a);
-    if (a.g.E <= 2048) return launch_kernel(k_decompress<4, PPW>, grid, block, s, a);
-    return launch_kernel(k_decompress<8, PPW>, grid, block, s, a);
+    const FastKernels* f = fast_kernels(a.g.N, a.g.d);
+    return f ? f->decompress(a, s) : hipErrorInvalidValue;
 }
 
 hipError_t launch_prefetch_plan(const PlanArgs& a, hipStream_t s) {
@@ -734,11 +296,8 @@ hipError_t launch_window_build(const WindowArgs& w, hipStream_t s) {
 hipError_t launch_decompress_window(const DecodeArgs& a, const WindowArgs& w, int32_t omega, hipStream_t s) {
     if (w.n_now <= 0) return hipSuccess;
     const unsigned grid = (unsigned)std::min<int64_t>(omega, w.n_now);
-    if (const FastKernels* f = fast_kernels(a.g.N, a.g.d)) return f->decompress_window(a, w, grid, s);
-    const dim3 block(kThreads);
-    if (a.g.E <= 512) return launch_kernel(k_decompress_window<1>, dim3(grid), block, s, a, w);
-    if (a.g.E <= 2048) return launch_kernel(k_decompress_window<4>, dim3(grid), block, s, a, w);
-    return launch_kernel(k_decompress_window<8>, dim3(grid), block, s, a, w);
+    const FastKernels* f = fast_kernels(a.g.N, a.g.d);
+    return f ? f->decompress_window(a, w, grid, s) : hipErrorInvalidValue;
 }
 
 hipError_t launch_fill_i32(int32_t* p, int32_t v, uint64_t n, hipStream_t s) {

@@ -119,15 +119,16 @@ def _soak_pages(rng, n, N, d):
 _SOAK_CASES = [(16, d, sc) for d in (64, 128, 256) for sc in (2, 3, 4, "mixed")] + \
               [(N, d, sc) for (N, d) in ((8, 128), (32, 64), (16, 32), (4, 256)) for sc in (3, "mixed")] + [(16, 128, 5), (16, 256, 5)] + \
               [(N, d, sc) for (N, d) in ((16, 96), (16, 160), (16, 192), (16, 224), (8, 96), (32, 96), (8, 192),
-                                         (8, 64), (8, 256), (32, 32), (32, 128)) for sc in (3, "mixed")]
+                                         (8, 64), (8, 256), (32, 32), (32, 128)) for sc in (3, "mixed")] + \
+              [(N, d, sc) for (N, d) in ((7, 128), (24, 160), (3, 256), (15, 256), (21, 192), (100, 32), (4, 128), (12, 96),
+                                         (18, 224), (40, 64)) for sc in (2, "mixed")]  # pages with a short last pass, one to eight passes
 
 
 @pytest.mark.parametrize("N,d,scheme", _SOAK_CASES)
 def test_every_kernel_instantiation_under_full_occupancy(N, d, scheme):
-    """Each instantiation of the 16-token kernels (three head dimensions; the compile-time scheme, the
-    run-time scheme and the per-block scheme) and of the generic kernels (one, four or eight passes per
-    page) on enough pages that several workgroups share every compute unit, three launches each, every
-    page compared with the oracle bit for bit."""
+    """Instantiations of the kernels for exact page shapes (the compile-time scheme, the run-time scheme and
+    the per-block scheme) and for pages with a short last pass, on enough pages that several workgroups share
+    every compute unit, three launches each, every page compared with the oracle bit for bit."""
     n = 24576
     rng = np.random.default_rng(7000 + 31 * N + d + (9 if scheme == "mixed" else scheme) + 100003 * int(os.environ.get("KVC_DIFF_SEED", "0")))
     x = _soak_pages(rng, n, N, d)
@@ -172,3 +173,41 @@ def test_every_kernel_instantiation_under_full_occupancy(N, d, scheme):
             badp = np.unique(np.searchsorted(np.cumsum(size), np.nonzero(got != ref)[0], side="right"))
             raise AssertionError(f"launch {launch}: payload bytes differ in {badp.size} pages, first {badp[:8]}")
         assert np.array_equal(out.cpu().numpy().view(np.uint16).reshape(-1, N, d), want), f"launch {launch}: decoded values differ"
+
+
+def _shape_pages(rng, n, N, d):
+    x = _soak_pages(rng, n, N, d)
+    x[0] = 0                                         # all zero
+    x[1] = 0
+    x[1, N - 1, d - 1] = -3.5                        # one element, the page's last
+    x[2].view(np.uint16)[N // 2, d // 3] = 0x7E00    # a NaN: stored raw
+    x[3] = np.float16(2.0)                           # every delta but the rows' first is zero
+    x[4] = (np.arange(N * d).reshape(N, d) % 251).astype(np.float16)
+    return x
+
+
+@pytest.mark.parametrize("d", [32, 64, 96, 128, 160, 192, 224, 256])
+def test_every_page_shape(d):
+    """Every accepted token count for this channel count (N * d <= 4096): pages that fill their last pass of
+    512 elements and pages that do not, with one to eight passes, an odd and an even number of packet
+    groups.  Two requested modes per shape, both launch shapes of the encoder over the sweep."""
+    for N in range(1, 4096 // d + 1):
+        rng = np.random.default_rng(50000 + 97 * N + d)
+        n = 2100 if N % 7 == 3 else 160  # some shapes with more than 2048 pages: the large-call launch shape
+        x = _shape_pages(rng, n, N, d)
+        xt = torch.from_numpy(x.reshape(-1, 1, N, d)).to(DEV)
+        for scheme in (3, (N + d // 32) % 5):
+            print(f"[case] page shape N={N} d={d} pages={n} scheme={scheme}", flush=True)
+            c = kvc.Codec(N, d, 1, scheme)
+            c.alloc_pool(n, n * N * d * 2 + 64, DEV)
+            c.compress_blocks(xt)
+            out = torch.full_like(xt, 7.0)
+            c.decompress_blocks(out)
+            st = c.stats()
+            assert st["rc"] == 0, (N, d, scheme, st)
+            desc, pool = c.desc_numpy(), c.pool.cpu().numpy()
+            check_pool_invariants(desc, st["pool_bytes_used"], pool.size)
+            od, op = compare_pages_with_oracle(x.view(np.uint16), desc, pool, N, d, scheme)
+            want, bad = o.decompress_pages(op, od, N, d, n_threads=8)
+            assert bad == 0
+            assert np.array_equal(out.cpu().numpy().view(np.uint16).reshape(-1, N, d), want), (N, d, scheme)

@@ -573,7 +573,9 @@ def bench_prefetch_window(args):
     def preds(pattern, t):
         if pattern == "uniform":
             return pat.predictions(t)
-        pos = (t // N + np.arange(n_seq) * 7) % pat.n_blocks
+        # a window sliding over consecutive blocks, at the steps where it moves (every 16th token of a decode):
+        # one new block per sequence and layer, 5,120 transfers per step
+        pos = (t + np.arange(n_seq) * 7) % pat.n_blocks
         return ((pos[:, None] + 1 + np.arange(k)[None, :]) % pat.n_blocks[:, None]).astype(np.int32)
 
     def prefetch(omega, fill, pred_t, st):

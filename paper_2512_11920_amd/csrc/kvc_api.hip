@@ -15,6 +15,7 @@ static __device__ __align__(256) unsigned char scratch[kStaticWindowBytes];
 
 struct kvc_ctx {
     int prefetch_policy = 0;
+    int window_capacity = 0;      // window engines this device holds at once (0: unknown); an upper bound on useful omega
     void* static_work = nullptr;  // device address of `scratch` on this context's device
     kvc_config cfg;
     kvc::Geometry g;
@@ -103,6 +104,7 @@ int kvc_create(kvc_ctx** out, const kvc_config* cfg) {
         delete c;
         return KVC_ERR_HIP;
     }
+    c->window_capacity = kvc::window_engine_capacity(c->g);
     *out = c;
     return KVC_OK;
 }
@@ -353,6 +355,8 @@ static int prefetch_impl(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_f
     a.pool_ids = d_fetch + first;
     a.n_pages = n_now * ctx->g.ppb;
     if (omega == 0) return hip_ok(kvc::launch_decompress(a, s)) ? KVC_OK : KVC_ERR_HIP;
+    // engines beyond what the device holds at once would never get a turn: the bound stays "at most omega"
+    if (ctx->window_capacity > 0) omega = std::min(omega, ctx->window_capacity);
     kvc::WindowArgs w;
     char* wb = static_cast<char*>(work);
     w.hdr = reinterpret_cast<kvc::WindowHdr*>(wb);

@@ -122,6 +122,7 @@ inline hipError_t launch_kernel(void (*kernel)(P...), dim3 grid, dim3 block, hip
 hipError_t launch_prefetch_plan(const PlanArgs& a, hipStream_t s);
 hipError_t launch_window_build(const WindowArgs& w, hipStream_t s);
 hipError_t launch_decompress_window(const DecodeArgs& a, const WindowArgs& w, int32_t omega, hipStream_t s);
+int window_engine_capacity(const Geometry& g);
 hipError_t launch_fill_i32(int32_t* p, int32_t v, uint64_t n, hipStream_t s);
 hipError_t launch_compress(const EncodeArgs& a, hipStream_t s);
 hipError_t launch_decompress(const DecodeArgs& a, hipStream_t s);

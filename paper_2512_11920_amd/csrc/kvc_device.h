@@ -467,6 +467,7 @@ struct FastKernels {
     hipError_t (*compress)(const EncodeArgs& a, hipStream_t s);
     hipError_t (*decompress)(const DecodeArgs& a, hipStream_t s);
     hipError_t (*decompress_window)(const DecodeArgs& a, const WindowArgs& w, unsigned grid, hipStream_t s);
+    int (*window_capacity)();  // window engines resident on the current device at once (0: unknown)
 };
 constexpr int kFastGroups = 16;
 using FastLookup = const FastKernels* (*)(int d, int np, bool partial);

@@ -965,7 +965,19 @@ struct FastOps {
         return launch_kernel(k_decompress_window_fast<P, kFastWaves>, dim3(grid), dim3(kFastWaves * 64), s, a, w);
     }
 
-    static constexpr FastKernels kTable = {D, NP, PARTIAL, &compress, &decompress, &decompress_window};
+    // engines the current device holds at once: a larger grid would only queue workgroups behind the
+    // resident ones, which keep taking turns until the queue is empty
+    static int window_capacity() {
+        int dev = 0, cus = 0, per_cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_decompress_window_fast<P, kFastWaves>, kFastWaves * 64, 0) != hipSuccess) {
+            (void)hipGetLastError();
+            return 0;  // unknown: no cap
+        }
+        return cus * per_cu;
+    }
+
+    static constexpr FastKernels kTable = {D, NP, PARTIAL, &compress, &decompress, &decompress_window, &window_capacity};
 };
 
 }  // namespace

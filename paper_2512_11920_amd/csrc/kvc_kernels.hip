@@ -300,6 +300,11 @@ hipError_t launch_decompress_window(const DecodeArgs& a, const WindowArgs& w, in
     return f ? f->decompress_window(a, w, grid, s) : hipErrorInvalidValue;
 }
 
+int window_engine_capacity(const Geometry& g) {
+    const FastKernels* f = fast_kernels(g.N, g.d);
+    return f ? f->window_capacity() : 0;
+}
+
 hipError_t launch_fill_i32(int32_t* p, int32_t v, uint64_t n, hipStream_t s) {
     if (n == 0) return hipSuccess;
     const unsigned blocks = (unsigned)std::min<uint64_t>((n + 255) / 256, 4096);

@@ -497,6 +497,9 @@ __device__ __forceinline__ void encode_into_slot(const EncodeArgs& a, const uint
 #ifndef KVC_ENC_MIN_WAVES
 #define KVC_ENC_MIN_WAVES 4
 #endif
+#ifndef KVC_ENC_WAVES_1KB
+#define KVC_ENC_WAVES_1KB 8
+#endif
 
 // Pages a wave holds in registers at once: while one is encoded the loads of the others are in flight.
 // Measured best with the ring as long as the wave's whole share (all loads issued up front, about 16 KB
@@ -905,9 +908,11 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_window_fast(DecodeArg
 // Launch shapes by page size (NP passes of 1 KB): waves per workgroup, pages per wave.
 constexpr int kFastWaves = 4;
 // large calls: about 64 KB of input per workgroup and one pool-cursor atomic for it
-constexpr int enc_ppw_large(int np) { return np == 1 ? 16 : np == 2 ? 8 : np == 3 ? 5 : np == 4 ? 4 : np == 5 ? KVC_PPW5 : np == 6 ? KVC_PPW6 : np == 7 ? KVC_PPW7 : KVC_PPW8; }
+constexpr int enc_ppw_large(int np) { return np == 1 ? 64 / KVC_ENC_WAVES_1KB : np == 2 ? 8 : np == 3 ? 5 : np == 4 ? 4 : np == 5 ? KVC_PPW5 : np == 6 ? KVC_PPW6 : np == 7 ? KVC_PPW7 : KVC_PPW8; }
 // waves per encoder workgroup in large calls
-constexpr int enc_waves_large(int np) { return np >= 5 ? KVC_ENC_WAVES_LONG : 4; }
+// (one-pass pages: eight waves share the workgroup's 64 slots, so that six waves instead of four fit a SIMD
+// beside the LDS the slots take: 0.41 -> 0.51 of HBM peak at 16 x 32; two-pass pages lose by the same change)
+constexpr int enc_waves_large(int np) { return np >= 5 ? KVC_ENC_WAVES_LONG : np == 1 ? KVC_ENC_WAVES_1KB : 4; }
 // A small call (a decode step's offload of a few blocks) is latency: one page per wave (more only for
 // the smallest pages), so the pages are encoded side by side instead of several in a row.  The cursor
 // then takes an atomic per four pages, which only a large call would feel.

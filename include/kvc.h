@@ -211,9 +211,10 @@ int kvc_prefetch_layers(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fe
  *             ticks, never 0) at which its last transfer completed -- the ready notification a consumer
  *             may poll or wait for; a layer that needed no transfer is stamped when the window opens.
  *             [n_layers] = clock when the window opened, [n_layers+1] = transfers issued by the call,
- *             [n_layers+2] = transfer engines the call put to work: min(omega, transfers issued, the number
- *             of engines the GPU holds at once -- 1,024 to 2,048 on MI355X, by page shape); no more blocks
- *             than that are ever in flight,
+ *             [n_layers+2] = transfer engines the call put to work: at most omega, at most one per transfer
+ *             issued, at most what the GPU holds at once (1,024 to 2,048 on MI355X, by page shape), and
+ *             beyond 256 only while each engine has at least eight transfers; no more blocks than that are
+ *             ever in flight,
  *             [n_layers+3] = 0 until every transfer of the call has completed, then that clock value.
  *   d_work    device workspace of at least kvc_prefetch_window_workspace(n_blocks, n_layers_call) bytes,
  *             256-byte aligned, n_blocks = (layer_end - layer_begin) * n_seq * k, n_layers_call =

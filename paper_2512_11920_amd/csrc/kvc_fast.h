@@ -866,6 +866,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_window_fast(DecodeArg
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int ppb = a.g.ppb;
+    if (blockIdx.x >= w.hdr->engines) return;  // the window was opened for fewer engines than the grid holds
     WindowTurn none;
     none.first = none.count = 0;
     WindowTurn turn = window_next(w, s_turn, none);

@@ -188,47 +188,77 @@ __global__ void k_prefetch_plan(PlanArgs a) {
 // Opens the outstanding-request window of a prefetch call: the transfers the planner issued (entries
 // >= 0 of the call's part of the fetch list) are queued in issue order -- layer, sequence, slot -- each
 // layer's count becomes its pending counter, and the notification words are reset: a layer with nothing
-// to transfer is ready at once, the others when their last transfer completes.  One workgroup.
-__global__ __launch_bounds__(256) void k_window_build(WindowArgs w) {
+// to transfer is ready at once, the others when their last transfer completes.  Two launches, one
+// workgroup per layer each: count, then place (a layer's entries begin where the layers before it end).
+__global__ __launch_bounds__(256) void k_window_count(WindowArgs w) {
     __shared__ uint32_t s_cnt[4];
+    const int l = blockIdx.x;
+    uint32_t n = 0;
+    for (int i = threadIdx.x; i < w.per_layer; i += 256) n += w.fetch[(int64_t)l * w.per_layer + i] >= 0 ? 1u : 0u;
+    n = wave_incl_scan_dpp(n);
+    if (lane_id() == 63) s_cnt[threadIdx.x >> 6] = n;
+    __syncthreads();
+    if (threadIdx.x == 0) w.pending[l] = (int32_t)(s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3]);
+}
+
+__global__ __launch_bounds__(256) void k_window_place(WindowArgs w) {
+    __shared__ uint32_t s_cnt[4];
+    __shared__ uint32_t s_sum[2][4];
     const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int l = blockIdx.x;
     const long long now = max(wall_clock64(), 1ll);
-    uint32_t base = 0;  // queue entries so far (workgroup-uniform)
-    for (int l = 0; l < w.n_layers_call; ++l) {
-        uint32_t in_layer = 0;
-        for (int c0 = 0; c0 < w.per_layer; c0 += 256) {
-            const int i = c0 + (int)threadIdx.x;
-            const bool live = i < w.per_layer && w.fetch[(int64_t)l * w.per_layer + i] >= 0;
-            const uint64_t m = __builtin_amdgcn_ballot_w64(live);
-            if (lane == 0) s_cnt[wave] = (uint32_t)__builtin_popcountll(m);
-            __syncthreads();
-            uint32_t before = 0, all = 0;
-            for (int k = 0; k < 4; ++k) {
-                before += k < wave ? s_cnt[k] : 0u;
-                all += s_cnt[k];
-            }
-            if (live) w.queue[base + in_layer + before + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u))] = l * w.per_layer + i;
-            in_layer += all;
-            __syncthreads();
+    // entries of the layers before this one, and of all layers
+    uint32_t before_l = 0, all_l = 0;
+    for (int j = threadIdx.x; j < w.n_layers_call; j += 256) {
+        const uint32_t c = (uint32_t)w.pending[j];
+        before_l += j < l ? c : 0u;
+        all_l += c;
+    }
+    before_l = wave_incl_scan_dpp(before_l);
+    all_l = wave_incl_scan_dpp(all_l);
+    if (lane == 63) {
+        s_sum[0][wave] = before_l;
+        s_sum[1][wave] = all_l;
+    }
+    __syncthreads();
+    const uint32_t base = s_sum[0][0] + s_sum[0][1] + s_sum[0][2] + s_sum[0][3];
+    const uint32_t total = s_sum[1][0] + s_sum[1][1] + s_sum[1][2] + s_sum[1][3];
+    uint32_t in_layer = 0;  // entries of this layer placed so far (workgroup-uniform)
+    for (int c0 = 0; c0 < w.per_layer; c0 += 256) {
+        const int i = c0 + (int)threadIdx.x;
+        const bool live = i < w.per_layer && w.fetch[(int64_t)l * w.per_layer + i] >= 0;
+        const uint64_t m = __builtin_amdgcn_ballot_w64(live);
+        __syncthreads();  // the counts of the chunk before have been read
+        if (lane == 0) s_cnt[wave] = (uint32_t)__builtin_popcountll(m);
+        __syncthreads();
+        uint32_t before = 0, all = 0;
+        for (int k = 0; k < 4; ++k) {
+            before += k < wave ? s_cnt[k] : 0u;
+            all += s_cnt[k];
         }
-        if (threadIdx.x == 0) {
-            w.pending[l] = (int32_t)in_layer;
-            w.notify[w.layer_begin + l] = in_layer ? 0ll : now;
-        }
-        base += in_layer;
+        if (live) w.queue[base + in_layer + before + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u))] = l * w.per_layer + i;
+        in_layer += all;
     }
     if (threadIdx.x == 0) {
-        const unsigned int engines = min(base, (uint32_t)w.omega);
-        w.hdr->n_issued = base;
-        w.hdr->engines = engines;
-        // entries per turn: long queues space out the bookkeeping, short ones keep every engine busy
-        w.hdr->chunk = engines ? min(max(base / (4u * engines), 1u), 8u) : 1u;
-        w.hdr->ticket = 0;
-        w.hdr->done = 0;
-        w.notify[w.n_layers] = now;                       // window opened
-        w.notify[w.n_layers + 1] = (long long)base;       // transfers issued
-        w.notify[w.n_layers + 2] = (long long)engines;    // engines at work: the bound on blocks in flight
-        w.notify[w.n_layers + 3] = base ? 0ll : now;      // all complete
+        w.notify[w.layer_begin + l] = in_layer ? 0ll : now;
+        if (l == 0) {
+            // Engines at work: at most omega, at most one per transfer -- and beyond 256 of them only as far
+            // as each still has eight transfers to carry out: every turn of every engine is three atomics on
+            // shared counters, and a short queue spread over a thousand engines spends its time there
+            // (5,120 transfers: 0.51 ms with 1,024 engines, 0.33 ms with 256).
+            unsigned int engines = min(total, (uint32_t)w.omega);
+            if (engines > 256u) engines = min(engines, max(256u, total / 8u));
+            w.hdr->n_issued = total;
+            w.hdr->engines = engines;
+            // entries per turn: long queues space out the bookkeeping, short ones keep every engine busy
+            w.hdr->chunk = engines ? min(max(total / (4u * engines), 1u), 8u) : 1u;
+            w.hdr->ticket = 0;
+            w.hdr->done = 0;
+            w.notify[w.n_layers] = now;                        // window opened
+            w.notify[w.n_layers + 1] = (long long)total;       // transfers issued
+            w.notify[w.n_layers + 2] = (long long)engines;     // engines at work: the bound on blocks in flight
+            w.notify[w.n_layers + 3] = total ? 0ll : now;      // all complete
+        }
     }
 }
 
@@ -288,7 +318,10 @@ hipError_t launch_prefetch_plan(const PlanArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_window_build(const WindowArgs& w, hipStream_t s) {
-    return launch_kernel(k_window_build, dim3(1), dim3(256), s, w);
+    if (w.n_layers_call <= 0) return hipSuccess;
+    const hipError_t e = launch_kernel(k_window_count, dim3((unsigned)w.n_layers_call), dim3(256), s, w);
+    if (e != hipSuccess) return e;
+    return launch_kernel(k_window_place, dim3((unsigned)w.n_layers_call), dim3(256), s, w);
 }
 
 // At most omega workgroups, one block in flight each; the queue may turn out shorter than the grid, in

@@ -56,7 +56,7 @@ def read_traffic(tag: str, kernel: str):
         return None, {"file": None, "note": "no rocprofv3 --pmc summary is committed for this workload"}
     val, fp, name = None, None, None
     for line in open(p):
-        # `kernel` is k_compress or k_decompress; the summary names the kernel that ran (k_compress_fast, ...)
+        # `kernel` is k_compress or k_decompress
         if line.startswith(kernel) and "_traffic_bytes:" in line:
             name, val = line.split("_traffic_bytes:")[0], int(float(line.split(":")[1].split()[0]))
         if line.startswith("kernel_fingerprint:"):
@@ -279,7 +279,7 @@ def main():
     tag = shape.name + (f"_scheme{args.scheme}" if args.scheme != 3 else "")
     traffic, traffic_source = (None, {"file": None, "note": "layer count overridden"}) if args.layers else read_traffic(tag, "k_" + dom)
     # the kernel behind the entry point; the committed profile of the workload names it
-    kname = traffic_source.get("kernel") or f"k_{dom}_fast"
+    kname = traffic_source.get("kernel") or f"k_{dom}"
     res = {
         "metric": "KV codec GB/s (uncompressed fp16) compress+decompress; % of HBM peak",
         "value": round((2 * unc + g_unc) / (ms_step * 1e-3) / 1e9, 2),
@@ -372,7 +372,7 @@ def bench_decode_gather(args):
         "config": {"workload": f"decode_gather: 80 layers x 8 KV heads x 128, 64 sequences U[512,8192], "
                                f"8 predicted blocks/seq/layer, {n_pages} pages = {unc / 1e9:.2f} GB out per step",
                    "ratio": round(codec.ratio(), 4)},
-        "roofline": {"bound": "hbm", "kernel": "k_decompress_fast", "achieved": round(alg / ts.mean() / 1e6, 1),
+        "roofline": {"bound": "hbm", "kernel": "k_decompress", "achieved": round(alg / ts.mean() / 1e6, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(alg / ts.mean() / 1e6 / HBM_PEAK_GBS, 4),
                      "traffic": dg_traffic, "traffic_source": dg_source, "alg_bytes_per_launch": int(alg),
                      "launch_ms": round(float(ts.mean()), 4)},

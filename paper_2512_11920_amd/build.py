@@ -1,7 +1,7 @@
 """Build libkvc.so (HIP, gfx950) in-tree with hipcc.  No GPU is needed to compile.
 
-The specialised kernels (csrc/kvc_fast.hip) are compiled once per group of page shapes
-(-DKVC_FAST_GROUP=k), side by side with the other sources; the objects are then linked."""
+The codec kernels (csrc/kvc_codec.hip) are compiled once per group of page shapes
+(-DKVC_SHAPE_GROUP=k), side by side with the other sources; the objects are then linked."""
 from __future__ import annotations
 
 import concurrent.futures
@@ -12,12 +12,12 @@ import sys
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
 _CSRC = os.path.join(_PKG, "csrc")
-FAST_GROUPS = 16  # see csrc/kvc_fast.hip
+SHAPE_GROUPS = 16  # see csrc/kvc_codec.hip
 #: (source, extra defines, object name)
 UNITS = [("kvc_kernels.hip", (), "kvc_kernels.o"), ("kvc_api.hip", (), "kvc_api.o")] + \
-        [("kvc_fast.hip", (f"-DKVC_FAST_GROUP={g}",), f"kvc_fast_{g}.o") for g in range(FAST_GROUPS)]
-SOURCES = [os.path.join(_CSRC, f) for f in ("kvc_kernels.hip", "kvc_fast.hip", "kvc_api.hip")]
-HEADERS = [os.path.join(_CSRC, f) for f in ("kvc_common.h", "kvc_device.h", "kvc_fast.h")] + [os.path.join(_ROOT, "include", "kvc.h")]
+        [("kvc_codec.hip", (f"-DKVC_SHAPE_GROUP={g}",), f"kvc_codec_{g}.o") for g in range(SHAPE_GROUPS)]
+SOURCES = [os.path.join(_CSRC, f) for f in ("kvc_kernels.hip", "kvc_codec.hip", "kvc_api.hip")]
+HEADERS = [os.path.join(_CSRC, f) for f in ("kvc_common.h", "kvc_device.h", "kvc_codec.h")] + [os.path.join(_ROOT, "include", "kvc.h")]
 LIB = os.path.join(_PKG, "libkvc.so")
 #: the same library with every LDS index and pool span the kernels compute checked against its bounds
 #: (a violation sets status bit 8); a GPU test runs the parity cases through it

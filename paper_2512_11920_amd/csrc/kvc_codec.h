@@ -3,7 +3,7 @@
 // (N = NP * 512 / D tokens; 16 x 128 FP16, D = 128 and NP = 4, is the paper's 4 KB page and the shape the
 // tuning was done on), where every quantity is a constant and no lane is ever inactive, and -- PARTIAL --
 // pages of any other token count that needs NP passes, where the element count is read at run time and the
-// last pass is short.  This file holds the templates; kvc_fast.hip instantiates them.
+// last pass is short.  This file holds the templates; kvc_codec.hip instantiates them.
 //
 // Lane mapping: one wave per page, passes of 512 elements, a lane owns 8 consecutive channels (one 128-bit
 // access), a packet group is a quad of lanes, a token row is D/8 neighbouring lanes (one 16-lane DPP row at
@@ -341,7 +341,7 @@ __device__ __forceinline__ void load_page(const EncodeArgs& a, const EncTask& ta
 // compile-time SCHEME when that is >= 0 (one mode for the whole launch: its branches fold away), else
 // the wave-uniform run-time value.
 template <class P, int SCHEME>
-__device__ __forceinline__ PageResult encode_page_fast(const uint4 (&raw)[P::kPasses], const LanePos& lp, const Extent& x, int scheme_rt,
+__device__ __forceinline__ PageResult encode_page(const uint4 (&raw)[P::kPasses], const LanePos& lp, const Extent& x, int scheme_rt,
                                                  uint32_t* stage, const uint8_t* lut, DevState* st) {
     const int scheme = SCHEME >= 0 ? SCHEME : scheme_rt;
     constexpr int kE = P::kE, NP = P::kPasses;
@@ -460,7 +460,7 @@ __device__ __forceinline__ void encode_into_slot(const EncodeArgs& a, const uint
     r.n16 = 0;
     r.mode = KVC_MODE_INVALID;
     r.scale = 0.0f;
-    if (task.desc_idx >= 0) r = encode_page_fast<P, SCHEME>(raw, lp, page_extent<P>(a.g), task.scheme, stage, lut, a.st);
+    if (task.desc_idx >= 0) r = encode_page<P, SCHEME>(raw, lp, page_extent<P>(a.g), task.scheme, stage, lut, a.st);
     if (lane_id() == 0) {
         book.n16[slot] = r.n16;
         book.mode[slot] = r.mode;
@@ -520,7 +520,7 @@ constexpr int enc_min_waves() {
     return ((P::kD == 256 && SCHEME == KVC_MODE_CHAN) || (P::kPasses >= 7 && (!P::kAligned || P::kPartial) && SCHEME < 0)) ? 3 : KVC_ENC_MIN_WAVES;
 }
 template <class P, int WAVES, int PPW, int SCHEME>
-__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(enc_min_waves<P, SCHEME>()))) void k_compress_fast(EncodeArgs a) {
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(enc_min_waves<P, SCHEME>()))) void k_compress(EncodeArgs a) {
     constexpr int kSlots = WAVES * PPW;
     constexpr int NP = P::kPasses;
     constexpr bool CHAN = SCHEME == KVC_MODE_CHAN;
@@ -823,7 +823,7 @@ __device__ __forceinline__ bool dec_finish(const DecodeArgs& a, const DecPage<P>
 }
 
 template <class P, int WAVES, int PPW>
-__global__ __launch_bounds__(WAVES * 64) void k_decompress_fast(DecodeArgs a) {
+__global__ __launch_bounds__(WAVES * 64) void k_decompress(DecodeArgs a) {
     __shared__ __align__(16) uint32_t s_stage[WAVES][Slot<P::kPasses>::kWords];
     __shared__ uint32_t s_ginfo[WAVES][P::kGroups];
     const int lane = lane_id();
@@ -859,7 +859,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_fast(DecodeArgs a) {
 // workgroup takes the next issued block from the queue, its waves decode the block's pages, and the
 // completion is reported before the next block is taken.
 template <class P, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void k_decompress_window_fast(DecodeArgs a, WindowArgs w) {
+__global__ __launch_bounds__(WAVES * 64) void k_decompress_window(DecodeArgs a, WindowArgs w) {
     __shared__ __align__(16) uint32_t s_stage[WAVES][Slot<P::kPasses>::kWords];
     __shared__ uint32_t s_ginfo[WAVES][P::kGroups];
     __shared__ uint32_t s_turn[2];
@@ -907,7 +907,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_window_fast(DecodeArg
 }
 
 // Launch shapes by page size (NP passes of 1 KB): waves per workgroup, pages per wave.
-constexpr int kFastWaves = 4;
+constexpr int kCodecWaves = 4;
 // large calls: about 64 KB of input per workgroup and one pool-cursor atomic for it
 constexpr int enc_ppw_large(int np) { return np == 1 ? 64 / KVC_ENC_WAVES_1KB : np == 2 ? 8 : np == 3 ? 5 : np == 4 ? 4 : np == 5 ? KVC_PPW5 : np == 6 ? KVC_PPW6 : np == 7 ? KVC_PPW7 : KVC_PPW8; }
 // waves per encoder workgroup in large calls
@@ -925,23 +925,23 @@ constexpr int dec_ppw(int np) { return np == 1 ? 4 : np == 2 ? 2 : 1; }
 #define KVC_ENC_SMALL_PAGES 2048
 #endif
 
-inline dim3 fast_grid(int64_t n_pages, int ppw, int waves = kFastWaves) {
+inline dim3 page_grid(int64_t n_pages, int ppw, int waves = kCodecWaves) {
     const int64_t per_wg = (int64_t)waves * ppw;
     return dim3((unsigned)((n_pages + per_wg - 1) / per_wg));
 }
 
 // The host side of one page shape: picks the instantiation and launches it.
 template <int D, int NP, bool PARTIAL>
-struct FastOps {
+struct ShapeOps {
     using P = Page<D, NP, PARTIAL>;
 
     template <int SCHEME>
     static hipError_t compress_scheme(const EncodeArgs& a, hipStream_t s) {
-        const dim3 block(kFastWaves * 64);
+        const dim3 block(kCodecWaves * 64);
         if (a.n_pages <= KVC_ENC_SMALL_PAGES)
-            return launch_kernel(k_compress_fast<P, kFastWaves, enc_ppw_small(NP), SCHEME>, fast_grid(a.n_pages, enc_ppw_small(NP)), block, s, a);
+            return launch_kernel(k_compress<P, kCodecWaves, enc_ppw_small(NP), SCHEME>, page_grid(a.n_pages, enc_ppw_small(NP)), block, s, a);
         constexpr int W = enc_waves_large(NP);
-        return launch_kernel(k_compress_fast<P, W, enc_ppw_large(NP), SCHEME>, fast_grid(a.n_pages, enc_ppw_large(NP), W), dim3(W * 64), s, a);
+        return launch_kernel(k_compress<P, W, enc_ppw_large(NP), SCHEME>, page_grid(a.n_pages, enc_ppw_large(NP), W), dim3(W * 64), s, a);
     }
 
     static hipError_t compress(const EncodeArgs& a, hipStream_t s) {
@@ -964,11 +964,11 @@ struct FastOps {
     }
 
     static hipError_t decompress(const DecodeArgs& a, hipStream_t s) {
-        return launch_kernel(k_decompress_fast<P, kFastWaves, dec_ppw(NP)>, fast_grid(a.n_pages, dec_ppw(NP)), dim3(kFastWaves * 64), s, a);
+        return launch_kernel(k_decompress<P, kCodecWaves, dec_ppw(NP)>, page_grid(a.n_pages, dec_ppw(NP)), dim3(kCodecWaves * 64), s, a);
     }
 
     static hipError_t decompress_window(const DecodeArgs& a, const WindowArgs& w, unsigned grid, hipStream_t s) {
-        return launch_kernel(k_decompress_window_fast<P, kFastWaves>, dim3(grid), dim3(kFastWaves * 64), s, a, w);
+        return launch_kernel(k_decompress_window<P, kCodecWaves>, dim3(grid), dim3(kCodecWaves * 64), s, a, w);
     }
 
     // engines the current device holds at once: a larger grid would only queue workgroups behind the
@@ -976,14 +976,14 @@ struct FastOps {
     static int window_capacity() {
         int dev = 0, cus = 0, per_cu = 0;
         if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_decompress_window_fast<P, kFastWaves>, kFastWaves * 64, 0) != hipSuccess) {
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_decompress_window<P, kCodecWaves>, kCodecWaves * 64, 0) != hipSuccess) {
             (void)hipGetLastError();
             return 0;  // unknown: no cap
         }
         return cus * per_cu;
     }
 
-    static constexpr FastKernels kTable = {D, NP, PARTIAL, &compress, &decompress, &decompress_window, &window_capacity};
+    static constexpr ShapeKernels kTable = {D, NP, PARTIAL, &compress, &decompress, &decompress_window, &window_capacity};
 };
 
 }  // namespace

@@ -456,12 +456,12 @@ __device__ __forceinline__ WindowTurn window_next(const WindowArgs& w, uint32_t*
     return r;
 }
 
-// The codec kernels are specialised at compile time for the page shape (kvc_fast.h): d channels, np
+// The codec kernels are specialised at compile time for the page shape (kvc_codec.h): d channels, np
 // passes of 512 elements, and whether the page fills its last pass (exact: d * N = 512 * np) or not
 // (partial: the token count N is read at run time).  These are the host-side entry points of one shape.
-// The shapes are compiled in groups (kvc_fast.hip), one lookup function per group; fast_kernels() finds
+// The shapes are compiled in groups (kvc_codec.hip), one lookup function per group; shape_kernels() finds
 // the set for N tokens x d channels (nullptr: N * d exceeds eight passes).
-struct FastKernels {
+struct ShapeKernels {
     int d, np;
     bool partial;
     hipError_t (*compress)(const EncodeArgs& a, hipStream_t s);
@@ -469,13 +469,13 @@ struct FastKernels {
     hipError_t (*decompress_window)(const DecodeArgs& a, const WindowArgs& w, unsigned grid, hipStream_t s);
     int (*window_capacity)();  // window engines resident on the current device at once (0: unknown)
 };
-constexpr int kFastGroups = 16;
-using FastLookup = const FastKernels* (*)(int d, int np, bool partial);
-#define KVC_DECLARE_GROUP(G) const FastKernels* fast_kernels_group##G(int d, int np, bool partial);
+constexpr int kShapeGroups = 16;
+using ShapeLookup = const ShapeKernels* (*)(int d, int np, bool partial);
+#define KVC_DECLARE_GROUP(G) const ShapeKernels* shape_kernels_group##G(int d, int np, bool partial);
 KVC_DECLARE_GROUP(0) KVC_DECLARE_GROUP(1) KVC_DECLARE_GROUP(2) KVC_DECLARE_GROUP(3) KVC_DECLARE_GROUP(4) KVC_DECLARE_GROUP(5)
 KVC_DECLARE_GROUP(6) KVC_DECLARE_GROUP(7) KVC_DECLARE_GROUP(8) KVC_DECLARE_GROUP(9) KVC_DECLARE_GROUP(10) KVC_DECLARE_GROUP(11)
 KVC_DECLARE_GROUP(12) KVC_DECLARE_GROUP(13) KVC_DECLARE_GROUP(14) KVC_DECLARE_GROUP(15)
 #undef KVC_DECLARE_GROUP
-const FastKernels* fast_kernels(int N, int d);
+const ShapeKernels* shape_kernels(int N, int d);
 
 }  // namespace kvc

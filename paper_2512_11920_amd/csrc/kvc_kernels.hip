@@ -1,7 +1,7 @@
 // The small kernels around the codec (pool reset, statistics, yardstick copy, prefetch planner and the
 // window's queue builder) and the launchers of every kernel.  The codec kernels themselves -- Algorithm 2
-// of the paper and its inverse, Section 3.5.3 -- are the templates of kvc_fast.h, instantiated per page
-// shape by kvc_fast.hip and found here through fast_kernels().
+// of the paper and its inverse, Section 3.5.3 -- are the templates of kvc_codec.h, instantiated per page
+// shape by kvc_codec.hip and found here through shape_kernels().
 #include <algorithm>
 
 #include "kvc_device.h"
@@ -283,28 +283,28 @@ __global__ void k_page_scales(const uint16_t* amax, float* s, float* s_inv, uint
 
 // the kernels of a page shape: the exact instantiation when there is one, else the one that reads the
 // token count at run time
-const FastKernels* fast_kernels(int N, int d) {
-    static const FastLookup groups[kFastGroups] = {
-        fast_kernels_group0, fast_kernels_group1, fast_kernels_group2,  fast_kernels_group3,  fast_kernels_group4,  fast_kernels_group5,
-        fast_kernels_group6, fast_kernels_group7, fast_kernels_group8,  fast_kernels_group9,  fast_kernels_group10, fast_kernels_group11,
-        fast_kernels_group12, fast_kernels_group13, fast_kernels_group14, fast_kernels_group15};
+const ShapeKernels* shape_kernels(int N, int d) {
+    static const ShapeLookup groups[kShapeGroups] = {
+        shape_kernels_group0, shape_kernels_group1, shape_kernels_group2,  shape_kernels_group3,  shape_kernels_group4,  shape_kernels_group5,
+        shape_kernels_group6, shape_kernels_group7, shape_kernels_group8,  shape_kernels_group9,  shape_kernels_group10, shape_kernels_group11,
+        shape_kernels_group12, shape_kernels_group13, shape_kernels_group14, shape_kernels_group15};
     if (N < 1 || d < 32 || d > 256 || d % 32 != 0 || (int64_t)N * d > 4096) return nullptr;
     const int E = N * d, np = (E + 511) / 512;
     for (int partial = E == np * 512 ? 0 : 1; partial < 2; ++partial)
-        for (FastLookup f : groups)
-            if (const FastKernels* k = f(d, np, partial != 0)) return k;
+        for (ShapeLookup f : groups)
+            if (const ShapeKernels* k = f(d, np, partial != 0)) return k;
     return nullptr;
 }
 
 hipError_t launch_compress(const EncodeArgs& a, hipStream_t s) {
     if (a.n_pages == 0) return hipSuccess;
-    const FastKernels* f = fast_kernels(a.g.N, a.g.d);
+    const ShapeKernels* f = shape_kernels(a.g.N, a.g.d);
     return f ? f->compress(a, s) : hipErrorInvalidValue;
 }
 
 hipError_t launch_decompress(const DecodeArgs& a, hipStream_t s) {
     if (a.n_pages == 0) return hipSuccess;
-    const FastKernels* f = fast_kernels(a.g.N, a.g.d);
+    const ShapeKernels* f = shape_kernels(a.g.N, a.g.d);
     return f ? f->decompress(a, s) : hipErrorInvalidValue;
 }
 
@@ -329,12 +329,12 @@ hipError_t launch_window_build(const WindowArgs& w, hipStream_t s) {
 hipError_t launch_decompress_window(const DecodeArgs& a, const WindowArgs& w, int32_t omega, hipStream_t s) {
     if (w.n_now <= 0) return hipSuccess;
     const unsigned grid = (unsigned)std::min<int64_t>(omega, w.n_now);
-    const FastKernels* f = fast_kernels(a.g.N, a.g.d);
+    const ShapeKernels* f = shape_kernels(a.g.N, a.g.d);
     return f ? f->decompress_window(a, w, grid, s) : hipErrorInvalidValue;
 }
 
 int window_engine_capacity(const Geometry& g) {
-    const FastKernels* f = fast_kernels(g.N, g.d);
+    const ShapeKernels* f = shape_kernels(g.N, g.d);
     return f ? f->window_capacity() : 0;
 }
 

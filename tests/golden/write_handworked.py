@@ -93,6 +93,26 @@ add("channel_pairs_mode5_d256", 16, 256, x, 5, "3f800000",
          "41 = 3 (byte 20 high), 73 = 3 (byte 36 high), 80 = 1 (byte 40 low), 111 = 9 (byte 55 high); all other groups "
          "zero-run. 64+32+12+12+4+1 = 125 -> 128 B")
 
+x = np.zeros((3, 32))
+x[1:, :] = 127
+add("odd_group_count_n3_d32", 3, 32, x, 3, "3f800000",
+    "8008" + ("fe" + "00" * 31) * 2 + "00" * 14,
+    note="three groups (one per token row), so the header is two bytes and the second one's high nibble is unused: row 0 all "
+         "zero -> code 0; rows 1 and 2 all 127 -> delta [127, 0, ...], u0 = 254, w = 8 (32 B each). Header byte 0 = g0 | g1<<4 = "
+         "0x80, byte 1 = g2 = 0x08. 2 + 32 + 32 = 66 -> 80 B, below the 96 B of the INT8 form")
+x = np.zeros((5, 96))
+x[0, 0] = 127
+x[2, 32:64] = 3
+x[4, 95] = -1
+add("short_last_pass_n5_d96", 5, 96, x, 3, "3f800000",
+    "08000030" + "03000001" + "fefd" + "00" * 30 + "06" + "00" * 11 + "05" + "00" * 11 + "00000080" + "00" * 12,
+    note="480 elements: 15 groups (three per token row of 96 channels), 8 header bytes, the last nibble unused. g0 (row 0, "
+         "channels 0-31): q = [127, 0, ...] -> delta [127, -127, 0, ...] -> u = [254, 253, 0, ...], w = 8 (32 B: fe fd 00..). "
+         "g7 (row 2, channels 32-63, all 3): delta [3, 0, ...] -> u0 = 6, w = 3 (12 B, byte 0 = 0x06). g8 (row 2, channels 64-95): "
+         "delta [-3, 0, ...] -> u0 = 5, w = 3 (byte 0 = 0x05). g14 (row 4, channels 64-95): last element -1 -> position 31, u = 1, "
+         "w = 1 (4 B, bit 31 -> byte 3 = 0x80). Header nibbles: g0 = 8 (byte 0 low), g7 = 3 (byte 3 high), g8 = 3 (byte 4 low), "
+         "g14 = 1 (byte 7 low). 8 + 32 + 12 + 12 + 4 = 68 -> 80 B")
+
 doc = dict(citation="Algorithm 2 (KV-Cache Compression) and Section 3.5.3 (inverse), under the KVC-1 reading of the "
            "unspecified byte format; worked by hand, not produced by any implementation. The paper prints no numeric example.",
            cases=cases)

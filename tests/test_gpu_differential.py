@@ -71,7 +71,7 @@ def _families(rng, n, N, d):
                                           # head dimensions that are not powers of two: token rows of 12, 20, 24, 28 lanes
                                           (16, 96, 3000, 3), (16, 160, 3000, 3), (16, 192, 3000, 3), (16, 224, 3000, 3),
                                           (16, 96, 2000, 4), (16, 192, 2000, 2), (8, 96, 2000, 3), (21, 192, 1500, 3), (3, 160, 2000, 3),
-                                          # every other specialised page shape, both launch shapes (large calls, calls of at most 2048 pages)
+                                          # every other exact page shape, both launch shapes (large calls, calls of at most 2048 pages)
                                           (8, 64, 5000, 3), (8, 128, 4000, 2), (8, 192, 3000, 3), (8, 256, 3000, 4), (32, 32, 4000, 3),
                                           (32, 64, 3000, 3), (32, 96, 2500, 4), (32, 128, 2500, 3),
                                           (16, 32, 2000, 3), (16, 96, 1500, 3), (16, 160, 2048, 3), (16, 192, 1000, 3), (16, 224, 900, 4),

@@ -69,6 +69,20 @@ def read_traffic(tag: str, kernel: str):
     return val, src
 
 
+def device_info():
+    """What the runtime reports about the GPU, recorded beside the pinned 8 TB/s peak."""
+    import torch
+
+    p = torch.cuda.get_device_properties(0)
+    info = {"name": p.name, "compute_units": p.multi_processor_count, "hbm_GB": round(p.total_memory / 1e9, 1)}
+    from paper_2512_11920_amd import kvc
+
+    ck = kvc.device_clocks()
+    info.update({"arch": p.gcnArchName, "shader_clock_MHz": round(ck["shader_khz"] / 1e3), "memory_clock_MHz": round(ck["memory_khz"] / 1e3),
+                 "memory_bus_bits": ck["memory_bus_bits"]})
+    return info
+
+
 def sample_check(codec, cache_blocks, out_blocks, n_sample, N, d, ppb, scheme):
     """Compare a random sample of pages (descriptor, payload, decoded values) with the oracle."""
     import numpy as np
@@ -259,7 +273,7 @@ def main():
     }
     for k_, v in kern.items():
         v["frac_of_peak"] = v["hbm_GBps"] / HBM_PEAK_GBS
-        v["ms_min"], v["ms_max"] = min(per_step[k_]), max(per_step[k_])
+        v["ms_min"], v["ms_max"], v["ms_p50"] = min(per_step[k_]), max(per_step[k_]), float(np.median(per_step[k_]))
     # same-run yardstick: plain 128-bit copy of the cache
     cp = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     src8, dst8 = blocks.view(torch.uint8).view(-1), out.view(torch.uint8).view(-1)
@@ -305,6 +319,7 @@ def main():
         "kernels": {k_: {a: (round(b, 4) if isinstance(b, float) else b) for a, b in v.items()} for k_, v in kern.items()},
         "copy_kernel_GBps": round(copy_gbps, 1),
         "sample_parity_vs_oracle": check_ok,
+        "device": device_info(),
     }
     if not args.no_cpu_baseline:
         # the first layers of the same cache, moved to the host

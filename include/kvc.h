@@ -252,9 +252,14 @@ int kvc_stats(kvc_ctx* ctx, kvc_stats_t* out, void* stream);
 const char* kvc_strerror(int code);
 
 /* ---- Verification and measurement hooks -------------------------------------------------------
- * The two calls below are not steps of the codec path and no codec call depends on them.  They exist so
- * that a test can check the encoder's scale arithmetic exhaustively and so that a benchmark can time a
- * plain copy with the codec's access shape on the same device, through the same library. */
+ * The calls below are not steps of the codec path and no codec call depends on them.  They exist so
+ * that a test can check the encoder's scale arithmetic exhaustively, so that a benchmark can time a
+ * plain copy with the codec's access shape on the same device, through the same library, and so that it
+ * can record the clocks the runtime reports beside the bandwidth it measures. */
+
+/* Shader clock, memory clock (both kHz) and memory bus width (bits) of the current device, as
+ * hipDeviceGetAttribute reports them; any pointer may be NULL.  KVC_ERR_HIP if a query fails. */
+int kvc_device_clocks(int32_t* shader_khz, int32_t* memory_khz, int32_t* memory_bus_bits);
 
 /* The scaling step of Algorithm 2 on its own: for n page maxima given as FP16 bit patterns (sign
  * ignored) write s = amax / 127 and s_inv = 1 / s as the encoder computes them (binary32); 0, Inf

@@ -395,6 +395,22 @@ int kvc_wall_clock_khz(int32_t* khz) {
     return KVC_OK;
 }
 
+int kvc_device_clocks(int32_t* shader_khz, int32_t* memory_khz, int32_t* memory_bus_bits) {
+    int dev = -1;
+    if (!hip_ok(hipGetDevice(&dev))) return KVC_ERR_HIP;
+    const struct {
+        int32_t* out;
+        hipDeviceAttribute_t attr;
+    } q[3] = {{shader_khz, hipDeviceAttributeClockRate}, {memory_khz, hipDeviceAttributeMemoryClockRate}, {memory_bus_bits, hipDeviceAttributeMemoryBusWidth}};
+    for (const auto& e : q) {
+        int v = 0;
+        if (!e.out) continue;
+        if (!hip_ok(hipDeviceGetAttribute(&v, e.attr, dev))) return KVC_ERR_HIP;
+        *e.out = v;
+    }
+    return KVC_OK;
+}
+
 int kvc_prefetch_layers_window(kvc_ctx* ctx, void* d_l2, int32_t* d_tags, int32_t* d_fetch, int32_t* d_loc,
                                const int32_t* d_block_table, int32_t max_blocks, const int32_t* d_pred,
                                const int32_t* d_l1_first_block, int32_t n_seq, int32_t k, int32_t n_layers,

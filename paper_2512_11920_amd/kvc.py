@@ -22,7 +22,7 @@ DESC_DTYPE = np.dtype([("off", "<u8"), ("scale", "<f4"), ("n16", "<u2"), ("mode"
 
 EXPORTS = ("kvc_create", "kvc_destroy", "kvc_set_scheme", "kvc_set_cache_layout", "kvc_bind_pool", "kvc_reset_pool", "kvc_compress_blocks",
            "kvc_compress_blocks_mixed", "kvc_decompress_blocks", "kvc_gather_decompress", "kvc_set_prefetch_policy", "kvc_prefetch_reset", "kvc_prefetch_layers", "kvc_prefetch_window_workspace",
-           "kvc_prefetch_layers_window", "kvc_prefetch_layers_window_static", "kvc_wall_clock_khz", "kvc_stats", "kvc_page_scales",
+           "kvc_prefetch_layers_window", "kvc_prefetch_layers_window_static", "kvc_wall_clock_khz", "kvc_device_clocks", "kvc_stats", "kvc_page_scales",
            "kvc_copy_bytes", "kvc_strerror")
 
 
@@ -96,6 +96,8 @@ def load():
                                                     C.c_int32, C.c_int32, C.c_int64, C.c_int32, C.c_int32, vp, vp]
     L.kvc_wall_clock_khz.restype = C.c_int
     L.kvc_wall_clock_khz.argtypes = [C.POINTER(C.c_int32)]
+    L.kvc_device_clocks.restype = C.c_int
+    L.kvc_device_clocks.argtypes = [C.POINTER(C.c_int32)] * 3
     L.kvc_stats.restype = C.c_int
     L.kvc_stats.argtypes = [vp, C.POINTER(Stats), vp]
     L.kvc_page_scales.restype = C.c_int
@@ -329,6 +331,13 @@ class Codec:
 def window_workspace(n_blocks: int, n_layers_call: int) -> int:
     """Bytes of device workspace prefetch_layers_window needs for a call over n_blocks slots."""
     return int(load().kvc_prefetch_window_workspace(int(n_blocks), int(n_layers_call)))
+
+
+def device_clocks() -> dict:
+    """Shader and memory clock (kHz) and memory bus width (bits) of the current device, as the runtime reports them."""
+    a, b, c = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+    _check(load().kvc_device_clocks(C.byref(a), C.byref(b), C.byref(c)), "kvc_device_clocks")
+    return {"shader_khz": a.value, "memory_khz": b.value, "memory_bus_bits": c.value}
 
 
 def wall_clock_khz() -> int:

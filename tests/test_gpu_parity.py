@@ -468,3 +468,9 @@ def test_copy_yardstick_copies_every_byte(nbytes):
     kvc.copy_bytes(buf[:nbytes], src)
     torch.cuda.synchronize()
     assert torch.equal(buf[:nbytes], src) and bool((buf[nbytes:] == 0xA5).all())
+
+
+def test_device_clocks_hook():
+    ck = kvc.device_clocks()
+    assert ck["shader_khz"] > 100_000 and ck["memory_khz"] > 100_000 and ck["memory_bus_bits"] >= 1024, ck
+    assert kvc.load().kvc_device_clocks(None, None, None) == kvc.OK

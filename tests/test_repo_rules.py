@@ -45,3 +45,22 @@ def test_no_cuda_compat_layers_in_kernels():
         if path.endswith((".hip", ".h")):
             text = open(path, errors="replace").read()
             assert "__HIP_PLATFORM" not in text and "cuda_runtime" not in text and "hipify" not in text.lower(), path
+
+
+def test_traffic_lookup_refuses_a_summary_taken_on_other_sources(tmp_path, monkeypatch):
+    """bench.py reports HBM traffic from a committed rocprofv3 summary only when the summary carries the
+    fingerprint of the kernel sources in the tree."""
+    sys.path.insert(0, ROOT)
+    import bench
+
+    fp = bench.kernel_fingerprint()
+    assert re.fullmatch(r"[0-9a-f]{16}", fp) and fp == bench.kernel_fingerprint()
+    monkeypatch.setattr(bench, "ROOT", str(tmp_path))
+    monkeypatch.setattr(bench, "kernel_fingerprint", lambda: fp)
+    os.makedirs(tmp_path / "profiles")
+    assert bench.read_traffic("w", "k_compress")[0] is None  # no summary at all
+    (tmp_path / "profiles" / "hbm_traffic_w.txt").write_text(f"kernel_fingerprint: {fp}\nk_compress_traffic_bytes: 123\nk_decompress_traffic_bytes: 456\n")
+    assert bench.read_traffic("w", "k_compress")[0] == 123 and bench.read_traffic("w", "k_decompress")[0] == 456
+    (tmp_path / "profiles" / "hbm_traffic_w.txt").write_text("kernel_fingerprint: 0000000000000000\nk_compress_traffic_bytes: 123\n")
+    val, src = bench.read_traffic("w", "k_compress")
+    assert val is None and "other kernel sources" in src["note"]

@@ -858,11 +858,13 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress(DecodeArgs a) {
 // Transfer engines of the prefetch window (Algorithm 1: at most Omega_max transfers outstanding): a
 // workgroup takes the next issued block from the queue, its waves decode the block's pages, and the
 // completion is reported before the next block is taken.
+// (pages of up to four passes whose rows do not cross passes: held within 128 VGPRs, so that four waves fit a SIMD)
 template <class P, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void k_decompress_window(DecodeArgs a, WindowArgs w) {
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(P::kPasses <= 4 && P::kAligned ? 4 : 1))) void k_decompress_window(DecodeArgs a, WindowArgs w) {
     __shared__ __align__(16) uint32_t s_stage[WAVES][Slot<P::kPasses>::kWords];
     __shared__ uint32_t s_ginfo[WAVES][P::kGroups];
     __shared__ uint32_t s_turn[2];
+    __shared__ int32_t s_q[WAVES][2][64];
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int ppb = a.g.ppb;
@@ -871,8 +873,17 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_window(DecodeArgs a, 
     none.first = none.count = 0;
     WindowTurn turn = window_next(w, s_turn, none);
     while (turn.count) {
+      // the turn's queue entries (at most 64) and the pool blocks they name, fetched one per lane and parked
+      // in the wave's row of LDS: two trips to memory per turn instead of two per block
+      if ((uint32_t)lane < turn.count) {
+          const int32_t slot_l = w.queue[turn.first + lane];
+          s_q[wave][0][lane] = slot_l;
+          s_q[wave][1][lane] = a.pool_ids[slot_l];
+      }
+      wave_sync();
       for (uint32_t i = 0; i < turn.count; ++i) {
-        const int32_t slot = __builtin_amdgcn_readfirstlane(w.queue[turn.first + i]);
+        const int32_t slot = __builtin_amdgcn_readfirstlane(s_q[wave][0][i]);
+        const int32_t pb = __builtin_amdgcn_readfirstlane(s_q[wave][1][i]);
         // a wave takes the block's pages wave, wave + WAVES, ... four at a time: all four descriptor loads
         // are issued before the first is looked at, then all payload loads before the first page is decoded
         constexpr int kSide = 4;
@@ -883,10 +894,8 @@ __global__ __launch_bounds__(WAVES * 64) void k_decompress_window(DecodeArgs a, 
 #pragma unroll
             for (int j = 0; j < kSide; ++j) {
                 const int pg = pg0 + j * WAVES;
-                TaskPos pos;
-                pos.blk = slot;
-                pos.pg = pg;
-                task[j] = resolve_dec_task(a, pg < ppb ? (int64_t)slot * ppb + pg : a.n_pages, pos);  // past the block: no task
+                task[j].kind = 0;  // past the block: no task
+                if (pg < ppb) task[j] = place_dec_task(a, pb, slot, pg, false);
                 if (task[j].kind == 1) dw[j] = reinterpret_cast<const uint4*>(a.desc)[task[j].desc_idx];
             }
 #pragma unroll

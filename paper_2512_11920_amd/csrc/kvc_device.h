@@ -271,15 +271,38 @@ struct DecTask {
     uint16_t* dst;
 };
 
-__device__ __forceinline__ DecTask resolve_dec_task(const DecodeArgs& a, int64_t t, const TaskPos& pos) {
+// Second half of the resolution: pool block pb (< 0: nothing stored there) into output block db.
+__device__ __forceinline__ DecTask place_dec_task(const DecodeArgs& a, int64_t pb, int64_t db, int pg, bool bad_index) {
     DecTask r;
     r.kind = 0;
     r.desc_idx = 0;
     r.dst = nullptr;
-    if (t >= a.n_pages) return r;
     const Geometry& g = a.g;
+    if (db < 0 || db >= a.n_out_blocks) {
+        if (db >= 0 && lane_id() == 0) atomicOr(&a.st->status, KVC_ST_BAD_INDEX);
+        return r;
+    }
+    r.dst = a.out + page_base(g, db, pg);
+    if (!bad_index && pb < 0) return r;  // skip
+    r.desc_idx = (uint64_t)pb * (uint64_t)g.ppb + (uint64_t)pg;
+    if (bad_index || r.desc_idx >= a.n_desc) {
+        if (lane_id() == 0) atomicOr(&a.st->status, KVC_ST_BAD_INDEX);
+        r.kind = 2;
+        return r;
+    }
+    r.kind = 1;
+    return r;
+}
+
+__device__ __forceinline__ DecTask resolve_dec_task(const DecodeArgs& a, int64_t t, const TaskPos& pos) {
+    if (t >= a.n_pages) {
+        DecTask r;
+        r.kind = 0;
+        r.desc_idx = 0;
+        r.dst = nullptr;
+        return r;
+    }
     const int64_t blk = pos.blk;
-    const int pg = pos.pg;
     int64_t pb, db;
     bool bad_index = false;
     if (a.block_table) {  // translate (layer, sequence, predicted logical block) -> pool block
@@ -304,20 +327,7 @@ __device__ __forceinline__ DecTask resolve_dec_task(const DecodeArgs& a, int64_t
         pb = a.pool_ids ? (int64_t)wave_uniform(a.pool_ids[blk]) : blk;
         db = a.dst_ids ? (int64_t)wave_uniform(a.dst_ids[blk]) : blk;
     }
-    if (db < 0 || db >= a.n_out_blocks) {
-        if (db >= 0 && lane_id() == 0) atomicOr(&a.st->status, KVC_ST_BAD_INDEX);
-        return r;
-    }
-    r.dst = a.out + page_base(g, db, pg);
-    if (!bad_index && pb < 0) return r;  // skip
-    r.desc_idx = (uint64_t)pb * (uint64_t)g.ppb + (uint64_t)pg;
-    if (bad_index || r.desc_idx >= a.n_desc) {
-        if (lane_id() == 0) atomicOr(&a.st->status, KVC_ST_BAD_INDEX);
-        r.kind = 2;
-        return r;
-    }
-    r.kind = 1;
-    return r;
+    return place_dec_task(a, pb, db, pos.pg, bad_index);
 }
 
 __device__ __forceinline__ void zero_page(uint16_t* dst, const Geometry& g) {

@@ -40,4 +40,30 @@ for N, d in ((16, 128), (16, 64), (16, 256), (16, 96), (16, 224), (8, 192), (32,
         want, bad = o.decompress_pages(op, od, N, d, n_threads=8)
         assert bad == 0 and np.array_equal(out.cpu().numpy().view(np.uint16).reshape(-1, N, d), want)
         n_cases += 1
+# pages with a short last pass: for every channel count the smallest, an odd, a middle and the largest token count
+for d in (32, 64, 96, 128, 160, 192, 224, 256):
+    n_max = 4096 // d
+    for N in sorted({1, 3, n_max // 2 + 1, n_max - 1, n_max}):
+        rng = np.random.default_rng(7 * N + d)
+        x = td._shape_pages(rng, 300, N, d)
+        for scheme in (3, (N + d // 32) % 5):
+            print(f"[case] bounds-checking build N={N} d={d} scheme={scheme} pages={x.shape[0]}", flush=True)
+            xt = torch.from_numpy(x.reshape(-1, 1, N, d)).to(DEV)
+            c = kvc.Codec(N, d, 1, scheme)
+            c.alloc_pool(x.shape[0], x.shape[0] * N * d * 2 + 64, DEV)
+            c.compress_blocks(xt)
+            out = torch.empty_like(xt)
+            c.decompress_blocks(out)
+            st = c.stats()
+            assert st["status"] == 0, f"status {st['status']:#x}: bit 8 = an index or span left its bounds"
+            od, op = o.compress_pages(x.view(np.uint16), N, d, scheme, n_threads=8)
+            want, bad = o.decompress_pages(op, od, N, d, n_threads=8)
+            assert bad == 0 and np.array_equal(out.cpu().numpy().view(np.uint16).reshape(-1, N, d), want)
+            n_cases += 1
+# the prefetch window's queue builder and engines (these tests end with status == 0, which includes bit 8)
+import test_gpu_prefetch as tpf  # noqa: E402
+
+for omega, geom in ((5, (16, 128, 4, 5, 8, 4, 48, 200)), (16, (8, 32, 2, 5, 8, 4, 48, 200)), (4096, (16, 32, 1, 48, 16, 5, 400, 800))):
+    tpf.test_window_prefetch_matches_unbounded_and_model(omega, geom)
+    n_cases += 1
 print(f"debug-bounds ok: {n_cases} cases", flush=True)

@@ -140,6 +140,14 @@ int kvc_bind_pool(kvc_ctx* ctx, void* d_pool, uint64_t pool_bytes, kvc_desc* d_d
 /* Cursor = 0, status = 0, every descriptor = INVALID.  Enqueues fill kernels only. */
 int kvc_reset_pool(kvc_ctx* ctx, void* stream);
 
+/* Resume on a pool that was filled earlier: the cursor continues at used_bytes (a multiple of 16, at most
+ * the pool size; the value kvc_stats reported as pool_bytes_used when the pool was saved), the status is
+ * cleared, the descriptors are left as they are.  A pool, its descriptor table and that one number are a
+ * complete checkpoint of the compressed tier: copy them back into buffers of the same sizes, bind them to
+ * a context of the same geometry, call this, and compress, decompress and gather go on as before.
+ * Enqueues one small kernel. */
+int kvc_restore_pool(kvc_ctx* ctx, uint64_t used_bytes, void* stream);
+
 /* Algorithm 2 over n blocks.  Block i is read from cache block src[i] (NULL: i) and stored as pool
  * block pool[i] (NULL: i).  d_cache: FP16 [n_cache_blocks][ppb][N][d].  Space comes from a bump
  * cursor; placement order inside the pool is unspecified, descriptors say where each page is.

@@ -182,6 +182,14 @@ int kvc_reset_pool(kvc_ctx* ctx, void* stream) {
                : KVC_ERR_HIP;
 }
 
+int kvc_restore_pool(kvc_ctx* ctx, uint64_t used_bytes, void* stream) {
+    if (!ctx) return KVC_ERR_ARG;
+    if (!ctx->pool) return KVC_ERR_NOT_BOUND;
+    if ((used_bytes & 15u) || used_bytes > ctx->pool_bytes) return KVC_ERR_ARG;
+    if (!on_ctx_device(ctx)) return KVC_ERR_ARG;
+    return hip_ok(kvc::launch_set_cursor(ctx->st, used_bytes / 16, static_cast<hipStream_t>(stream))) ? KVC_OK : KVC_ERR_HIP;
+}
+
 static int compress_impl(kvc_ctx* ctx, const void* d_cache, int64_t n_cache_blocks, const int32_t* d_src_block_ids,
                          const int32_t* d_pool_block_ids, const uint8_t* d_block_scheme, int32_t n, void* stream) {
     if (!ctx || n < 0 || n_cache_blocks < 0) return KVC_ERR_ARG;

@@ -127,6 +127,7 @@ hipError_t launch_fill_i32(int32_t* p, int32_t v, uint64_t n, hipStream_t s);
 hipError_t launch_compress(const EncodeArgs& a, hipStream_t s);
 hipError_t launch_decompress(const DecodeArgs& a, hipStream_t s);
 hipError_t launch_reset(DevState* st, kvc_desc* desc, uint64_t n_desc, hipStream_t s);
+hipError_t launch_set_cursor(DevState* st, uint64_t cursor16, hipStream_t s);
 hipError_t launch_stats(DevState* st, const kvc_desc* desc, uint64_t n_desc, hipStream_t s);
 hipError_t launch_page_scales(const uint16_t* amax, float* s, float* s_inv, uint64_t n, hipStream_t st);
 hipError_t launch_copy(void* dst, const void* src, uint64_t n16, hipStream_t s);

@@ -20,6 +20,13 @@ __global__ void k_reset(DevState* st, kvc_desc* desc, uint64_t n_desc) {
         reinterpret_cast<uint4*>(desc)[k] = make_uint4(0, 0, 0, (uint32_t)KVC_MODE_INVALID << 16);
 }
 
+__global__ void k_set_cursor(DevState* st, unsigned long long cursor16) {
+    if (threadIdx.x == 0) {
+        st->cursor16 = cursor16;
+        st->status = 0;
+    }
+}
+
 __global__ void k_stats_zero(DevState* st) {
     if (threadIdx.x < 8) st->stats[threadIdx.x] = 0;
 }
@@ -347,6 +354,10 @@ hipError_t launch_fill_i32(int32_t* p, int32_t v, uint64_t n, hipStream_t s) {
 hipError_t launch_reset(DevState* st, kvc_desc* desc, uint64_t n_desc, hipStream_t s) {
     const unsigned blocks = (unsigned)std::min<uint64_t>(std::max<uint64_t>((n_desc + 255) / 256, 1), 65536);
     return launch_kernel(k_reset, dim3(blocks), dim3(256), s, st, desc, n_desc);
+}
+
+hipError_t launch_set_cursor(DevState* st, uint64_t cursor16, hipStream_t s) {
+    return launch_kernel(k_set_cursor, dim3(1), dim3(64), s, st, (unsigned long long)cursor16);
 }
 
 hipError_t launch_stats(DevState* st, const kvc_desc* desc, uint64_t n_desc, hipStream_t s) {

@@ -20,7 +20,7 @@ ST_POOL_FULL, ST_CORRUPT, ST_BAD_INDEX = 1, 2, 4
 #: numpy view of kvc_desc
 DESC_DTYPE = np.dtype([("off", "<u8"), ("scale", "<f4"), ("n16", "<u2"), ("mode", "u1"), ("rsvd", "u1")])
 
-EXPORTS = ("kvc_create", "kvc_destroy", "kvc_set_scheme", "kvc_set_cache_layout", "kvc_bind_pool", "kvc_reset_pool", "kvc_compress_blocks",
+EXPORTS = ("kvc_create", "kvc_destroy", "kvc_set_scheme", "kvc_set_cache_layout", "kvc_bind_pool", "kvc_reset_pool", "kvc_restore_pool", "kvc_compress_blocks",
            "kvc_compress_blocks_mixed", "kvc_decompress_blocks", "kvc_gather_decompress", "kvc_set_prefetch_policy", "kvc_prefetch_reset", "kvc_prefetch_layers", "kvc_prefetch_window_workspace",
            "kvc_prefetch_layers_window", "kvc_prefetch_layers_window_static", "kvc_wall_clock_khz", "kvc_device_clocks", "kvc_stats", "kvc_page_scales",
            "kvc_copy_bytes", "kvc_strerror")
@@ -71,6 +71,8 @@ def load():
     L.kvc_bind_pool.argtypes = [vp, vp, C.c_uint64, vp, C.c_uint64]
     L.kvc_reset_pool.restype = C.c_int
     L.kvc_reset_pool.argtypes = [vp, vp]
+    L.kvc_restore_pool.restype = C.c_int
+    L.kvc_restore_pool.argtypes = [vp, C.c_uint64, vp]
     L.kvc_compress_blocks.restype = C.c_int
     L.kvc_compress_blocks.argtypes = [vp, vp, C.c_int64, i32p, i32p, C.c_int32, vp]
     L.kvc_compress_blocks_mixed.restype = C.c_int
@@ -195,6 +197,10 @@ class Codec:
 
     def reset_pool(self, stream=None):
         _check(self._L.kvc_reset_pool(self._ctx, _stream(stream)), "kvc_reset_pool")
+
+    def restore_pool(self, used_bytes: int, stream=None):
+        """Continue on a bound pool that holds an earlier run's payloads: the cursor resumes at used_bytes."""
+        _check(self._L.kvc_restore_pool(self._ctx, int(used_bytes), _stream(stream)), "kvc_restore_pool")
 
     def set_scheme(self, scheme: int):
         _check(self._L.kvc_set_scheme(self._ctx, scheme), "kvc_set_scheme")

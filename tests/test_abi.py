@@ -56,6 +56,7 @@ def test_host_side_argument_checks_need_no_device():
     assert lib.kvc_set_cache_layout(None, 0, 0, 0) == kvc.ERR_ARG
     assert lib.kvc_bind_pool(None, None, 0, None, 0) == kvc.ERR_ARG
     assert lib.kvc_reset_pool(None, None) == kvc.ERR_ARG
+    assert lib.kvc_restore_pool(None, 0, None) == kvc.ERR_ARG
     assert lib.kvc_compress_blocks(None, None, 0, None, None, 0, None) == kvc.ERR_ARG
     assert lib.kvc_compress_blocks_mixed(None, None, 0, None, None, None, 0, None) == kvc.ERR_ARG
     assert lib.kvc_decompress_blocks(None, None, 0, None, None, 0, None) == kvc.ERR_ARG

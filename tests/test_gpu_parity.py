@@ -474,3 +474,42 @@ def test_device_clocks_hook():
     ck = kvc.device_clocks()
     assert ck["shader_khz"] > 100_000 and ck["memory_khz"] > 100_000 and ck["memory_bus_bits"] >= 1024, ck
     assert kvc.load().kvc_device_clocks(None, None, None) == kvc.OK
+
+
+def test_pool_checkpoint_and_resume():
+    """Pool bytes, descriptor table and the used-byte count are a complete checkpoint: restored into fresh
+    buffers of another context, the saved pages decode as before and compression goes on behind them."""
+    N, d, ppb, scheme = 16, 128, 2, 3
+    rng = np.random.default_rng(2024)
+    x = (rng.standard_normal((600, ppb, N, d)) * np.exp(0.5 * rng.standard_normal(d))).astype(np.float16)
+    x[17] = 0
+    xt = torch.from_numpy(x).to(DEV)
+    a = kvc.Codec(N, d, ppb, scheme)
+    a.alloc_pool(600, 600 * ppb * N * d * 2 + 64, DEV)
+    a.compress_blocks(xt[:350], n=350)  # pool blocks 0..349
+    st = a.stats()
+    assert st["rc"] == 0
+    used = st["pool_bytes_used"]
+    saved_pool, saved_desc = a.pool.cpu(), a.desc.cpu()
+    del a
+    b = kvc.Codec(N, d, ppb, scheme)
+    b.bind_pool(saved_pool.to(DEV), saved_desc.to(DEV))
+    with pytest.raises(kvc.KvcError) as e:
+        b.restore_pool(used + 8)  # not a multiple of 16
+    assert e.value.code == kvc.ERR_ARG
+    with pytest.raises(kvc.KvcError) as e:
+        b.restore_pool(saved_pool.numel() + 16)  # beyond the pool
+    assert e.value.code == kvc.ERR_ARG
+    b.restore_pool(used)
+    ids = torch.arange(350, 600, dtype=torch.int32, device=DEV)
+    b.compress_blocks(xt, src_ids=ids, pool_ids=ids)  # the rest, behind the restored payloads
+    out = torch.empty_like(xt)
+    b.decompress_blocks(out)
+    st = b.stats()
+    assert st["rc"] == 0 and st["pool_bytes_used"] > used
+    desc, pool = b.desc_numpy(), b.pool.cpu().numpy()
+    check_pool_invariants(desc, st["pool_bytes_used"], pool.size)
+    od, op = compare_pages_with_oracle(x.reshape(-1, N, d).view(np.uint16), desc, pool, N, d, scheme)
+    want, bad = o.decompress_pages(op, od, N, d, n_threads=8)
+    assert bad == 0 and np.array_equal(out.cpu().numpy().view(np.uint16).reshape(-1, N, d), want)
+    assert np.array_equal(pool[:used], saved_pool.numpy()[:used]), "the restored payloads were not touched"

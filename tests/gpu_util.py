@@ -20,7 +20,7 @@ def make_codec(N, d, ppb, scheme, n_pool_blocks, pool_bytes=None):
 
 def gpu_compress(x: np.ndarray, N, d, ppb, scheme, **kw):
     """x: float16/uint16 [..., N, d] with a whole number of blocks.  -> (codec, cache tensor)."""
-    xt = torch.from_numpy(np.ascontiguousarray(x).view(np.float16).reshape(-1, ppb, N, d)).to(DEV)
+    xt = torch.from_numpy(np.require(x, requirements=["C", "W"]).view(np.float16).reshape(-1, ppb, N, d)).to(DEV)
     c = make_codec(N, d, ppb, scheme, xt.shape[0], **kw)
     c.compress_blocks(xt)
     torch.cuda.synchronize()

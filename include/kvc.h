@@ -27,7 +27,7 @@
  *   4 PACK   as 3 with u = zig-zag of q itself, no differencing (for data without correlation
  *            along the channel index; not part of the paper's algorithm);
  *   5 CHAN   as 4 with the values regrouped so that a group holds one pair of neighbouring channels
- *            over the 16 tokens of the page (see KVC_MODE_CHAN below; N = 16, d = 128 or 256 only; not part
+ *            over the 16 tokens of the page (see KVC_MODE_CHAN below; N = 16, d = 64, 128 or 256 only; not part
  *            of the paper's algorithm);
  *   payloads are zero-padded to 16 bytes; a mode-2/3/4/5 page whose payload would not be smaller
  *   than its INT8 payload is stored as mode 1.
@@ -78,7 +78,7 @@ extern "C" {
  * With o = c / 8 the channel's octet, j = (c / 2) mod 4 its pair inside the octet and W = min(16, d / 8),
  * element (t, c) goes to group ((o div W) * 4 + j) * W + o mod W, position
  * (t mod 4) * 8 + (t div 4) * 2 + c mod 2.  Compress produces it, and decompress reads it, for
- * tokens_per_block = 16 and head_dim 128 or 256 only. */
+ * tokens_per_block = 16 and head_dim 64, 128 or 256 only. */
 #define KVC_MODE_CHAN 5
 #define KVC_MODE_INVALID 0xFF
 
@@ -102,7 +102,7 @@ typedef struct {
     int32_t tokens_per_block; /* N >= 1 */
     int32_t head_dim;         /* d: a multiple of 32, 32..256;  N*d <= 4096 */
     int32_t pages_per_block;  /* ppb >= 1 */
-    int32_t scheme;           /* mode requested from compress: 0..5 (5: N = 16, d = 128 or 256 only, else KVC_ERR_UNSUPPORTED) */
+    int32_t scheme;           /* mode requested from compress: 0..5 (5: N = 16, d = 64, 128 or 256 only, else KVC_ERR_UNSUPPORTED) */
 } kvc_config;
 
 typedef struct {

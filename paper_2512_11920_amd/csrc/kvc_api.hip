@@ -50,7 +50,7 @@ static bool config_ok(const kvc_config* c) {
     if (!c) return false;
     if (c->tokens_per_block < 1 || c->pages_per_block < 1) return false;
     if (c->scheme < 0 || c->scheme > KVC_MODE_CHAN) return false;
-    if (c->scheme == KVC_MODE_CHAN && !(c->tokens_per_block == 16 && (c->head_dim == 128 || c->head_dim == 256))) return false;
+    if (c->scheme == KVC_MODE_CHAN && !(c->tokens_per_block == 16 && (c->head_dim == 64 || c->head_dim == 128 || c->head_dim == 256))) return false;
     const int d = c->head_dim;
     if (d < 32 || d > 256 || d % 32 != 0) return false;
     const int64_t E = (int64_t)c->tokens_per_block * d;
@@ -117,7 +117,7 @@ void kvc_destroy(kvc_ctx* ctx) {
 
 int kvc_set_scheme(kvc_ctx* ctx, int32_t scheme) {
     if (!ctx || scheme < 0 || scheme > KVC_MODE_CHAN) return KVC_ERR_ARG;
-    if (scheme == KVC_MODE_CHAN && !(ctx->g.N == 16 && (ctx->g.d == 128 || ctx->g.d == 256))) return KVC_ERR_UNSUPPORTED;
+    if (scheme == KVC_MODE_CHAN && !(ctx->g.N == 16 && (ctx->g.d == 64 || ctx->g.d == 128 || ctx->g.d == 256))) return KVC_ERR_UNSUPPORTED;
     ctx->cfg.scheme = scheme;
     return KVC_OK;
 }
@@ -489,7 +489,7 @@ const char* kvc_strerror(int code) {
         case KVC_ERR_POOL_FULL: return "compressed pool exhausted; some pages were not stored";
         case KVC_ERR_CORRUPT: return "invalid descriptor, payload or block index met on the device";
         case KVC_ERR_TOO_LARGE: return "call exceeds the library's static workspace (at most 65536 slots and 1024 layers per call)";
-        case KVC_ERR_UNSUPPORTED: return "page geometry not supported (head_dim a multiple of 32 up to 256, N*d <= 4096; mode 5: N = 16, d = 128 or 256)";
+        case KVC_ERR_UNSUPPORTED: return "page geometry not supported (head_dim a multiple of 32 up to 256, N*d <= 4096; mode 5: N = 16, d = 64, 128 or 256)";
         default: return "unknown error";
     }
 }

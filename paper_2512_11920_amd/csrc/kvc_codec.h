@@ -73,7 +73,7 @@ struct Page {
     static constexpr bool kAligned = 512 % D == 0;  // a token row never continues into the next pass
     static constexpr int kRowsPerPass = 512 / D;    // (whole rows; exact when kAligned)
     static constexpr int kRounds = (NP + 1) / 2;    // rounds of 64 lanes x 16 bytes that cover a payload (< kE bytes)
-    static constexpr bool kChan = !PARTIAL && kN == 16 && (D == 128 || D == 256);  // mode 5 is built for these pages
+    static constexpr bool kChan = !PARTIAL && kN == 16 && (D == 64 || D == 128 || D == 256);  // mode 5 is built for these pages
 };
 
 // Extent of a page: elements, header bytes (4 bits per group of 32, rounded up to a byte) and the number
@@ -115,7 +115,8 @@ __device__ __forceinline__ LanePos lane_pos(const Geometry& g) {
     lp.row0 = lane / P::kLpr;
     lp.col0 = lane % P::kLpr;
     lp.off0 = (lp.row0 * (uint32_t)g.row_stride + lp.col0 * 8u) * 2u;
-    lp.off0_chan = ((lane & 3u) * (uint32_t)g.row_stride + (lane >> 2) * 8u) * 2u;
+    lp.off0_chan = P::kD == 64 ? (((lane >> 5) * 8u + (lane & 3u)) * (uint32_t)g.row_stride + ((lane >> 2) & 7u) * 8u) * 2u
+                               : ((lane & 3u) * (uint32_t)g.row_stride + (lane >> 2) * 8u) * 2u;
     return lp;
 }
 // ... and in pass p (p is a constant after unrolling): 64 * p lanes further on.
@@ -149,12 +150,15 @@ __device__ __forceinline__ void quantize8_bits(const uint4& raw, float s_inv, ui
 }
 
 // Two ways of dealing a page's 128-bit pieces (one token, eight channels = one octet) to the lanes.
-// Row-major (CHAN = false): piece number p*64 + lane in pass p.  Channel-pair mode 5 (CHAN = true,
-// D = 128 or 256): lane 4*l + r takes, in pass p, token 4*(p mod 4) + r of octet 16*(p div 4) + l, so
-// that the four lanes of a quad hold the 16 tokens of one octet over four passes.
+// Row-major (CHAN = false): piece number p*64 + lane in pass p.  Channel-pair mode 5 (CHAN = true):
+// at D = 128 or 256 lane 4*l + r takes, in pass p, token 4*(p mod 4) + r of octet 16*(p div 4) + l, so
+// that the four lanes of a quad hold the 16 tokens of one octet over four passes; at D = 64 (eight octets,
+// two passes) lane 32*h + 4*l + r takes token 8*h + 4*p + r of octet l, so that a quad and its partner 32
+// lanes away hold the 16 tokens of one octet between them.
 template <class P, bool CHAN>
 __device__ __forceinline__ int piece_index(int p, int lane) {  // position in row-major piece order
     if (!CHAN) return p * 64 + lane;
+    if (P::kD == 64) return (8 * (lane >> 5) + 4 * p + (lane & 3)) * P::kLpr + ((lane >> 2) & 7);
     return (4 * (p & 3) + (lane & 3)) * P::kLpr + 16 * (p >> 2) + (lane >> 2);
 }
 
@@ -312,7 +316,7 @@ __device__ __forceinline__ void encode_groups(const uint32_t (&u)[8], bool RLE, 
 // lane 4l + r takes token 4 (p mod 4) + r of octet 16 (p div 4) + l.
 template <class P, bool CHAN>
 __device__ __forceinline__ int64_t pass_base_off(const Geometry& g, int p) {
-    if (CHAN) return (int64_t)(p & 3) * 4 * g.row_stride * 2 + (p >> 2) * 256;
+    if (CHAN) return (int64_t)(p & 3) * 4 * g.row_stride * 2 + (P::kD == 64 ? 0 : (p >> 2) * 256);
     return (int64_t)((p * 64) / P::kLpr) * g.row_stride * 2;  // the whole rows before the pass
 }
 template <class P, bool CHAN>
@@ -388,7 +392,38 @@ __device__ __forceinline__ PageResult encode_page(const uint4 (&raw)[P::kPasses]
     wave_sync();
 
     uint32_t run = x.hdr;  // payload bytes so far (wave-uniform)
-    if constexpr (SCHEME == KVC_MODE_CHAN) {
+    if constexpr (SCHEME == KVC_MODE_CHAN && P::kD == 64) {
+        // Mode 5 with eight octets: a lane holds tokens 8h + r and 8h + 4 + r of its octet (two passes), its
+        // partner 32 lanes away the other eight tokens' share.  Of the octet's four channel pairs the lane
+        // packs pairs h and 2 + h (group sets 0 and 1), the partner the other two; each hands the other the
+        // four values it holds of the other's pair.  Value index inside a packet: 2 * (token div 4) + (channel
+        // mod 2), token div 4 = 2h + p.
+        static_assert(P::kChan && NP == 2, "sixteen tokens of eight octets are two passes");
+        const bool hi = lane >= 32;
+        uint32_t uu[2][8];
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            uint32_t t[8];
+            quantize8_bits(raw[p], s_inv, t);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) uu[p][k] = lut[t[k] - (kMagicBits + 256u * (uint32_t)k - 256u)];
+        }
+#pragma unroll
+        for (int sset = 0; sset < 2; ++sset) {
+            uint32_t u[8];
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const uint32_t lo_pair = uu[p][4 * sset + e], hi_pair = uu[p][4 * sset + 2 + e];  // pairs 2 sset, 2 sset + 1
+                    const uint32_t mine = hi ? hi_pair : lo_pair;
+                    const uint32_t got = (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, (int)(hi ? lo_pair : hi_pair));
+                    u[2 * p + e] = hi ? got : mine;
+                    u[4 + 2 * p + e] = hi ? mine : got;
+                }
+            encode_groups<P>(u, true, 0u, qi, sset, true, run, stage, st);
+        }
+    } else if constexpr (SCHEME == KVC_MODE_CHAN) {
         // Mode 5: the lanes hold the page dealt as piece_index says.  The four passes of a run of 16
         // octets are quantized and mapped first; group set j of the run then takes channels 2j, 2j + 1
         // of each of them: the quad's 32 values are one channel pair over the 16 tokens.
@@ -759,7 +794,42 @@ __device__ __forceinline__ bool dec_finish(const DecodeArgs& a, const DecPage<P>
         return false;
     }
     wave_sync();
-    if (P::kChan && mode == KVC_MODE_CHAN) {
+    if constexpr (P::kChan && P::kD == 64) {
+        if (mode == KVC_MODE_CHAN) {
+            // Mode 5 with eight octets (see the encoder): group set s holds, for this lane, pair 2s + h of its
+            // octet over all 16 tokens; the lane's own tokens are values 4h .. 4h + 3 of the packet, the
+            // partner's the other four.  The biased codes of a set are kept as bytes, two dwords per set; the
+            // lane hands the partner the dword with the partner's tokens and receives the partner's pair for
+            // its own tokens.
+            const bool hi = lane >= 32;
+            uint32_t pair_lo[2], pair_hi[2];  // per set: the dwords of pairs 2s and 2s + 1 for this lane's tokens
+#pragma unroll
+            for (int sset = 0; sset < 2; ++sset) {
+                uint32_t hb[8];
+                int sg[8];
+                unpack8<NP>(a, stage, ginfo, sset, special, x.hdr, hb, sg);
+                uint32_t b[8];
+#pragma unroll
+                for (int m = 0; m < 8; ++m) b[m] = (hb[m] ^ (uint32_t)sg[m]) + 128u;
+                const uint32_t w0 = __builtin_amdgcn_perm(__builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u), __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u), 0x05040100u);
+                const uint32_t w1 = __builtin_amdgcn_perm(__builtin_amdgcn_perm(b[7], b[6], 0x0c0c0400u), __builtin_amdgcn_perm(b[5], b[4], 0x0c0c0400u), 0x05040100u);
+                const uint32_t own = hi ? w1 : w0;  // values 4h .. 4h + 3: this lane's tokens
+                const uint32_t got = (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, (int)(hi ? w0 : w1));
+                pair_lo[sset] = hi ? got : own;  // pair 2s: packed by the lower half's lane
+                pair_hi[sset] = hi ? own : got;  // pair 2s + 1: packed by the upper half's lane
+            }
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                uint32_t pb[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k)  // channel k = pair k / 2 = 2 (k / 4) + (k / 2) % 2, value 2p + k % 2 of the dword
+                    pb[k] = (((k >> 1) & 1) ? pair_hi[k >> 2] : pair_lo[k >> 2]) >> (8 * (2 * p + (k & 1)));
+                store_stream(reinterpret_cast<uint4*>(dst_b + pass_base_off<P, true>(a.g, p) + pass_lane_off<P, true>(a.g, lp, p)),
+                             dequant8_biased(pb, s, neg128s));
+            }
+            return true;
+        }
+    } else if (P::kChan && mode == KVC_MODE_CHAN) {
         // Mode 5: of a run of 16 octets, group set j holds channels 2j, 2j + 1 of the lane's octet,
         // tokens 4p + (lane & 3) for p = 0..3 (value 2p + e of the packet = pass p, channel 2j + e).  The
         // biased codes of a set are kept as bytes, so that pass p then finds its eight codes at fixed

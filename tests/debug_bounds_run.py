@@ -24,7 +24,7 @@ for N, d in ((16, 128), (16, 64), (16, 256), (16, 96), (16, 224), (8, 192), (32,
     special = tp._special_pages(N, d, rng)
     families, _ = td._families(rng, 1500, N, d)
     x = np.concatenate([special, families])
-    for scheme in ((3, 2, 4, 5) if (N == 16 and d in (128, 256)) else (3, 2, 4)):
+    for scheme in ((3, 2, 4, 5) if (N == 16 and d in (64, 128, 256)) else (3, 2, 4)):
         print(f"[case] bounds-checking build N={N} d={d} scheme={scheme} pages={x.shape[0]}", flush=True)
         xt = torch.from_numpy(x.reshape(-1, 1, N, d)).to(DEV)
         c = kvc.Codec(N, d, 1, scheme)

@@ -47,7 +47,7 @@ def test_host_side_argument_checks_need_no_device():
                       (kvc.Config(16, 128, 1, -1), kvc.ERR_ARG), (kvc.Config(16, 100, 1, 3), kvc.ERR_ARG),
                       (kvc.Config(16, 288, 1, 3), kvc.ERR_UNSUPPORTED), (kvc.Config(64, 128, 1, 3), kvc.ERR_UNSUPPORTED),
                       (kvc.Config(16, 96, 1, 5), kvc.ERR_UNSUPPORTED),
-                      (kvc.Config(16, 64, 1, 5), kvc.ERR_UNSUPPORTED), (kvc.Config(8, 128, 1, 5), kvc.ERR_UNSUPPORTED),
+                      (kvc.Config(16, 160, 1, 5), kvc.ERR_UNSUPPORTED), (kvc.Config(8, 128, 1, 5), kvc.ERR_UNSUPPORTED),
                       (kvc.Config(8, 256, 1, 5), kvc.ERR_UNSUPPORTED),
                       (kvc.Config(16, 128, 1, 6), kvc.ERR_ARG)):
         assert lib.kvc_create(C.byref(ctx), C.byref(cfg)) == want

@@ -68,6 +68,7 @@ def _families(rng, n, N, d):
                                           (16, 64, 777, 2), (16, 256, 999, 1), (16, 128, 2049, 3),
                                           # mode 5: channel-pair groups (16 x 128 pages), both launch shapes
                                           (16, 128, 9000, 5), (16, 128, 2048, 5), (16, 128, 333, 5), (16, 256, 5000, 5), (16, 256, 1200, 5),
+                                          (16, 64, 9000, 5), (16, 64, 2048, 5), (16, 64, 411, 5),
                                           # head dimensions that are not powers of two: token rows of 12, 20, 24, 28 lanes
                                           (16, 96, 3000, 3), (16, 160, 3000, 3), (16, 192, 3000, 3), (16, 224, 3000, 3),
                                           (16, 96, 2000, 4), (16, 192, 2000, 2), (8, 96, 2000, 3), (21, 192, 1500, 3), (3, 160, 2000, 3),
@@ -117,7 +118,7 @@ def _soak_pages(rng, n, N, d):
 
 
 _SOAK_CASES = [(16, d, sc) for d in (64, 128, 256) for sc in (2, 3, 4, "mixed")] + \
-              [(N, d, sc) for (N, d) in ((8, 128), (32, 64), (16, 32), (4, 256)) for sc in (3, "mixed")] + [(16, 128, 5), (16, 256, 5)] + \
+              [(N, d, sc) for (N, d) in ((8, 128), (32, 64), (16, 32), (4, 256)) for sc in (3, "mixed")] + [(16, 128, 5), (16, 256, 5), (16, 64, 5)] + \
               [(N, d, sc) for (N, d) in ((16, 96), (16, 160), (16, 192), (16, 224), (8, 96), (32, 96), (8, 192),
                                          (8, 64), (8, 256), (32, 32), (32, 128)) for sc in (3, "mixed")] + \
               [(N, d, sc) for (N, d) in ((7, 128), (24, 160), (3, 256), (15, 256), (21, 192), (100, 32), (4, 128), (12, 96),

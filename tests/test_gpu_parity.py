@@ -139,9 +139,9 @@ def test_special_pages_all_geometries(N, d, scheme):
         assert pool_codes >= set(range(0, 10)), pool_codes
 
 
-@pytest.mark.parametrize("d", [128, 256])
+@pytest.mark.parametrize("d", [64, 128, 256])
 def test_special_pages_channel_pair_mode(d):
-    """Mode 5 (channel-pair groups; the GPU builds it for 16-token pages of 128 or 256 channels): every
+    """Mode 5 (channel-pair groups; the GPU builds it for 16-token pages of 64, 128 or 256 channels): every
     branch page, and the geometries it is not built for are refused on the host."""
     rng = np.random.default_rng(777 + d)
     x = _special_pages(16, d, rng)
@@ -158,7 +158,7 @@ def test_special_pages_channel_pair_mode(d):
             pl = o.page_payload(op, od[i])
             codes |= {(pl[g >> 1] >> 4) if g & 1 else (pl[g >> 1] & 15) for g in range(d // 2)}
     assert codes >= set(range(0, 10)), codes
-    for N, d in ((16, 64), (8, 128), (16, 32), (8, 256)):
+    for N, d in ((16, 96), (8, 128), (16, 32), (8, 256)):
         with pytest.raises(kvc.KvcError) as e:
             kvc.Codec(N, d, 1, 5)
         assert e.value.code == kvc.ERR_UNSUPPORTED
@@ -167,12 +167,12 @@ def test_special_pages_channel_pair_mode(d):
             c.set_scheme(5)
         assert e.value.code == kvc.ERR_UNSUPPORTED
     # a mode-5 page met by a decoder of another geometry is contained like any unknown mode
-    x64 = (rng.standard_normal((3, 16, 64)) * np.exp(rng.standard_normal(64))).astype(np.float16)
-    od64, op64 = o.compress_pages(x64.view(np.uint16), 16, 64, 5)
+    x64 = (rng.standard_normal((3, 16, 96)) * np.exp(rng.standard_normal(96))).astype(np.float16)
+    od64, op64 = o.compress_pages(x64.view(np.uint16), 16, 96, 5)
     assert (od64["mode"] == 5).all()
-    c = kvc.Codec(16, 64, 1, 3)
+    c = kvc.Codec(16, 96, 1, 3)
     upload_oracle_pool(c, od64, op64)
-    out = torch.full((3, 1, 16, 64), 7.0, dtype=torch.float16, device=DEV)
+    out = torch.full((3, 1, 16, 96), 7.0, dtype=torch.float16, device=DEV)
     c.decompress_blocks(out)
     st = c.stats()
     assert st["rc"] == kvc.ERR_CORRUPT and st["status"] & kvc.ST_CORRUPT and bool((out == 0).all())

@@ -93,6 +93,21 @@ add("channel_pairs_mode5_d256", 16, 256, x, 5, "3f800000",
          "41 = 3 (byte 20 high), 73 = 3 (byte 36 high), 80 = 1 (byte 40 low), 111 = 9 (byte 55 high); all other groups "
          "zero-run. 64+32+12+12+4+1 = 125 -> 128 B")
 
+x = np.zeros((16, 64))
+x[0, 0] = 127
+x[15, 45] = -3
+x[9, 33] = 3
+x[:, 62:64] = 2
+add("channel_pairs_mode5_d64", 16, 64, x, 5, "3f800000",
+    "08" + "00" + "03" + "00" * 7 + "30" + "00" * 4 + "90"
+    + "fe" + "00" * 31 + "00" * 5 + "03" + "00" * 6 + "00" * 11 + "a0" + "04" + "00" * 7, scheme=5,
+    note="mode 5 at d = 64 (extension): 8 channel octets, W = 8, so channel c (octet o = c div 8, pair j = (c div 2) mod 4) "
+         "goes to group j*8 + o, position (t mod 4)*8 + (t div 4)*2 + c mod 2; 32 groups, 16 header bytes. x[0][0]=127: group 0, "
+         "pos 0, u=254, w=8 (32 B). x[9][33]=3: o=4 j=0 -> group 4, pos 8+4+1=13, u=6, w=3 (12 B), bits 39..41 = 110b -> byte 5 = "
+         "0x03. x[15][45]=-3: o=5 j=2 -> group 21, pos 24+6+1=31, u=5, w=3, bits 93..95 = 101b -> byte 11 = 0xA0. channels 62,63 "
+         "all 2: o=7 j=3 -> group 31, 32 equal u=4 -> run packet, body 0x04. Header nibbles: group 0 = 8 (byte 0 low), 4 = 3 (byte 2 "
+         "low), 21 = 3 (byte 10 high), 31 = 9 (byte 15 high). 16+32+12+12+1 = 73 -> 80 B")
+
 x = np.zeros((3, 32))
 x[1:, :] = 127
 add("odd_group_count_n3_d32", 3, 32, x, 3, "3f800000",

@@ -155,8 +155,9 @@ int kvc_restore_pool(kvc_ctx* ctx, uint64_t used_bytes, void* stream);
 int kvc_compress_blocks(kvc_ctx* ctx, const void* d_cache, int64_t n_cache_blocks, const int32_t* d_src_block_ids,
                         const int32_t* d_pool_block_ids, int32_t n, void* stream);
 
-/* As kvc_compress_blocks, with the requested mode given per block: d_block_scheme[i] in 0..4 (values
- * above 4 are read as 4) applies to block i of the call.  This is the mechanism behind the paper's
+/* As kvc_compress_blocks, with the requested mode given per block: d_block_scheme[i] in 0..5 where the
+ * geometry has mode 5 (N = 16, d = 64, 128 or 256), else 0..4; higher values are read as the highest.
+ * It applies to block i of the call.  This is the mechanism behind the paper's
  * layer-wise algorithm selection (Sections 3.1 (vi) and 3.6.3); the selection policy is the caller's. */
 int kvc_compress_blocks_mixed(kvc_ctx* ctx, const void* d_cache, int64_t n_cache_blocks, const int32_t* d_src_block_ids,
                               const int32_t* d_pool_block_ids, const uint8_t* d_block_scheme, int32_t n, void* stream);

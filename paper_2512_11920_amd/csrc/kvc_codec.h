@@ -131,6 +131,11 @@ __device__ __forceinline__ uint32_t pass_row(const LanePos& lp, int p) {
     return lp.row0 + (uint32_t)((p * 64) / P::kLpr) + wrap;
 }
 
+// Values of the encoder's SCHEME parameter below zero: the mode is read per page at run time, from modes
+// 0..4, or from 0..5 (only built for the page shapes that have mode 5).
+constexpr int kSchemeRowMajor = -1;
+constexpr int kSchemeAny = -2;
+
 constexpr float kMagic = 12582912.0f;  // 1.5 * 2^23: adding it rounds to an integer, ties to even
 constexpr uint32_t kMagicBits = 0x4B400000u;
 
@@ -343,12 +348,15 @@ __device__ __forceinline__ void load_page(const EncodeArgs& a, const EncTask& ta
 
 // Encode one page (already in registers) into the LDS slot `stage`.  The requested mode is the
 // compile-time SCHEME when that is >= 0 (one mode for the whole launch: its branches fold away), else
-// the wave-uniform run-time value.
+// the wave-uniform run-time value: any of modes 0..4 (SCHEME -1), or any of 0..5 (SCHEME -2, built for
+// the page shapes that have mode 5; the page must then have been loaded in the deal of its mode).
 template <class P, int SCHEME>
 __device__ __forceinline__ PageResult encode_page(const uint4 (&raw)[P::kPasses], const LanePos& lp, const Extent& x, int scheme_rt,
                                                  uint32_t* stage, const uint8_t* lut, DevState* st) {
     const int scheme = SCHEME >= 0 ? SCHEME : scheme_rt;
     constexpr int kE = P::kE, NP = P::kPasses;
+    constexpr bool kMayChan = SCHEME == KVC_MODE_CHAN || SCHEME == kSchemeAny;
+    const bool chan = SCHEME == KVC_MODE_CHAN || (SCHEME == kSchemeAny && scheme == KVC_MODE_CHAN);
     const bool RLE = scheme != KVC_MODE_DELTA;  // zero-run and run packets (modes 3 and 4)
     const bool no_delta = scheme == KVC_MODE_PACK;
     const uint32_t c_min = RLE ? 0u : 1u;  // without run packets an all-zero group is a 1-bit literal
@@ -379,8 +387,17 @@ __device__ __forceinline__ PageResult encode_page(const uint4 (&raw)[P::kPasses]
         s_inv = ps.s_inv;
     }
     r.scale = s;
+    auto codes_to_stage = [&]() {  // the plain INT8 payload, from whichever deal the lanes hold
+        if constexpr (kMayChan) {
+            if (chan) {
+                store_codes<P, true>(raw, s_inv, x, stage);
+                return;
+            }
+        }
+        store_codes<P, false>(raw, s_inv, x, stage);
+    };
     if (scheme == KVC_MODE_INT8) {
-        store_codes<P, SCHEME == KVC_MODE_CHAN>(raw, s_inv, x, stage);
+        codes_to_stage();
         r.n16 = x.E >> 4;
         r.mode = KVC_MODE_INT8;
         return r;
@@ -392,7 +409,10 @@ __device__ __forceinline__ PageResult encode_page(const uint4 (&raw)[P::kPasses]
     wave_sync();
 
     uint32_t run = x.hdr;  // payload bytes so far (wave-uniform)
-    if constexpr (SCHEME == KVC_MODE_CHAN && P::kD == 64) {
+    bool packed_by_pairs = false;
+    if constexpr (kMayChan && P::kD == 64) {
+      if (chan) {
+        packed_by_pairs = true;
         // Mode 5 with eight octets: a lane holds tokens 8h + r and 8h + 4 + r of its octet (two passes), its
         // partner 32 lanes away the other eight tokens' share.  Of the octet's four channel pairs the lane
         // packs pairs h and 2 + h (group sets 0 and 1), the partner the other two; each hands the other the
@@ -423,7 +443,10 @@ __device__ __forceinline__ PageResult encode_page(const uint4 (&raw)[P::kPasses]
                 }
             encode_groups<P>(u, true, 0u, qi, sset, true, run, stage, st);
         }
-    } else if constexpr (SCHEME == KVC_MODE_CHAN) {
+      }
+    } else if constexpr (kMayChan) {
+      if (chan) {
+        packed_by_pairs = true;
         // Mode 5: the lanes hold the page dealt as piece_index says.  The four passes of a run of 16
         // octets are quantized and mapped first; group set j of the run then takes channels 2j, 2j + 1
         // of each of them: the quad's 32 values are one channel pair over the 16 tokens.
@@ -446,7 +469,9 @@ __device__ __forceinline__ PageResult encode_page(const uint4 (&raw)[P::kPasses]
                 encode_groups<P>(u, true, 0u, qi, 4 * h + j, true, run, stage, st);
             }
         }
-    } else {
+      }
+    }
+    if (!packed_by_pairs) {
         uint32_t carry = kMagicBits - 256u;  // last value of the pass before, for a row that continues
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
@@ -477,7 +502,7 @@ __device__ __forceinline__ PageResult encode_page(const uint4 (&raw)[P::kPasses]
     const uint32_t n = (run + 15u) & ~15u;
     wave_sync();
     if (n >= x.E) {  // packing did not beat plain INT8
-        store_codes<P, SCHEME == KVC_MODE_CHAN>(raw, s_inv, x, stage);
+        codes_to_stage();
         r.n16 = x.E >> 4;
         r.mode = KVC_MODE_INT8;
     } else {
@@ -552,13 +577,13 @@ constexpr int enc_ring_max(int np, int scheme) {
 // pass may be short, which would spill at four)
 template <class P, int SCHEME>
 constexpr int enc_min_waves() {
-    return ((P::kD == 256 && SCHEME == KVC_MODE_CHAN) || (P::kPasses >= 7 && (!P::kAligned || P::kPartial) && SCHEME < 0)) ? 3 : KVC_ENC_MIN_WAVES;
+    return ((P::kD == 256 && (SCHEME == KVC_MODE_CHAN || SCHEME == kSchemeAny)) || (P::kPasses >= 7 && (!P::kAligned || P::kPartial) && SCHEME < 0)) ? 3 : KVC_ENC_MIN_WAVES;
 }
 template <class P, int WAVES, int PPW, int SCHEME>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(enc_min_waves<P, SCHEME>()))) void k_compress(EncodeArgs a) {
     constexpr int kSlots = WAVES * PPW;
     constexpr int NP = P::kPasses;
-    constexpr bool CHAN = SCHEME == KVC_MODE_CHAN;
+    constexpr int kMaxMode = SCHEME == kSchemeAny ? KVC_MODE_CHAN : KVC_MODE_PACK;  // what a per-block request may ask for
     constexpr int kRing = enc_ring_max(NP, SCHEME) < PPW ? enc_ring_max(NP, SCHEME) : PPW;
     static_assert(PPW % kRing == 0, "the loop handles pages in groups of kRing");
     __shared__ __align__(16) uint32_t s_stage[kSlots][Slot<NP>::kWords];
@@ -571,6 +596,17 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(enc_
     TaskPos pos = task_pos(t0, a.g.ppb);
     const LanePos lp = lane_pos<P>(a.g);
     const int slot0 = wave * PPW;
+    // the deal of the page to the lanes follows the mode requested for it
+    auto load = [&](const EncTask& task, uint4 (&raw)[NP]) {
+        if constexpr (SCHEME == kSchemeAny) {
+            if (task.scheme == KVC_MODE_CHAN)
+                load_page<P, true>(a, task, lp, raw);
+            else
+                load_page<P, false>(a, task, lp, raw);
+        } else {
+            load_page<P, SCHEME == KVC_MODE_CHAN>(a, task, lp, raw);
+        }
+    };
     if (kRing > 1) {
         // The register sets take turns (the inner loop is unrolled, so every index is a constant):
         // nothing is copied between them.
@@ -579,8 +615,8 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(enc_
 #pragma unroll
         for (int j = 0; j < kRing - 1; ++j) {
             if (j > 0) task_advance(pos, a.g.ppb);
-            t[j] = resolve_enc_task(a, t0 + j, pos);
-            if (t[j].desc_idx >= 0) load_page<P, CHAN>(a, t[j], lp, r[j]);
+            t[j] = resolve_enc_task(a, t0 + j, pos, kMaxMode);
+            if (t[j].desc_idx >= 0) load(t[j], r[j]);
         }
 #pragma unroll 1
         for (int i = 0; i < PPW; i += kRing) {
@@ -589,18 +625,18 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(enc_
                 constexpr int kAhead = kRing - 1;
                 const int nb = (j + kAhead) % kRing;
                 task_advance(pos, a.g.ppb);
-                t[nb] = resolve_enc_task(a, i + j + kAhead < PPW ? t0 + i + j + kAhead : a.n_pages, pos);  // past the end: no task
-                if (t[nb].desc_idx >= 0) load_page<P, CHAN>(a, t[nb], lp, r[nb]);
+                t[nb] = resolve_enc_task(a, i + j + kAhead < PPW ? t0 + i + j + kAhead : a.n_pages, pos, kMaxMode);  // past the end: no task
+                if (t[nb].desc_idx >= 0) load(t[nb], r[nb]);
                 encode_into_slot<P, SCHEME>(a, r[j], lp, t[j], slot0 + i + j, s_stage[slot0 + i + j], s_lut, s_book);
             }
         }
     } else {
 #pragma unroll 1
         for (int i = 0; i < PPW; ++i) {
-            const EncTask task = resolve_enc_task(a, t0 + i, pos);
+            const EncTask task = resolve_enc_task(a, t0 + i, pos, kMaxMode);
             task_advance(pos, a.g.ppb);
             uint4 raw[NP];
-            if (task.desc_idx >= 0) load_page<P, CHAN>(a, task, lp, raw);
+            if (task.desc_idx >= 0) load(task, raw);
             encode_into_slot<P, SCHEME>(a, raw, lp, task, slot0 + i, s_stage[slot0 + i], s_lut, s_book);
         }
     }
@@ -1028,7 +1064,7 @@ struct ShapeOps {
         // instantiation; any other request (another mode, or one mode per block) reads it at run time,
         // and so do all requests for pages with a short last pass
         if constexpr (PARTIAL) {
-            return a.scheme == KVC_MODE_CHAN ? hipErrorInvalidValue : compress_scheme<-1>(a, s);
+            return a.scheme == KVC_MODE_CHAN ? hipErrorInvalidValue : compress_scheme<kSchemeRowMajor>(a, s);
         } else {
             if (a.block_scheme == nullptr && a.scheme == KVC_MODE_RLE) return compress_scheme<KVC_MODE_RLE>(a, s);
             if (a.block_scheme == nullptr && a.scheme == KVC_MODE_CHAN) {
@@ -1038,7 +1074,11 @@ struct ShapeOps {
                 else
                     return hipErrorInvalidValue;
             }
-            return compress_scheme<-1>(a, s);
+            // one mode per block: where the shape has mode 5, the instantiation that can also deal a page by channel pairs
+            if constexpr (P::kChan) {
+                if (a.block_scheme != nullptr) return compress_scheme<kSchemeAny>(a, s);
+            }
+            return compress_scheme<kSchemeRowMajor>(a, s);
         }
     }
 

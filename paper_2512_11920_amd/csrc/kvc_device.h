@@ -241,7 +241,8 @@ __device__ __forceinline__ void task_advance(TaskPos& p, int ppb) {
     }
 }
 
-__device__ __forceinline__ EncTask resolve_enc_task(const EncodeArgs& a, int64_t t, const TaskPos& pos) {
+// max_mode: the highest mode a per-block request may name for this page shape (higher values are read as it)
+__device__ __forceinline__ EncTask resolve_enc_task(const EncodeArgs& a, int64_t t, const TaskPos& pos, int max_mode = KVC_MODE_PACK) {
     EncTask r;
     r.desc_idx = -1;
     r.src_off = -1;
@@ -260,7 +261,7 @@ __device__ __forceinline__ EncTask resolve_enc_task(const EncodeArgs& a, int64_t
     }
     r.src_off = page_base(a.g, sb, pg);
     r.desc_idx = (long long)d_idx;
-    if (a.block_scheme) r.scheme = min(wave_uniform((int32_t)a.block_scheme[blk]), (int32_t)KVC_MODE_PACK);
+    if (a.block_scheme) r.scheme = min(wave_uniform((int32_t)a.block_scheme[blk]), (int32_t)max_mode);
     return r;
 }
 

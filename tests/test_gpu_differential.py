@@ -135,11 +135,12 @@ def test_every_kernel_instantiation_under_full_occupancy(N, d, scheme):
     x = _soak_pages(rng, n, N, d)
     xt = torch.from_numpy(x.reshape(-1, 1, N, d)).to(DEV)
     if scheme == "mixed":
-        per_block = rng.integers(0, 5, n).astype(np.uint8)
+        n_modes = 6 if (N == 16 and d in (64, 128, 256)) else 5  # shapes that have mode 5 take it per block too
+        per_block = rng.integers(0, n_modes, n).astype(np.uint8)
         bs = torch.from_numpy(per_block).to(DEV)
         od = np.zeros(n, o.DESC_DTYPE)
         chunks, off = [], 0
-        for sc in range(5):
+        for sc in range(n_modes):
             idx = np.nonzero(per_block == sc)[0]
             dd, pp = o.compress_pages(x[idx].view(np.uint16), N, d, sc, n_threads=16)
             dd = dd.copy()

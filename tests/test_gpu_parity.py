@@ -363,8 +363,8 @@ def test_per_block_scheme_selection():
     rng = np.random.default_rng(44)
     N, d, ppb, nb = 16, 128, 4, 40
     x = (rng.standard_normal((nb, ppb, N, d)) * np.exp(0.7 * rng.standard_normal(d))).astype(np.float16)
-    schemes = rng.integers(0, 5, nb).astype(np.uint8)
-    schemes[:5] = [0, 1, 2, 3, 4]
+    schemes = rng.integers(0, 6, nb).astype(np.uint8)
+    schemes[:6] = [0, 1, 2, 3, 4, 5]
     xt = torch.from_numpy(x).to(DEV)
     c = make_codec(N, d, ppb, 3, nb, pool_bytes=nb * ppb * N * d * 2 + 64)
     c.compress_blocks(xt, block_scheme=torch.from_numpy(schemes).to(DEV))

@@ -346,6 +346,71 @@ __device__ __forceinline__ void load_page(const EncodeArgs& a, const EncTask& ta
     }
 }
 
+// Mode 5: the packets of a page whose 128-bit pieces were dealt to the lanes as piece_index<P, true> says;
+// every group holds one pair of neighbouring channels over the 16 tokens.
+template <class P>
+__device__ __forceinline__ void pack_channel_pairs(const uint4 (&raw)[P::kPasses], float s_inv, uint32_t& run, uint32_t* stage,
+                                                   const uint8_t* lut, DevState* st) {
+    static_assert(P::kChan, "mode 5 is built for 16-token pages of 64, 128 or 256 channels");
+    constexpr int NP = P::kPasses;
+    const int lane = lane_id();
+    const uint32_t qi = (uint32_t)lane & 3u;
+    if constexpr (P::kD == 64) {
+        // Eight octets: a lane holds tokens 8h + r and 8h + 4 + r of its octet (two passes), its partner 32
+        // lanes away the other eight tokens' share.  Of the octet's four channel pairs the lane packs pairs h
+        // and 2 + h (group sets 0 and 1), the partner the other two; each hands the other the four values it
+        // holds of the other's pair.  Value index inside a packet: 2 * (token div 4) + (channel mod 2), token
+        // div 4 = 2h + p.
+        static_assert(NP == 2, "sixteen tokens of eight octets are two passes");
+        const bool hi = lane >= 32;
+        uint32_t uu[2][8];
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            uint32_t t[8];
+            quantize8_bits(raw[p], s_inv, t);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) uu[p][k] = lut[t[k] - (kMagicBits + 256u * (uint32_t)k - 256u)];
+        }
+#pragma unroll
+        for (int sset = 0; sset < 2; ++sset) {
+            uint32_t u[8];
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const uint32_t lo_pair = uu[p][4 * sset + e], hi_pair = uu[p][4 * sset + 2 + e];  // pairs 2 sset, 2 sset + 1
+                    const uint32_t mine = hi ? hi_pair : lo_pair;
+                    const uint32_t got = (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, (int)(hi ? lo_pair : hi_pair));
+                    u[2 * p + e] = hi ? got : mine;
+                    u[4 + 2 * p + e] = hi ? mine : got;
+                }
+            encode_groups<P>(u, true, 0u, qi, sset, true, run, stage, st);
+        }
+    } else {
+        // Sixteen or 32 octets: the four passes of a run of 16 octets are quantized and mapped first; group
+        // set j of the run then takes channels 2j, 2j + 1 of each of them: the quad's 32 values are one
+        // channel pair over the 16 tokens.
+#pragma unroll
+        for (int h = 0; h < NP / 4; ++h) {
+            uint32_t uu[4][8];
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                uint32_t t[8];
+                quantize8_bits(raw[4 * h + p], s_inv, t);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) uu[p][k] = lut[t[k] - (kMagicBits + 256u * (uint32_t)k - 256u)];
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint32_t u[8];
+#pragma unroll
+                for (int m = 0; m < 8; ++m) u[m] = uu[m >> 1][2 * j + (m & 1)];
+                encode_groups<P>(u, true, 0u, qi, 4 * h + j, true, run, stage, st);
+            }
+        }
+    }
+}
+
 // Encode one page (already in registers) into the LDS slot `stage`.  The requested mode is the
 // compile-time SCHEME when that is >= 0 (one mode for the whole launch: its branches fold away), else
 // the wave-uniform run-time value: any of modes 0..4 (SCHEME -1), or any of 0..5 (SCHEME -2, built for
@@ -410,66 +475,11 @@ __device__ __forceinline__ PageResult encode_page(const uint4 (&raw)[P::kPasses]
 
     uint32_t run = x.hdr;  // payload bytes so far (wave-uniform)
     bool packed_by_pairs = false;
-    if constexpr (kMayChan && P::kD == 64) {
-      if (chan) {
-        packed_by_pairs = true;
-        // Mode 5 with eight octets: a lane holds tokens 8h + r and 8h + 4 + r of its octet (two passes), its
-        // partner 32 lanes away the other eight tokens' share.  Of the octet's four channel pairs the lane
-        // packs pairs h and 2 + h (group sets 0 and 1), the partner the other two; each hands the other the
-        // four values it holds of the other's pair.  Value index inside a packet: 2 * (token div 4) + (channel
-        // mod 2), token div 4 = 2h + p.
-        static_assert(P::kChan && NP == 2, "sixteen tokens of eight octets are two passes");
-        const bool hi = lane >= 32;
-        uint32_t uu[2][8];
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            uint32_t t[8];
-            quantize8_bits(raw[p], s_inv, t);
-#pragma unroll
-            for (int k = 0; k < 8; ++k) uu[p][k] = lut[t[k] - (kMagicBits + 256u * (uint32_t)k - 256u)];
+    if constexpr (kMayChan) {
+        if (chan) {
+            pack_channel_pairs<P>(raw, s_inv, run, stage, lut, st);
+            packed_by_pairs = true;
         }
-#pragma unroll
-        for (int sset = 0; sset < 2; ++sset) {
-            uint32_t u[8];
-#pragma unroll
-            for (int p = 0; p < 2; ++p)
-#pragma unroll
-                for (int e = 0; e < 2; ++e) {
-                    const uint32_t lo_pair = uu[p][4 * sset + e], hi_pair = uu[p][4 * sset + 2 + e];  // pairs 2 sset, 2 sset + 1
-                    const uint32_t mine = hi ? hi_pair : lo_pair;
-                    const uint32_t got = (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, (int)(hi ? lo_pair : hi_pair));
-                    u[2 * p + e] = hi ? got : mine;
-                    u[4 + 2 * p + e] = hi ? mine : got;
-                }
-            encode_groups<P>(u, true, 0u, qi, sset, true, run, stage, st);
-        }
-      }
-    } else if constexpr (kMayChan) {
-      if (chan) {
-        packed_by_pairs = true;
-        // Mode 5: the lanes hold the page dealt as piece_index says.  The four passes of a run of 16
-        // octets are quantized and mapped first; group set j of the run then takes channels 2j, 2j + 1
-        // of each of them: the quad's 32 values are one channel pair over the 16 tokens.
-        static_assert(P::kChan, "a lane's share of a channel pair is 8 values when an octet's 16 tokens are 4 passes");
-#pragma unroll
-        for (int h = 0; h < NP / 4; ++h) {
-            uint32_t uu[4][8];
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                uint32_t t[8];
-                quantize8_bits(raw[4 * h + p], s_inv, t);
-#pragma unroll
-                for (int k = 0; k < 8; ++k) uu[p][k] = lut[t[k] - (kMagicBits + 256u * (uint32_t)k - 256u)];
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                uint32_t u[8];
-#pragma unroll
-                for (int m = 0; m < 8; ++m) u[m] = uu[m >> 1][2 * j + (m & 1)];
-                encode_groups<P>(u, true, 0u, qi, 4 * h + j, true, run, stage, st);
-            }
-        }
-      }
     }
     if (!packed_by_pairs) {
         uint32_t carry = kMagicBits - 256u;  // last value of the pass before, for a row that continues

@@ -40,6 +40,31 @@ for N, d in ((16, 128), (16, 64), (16, 256), (16, 96), (16, 224), (8, 192), (32,
         want, bad = o.decompress_pages(op, od, N, d, n_threads=8)
         assert bad == 0 and np.array_equal(out.cpu().numpy().view(np.uint16).reshape(-1, N, d), want)
         n_cases += 1
+# one requested mode per block: the encoder instantiations that read the mode of every page (0..5 where the
+# shape has mode 5, 0..4 elsewhere), decoded values against the oracle's for the same modes
+for N, d in ((16, 64), (16, 128), (16, 256), (16, 96), (8, 64)):
+    rng = np.random.default_rng(1300 + N + d)
+    x = td._soak_pages(rng, 3000, N, d)
+    n_modes = 6 if (N == 16 and d in (64, 128, 256)) else 5
+    per_block = rng.integers(0, n_modes, x.shape[0]).astype(np.uint8)
+    print(f"[case] bounds-checking build N={N} d={d} one of {n_modes} modes per block, pages={x.shape[0]}", flush=True)
+    xt = torch.from_numpy(x.reshape(-1, 1, N, d)).to(DEV)
+    c = kvc.Codec(N, d, 1, 3)
+    c.alloc_pool(x.shape[0], x.shape[0] * N * d * 2 + 64, DEV)
+    c.compress_blocks(xt, block_scheme=torch.from_numpy(per_block).to(DEV))
+    out = torch.empty_like(xt)
+    c.decompress_blocks(out)
+    st = c.stats()
+    assert st["status"] == 0, f"status {st['status']:#x}: bit 8 = an index or span left its bounds"
+    desc = c.desc_numpy()
+    got = out.cpu().numpy().view(np.uint16).reshape(-1, N, d)
+    for sc in range(n_modes):
+        idx = np.nonzero(per_block == sc)[0]
+        od, op = o.compress_pages(x[idx].view(np.uint16), N, d, sc, n_threads=8)
+        assert np.array_equal(desc["mode"][idx], od["mode"]) and np.array_equal(desc["n16"][idx], od["n16"])
+        want, bad = o.decompress_pages(op, od, N, d, n_threads=8)
+        assert bad == 0 and np.array_equal(got[idx], want)
+    n_cases += 1
 # pages with a short last pass: for every channel count the smallest, an odd, a middle and the largest token count
 for d in (32, 64, 96, 128, 160, 192, 224, 256):
     n_max = 4096 // d

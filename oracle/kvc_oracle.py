@@ -16,8 +16,10 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "kvc_oracle.c")
-_LIB = os.path.join(_HERE, "libkvc_oracle.so")
+# The two paths can be redirected so that tests/test_oracle_mutations.py can build copies of the C file with a
+# mistake planted in them and show that the pins notice; nothing else sets these variables.
+_SRC = os.environ.get("KVC_ORACLE_SRC") or os.path.join(_HERE, "kvc_oracle.c")
+_LIB = os.environ.get("KVC_ORACLE_LIB") or os.path.join(_HERE, "libkvc_oracle.so")
 
 MODE_RAW, MODE_INT8, MODE_DELTA, MODE_RLE, MODE_PACK, MODE_CHAN, MODE_INVALID = 0, 1, 2, 3, 4, 5, 0xFF
 

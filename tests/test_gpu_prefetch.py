@@ -96,6 +96,52 @@ def test_prefetch_bad_index_sets_status():
         c.prefetch_layers(l2, tags, fetch, loc, torch.from_numpy(pat.block_table).to(DEV), torch.from_numpy(pred).to(DEV), 1, pbl, 2)
 
 
+def _plan_on_gpu(policy, tags_np, fill, table_np, pred_np, n_layers, pbl):
+    """One planner + fetch step on small hand-made tables: -> (fetch, loc, tags after, codec)."""
+    N, d, ppb = 16, 128, 1
+    rng = np.random.default_rng(77)
+    x = rng.standard_normal((n_layers * pbl, ppb, N, d)).astype(np.float16)
+    c, _ = gpu_compress(x, N, d, ppb, 3)
+    c.set_prefetch_policy(policy)
+    n_seq, k = pred_np.shape
+    n_slots = n_layers * n_seq * k
+    l2 = torch.zeros((2 * n_slots, ppb, N, d), dtype=torch.float16, device=DEV)
+    tags = torch.from_numpy(np.ascontiguousarray(tags_np, np.int32).reshape(-1)).to(DEV)
+    fetch = torch.empty(n_slots, dtype=torch.int32, device=DEV)
+    loc = torch.empty(n_slots, dtype=torch.int32, device=DEV)
+    c.prefetch_layers(l2, tags, fetch, loc, torch.from_numpy(table_np).to(DEV), torch.from_numpy(pred_np).to(DEV), n_layers, pbl, fill)
+    torch.cuda.synchronize()
+    return (fetch.cpu().numpy().reshape(n_layers, n_seq, k), loc.cpu().numpy().reshape(n_layers, n_seq, k),
+            tags.cpu().numpy().reshape(2, n_layers, n_seq, k), c)
+
+
+@pytest.mark.parametrize("policy", [0, 1])
+def test_hand_counted_plans_boundary_entry(policy):
+    """The same hand-counted case as the model's pin: table entries 6 (the last valid block of a 7-block
+    layer), 7 and 9; two layers."""
+    table = np.array([[6, 7, 9]], np.int32)
+    pred = np.array([[0, 1, 2]], np.int32)
+    f, l, _, c = _plan_on_gpu(policy, np.full((2, 2, 1, 3), -1), 0, table, pred, 2, 7)
+    assert f[:, 0].tolist() == [[6, -1, -1], [13, -1, -1]] and l[:, 0].tolist() == [[0, -1, -1], [3, -1, -1]]
+    assert c.stats()["status"] & kvc.ST_BAD_INDEX
+
+
+def test_hand_counted_plan_slot_reuse_with_a_block_held_twice():
+    """The model's hand-counted cases: the half being filled holds a block twice; only its first copy is kept."""
+    table = np.array([[4, 5]], np.int32)
+    tags = np.full((2, 1, 1, 2), -1, np.int32)
+    tags[0, 0, 0] = [4, 4]
+    f, l, t, c = _plan_on_gpu(1, tags, 0, table, np.array([[0, 1]], np.int32), 1, 8)
+    assert f[0, 0].tolist() == [-1, 5] and l[0, 0].tolist() == [0, 1] and t[0, 0, 0].tolist() == [4, 5]
+    assert c.stats()["status"] == 0
+    table = np.array([[4, 5, 6, 7]], np.int32)
+    tags = np.full((2, 1, 1, 3), -1, np.int32)
+    tags[1, 0, 0] = [4, 4, 6]
+    f, l, t, c = _plan_on_gpu(1, tags, 1, table, np.array([[1, 0, 3]], np.int32), 1, 8)
+    assert f[0, 0].tolist() == [-1, 5, 7] and l[0, 0].tolist() == [4, 3, 5] and t[1, 0, 0].tolist() == [4, 5, 7]
+    assert c.stats()["status"] == 0
+
+
 def test_hip_graph_replays_match_eager():
     """The codec's launches are capturable: one graph holds reset + compress + decompress + a prefetch step
     on two streams.  It is replayed several times with eager work and synchronisations in between and

@@ -1,0 +1,127 @@
+"""Are the pins of tests/test_oracle_pins.py sharp enough?  Each case below plants one plausible mistake in a
+copy of oracle/kvc_oracle.c (a wrong divisor, the delta taken along the wrong axis, a swapped nibble, a
+transposed index of the channel-pair order, ...), builds the copy and runs the pin tests against it in a
+process of its own: the run has to fail.  The untouched copy has to pass the same way.  Everything happens on
+the CPU and in a temporary folder; the oracle's own files are only read."""
+import concurrent.futures
+import os
+import shutil
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "kvc_oracle.c")
+
+# (name, text in the oracle, what it is replaced by)
+MUTANTS = [
+    ("scale divides by 128", "amax / 127.0f", "amax / 128.0f"),
+    ("delta along tokens instead of channels", "int left = (i == 0) ? 0 : q[j * d + i - 1];",
+     "int left = (j == 0) ? 0 : q[(j - 1) * d + i];"),
+    ("zig-zag sends negative values to even codes", "v >= 0 ? 2 * v : -2 * v - 1", "v >= 0 ? 2 * v + 1 : -2 * v - 2"),
+    ("zig-zag off by one on the negative side", "v >= 0 ? 2 * v : -2 * v - 1", "v >= 0 ? 2 * v : -2 * v + 1"),
+    ("round half up instead of ties to even", "double r = nearbyint(p);", "double r = floor(p + 0.5);"),
+    ("header nibbles swapped", "(g & 1) ? (code << 4) : code", "(g & 1) ? code : (code << 4)"),
+    ("bits of a literal packet filled from the top of each byte", "(uint8_t)(bit << (p & 7))", "(uint8_t)(bit << (7 - (p & 7)))"),
+    ("fallback only when strictly larger than INT8", "if (n >= int8_bytes)", "if (n > int8_bytes)"),
+    ("inverse scale as 127 / amax instead of 1 / s", "*s_inv = 1.0f / *s;", "*s_inv = 127.0f / amax;"),
+    ("un-zig-zag without the negation", "int delta = (int)(uu >> 1) ^ -(int)(uu & 1);", "int delta = (int)(uu >> 1) ^ (int)(uu & 1);"),
+    ("dequantize with a scale that is slightly off", "float r = (float)q[i] * desc->scale;", "float r = (float)q[i] * desc->scale * 1.0001f;"),
+    ("run packet under another code", "code = 9; /* run packet: one byte */", "code = 10;"),
+    ("all-zero literal group at width 2", "if (w == 0) w = 1;", "if (w == 0) w = 2;"),
+    ("mode 5: groups in octet-major order", "return ((o / W) * 4 + j) * W + o % W;", "return o * 4 + j;"),
+    ("mode 5: groups in pair-major order over the whole row", "return ((o / W) * 4 + j) * W + o % W;", "return (j * (d / 8)) + o;"),
+    ("mode 5: runs of 8 octets instead of 16", "int W = d / 8 < 16 ? d / 8 : 16;", "int W = d / 8 < 8 ? d / 8 : 8;"),
+    ("mode 5: token roles swapped inside a group", "int k = (t % 4) * 8 + (t / 4) * 2 + (c % 2);", "int k = (t / 4) * 8 + (t % 4) * 2 + (c % 2);"),
+    ("mode 5: the decoder reads the pair's channels the other way round",
+     "unsigned uu = u[32 * chan_group(c, d) + (t % 4) * 8 + (t / 4) * 2 + (c % 2)];",
+     "unsigned uu = u[32 * chan_group(c, d) + (t % 4) * 8 + (t / 4) * 2 + 1 - (c % 2)];"),
+]
+
+
+def _run_pins(folder, text):
+    os.makedirs(folder, exist_ok=True)
+    src = os.path.join(folder, "kvc_oracle.c")
+    with open(src, "w") as f:
+        f.write(text)
+    env = dict(os.environ, KVC_ORACLE_SRC=src, KVC_ORACLE_LIB=os.path.join(folder, "libkvc_oracle.so"))
+    # the copy has to compile: a planted mistake that does not build would "fail" for the wrong reason
+    subprocess.run([sys.executable, "-c", "from oracle import kvc_oracle; kvc_oracle.build(force=True)"], cwd=ROOT, env=env,
+                   check=True, capture_output=True, timeout=300)
+    return subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), "-x", "-q",
+                           "-p", "no:cacheprovider"], cwd=ROOT, env=env, capture_output=True, text=True, timeout=600)
+
+
+@pytest.mark.skipif(shutil.which("gcc") is None, reason="gcc not installed")
+def test_every_planted_mistake_fails_a_pin(tmp_path):
+    text = open(SRC).read()
+    for name, old, new in MUTANTS:
+        assert text.count(old) >= 1, f"'{name}': the line it changes is no longer in the oracle; update the case"
+    control = _run_pins(str(tmp_path / "control"), text)
+    assert control.returncode == 0, control.stdout[-2000:]
+    with concurrent.futures.ThreadPoolExecutor(max_workers=min(6, os.cpu_count() or 1)) as ex:
+        runs = {name: ex.submit(_run_pins, str(tmp_path / f"m{i}"), text.replace(old, new, 1))
+                for i, (name, old, new) in enumerate(MUTANTS)}
+        survivors = []
+        for name, fut in runs.items():
+            r = fut.result()
+            # a mistake is noticed by a failing pin (pytest exit status 1) or by one of the oracle's own assertions
+            # (the process aborts: -6); any other status means the run itself broke
+            assert r.returncode in (0, 1, -6), f"'{name}': the run broke instead of failing a pin\n{r.stdout[-1500:]}\n{r.stderr[-1500:]}"
+            if r.returncode == 0:
+                survivors.append(name)
+    assert not survivors, f"no pin noticed: {survivors}"
+
+
+# ------------------------------------------------------------------ the prefetch model (Algorithm 1)
+
+MODEL = os.path.join(ROOT, "oracle", "prefetch_model.py")
+
+MODEL_MUTANTS = [
+    ("the half being filled is searched instead of the other one", "other = 1 - fill", "other = fill"),
+    ("slots of the half being filled that are still to be overwritten count as resident", "for j2 in range(j):  # slots", "for j2 in range(k):  # slots"),
+    ("the layer's offset into the pool is dropped", "phys = l * pool_blocks_per_layer + e", "phys = e"),
+    ("the first block held in L1 is fetched all the same", "lb >= int(l1_first[s])", "lb > int(l1_first[s])"),
+    ("a block already in its slot is transferred again", "if tags[fill, l, s, j] != phys:", "if True:"),
+    ("window pieces one entry too long", "queue[i:i + omega]", "queue[i:i + omega + 1]"),
+    ("a layer counts as ready one batch early", "return (done + omega - 1) // omega", "return done // omega"),
+    ("slot reuse keeps duplicates", "keep.append(t in wanted and t not in seen)", "keep.append(t in wanted)"),
+    ("an entry beyond the pool's blocks is taken as a block", "if e >= pbpl:\n        return NO_BLOCK, True", "if e > pbpl:\n        return NO_BLOCK, True"),
+]
+
+# runs the model's pin tests with the module text given on stdin standing in for oracle.prefetch_model
+_RUNNER = """
+import sys, types
+sys.path.insert(0, {root!r})
+import oracle
+m = types.ModuleType("oracle.prefetch_model")
+m.__file__ = "planted"
+exec(compile(sys.stdin.read(), "planted_prefetch_model.py", "exec"), m.__dict__)
+sys.modules["oracle.prefetch_model"] = m
+oracle.prefetch_model = m
+import pytest
+sys.exit(int(pytest.main([{test!r}, "-x", "-q", "-p", "no:cacheprovider"])))
+"""
+
+
+def _run_model_pins(text):
+    code = _RUNNER.format(root=ROOT, test=os.path.join(ROOT, "tests", "test_prefetch_model.py"))
+    return subprocess.run([sys.executable, "-c", code], cwd=ROOT, input=text, capture_output=True, text=True, timeout=600)
+
+
+def test_every_mistake_planted_in_the_prefetch_model_fails_a_pin():
+    text = open(MODEL).read()
+    for name, old, new in MODEL_MUTANTS:
+        assert text.count(old) >= 1, f"'{name}': the line it changes is no longer in the model; update the case"
+    control = _run_model_pins(text)
+    assert control.returncode == 0, control.stdout[-2000:] + control.stderr[-2000:]
+    with concurrent.futures.ThreadPoolExecutor(max_workers=min(6, os.cpu_count() or 1)) as ex:
+        runs = {name: ex.submit(_run_model_pins, text.replace(old, new)) for name, old, new in MODEL_MUTANTS}
+        survivors = []
+        for name, fut in runs.items():
+            r = fut.result()
+            assert r.returncode in (0, 1), f"'{name}': the run broke instead of failing a pin\n{r.stdout[-1500:]}\n{r.stderr[-1500:]}"
+            if r.returncode == 0:
+                survivors.append(name)
+    assert not survivors, f"no pin noticed: {survivors}"

@@ -104,6 +104,39 @@ def test_layer_ranges_compose_and_bad_indices_are_flagged():
     assert bad and (l[:, 0, 0] == -1).all() and (f[:, 0, 0] == -1).all()
 
 
+@pytest.mark.parametrize("fn", [pm.prefetch_step, pm.prefetch_step_reuse], ids=["positional", "reuse"])
+def test_table_entries_at_and_beyond_the_pool_size_are_bad_indices(fn):
+    """A layer's pool holds blocks 0 .. pool_blocks_per_layer - 1: an entry equal to that count is the first
+    invalid one.  Hand-counted: one sequence, three predictions, table entries 6 (last valid), 7 (= the count)
+    and 9; two layers."""
+    table = np.array([[6, 7, 9]], np.int32)
+    pred = np.array([[0, 1, 2]], np.int32)
+    tags = np.full((2, 2, 1, 3), -1, np.int32)
+    f, l, bad = fn(tags, 0, table, pred, None, 2, 7)
+    assert bad
+    assert f[:, 0].tolist() == [[6, -1, -1], [13, -1, -1]]  # layer l's block e is pool block 7 l + e
+    assert l[:, 0].tolist() == [[0, -1, -1], [3, -1, -1]]
+    f, l, bad = fn(np.full((2, 2, 1, 3), -1, np.int32), 0, table[:, :1], pred[:, :1].repeat(3, 1), None, 2, 7)
+    assert not bad  # the last valid entry alone raises no flag
+
+
+def test_slot_reuse_counts_a_block_held_twice_only_once():
+    """The half being filled may hold one block in two slots (the positional policy leaves such states behind).
+    Only the first copy is worth keeping: the second slot is free for a new block.  Hand-counted, k = 2: the
+    half holds [X, X], the step wants [X, Y] -> Y goes into slot 1, X stays in slot 0, nothing else moves."""
+    table = np.array([[4, 5]], np.int32)  # logical block 0 -> X = 4, 1 -> Y = 5
+    tags = np.full((2, 1, 1, 2), -1, np.int32)
+    tags[0, 0, 0] = [4, 4]
+    f, l, bad = pm.prefetch_step_reuse(tags, 0, table, np.array([[0, 1]], np.int32), None, 1, 8)
+    assert not bad and f[0, 0].tolist() == [-1, 5] and l[0, 0].tolist() == [0, 1] and tags[0, 0, 0].tolist() == [4, 5]
+    # three slots [X, X, Z], wanted [Y, X, W]: slot 0 keeps X, the duplicate in slot 1 takes Y, slot 2 takes W
+    table = np.array([[4, 5, 6, 7]], np.int32)
+    tags = np.full((2, 1, 1, 3), -1, np.int32)
+    tags[1, 0, 0] = [4, 4, 6]
+    f, l, bad = pm.prefetch_step_reuse(tags, 1, table, np.array([[1, 0, 3]], np.int32), None, 1, 8)
+    assert f[0, 0].tolist() == [-1, 5, 7] and l[0, 0].tolist() == [3 + 1, 3 + 0, 3 + 2] and tags[1, 0, 0].tolist() == [4, 5, 7]
+
+
 def test_slot_reuse_transfers_one_block_per_new_block_on_a_sliding_window():
     """Predictions pos+1..pos+k with pos advancing one block at a time: after warm-up the reuse policy moves
     exactly one block per sequence per advance, the positional policy k."""

@@ -319,6 +319,9 @@ int kvo_decode_codes(const uint8_t* payload, size_t nbytes, int mode, int N, int
     const int runs = mode != KVO_MODE_DELTA; /* zero-run and run packets allowed */
     size_t hdr = (size_t)(G + 1) / 2;
     if (nbytes < hdr) return KVO_ERR_CORRUPT;
+    /* the encoder stores a page whose packed form is not smaller than its INT8 form as INT8 (the fallback
+     * step of kvo_encode_page), so no valid packed page is that large */
+    if (nbytes >= kvo_pad16((size_t)E)) return KVO_ERR_CORRUPT;
     size_t pos = hdr;
     uint8_t* u = (uint8_t*)malloc((size_t)E);
     for (int g = 0; g < G; ++g) {

@@ -329,6 +329,34 @@ def test_corrupt_descriptors_and_payloads_are_contained():
     assert st["status"] & kvc.ST_CORRUPT and st["rc"] == kvc.ERR_CORRUPT
 
 
+def test_hand_built_payloads_decode_or_are_refused_on_gpu():
+    """The payloads typed in by hand that pin the oracle's decoder (tests/handbuilt_payloads.py), through the GPU
+    decoder: packet codes, the codes a mode admits, exact payload size, the bound below the INT8 size."""
+    import handbuilt_payloads as hb
+
+    desc = np.zeros(len(hb.CASES), o.DESC_DTYPE)
+    chunks, off = [], 0
+    for i, (name, mode, payload, ok, values) in enumerate(hb.CASES):
+        desc[i]["off"], desc[i]["scale"], desc[i]["n16"], desc[i]["mode"] = off, hb.SCALE, len(payload) // 16, mode
+        chunks.append(np.frombuffer(payload, np.uint8))
+        off += len(payload)
+    pool = np.concatenate(chunks)
+    c = kvc.Codec(hb.N, hb.D, 1, 3)
+    upload_oracle_pool(c, desc, pool)
+    out = torch.full((len(hb.CASES), 1, hb.N, hb.D), 2.0, dtype=torch.float16, device=DEV)
+    c.decompress_blocks(out)
+    got = out.cpu().numpy().view(np.uint16).reshape(len(hb.CASES), hb.N, hb.D)
+    want, nbad = o.decompress_pages(pool, desc, hb.N, hb.D)
+    assert np.array_equal(got, want.reshape(got.shape)) and nbad == sum(not ok for _, _, _, ok, _ in hb.CASES)
+    for i, (name, mode, payload, ok, values) in enumerate(hb.CASES):
+        if ok:
+            assert np.array_equal(got[i], values.view(np.uint16)), name
+        else:
+            assert not got[i].any(), name
+    st = c.stats()
+    assert st["status"] & kvc.ST_CORRUPT and st["rc"] == kvc.ERR_CORRUPT
+
+
 def test_host_side_argument_errors():
     c = kvc.Codec(16, 128, 2, 3)
     x = torch.zeros((4, 2, 16, 128), dtype=torch.float16, device=DEV)

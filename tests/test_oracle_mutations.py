@@ -30,6 +30,25 @@ MUTANTS = [
     ("dequantize with a scale that is slightly off", "float r = (float)q[i] * desc->scale;", "float r = (float)q[i] * desc->scale * 1.0001f;"),
     ("run packet under another code", "code = 9; /* run packet: one byte */", "code = 10;"),
     ("all-zero literal group at width 2", "if (w == 0) w = 1;", "if (w == 0) w = 2;"),
+    ("page maximum taken over x instead of |x|", "float a = fabsf(kvo_half_to_float(x[i]));", "float a = kvo_half_to_float(x[i]);"),
+    ("infinities not recognised, only NaN", "if ((x[i] & 0x7C00u) == 0x7C00u) return 1;", "if ((x[i] & 0x7FFFu) > 0x7C00u) return 1;"),
+    ("header of an odd number of groups one byte short", "size_t hdr = (size_t)(G + 1) / 2;\n    memset(out, 0, hdr);", "size_t hdr = (size_t)G / 2;\n    memset(out, 0, hdr);"),
+    ("payload padded to 8 bytes", "return (n + 15u) & ~(size_t)15u;", "return (n + 7u) & ~(size_t)7u;"),
+    ("run packet also for groups of equal zeros under scheme 2", "if (with_runs && umax == 0) {", "if (umax == 0) {"),
+    ("run test compares with the neighbour's first value", "if (ug[k] != ug[0]) all_equal = 0;", "if (ug[k] != u[0]) all_equal = 0;"),
+    ("literal width from the first value instead of the maximum", "int w = bit_length(umax);", "int w = bit_length(ug[0] > 0 ? ug[0] : umax);"),
+    ("scheme 2 written with run packets", "kvo_rle_pack(u, E, scheme != KVO_MODE_DELTA, tmp)", "kvo_rle_pack(u, E, 1, tmp)"),
+    ("mode 4 keeps the delta step", "if (scheme == KVO_MODE_PACK)\n            kvo_zigzag_codes(q, E, u);", "if (0)\n            kvo_zigzag_codes(q, E, u);"),
+    ("decoder sums deltas across token rows", "    for (int j = 0; j < N; ++j) {\n        int acc = 0;\n        for (int i = 0; i < d; ++i) {\n            unsigned uu = u[j * d + i];",
+     "    int acc = 0;\n    for (int j = 0; j < N; ++j) {\n        for (int i = 0; i < d; ++i) {\n            unsigned uu = u[j * d + i];"),
+    ("decoder saturates the running sum instead of wrapping it", "acc = (int8_t)(uint8_t)((acc + delta) & 0xFF);",
+     "acc = acc + delta > 127 ? 127 : acc + delta < -128 ? -128 : acc + delta;"),
+    ("decoder admits zero-run and run packets in a mode-2 page", "const int runs = mode != KVO_MODE_DELTA;", "const int runs = 1;"),
+    ("decoder admits a packed page as large as its INT8 form", "if (nbytes >= kvo_pad16((size_t)E)) return KVO_ERR_CORRUPT;", "if (nbytes > kvo_pad16((size_t)E)) return KVO_ERR_CORRUPT;"),
+    ("decoder accepts a payload with trailing bytes", "if (kvo_pad16(pos) != nbytes) goto corrupt;", "if (kvo_pad16(pos) > nbytes) goto corrupt;"),
+    ("decoder accepts code 10 as a literal of width 8", "} else if (code >= 1 && code <= 8) {\n            int w = code;", "} else if (code >= 1) {\n            int w = code > 8 ? 8 : code;"),
+    ("scale of an all-zero page is 1", "*s = 0.0f;\n        *s_inv = 0.0f;", "*s = 1.0f;\n        *s_inv = 0.0f;"),
+    ("raw page reports the wrong size", "desc->n16 = (uint16_t)(E * 2 / 16);", "desc->n16 = (uint16_t)(E / 16);"),
     ("mode 5: groups in octet-major order", "return ((o / W) * 4 + j) * W + o % W;", "return o * 4 + j;"),
     ("mode 5: groups in pair-major order over the whole row", "return ((o / W) * 4 + j) * W + o % W;", "return (j * (d / 8)) + o;"),
     ("mode 5: runs of 8 octets instead of 16", "int W = d / 8 < 16 ? d / 8 : 16;", "int W = d / 8 < 8 ? d / 8 : 8;"),

@@ -378,6 +378,22 @@ def test_corrupt_descriptors_are_rejected_and_zero_filled():
     assert rc != 0 and not out.any()
 
 
+def test_hand_built_payloads_decode_or_are_refused():
+    """Payloads typed in by hand (tests/handbuilt_payloads.py): what the packet codes mean on decode, which codes
+    a mode admits, and that the payload size has to be exactly what the packets need and below the INT8 size."""
+    import handbuilt_payloads as hb
+
+    for name, mode, payload, ok, values in hb.CASES:
+        desc = np.zeros(1, o.DESC_DTYPE)[0]
+        desc["scale"], desc["n16"], desc["mode"] = hb.SCALE, len(payload) // 16, mode
+        rc, out = o.decode_page(payload, desc, hb.N, hb.D)
+        if ok:
+            assert rc == 0, name
+            assert np.array_equal(out.reshape(hb.N, hb.D), values.view(np.uint16)), name
+        else:
+            assert rc != 0 and not out.any(), name
+
+
 def test_batch_driver_is_thread_count_independent_and_contiguous():
     rng = np.random.default_rng(13)
     x = (rng.standard_normal((37, 16, 64)) * np.exp(rng.standard_normal((37, 1, 64)))).astype(np.float16)

@@ -143,7 +143,7 @@ def decode_page(payload: bytes, desc, N: int, d: int):
         buf = np.zeros(1, np.uint8)
     dd = np.zeros(1, DESC_DTYPE)
     dd[0] = desc
-    out = np.zeros(N * d, np.uint16)
+    out = np.full(N * d, 0xFFFF, np.uint16)  # the C side writes every element: values, or zeros for a refused page
     rc = lib().kvo_decode_page(_p(buf, C.c_uint8), dd.ctypes.data, N, d, _p(out, C.c_uint16))
     return rc, out
 
@@ -173,7 +173,7 @@ def decompress_pages(pool, desc, N: int, d: int, page_ids=None, n_threads: int =
     else:
         page_ids = np.ascontiguousarray(page_ids, np.int64)
         n_pages, ids_p = page_ids.size, _p(page_ids, C.c_int64)
-    out = np.zeros((n_pages, N, d), np.uint16)
+    out = np.full((n_pages, N, d), 0xFFFF, np.uint16)  # as in decode_page
     pool_arg = pool if pool.size else np.zeros(16, np.uint8)
     bad = lib().kvo_decompress_pages(_p(pool_arg, C.c_uint8), pool.size, desc.ctypes.data, ids_p, n_pages, N, d,
                                      _p(out, C.c_uint16), n_threads)

@@ -43,6 +43,16 @@ CASES = [
      np.concatenate([np.full(64, 63.5), np.zeros(64)]).astype(np.float16).reshape(N, D)),
     ("packed page as large as its INT8 form", 3, _pad(bytes([0x88, 0x78]) + _G0 + bytes(32) + bytes(32) + bytes(28)), False, None),
     ("packed page larger than its INT8 form", 3, _pad(bytes([0x88, 0x88]) + _G0 + bytes(32) + bytes(32) + bytes(32)), False, None),
+    # mode 1: the 128 codes as they are (two's complement), scale 0.5
+    ("INT8 page", 1, bytes([127, 0x81, 1, 0xFF] + [0] * 124), True,
+     np.array([63.5, -63.5, 0.5, -0.5] + [0.0] * 124, np.float16).reshape(N, D)),
+    ("INT8 page with sixteen bytes too many", 1, bytes([127, 0x81, 1, 0xFF] + [0] * 140), False, None),
+    ("INT8 page with sixteen bytes too few", 1, bytes([127, 0x81, 1, 0xFF] + [0] * 108), False, None),
+    # mode 0: the FP16 bit patterns, little-endian (0x3C00 = 1.0, 0xC000 = -2.0, 0x7E00 = a NaN)
+    ("raw page", 0, bytes([0x00, 0x3C, 0x00, 0xC0, 0x00, 0x7E] + [0] * 250), True,
+     np.array([0x3C00, 0xC000, 0x7E00] + [0] * 125, np.uint16).view(np.float16).reshape(N, D)),
+    ("raw page with sixteen bytes too many", 0, bytes([0x00, 0x3C] + [0] * 270), False, None),
+    ("raw page with sixteen bytes too few", 0, bytes([0x00, 0x3C] + [0] * 238), False, None),
 ]
 for _name, _mode, _pl, _ok, _val in CASES:
     assert len(_pl) % 16 == 0 and (_val is None) == (not _ok)

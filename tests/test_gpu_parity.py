@@ -357,6 +357,34 @@ def test_hand_built_payloads_decode_or_are_refused_on_gpu():
     assert st["status"] & kvc.ST_CORRUPT and st["rc"] == kvc.ERR_CORRUPT
 
 
+def test_products_next_to_a_tie_on_gpu():
+    """Pages whose elements multiply with s^-1 to a hair beside k + 1/2 (tests/adversarial_inputs.py, the inputs
+    of the oracle's pin): one page per page maximum, holding that maximum and every such element with both signs.
+    Codes compared through the INT8 scheme (the codes themselves) and the full scheme."""
+    import adversarial_inputs as adv
+
+    by_amax = {}
+    for amax, xv, q in adv.near_half_products():
+        by_amax.setdefault(float(amax), []).append((xv, q))
+    N, d = 16, 128
+    x = np.zeros((len(by_amax), N * d), np.float16)
+    want_q = np.zeros((len(by_amax), N * d), np.int8)
+    for i, (amax, lst) in enumerate(sorted(by_amax.items())):
+        x[i, 0], want_q[i, 0] = amax, 127
+        for j, (xv, q) in enumerate(lst):
+            x[i, 1 + 2 * j], x[i, 2 + 2 * j] = xv, -xv
+            want_q[i, 1 + 2 * j], want_q[i, 2 + 2 * j] = q, -q
+    x = x.reshape(-1, N, d)
+    for scheme in (1, 3):
+        c, _ = gpu_compress(x, N, d, 1, scheme)
+        desc, pool = c.desc_numpy(), c.pool.cpu().numpy()
+        compare_pages_with_oracle(x.view(np.uint16), desc, pool, N, d, scheme)
+        if scheme == 1:  # the payload is the codes: compare with the exact-arithmetic values directly
+            assert (desc["mode"] == 1).all()
+            got = np.stack([pool[int(o_):int(o_) + N * d] for o_ in desc["off"]]).view(np.int8)
+            assert np.array_equal(got, want_q)
+
+
 def test_host_side_argument_errors():
     c = kvc.Codec(16, 128, 2, 3)
     x = torch.zeros((4, 2, 16, 128), dtype=torch.float16, device=DEV)

@@ -49,6 +49,17 @@ MUTANTS = [
     ("decoder accepts code 10 as a literal of width 8", "} else if (code >= 1 && code <= 8) {\n            int w = code;", "} else if (code >= 1) {\n            int w = code > 8 ? 8 : code;"),
     ("scale of an all-zero page is 1", "*s = 0.0f;\n        *s_inv = 0.0f;", "*s = 1.0f;\n        *s_inv = 0.0f;"),
     ("raw page reports the wrong size", "desc->n16 = (uint16_t)(E * 2 / 16);", "desc->n16 = (uint16_t)(E / 16);"),
+    ("product rounded to binary32 before it is rounded to an integer", "double p = (double)kvo_half_to_float(x[i]) * (double)*s_inv;",
+     "double p = (double)(float)((double)kvo_half_to_float(x[i]) * (double)*s_inv);"),
+    ("mode 4 decoded as if it had a delta step", "if (mode == KVO_MODE_PACK) acc = 0;", ""),
+    ("INT8 page of any size accepted", "if (nbytes != kvo_pad16((size_t)E)) return KVO_ERR_CORRUPT;", ""),
+    ("raw page of any size accepted", "if (nbytes != (size_t)E * 2) goto bad;", ""),
+    ("a refused page keeps what the output held", "bad:\n    memset(out, 0, (size_t)E * 2);", "bad:"),
+    ("descriptor offsets of the second thread's pages not shifted", "desc[p].off += (uint64_t)total;", "desc[p].off += 0;"),
+    ("a span that ends outside the pool is decoded", "ds->off + (uint64_t)ds->n16 * 16 > j->pool_bytes", "ds->off > j->pool_bytes"),
+    ("a misaligned span is decoded", "if (ds->off % 16 != 0 || ", "if ("),
+    ("gathered decode ignores the page ids", "&j->desc[j->page_ids ? j->page_ids[p] : p]", "&j->desc[p]"),
+    ("mode 5 offered for 8-token pages", "static int chan_geometry_ok(int N, int d) {", "static int chan_geometry_ok(int N, int d) {\n    if (N == 8) return 1;"),
     ("mode 5: groups in octet-major order", "return ((o / W) * 4 + j) * W + o % W;", "return o * 4 + j;"),
     ("mode 5: groups in pair-major order over the whole row", "return ((o / W) * 4 + j) * W + o % W;", "return (j * (d / 8)) + o;"),
     ("mode 5: runs of 8 octets instead of 16", "int W = d / 8 < 16 ? d / 8 : 16;", "int W = d / 8 < 8 ? d / 8 : 8;"),
@@ -85,9 +96,10 @@ def test_every_planted_mistake_fails_a_pin(tmp_path):
         survivors = []
         for name, fut in runs.items():
             r = fut.result()
-            # a mistake is noticed by a failing pin (pytest exit status 1) or by one of the oracle's own assertions
-            # (the process aborts: -6); any other status means the run itself broke
-            assert r.returncode in (0, 1, -6), f"'{name}': the run broke instead of failing a pin\n{r.stdout[-1500:]}\n{r.stderr[-1500:]}"
+            # a mistake is noticed by a failing pin (pytest exit status 1), by one of the oracle's own assertions (the
+            # process aborts: -6) or, for a removed bounds check, by the crash it leads to (-11); any other status
+            # means the run itself broke
+            assert r.returncode in (0, 1, -6, -11), f"'{name}': the run broke instead of failing a pin\n{r.stdout[-1500:]}\n{r.stderr[-1500:]}"
             if r.returncode == 0:
                 survivors.append(name)
     assert not survivors, f"no pin noticed: {survivors}"

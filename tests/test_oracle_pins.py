@@ -100,6 +100,20 @@ def test_scale_is_binary32_quotient_and_codes_follow_exact_product():
         assert np.abs(q.astype(int)).max() == 127  # the amax element always maps to +-127
 
 
+def test_products_next_to_a_tie_are_rounded_once():
+    """x * s^-1 a hair away from k + 1/2 (tests/adversarial_inputs.py): a product first rounded to binary32 and then
+    to an integer lands on the tie and takes the wrong neighbour; the exact product rounded once does not."""
+    import adversarial_inputs as adv
+
+    cases = adv.near_half_products()
+    assert len(cases) > 100 and len({q for _, _, q in cases}) > 10
+    for amax, xv, q in cases:
+        page = np.zeros(32, np.float16)
+        page[0], page[1], page[2] = amax, xv, -xv
+        nf, s, si, got = o.quantize_page(page)
+        assert (int(got[0]), int(got[1]), int(got[2])) == (127, q, -q), (amax, xv)
+
+
 def test_quantization_error_bound():
     """|x*s_inv - q| <= 1/2 and s_inv = (1/s)(1+e), |e| <= 2^-24, |q| <= 127 give
     |x - q*s| <= s/2 + 127*s*2^-24 (1+2^-24) < s/2 (1 + 2^-15); after the binary32 product and the
@@ -392,6 +406,29 @@ def test_hand_built_payloads_decode_or_are_refused():
             assert np.array_equal(out.reshape(hb.N, hb.D), values.view(np.uint16)), name
         else:
             assert rc != 0 and not out.any(), name
+
+
+def test_batch_decoder_refuses_spans_that_are_misaligned_or_leave_the_pool():
+    """Hand-counted: a 256-byte pool with complete copies of one valid 48-byte page at byte 0, at byte 56 (not a
+    multiple of 16) and at byte 224 (its last 16 bytes lie behind the pool's end, in memory that exists).  Only
+    the first may be decoded, although the bytes of the other two are all there."""
+    import handbuilt_payloads as hb
+
+    name, mode, payload, ok, values = hb.CASES[0]
+    assert ok and len(payload) == 48
+    memory = np.zeros(272, np.uint8)
+    for at in (0, 56, 224):
+        memory[at:at + 48] = np.frombuffer(payload, np.uint8)
+    pool = memory[:256]
+    desc = np.zeros(3, o.DESC_DTYPE)
+    desc["scale"], desc["n16"], desc["mode"] = hb.SCALE, 3, mode
+    desc["off"] = [0, 56, 224]
+    out, nbad = o.decompress_pages(pool, desc, hb.N, hb.D)
+    assert nbad == 2 and np.array_equal(out[0], values.view(np.uint16)) and not out[1:].any()
+    memory[208:256] = np.frombuffer(payload, np.uint8)  # the last span that fits
+    desc["off"] = [0, 208, 0]
+    out, nbad = o.decompress_pages(pool, desc, hb.N, hb.D, n_threads=3)
+    assert nbad == 0 and all(np.array_equal(out[i], values.view(np.uint16)) for i in range(3))
 
 
 def test_batch_driver_is_thread_count_independent_and_contiguous():

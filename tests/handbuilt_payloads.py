@@ -43,6 +43,10 @@ CASES = [
      np.concatenate([np.full(64, 63.5), np.zeros(64)]).astype(np.float16).reshape(N, D)),
     ("packed page as large as its INT8 form", 3, _pad(bytes([0x88, 0x78]) + _G0 + bytes(32) + bytes(32) + bytes(28)), False, None),
     ("packed page larger than its INT8 form", 3, _pad(bytes([0x88, 0x88]) + _G0 + bytes(32) + bytes(32) + bytes(32)), False, None),
+    ("the first payload labelled mode 4: no delta step", 4, _pad(bytes([0x18, 0x11]) + _G0 + _G1 + _G2 + _G3), True,
+     np.array([63.5] + [0.0] * 31 + [-0.5] + [0.0] * 31 + [0.0] * 63 + [-0.5], np.float16).reshape(N, D)),
+    ("the first payload labelled mode 5, which 2-token pages do not have", 5, _pad(bytes([0x18, 0x11]) + _G0 + _G1 + _G2 + _G3), False, None),
+    ("the first payload labelled mode 6", 6, _pad(bytes([0x18, 0x11]) + _G0 + _G1 + _G2 + _G3), False, None),
     # mode 1: the 128 codes as they are (two's complement), scale 0.5
     ("INT8 page", 1, bytes([127, 0x81, 1, 0xFF] + [0] * 124), True,
      np.array([63.5, -63.5, 0.5, -0.5] + [0.0] * 124, np.float16).reshape(N, D)),

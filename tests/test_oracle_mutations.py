@@ -60,6 +60,18 @@ MUTANTS = [
     ("a misaligned span is decoded", "if (ds->off % 16 != 0 || ", "if ("),
     ("gathered decode ignores the page ids", "&j->desc[j->page_ids ? j->page_ids[p] : p]", "&j->desc[p]"),
     ("mode 5 offered for 8-token pages", "static int chan_geometry_ok(int N, int d) {", "static int chan_geometry_ok(int N, int d) {\n    if (N == 8) return 1;"),
+    ("FP16 subnormals scaled by 2^-25", "v = ldexp((double)m, -24);", "v = ldexp((double)m, -25);"),
+    ("FP16 normals lose the hidden bit", "v = ldexp((double)(m + 1024), e - 25);", "v = ldexp((double)m, e - 25);"),
+    ("FP16 exponent bias off by one", "v = ldexp((double)(m + 1024), e - 25);", "v = ldexp((double)(m + 1024), e - 24);"),
+    ("rounding to FP16 truncates", "double m = nearbyint(ldexp(a, 10 - e)); /* in [1024, 2048] */", "double m = floor(ldexp(a, 10 - e));"),
+    ("rounding to FP16 rounds ties away from zero", "double m = nearbyint(ldexp(a, 10 - e)); /* in [1024, 2048] */", "double m = floor(ldexp(a, 10 - e) + 0.5);"),
+    ("a mantissa that rounds up to 2048 keeps its exponent", "        m = 1024.0;\n        e += 1;", "        m = 2047.0;"),
+    ("values past 65504 stay finite", "if (e > 15) return (uint16_t)(sign | 0x7C00u);", "if (e > 15) return (uint16_t)(sign | 0x7BFFu);"),
+    ("FP16 subnormal results rounded ties away", "double m = nearbyint(ldexp(a, 24));", "double m = floor(ldexp(a, 24) + 0.5);"),
+    ("negative zero loses its sign on the way to FP16", "uint16_t sign = signbit(f) ? 0x8000u : 0u;", "uint16_t sign = f < 0 ? 0x8000u : 0u;"),
+    ("mode 5 offered for d = 192", "(d / 8 <= 16 || (d / 8) % 16 == 0)", "(d / 8 <= 16 || (d / 8) % 8 == 0)"),
+    ("thread ranges overlap by one page", "j->p1 = n_pages * (t + 1) / n_threads;", "j->p1 = n_pages * (t + 1) / n_threads + (t + 1 < n_threads ? 1 : 0);"),
+    ("pool space check off by one page", "if ((uint64_t)total + j->used > pool_bytes) {", "if ((uint64_t)total > pool_bytes) {"),
     ("mode 5: groups in octet-major order", "return ((o / W) * 4 + j) * W + o % W;", "return o * 4 + j;"),
     ("mode 5: groups in pair-major order over the whole row", "return ((o / W) * 4 + j) * W + o % W;", "return (j * (d / 8)) + o;"),
     ("mode 5: runs of 8 octets instead of 16", "int W = d / 8 < 16 ? d / 8 : 16;", "int W = d / 8 < 8 ? d / 8 : 8;"),

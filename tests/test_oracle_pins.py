@@ -431,6 +431,47 @@ def test_batch_decoder_refuses_spans_that_are_misaligned_or_leave_the_pool():
     assert nbad == 0 and all(np.array_equal(out[i], values.view(np.uint16)) for i in range(3))
 
 
+def test_channel_pair_mode_exists_only_where_its_group_order_covers_the_page():
+    """Mode 5 is defined for 16-token pages whose channel octets make whole runs of W = min(16, d / 8): d up to
+    128, and 256.  For 160, 192 and 224 channels the group formula would leave groups unfilled and fill others
+    twice (hand-counted at d = 192: 24 octets, W = 16; octet 23, pair 3 -> group (1 * 4 + 3) * 16 + 7 = 119,
+    but the page has only 96 groups), and other page lengths have no 16 tokens to spread over a group."""
+    rng = np.random.default_rng(15)
+    for N, d, has in ((16, 32, True), (16, 64, True), (16, 96, True), (16, 128, True), (16, 256, True),
+                      (16, 160, False), (16, 192, False), (16, 224, False), (8, 128, False), (32, 64, False), (4, 256, False)):
+        x = rng.integers(-3, 4, (N, d)).astype(np.float16)
+        x[0, 0] = 127  # s = 1: small codes, so the page packs
+        if has:
+            desc, payload = o.encode_page(x, N, d, 5)
+            rc, out = o.decode_page(payload, desc, N, d)
+            assert rc == 0 and desc["mode"] == 5 and np.array_equal(out.view(np.float16).reshape(N, d), x)
+        else:
+            with pytest.raises(ValueError):
+                o.encode_page(x, N, d, 5)
+            desc, payload = o.encode_page(x, N, d, 4)   # a well-formed packed page of that shape ...
+            assert desc["mode"] == 4
+            desc["mode"] = 5                            # ... relabelled as mode 5 is refused
+            rc, out = o.decode_page(payload, desc, N, d)
+            assert rc != 0 and not out.any()
+
+
+def test_batch_encoder_reports_a_pool_that_is_too_small():
+    """Hand-counted: three INT8 pages of 2 x 64 elements need 3 * 128 bytes; a pool of 383 bytes is too small by
+    one byte (error KVO_ERR_SPACE = -3, nothing may be written behind it), 384 bytes are enough."""
+    import ctypes as C
+
+    x = np.arange(3 * 128, dtype=np.float32).reshape(3, 2, 64).astype(np.float16)
+    L = o.lib()
+    for pool_bytes, want in ((383, -3), (384, 384), (256, -3), (0, -3)):
+        pool = np.full(1024, 0xEE, np.uint8)
+        desc = np.zeros(3, o.DESC_DTYPE)
+        for n_threads in (1, 3):
+            got = L.kvo_compress_pages(x.view(np.uint16).ctypes.data_as(C.POINTER(C.c_uint16)), 3, 2, 64, 1,
+                                       pool.ctypes.data_as(C.POINTER(C.c_uint8)), pool_bytes, desc.ctypes.data, n_threads)
+            assert got == want, (pool_bytes, n_threads)
+            assert (pool[pool_bytes:] == 0xEE).all()
+
+
 def test_batch_driver_is_thread_count_independent_and_contiguous():
     rng = np.random.default_rng(13)
     x = (rng.standard_normal((37, 16, 64)) * np.exp(rng.standard_normal((37, 1, 64)))).astype(np.float16)

@@ -126,6 +126,14 @@ def test_hand_counted_plans_boundary_entry(policy):
     assert c.stats()["status"] & kvc.ST_BAD_INDEX
 
 
+@pytest.mark.parametrize("policy", [0, 1])
+def test_hand_counted_plan_unmapped_logical_block(policy):
+    """The model's hand-counted case: a table entry of -1 is skipped and is no error."""
+    f, l, t, c = _plan_on_gpu(policy, np.full((2, 1, 1, 2), -1), 0, np.array([[4, -1]], np.int32), np.array([[0, 1]], np.int32), 1, 8)
+    assert f[0, 0].tolist() == [4, -1] and l[0, 0].tolist() == [0, -1] and t[0, 0, 0].tolist() == [4, -1]
+    assert c.stats()["status"] == 0
+
+
 def test_hand_counted_plan_slot_reuse_with_a_block_held_twice():
     """The model's hand-counted cases: the half being filled holds a block twice; only its first copy is kept."""
     table = np.array([[4, 5]], np.int32)

@@ -130,6 +130,15 @@ MODEL_MUTANTS = [
     ("window pieces one entry too long", "queue[i:i + omega]", "queue[i:i + omega + 1]"),
     ("a layer counts as ready one batch early", "return (done + omega - 1) // omega", "return done // omega"),
     ("slot reuse keeps duplicates", "keep.append(t in wanted and t not in seen)", "keep.append(t in wanted)"),
+    ("window queue in sequence-major order", "    for l in range(layer_begin, layer_end):\n        for s in range(fetch.shape[1]):\n            for j in range(fetch.shape[2]):\n                if fetch[l, s, j] >= 0:",
+     "    for s in range(fetch.shape[1]):\n        for l in range(layer_begin, layer_end):\n            for j in range(fetch.shape[2]):\n                if fetch[l, s, j] >= 0:"),
+    ("window counts a layer's slots instead of its transfers", "                    per_layer[l] += 1", "                per_layer[l] += 1"),
+    ("window queues slots that issued nothing", "if fetch[l, s, j] >= 0:\n                    queue.append", "if True:\n                    queue.append"),
+    ("unbounded window reports every layer ready at once, also those behind an empty prefix", "return (done > 0).astype(np.int64)", "return np.ones_like(done, dtype=np.int64)"),
+    ("a negative prediction is a bad index", "    if lb < 0:\n        return NO_BLOCK, False", "    if lb < 0:\n        return NO_BLOCK, True"),
+    ("an empty table entry is a bad index", "    if e < 0:\n        return NO_BLOCK, False", "    if e < 0:\n        return NO_BLOCK, True"),
+    ("positional policy: a prediction beyond the table is skipped silently", "                if lb >= max_blocks:\n                    bad_index = True", "                if lb >= max_blocks:\n                    bad_index = bad_index"),
+    ("slot reuse takes the highest free slot", "j2 = keep.index(False)", "j2 = len(keep) - 1 - keep[::-1].index(False)"),
     ("an entry beyond the pool's blocks is taken as a block", "if e >= pbpl:\n        return NO_BLOCK, True", "if e > pbpl:\n        return NO_BLOCK, True"),
 ]
 

@@ -204,3 +204,16 @@ def test_window_closed_forms():
     assert pm.batches_until_ready(per_layer, 0).tolist() == [1, 1, 1]
     q0, p0, b0 = pm.window_schedule(np.full((2, 2, 2), -1, np.int32), 4)
     assert q0.size == 0 and p0.tolist() == [0, 0] and b0 == []
+    # layers that come before the first transfer wait for nothing: transfers per layer (0, 3, 0, 2)
+    per = np.array([0, 3, 0, 2], np.int32)
+    assert pm.batches_until_ready(per, 0).tolist() == [0, 1, 1, 1]
+    assert pm.batches_until_ready(per, 2).tolist() == [0, 2, 2, 3]
+
+
+@pytest.mark.parametrize("fn", [pm.prefetch_step, pm.prefetch_step_reuse], ids=["positional", "reuse"])
+def test_an_unmapped_logical_block_is_skipped_without_a_flag(fn):
+    """A table entry of -1 means the sequence has no such block (tables are padded with it): nothing is
+    transferred for it, `loc` says -1, and it is not an error.  Hand-counted: table (4, -1), predictions (0, 1)."""
+    tags = np.full((2, 1, 1, 2), -1, np.int32)
+    f, l, bad = fn(tags, 0, np.array([[4, -1]], np.int32), np.array([[0, 1]], np.int32), None, 1, 8)
+    assert not bad and f[0, 0].tolist() == [4, -1] and l[0, 0].tolist() == [0, -1] and tags[0, 0, 0].tolist() == [4, -1]

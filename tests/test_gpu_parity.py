@@ -274,6 +274,30 @@ def test_gather_decompress_small_pattern():
     assert st["status"] & kvc.ST_BAD_INDEX and st["rc"] == kvc.ERR_CORRUPT
 
 
+def test_gather_hand_counted_table_entries():
+    """Hand-counted fetch through a translation table: two layers of 7 pool blocks, one sequence with table entries
+    (6, 7, -1) and predictions (0, 1, 2).  Entry 6 is the layer's last block: layer l reads pool block 7 l + 6.
+    Entry 7 equals the layer's block count: a bad index, its output block is zero-filled.  Entry -1: the
+    sequence has no such block, its output block is left as it was."""
+    rng = np.random.default_rng(31)
+    N, d, ppb, n_layers, pbl = 16, 64, 2, 2, 7
+    x = rng.standard_normal((n_layers * pbl, ppb, N, d)).astype(np.float16)
+    c, _ = gpu_compress(x, N, d, ppb, 3)
+    od, op = o.compress_pages(x.view(np.uint16), N, d, 3)
+    full = o.decompress_pages(op, od, N, d)[0].reshape(n_layers * pbl, ppb, N, d)
+    table = torch.tensor([[6, 7, -1]], dtype=torch.int32, device=DEV)
+    pred = torch.tensor([[0, 1, 2]], dtype=torch.int32, device=DEV)
+    out = torch.full((n_layers * 3, ppb, N, d), 3.0, dtype=torch.float16, device=DEV)
+    c.gather_decompress(out, table, pred, n_layers, pbl)
+    got = out.cpu().numpy().view(np.uint16).reshape(n_layers, 3, ppb, N, d)
+    for l in range(n_layers):
+        assert np.array_equal(got[l, 0], full[7 * l + 6])
+        assert not got[l, 1].any()
+        assert (got[l, 2].view(np.float16) == 3.0).all()
+    st = c.stats()
+    assert st["status"] == kvc.ST_BAD_INDEX and st["rc"] == kvc.ERR_CORRUPT
+
+
 def test_pool_exhaustion_marks_pages_invalid():
     rng = np.random.default_rng(5)
     N, d, ppb = 16, 128, 1

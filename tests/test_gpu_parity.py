@@ -469,6 +469,25 @@ def test_per_block_scheme_selection():
     assert (got[schemes == 0] == x.view(np.uint16)[schemes == 0]).all()  # RAW blocks come back bit-exact
 
 
+@pytest.mark.parametrize("N,d,highest", [(16, 128, 5), (16, 64, 5), (16, 96, 4), (8, 128, 4)])
+def test_per_block_modes_above_the_highest_are_read_as_the_highest(N, d, highest):
+    """kvc_compress_blocks_mixed documents that a requested mode above the highest the page shape has (5 where
+    mode 5 exists, else 4) is read as that highest mode."""
+    rng = np.random.default_rng(46 + d)
+    nb = 12
+    x = (rng.standard_normal((nb, 1, N, d)) * np.exp(0.7 * rng.standard_normal(d))).astype(np.float16)
+    asked = np.array([highest, highest + 1, 6, 7, 9, 100, 128, 200, 254, 255, 3, 0], np.uint8)
+    c = make_codec(N, d, 1, 3, nb)
+    c.compress_blocks(torch.from_numpy(x).to(DEV), block_scheme=torch.from_numpy(asked).to(DEV))
+    assert c.stats()["rc"] == 0
+    desc, pool = c.desc_numpy(), c.pool.cpu().numpy()
+    for b in range(nb):
+        dd, pl = o.encode_page(x[b, 0], N, d, min(int(asked[b]), highest))
+        g = desc[b]
+        assert (g["mode"], g["n16"]) == (dd["mode"], dd["n16"]) and g["scale"] == dd["scale"], (b, asked[b])
+        assert pool[int(g["off"]):int(g["off"]) + 16 * int(g["n16"])].tobytes() == pl
+
+
 def test_pool_in_pinned_host_memory():
     """The compressed pool behind the host link (slow-tier emulation): same bytes as the oracle, read
     straight from the pinned buffer on the CPU; pageable memory is refused."""
